@@ -1,0 +1,264 @@
+/*
+ * alch.h -- C ABI of the activation-reuse training hot path for AMD MI355X (gfx950).
+ *
+ * Method (Alchemist, arXiv 2503.01066): the activations a model produces while it
+ * serves a prompt are the ones a training forward pass over the same prompt would
+ * produce, so online continual training can skip that forward pass and start
+ * back-propagation from them (Section 1; Section 2.5.1; requirement R1 in
+ * Section 3).  Two kernel families implement the device side of that statement:
+ *
+ *   1. capture/pack  -- while the prompt is prefilled, the per-layer activations of
+ *      the tokens that are to be trained on are gathered into dense per-layer
+ *      records (Section 4.1: record only in the prefill phase; Section 5: every saved
+ *      tensor is tagged with the layer that owns it).
+ *   2. backward from the saved record -- the decoder-layer backward pass, one layer
+ *      at a time from the output layer to the input layer (Section 4.2: the trainer
+ *      can be pre-empted at the start of each layer's backward; Section 4.3.2: layers
+ *      are consumed in reverse order), topped by the cross-entropy loss on the saved
+ *      prefill output (Section 5, Section 6 "Training").
+ *
+ * The paper trains Llama-3.1-8B, Mistral and Phi-4 (Section 6): pre-norm decoder
+ * layers with RMSNorm, rotary position embedding, grouped-query causal attention and
+ * a SwiGLU MLP.  The paper prints no formulas; the layer function is
+ *
+ *   h1 = x * rsqrt(mean(x^2) + eps) * g1
+ *   q = RoPE(h1 Wq^T)   k = RoPE(h1 Wk^T)   v = h1 Wv^T
+ *   o = softmax_causal(q k^T / sqrt(D)) v          (query head h reads kv head h / (Hq/Hkv))
+ *   x2 = x + o Wo^T      h2 = x2 * rsqrt(mean(x2^2) + eps) * g2
+ *   y = x2 + (silu(h2 Wg^T) * (h2 Wu^T)) Wd^T
+ *
+ * with RoPE pairing element i with i + D/2 at angle position * base^(-2i/D).
+ * The saved record of a layer is { X, X2, Q, K, V, O, LSE, G, U }: layer input, the
+ * post-attention residual stream, Q and K after RoPE (what a KV cache holds, Section
+ * 4.1), V, the attention output, the natural-log softmax normaliser per (token, query
+ * head), and the gate / up projections before the activation.
+ *
+ * General conventions
+ *   - Every pointer is DEVICE memory unless marked "host".  The caller owns every
+ *     buffer, including the workspace; the library allocates no device memory and
+ *     keeps no state between calls.
+ *   - Every call validates its arguments on the host first, then enqueues kernels on
+ *     `hip_stream` (a hipStream_t passed as void*, NULL = the default stream) and
+ *     returns without synchronising.  ALCH_OK means "enqueued".
+ *   - Activations are packed row-major [tokens, width], heads contiguous inside a row
+ *     ([T, heads, D]).  Weights are row-major [out, in] (y = x W^T).  Base pointers must
+ *     be 16-byte aligned.
+ *   - Errors: negative alch_status; a human-readable message for the calling thread is
+ *     returned by alch_last_error().  No C++ exception crosses this boundary.
+ */
+#ifndef ALCH_H
+#define ALCH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ALCH_OK = 0,
+    ALCH_ERR_INVALID_ARG = -1, /* NULL / misaligned pointer, negative size, bad enum */
+    ALCH_ERR_SHAPE = -2,       /* inconsistent or unsupported dimensions */
+    ALCH_ERR_WORKSPACE = -3,   /* workspace missing or smaller than the *_workspace_bytes query */
+    ALCH_ERR_STALE = -4,       /* record captured under other weights than the ones passed */
+    ALCH_ERR_UNSUPPORTED = -5, /* valid request that this build does not implement */
+    ALCH_ERR_HIP = -6,         /* a HIP runtime call failed (message has the HIP error string) */
+    ALCH_ERR_ABORTED = -7      /* the preempt hook asked to stop */
+} alch_status;
+
+typedef enum { ALCH_F32 = 0, ALCH_BF16 = 1 } alch_dtype;
+
+/* Decoder-layer dimensions.  n_q_heads must be a multiple of n_kv_heads, head_dim even.
+ * dtype is the storage type of every activation, weight and gradient (LSE is always
+ * fp32); arithmetic accumulates in fp32. */
+typedef struct {
+    int32_t hidden, n_q_heads, n_kv_heads, head_dim, ffn;
+    float rms_eps, rope_base;
+    alch_dtype dtype;
+} alch_layer_shape;
+
+/* A ragged batch of prompts laid end to end (Section 4.1: the prefill batch). */
+typedef struct {
+    int32_t n_seqs, total_tokens, max_seqlen;
+    const int32_t* cu_seqlens; /* device [n_seqs+1]: cu[0]=0, non-decreasing, cu[n_seqs]=total_tokens */
+    const int32_t* positions;  /* device [total_tokens] RoPE positions, or NULL => index inside the sequence */
+    const int32_t* cu_seqlens_host; /* host copy of cu_seqlens (same values); used for validation and
+                                       launch planning so that no call has to read device memory */
+} alch_batch;
+
+/* ------------------------------------------------------------------------------------
+ * Family 1: capture/pack (Section 4.1 "Record and cache activation"; Section 5).
+ *
+ * One source/destination pair of the gather.  `src` has one row per token of the batch,
+ * rows `src_row_stride_bytes` apart (so a stream may be a column slice of a fused
+ * buffer, e.g. Q inside [T, (Hq+2Hkv) D]); `dst` is dense, rows `row_bytes` apart.
+ * row_bytes must be a multiple of 4; row_bytes, the stride and both pointers multiples of
+ * 16 take the fast path.
+ */
+typedef struct {
+    const void* src;
+    void* dst;
+    size_t row_bytes;
+    size_t src_row_stride_bytes;
+} alch_stream; /* the array of these lives in HOST memory */
+
+/*
+ * alch_capture_pack: kept = ascending list of tokens t with keep_mask[t] != 0;
+ *   kept_index[r] = kept[r];  cu_kept[s] = #{t in kept : t < cu_seqlens[s]};
+ *   for every stream k and r < n_kept: dst_k[r, :] = src_k[kept[r], :]  (bit-for-bit).
+ * The result is unique, so it is deterministic and bit-exact.
+ *
+ *   keep_mask          device uint8 [total_tokens]; any nonzero byte keeps the token
+ *   n_streams, streams host array of n_streams descriptors (may be 0 streams: index only)
+ *   dst_capacity_rows  rows every dst (and kept_index) can hold.  If n_kept exceeds it,
+ *                      nothing beyond the capacity is written and n_kept_and_status[1] = 1.
+ *   kept_index         device out int32 [dst_capacity_rows]
+ *   cu_kept            device out int32 [n_seqs+1]
+ *   n_kept_and_status  device out int32 [2]: { n_kept, overflow flag }
+ *   workspace          device scratch of at least alch_capture_pack_workspace_bytes(T) bytes
+ * Empty batches, empty sequences, all-zero and all-one masks are legal.
+ */
+int alch_capture_pack(const alch_batch* batch, const uint8_t* keep_mask, int32_t n_streams,
+                      const alch_stream* streams, int64_t dst_capacity_rows, int32_t* kept_index,
+                      int32_t* cu_kept, int32_t* n_kept_and_status, void* workspace,
+                      size_t workspace_bytes, void* hip_stream);
+
+size_t alch_capture_pack_workspace_bytes(int32_t total_tokens);
+
+/* ------------------------------------------------------------------------------------
+ * Family 2: backward from saved activations (Section 1; Section 4.2; Section 4.3.2).
+ */
+
+/* The saved record of one layer (all [total_tokens, width], dtype of the shape):
+ * X, X2 [T,hidden]; Q, O [T,n_q_heads*head_dim]; K, V [T,n_kv_heads*head_dim];
+ * G, U [T,ffn]; LSE fp32 [T,n_q_heads].  weights_version tags the weights the record
+ * was produced under: gradients from a record are only valid at those weights. */
+typedef struct {
+    const void *X, *X2, *Q, *K, *V, *O, *G, *U;
+    const float* LSE;
+    uint64_t weights_version;
+} alch_saved;
+
+/* Wq [Hq*D,hidden], Wk,Wv [Hkv*D,hidden], Wo [hidden,Hq*D], Wg,Wu [ffn,hidden],
+ * Wd [hidden,ffn], g1,g2 [hidden]. */
+typedef struct {
+    const void *Wq, *Wk, *Wv, *Wo, *Wg, *Wu, *Wd, *g1, *g2;
+    uint64_t weights_version;
+} alch_weights;
+
+/* Gradient outputs, same shapes and dtype as the weights.  A NULL member is skipped
+ * (frozen parameter; Section 3 assumption A1 trains adapters on a frozen base).
+ * accumulate != 0 adds to what the buffer holds (sum in fp32, one rounding). */
+typedef struct {
+    void *dWq, *dWk, *dWv, *dWo, *dWg, *dWu, *dWd, *dg1, *dg2;
+    int32_t accumulate;
+} alch_wgrads;
+
+/*
+ * alch_layer_backward: gradients of one decoder layer from its saved record.
+ *   dY        [T,hidden] gradient w.r.t. the layer output
+ *   loss_mask device uint8 [T] or NULL; where 0 the dY row is treated as zero
+ *   dX        [T,hidden] out: gradient w.r.t. the layer input (may alias dY)
+ *   wgrads    may be NULL (no weight gradients at all)
+ * Every record tensor is consumed as given: probabilities are exp(q.k/sqrt(D) - LSE)
+ * from the saved Q, K, LSE; nothing is recomputed from X and the weights except the
+ * cheap row-wise normalisations and the MLP activation.  saved->weights_version must
+ * equal weights->weights_version, else ALCH_ERR_STALE.
+ * Results match the fp64 definition to max|err| / max|ref| <= 2e-2 (bf16) or 1e-4 (f32)
+ * per output tensor.
+ */
+int alch_layer_backward(const alch_layer_shape* shape, const alch_batch* batch,
+                        const alch_saved* saved, const alch_weights* weights, const void* dY,
+                        const uint8_t* loss_mask, void* dX, const alch_wgrads* wgrads,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
+size_t alch_layer_backward_workspace_bytes(const alch_layer_shape* shape, int32_t total_tokens,
+                                           int32_t max_seqlen);
+
+/* Host callbacks of the stack walk (Section 4.2: a hook at the start of each layer's
+ * backward lets serving pre-empt training; Section 4.3.2: a layer's activations may
+ * still be on their way back to the GPU).  layer_ready(user, l) is called before layer
+ * l's kernels are enqueued and may block; it returns 0 to go on.  preempt(user, l)
+ * returning nonzero stops the walk before layer l: the call returns ALCH_ERR_ABORTED
+ * with layers above l already enqueued. */
+typedef struct {
+    int (*layer_ready)(void* user, int layer);
+    int (*preempt)(void* user, int layer);
+    void* user;
+} alch_hooks;
+
+/*
+ * alch_stack_backward: cross-entropy loss on the saved stack output and the backward
+ * walk over all layers (Section 5: loss from the prefill output and the prompt text).
+ *   saved, weights, wgrads  HOST arrays of n_layers structs (wgrads may be NULL)
+ *   X_final   [T,hidden] output of the last layer (the saved prefill output)
+ *   g_final   [hidden] gain of the final RMSNorm;  W_lm [vocab,hidden]
+ *   labels    device int32 [T]; a position counts if label >= 0 (and loss_mask != 0)
+ *   loss = -(1/N) sum_counted log softmax(RMSNorm(X_final) W_lm^T)[label]; N = 0 gives
+ *          loss 0 and zero gradients.  Logits are produced and consumed in row chunks and
+ *          never stored whole.
+ *   dg_final, dW_lm  out (NULL => skipped; `accumulate` of wgrads[0] applies, 0 if wgrads NULL)
+ *   dX_embed  [T,hidden] out: gradient w.r.t. the input of layer 0
+ *   loss_out  device float [1] out
+ */
+int alch_stack_backward(const alch_layer_shape* shape, int32_t n_layers, int32_t vocab,
+                        const alch_batch* batch, const alch_saved* saved, const alch_weights* weights,
+                        const void* X_final, const void* g_final, const void* W_lm,
+                        const int32_t* labels, const uint8_t* loss_mask, const alch_wgrads* wgrads,
+                        void* dg_final, void* dW_lm, void* dX_embed, float* loss_out,
+                        const alch_hooks* hooks, void* workspace, size_t workspace_bytes,
+                        void* hip_stream);
+
+size_t alch_stack_backward_workspace_bytes(const alch_layer_shape* shape, int32_t n_layers,
+                                           int32_t vocab, int32_t total_tokens, int32_t max_seqlen);
+
+/*
+ * alch_layer_forward: the forward pass of one layer, writing Y and the full record.
+ * It is the producer side of the record (what serving prefill computes, Section 4.1) and
+ * the "recompute" leg of the comparison in Section 6; record_out members are written,
+ * X is copied from the input pointer only if record_out->X differs from it.
+ */
+typedef struct {
+    void *X, *X2, *Q, *K, *V, *O, *G, *U;
+    float* LSE;
+} alch_record_out;
+
+int alch_layer_forward(const alch_layer_shape* shape, const alch_batch* batch, const void* X,
+                       const alch_weights* weights, void* Y, const alch_record_out* record_out,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+size_t alch_layer_forward_workspace_bytes(const alch_layer_shape* shape, int32_t total_tokens,
+                                          int32_t max_seqlen);
+
+/*
+ * alch_gemm: the dense contraction every projection gradient of the per-layer backward
+ * (Section 4.2 / 4.3.2) is made of, exposed for tests and for timing single launches:
+ *   C[M,N] (+)= sum_i A_i(M,K_i) B_i(K_i,N),  fp32 accumulation, C row-major with stride ldc.
+ *   a_kmajor != 0: A_i(m,k) = A_i[m*lda + k], else A_i(m,k) = A_i[k*lda + m]
+ *   b_kmajor != 0: B_i(k,n) = B_i[n*ldb + k], else B_i(k,n) = B_i[k*ldb + n]
+ * (data gradient: a_kmajor=1, b_kmajor=0; weight gradient: both 0; forward projection: both 1).
+ * terms is a HOST array of 1..3 operand pairs.  bf16 problems with 16-byte aligned operands and
+ * leading dimensions that are multiples of 8 run on the matrix cores; anything else takes a plain
+ * fp32 kernel.
+ */
+typedef struct {
+    const void* A;
+    const void* B;
+    int32_t K;
+    int64_t lda, ldb;
+} alch_gemm_term;
+
+int alch_gemm(alch_dtype dtype, int32_t M, int32_t N, int32_t a_kmajor, int32_t b_kmajor, int32_t n_terms,
+              const alch_gemm_term* terms, void* C, int64_t ldc, int32_t accumulate, void* hip_stream);
+
+/* Message describing the last error on the calling thread ("" if none). */
+const char* alch_last_error(void);
+
+/* Library version string (static storage). */
+const char* alch_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ALCH_H */

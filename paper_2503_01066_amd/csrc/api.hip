@@ -1,0 +1,569 @@
+// C ABI of libalch: argument validation, workspace planning and the order of kernel launches.
+// Every entry point checks its arguments on the host before anything is enqueued, so all
+// error paths can be exercised without a GPU.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "kernels.h"
+
+namespace alch {
+
+static thread_local char g_error[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+    return code;
+}
+void clear_error() { g_error[0] = 0; }
+
+static int check_shape(const alch_layer_shape* s) {
+    if (!s) return fail(ALCH_ERR_INVALID_ARG, "shape is NULL");
+    if (s->dtype != ALCH_F32 && s->dtype != ALCH_BF16) return fail(ALCH_ERR_INVALID_ARG, "bad dtype %d", (int)s->dtype);
+    if (s->hidden <= 0 || s->n_q_heads <= 0 || s->n_kv_heads <= 0 || s->head_dim <= 0 || s->ffn <= 0)
+        return fail(ALCH_ERR_SHAPE, "non-positive layer dimension");
+    if (s->n_q_heads % s->n_kv_heads) return fail(ALCH_ERR_SHAPE, "n_q_heads %d not a multiple of n_kv_heads %d", s->n_q_heads, s->n_kv_heads);
+    if (s->head_dim % 2) return fail(ALCH_ERR_SHAPE, "head_dim %d is odd", s->head_dim);
+    if (s->head_dim > 256) return fail(ALCH_ERR_UNSUPPORTED, "head_dim %d > 256", s->head_dim);
+    if (s->hidden > 8192) return fail(ALCH_ERR_UNSUPPORTED, "hidden %d > 8192", s->hidden);
+    if (!(s->rms_eps >= 0.f) || !(s->rope_base > 0.f)) return fail(ALCH_ERR_INVALID_ARG, "bad rms_eps / rope_base");
+    return ALCH_OK;
+}
+
+static int check_batch(const alch_batch* b) {
+    if (!b) return fail(ALCH_ERR_INVALID_ARG, "batch is NULL");
+    if (b->n_seqs < 0 || b->total_tokens < 0 || b->max_seqlen < 0) return fail(ALCH_ERR_INVALID_ARG, "negative batch size");
+    if (!b->cu_seqlens || !b->cu_seqlens_host) return fail(ALCH_ERR_INVALID_ARG, "cu_seqlens / cu_seqlens_host is NULL");
+    const int32_t* cu = b->cu_seqlens_host;
+    if (cu[0] != 0) return fail(ALCH_ERR_SHAPE, "cu_seqlens[0] = %d, expected 0", cu[0]);
+    for (int s = 0; s < b->n_seqs; ++s) {
+        const int len = cu[s + 1] - cu[s];
+        if (len < 0) return fail(ALCH_ERR_SHAPE, "cu_seqlens decreases at sequence %d", s);
+        if (len > b->max_seqlen) return fail(ALCH_ERR_SHAPE, "sequence %d has %d tokens > max_seqlen %d", s, len, b->max_seqlen);
+    }
+    if (cu[b->n_seqs] != b->total_tokens)
+        return fail(ALCH_ERR_SHAPE, "cu_seqlens[n_seqs] = %d but total_tokens = %d", cu[b->n_seqs], b->total_tokens);
+    return ALCH_OK;
+}
+
+#define REQUIRE_PTR(p, name)                                                                   \
+    do {                                                                                       \
+        if (!(p)) return fail(ALCH_ERR_INVALID_ARG, "%s is NULL", name);                       \
+        if (!aligned16(p)) return fail(ALCH_ERR_INVALID_ARG, "%s is not 16-byte aligned", name); \
+    } while (0)
+#define OPTIONAL_PTR(p, name)                                                                          \
+    do {                                                                                               \
+        if ((p) && !aligned16(p)) return fail(ALCH_ERR_INVALID_ARG, "%s is not 16-byte aligned", name); \
+    } while (0)
+
+// ---- workspace plans -----------------------------------------------------------------------
+
+struct LayerBwdPlan {
+    void *dYm, *dGU, *Act, *Hn, *dHn, *dX2, *dO, *dQKV;
+    float *delta, *partial;
+    size_t bytes;
+};
+
+static LayerBwdPlan plan_layer_bwd(const alch_layer_shape& s, int T, void* ws, size_t ws_bytes) {
+    Arena a(ws, ws_bytes);
+    const size_t E = dtype_size(s.dtype);
+    const size_t t = (size_t)(T > 0 ? T : 1);
+    const size_t H = s.hidden, F = s.ffn, QD = (size_t)s.n_q_heads * s.head_dim, KD = (size_t)s.n_kv_heads * s.head_dim;
+    LayerBwdPlan p;
+    p.dYm = a.take(t * H * E);
+    p.dGU = a.take(t * 2 * F * E);
+    p.Act = a.take(t * F * E);
+    p.Hn = a.take(t * H * E);
+    p.dHn = a.take(t * H * E);
+    p.dX2 = a.take(t * H * E);
+    p.dO = a.take(t * QD * E);
+    p.dQKV = a.take(t * (QD + 2 * KD) * E);
+    p.delta = static_cast<float*>(a.take(t * s.n_q_heads * sizeof(float)));
+    p.partial = static_cast<float*>(a.take((size_t)rmsnorm_bwd_blocks(T) * H * sizeof(float)));
+    p.bytes = round_up(a.used, 256);
+    return p;
+}
+
+struct LayerFwdPlan {
+    void *Hn, *Act;
+    size_t bytes;
+};
+static LayerFwdPlan plan_layer_fwd(const alch_layer_shape& s, int T, void* ws, size_t ws_bytes) {
+    Arena a(ws, ws_bytes);
+    const size_t E = dtype_size(s.dtype), t = (size_t)(T > 0 ? T : 1);
+    LayerFwdPlan p;
+    p.Hn = a.take(t * s.hidden * E);
+    p.Act = a.take(t * s.ffn * E);
+    p.bytes = round_up(a.used, 256);
+    return p;
+}
+
+static constexpr int kHeadChunkRows = 8192;
+
+struct StackPlan {
+    void *Hf, *dHf, *logits, *ping, *pong, *layer_ws;
+    float* row_loss;
+    int* n_counted;
+    float* partial;
+    size_t layer_ws_bytes, bytes;
+};
+static StackPlan plan_stack(const alch_layer_shape& s, int vocab, int T, void* ws, size_t ws_bytes) {
+    Arena a(ws, ws_bytes);
+    const size_t E = dtype_size(s.dtype), t = (size_t)(T > 0 ? T : 1), H = s.hidden;
+    const size_t chunk = t < (size_t)kHeadChunkRows ? t : (size_t)kHeadChunkRows;
+    StackPlan p;
+    p.Hf = a.take(t * H * E);
+    p.dHf = a.take(t * H * E);
+    p.logits = a.take(chunk * (size_t)vocab * E);
+    p.ping = a.take(t * H * E);
+    p.pong = a.take(t * H * E);
+    p.row_loss = static_cast<float*>(a.take(t * sizeof(float)));
+    p.n_counted = static_cast<int*>(a.take(256));
+    p.partial = static_cast<float*>(a.take((size_t)rmsnorm_bwd_blocks(T) * H * sizeof(float)));
+    p.layer_ws_bytes = plan_layer_bwd(s, T, nullptr, 0).bytes;
+    p.layer_ws = a.take(p.layer_ws_bytes);
+    p.bytes = round_up(a.used, 256);
+    return p;
+}
+
+// ---- layer backward --------------------------------------------------------------------------
+
+static GemmDesc gemm(alch_dtype dt, int M, int N, bool a_k, bool b_k) {
+    GemmDesc d;
+    d.M = M; d.N = N; d.a_kmajor = a_k; d.b_kmajor = b_k; d.dtype = dt;
+    return d;
+}
+static void add_seg(GemmDesc& d, const void* A, long long lda, const void* B, long long ldb, int K) {
+    d.seg[d.n_seg++] = GemmSeg{A, B, K, lda, ldb};
+}
+static void add_out(GemmDesc& d, void* C, int m_begin, long long ldc) { d.out[d.n_out++] = GemmOut{C, m_begin, ldc}; }
+
+static inline const char* at(const void* p, size_t elems, size_t E) { return static_cast<const char*>(p) + elems * E; }
+static inline char* at(void* p, size_t elems, size_t E) { return static_cast<char*>(p) + elems * E; }
+
+// Activation pointers may be NULL only when the batch holds no token.
+#define REQUIRE_ACT(p, name, T)                   \
+    do {                                          \
+        if ((T) > 0) REQUIRE_PTR(p, name);        \
+        else OPTIONAL_PTR(p, name);               \
+    } while (0)
+
+static int check_saved_weights(const alch_saved* sv, const alch_weights* w, int T) {
+    if (!sv || !w) return fail(ALCH_ERR_INVALID_ARG, "saved / weights is NULL");
+    REQUIRE_ACT(sv->X, "saved.X", T); REQUIRE_ACT(sv->X2, "saved.X2", T); REQUIRE_ACT(sv->Q, "saved.Q", T);
+    REQUIRE_ACT(sv->K, "saved.K", T); REQUIRE_ACT(sv->V, "saved.V", T); REQUIRE_ACT(sv->O, "saved.O", T);
+    REQUIRE_ACT(sv->G, "saved.G", T); REQUIRE_ACT(sv->U, "saved.U", T); REQUIRE_ACT(sv->LSE, "saved.LSE", T);
+    REQUIRE_PTR(w->Wq, "weights.Wq"); REQUIRE_PTR(w->Wk, "weights.Wk"); REQUIRE_PTR(w->Wv, "weights.Wv");
+    REQUIRE_PTR(w->Wo, "weights.Wo"); REQUIRE_PTR(w->Wg, "weights.Wg"); REQUIRE_PTR(w->Wu, "weights.Wu");
+    REQUIRE_PTR(w->Wd, "weights.Wd"); REQUIRE_PTR(w->g1, "weights.g1"); REQUIRE_PTR(w->g2, "weights.g2");
+    if (sv->weights_version != w->weights_version)
+        return fail(ALCH_ERR_STALE, "record was captured under weights version %llu, weights are version %llu",
+                    (unsigned long long)sv->weights_version, (unsigned long long)w->weights_version);
+    return ALCH_OK;
+}
+
+static int check_wgrads(const alch_wgrads* g) {
+    if (!g) return ALCH_OK;
+    OPTIONAL_PTR(g->dWq, "wgrads.dWq"); OPTIONAL_PTR(g->dWk, "wgrads.dWk"); OPTIONAL_PTR(g->dWv, "wgrads.dWv");
+    OPTIONAL_PTR(g->dWo, "wgrads.dWo"); OPTIONAL_PTR(g->dWg, "wgrads.dWg"); OPTIONAL_PTR(g->dWu, "wgrads.dWu");
+    OPTIONAL_PTR(g->dWd, "wgrads.dWd"); OPTIONAL_PTR(g->dg1, "wgrads.dg1"); OPTIONAL_PTR(g->dg2, "wgrads.dg2");
+    return ALCH_OK;
+}
+
+// Enqueues steps of one layer's backward pass; arguments already validated.
+static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b, const alch_saved& sv,
+                                  const alch_weights& w, const void* dY, const uint8_t* loss_mask, void* dX,
+                                  const alch_wgrads* wg, const LayerBwdPlan& p, hipStream_t st) {
+    const alch_dtype dt = s.dtype;
+    const size_t E = dtype_size(dt);
+    const int T = b.total_tokens, H = s.hidden, F = s.ffn, D = s.head_dim;
+    const int QD = s.n_q_heads * D, KD = s.n_kv_heads * D, QKV = QD + 2 * KD;
+    const int acc = wg ? (wg->accumulate != 0) : 0;
+    static const alch_wgrads none = {};
+    const alch_wgrads& g = wg ? *wg : none;
+
+    // the loss mask zeroes rows of dY once, up front
+    const void* dYp = dY;
+    if (loss_mask) {
+        ALCH_TRY(launch_masked_copy(dt, dY, loss_mask, p.dYm, T, H, st));
+        dYp = p.dYm;
+    }
+
+    // MLP down projection: dAct = dY Wd, fused with the SwiGLU gradient -> [dG | dU] and Act
+    {
+        GemmDesc d = gemm(dt, T, F, true, false);
+        add_seg(d, dYp, H, w.Wd, F, H);
+        add_out(d, p.dGU, 0, 2 * (long long)F);
+        d.epilogue = kEpiSwigluBwd;
+        d.G = sv.G; d.U = sv.U; d.ldgu = F;
+        d.act_out = g.dWd ? p.Act : nullptr;
+        ALCH_TRY(launch_gemm(d, st));
+    }
+    if (g.dWd) {  // dWd = dY^T Act
+        GemmDesc d = gemm(dt, H, F, false, false);
+        add_seg(d, dYp, H, p.Act, F, T);
+        add_out(d, g.dWd, 0, F);
+        d.accumulate = acc;
+        ALCH_TRY(launch_gemm(d, st));
+    }
+    {  // dH2 = dG Wg + dU Wu
+        GemmDesc d = gemm(dt, T, H, true, false);
+        add_seg(d, p.dGU, 2 * (long long)F, w.Wg, H, F);
+        add_seg(d, at(p.dGU, F, E), 2 * (long long)F, w.Wu, H, F);
+        add_out(d, p.dHn, 0, H);
+        ALCH_TRY(launch_gemm(d, st));
+    }
+    if (g.dWg || g.dWu) {  // [dWg; dWu] = [dG | dU]^T H2
+        ALCH_TRY(launch_rmsnorm_fwd(dt, sv.X2, w.g2, p.Hn, T, H, s.rms_eps, st));
+        if (g.dWg && g.dWu) {
+            GemmDesc d = gemm(dt, 2 * F, H, false, false);
+            add_seg(d, p.dGU, 2 * (long long)F, p.Hn, H, T);
+            add_out(d, g.dWg, 0, H);
+            add_out(d, g.dWu, F, H);
+            d.accumulate = acc;
+            if (F % 256 == 0) {
+                ALCH_TRY(launch_gemm(d, st));
+            } else {
+                d.M = F; d.n_out = 1;
+                ALCH_TRY(launch_gemm(d, st));
+                d.seg[0].A = at(p.dGU, F, E); d.out[0].C = g.dWu;
+                ALCH_TRY(launch_gemm(d, st));
+            }
+        } else {
+            GemmDesc d = gemm(dt, F, H, false, false);
+            add_seg(d, g.dWg ? p.dGU : at(p.dGU, F, E), 2 * (long long)F, p.Hn, H, T);
+            add_out(d, g.dWg ? g.dWg : g.dWu, 0, H);
+            d.accumulate = acc;
+            ALCH_TRY(launch_gemm(d, st));
+        }
+    }
+    // dX2 = dY + RMSNorm-2 backward(dH2); dg2
+    ALCH_TRY(launch_rmsnorm_bwd(dt, p.dHn, sv.X2, w.g2, dYp, nullptr, p.dX2, g.dg2, acc, p.partial, T, H, s.rms_eps, st));
+
+    {  // dO = dX2 Wo
+        GemmDesc d = gemm(dt, T, QD, true, false);
+        add_seg(d, p.dX2, H, w.Wo, QD, H);
+        add_out(d, p.dO, 0, QD);
+        ALCH_TRY(launch_gemm(d, st));
+    }
+    if (g.dWo) {  // dWo = dX2^T O
+        GemmDesc d = gemm(dt, H, QD, false, false);
+        add_seg(d, p.dX2, H, sv.O, QD, T);
+        add_out(d, g.dWo, 0, QD);
+        d.accumulate = acc;
+        ALCH_TRY(launch_gemm(d, st));
+    }
+
+    // attention backward from saved Q, K, V, O, LSE -> [dQ | dK | dV], then RoPE backward on dQ, dK
+    ALCH_TRY(launch_attn_delta(dt, p.dO, sv.O, p.delta, T, s.n_q_heads, D, st));
+    {
+        AttnArgs a;
+        a.dtype = dt; a.T = T; a.n_seqs = b.n_seqs; a.max_seqlen = b.max_seqlen;
+        a.Hq = s.n_q_heads; a.Hkv = s.n_kv_heads; a.D = D;
+        a.cu_seqlens = b.cu_seqlens; a.cu_seqlens_host = b.cu_seqlens_host;
+        a.Q = sv.Q; a.K = sv.K; a.V = sv.V; a.O = sv.O; a.dO = p.dO; a.LSE = sv.LSE; a.delta = p.delta;
+        a.dQ = p.dQKV; a.dK = at(p.dQKV, QD, E); a.dV = at(p.dQKV, QD + KD, E); a.ld_dqkv = QKV;
+        ALCH_TRY(launch_attn_bwd(a, st));
+    }
+    ALCH_TRY(launch_rope(dt, p.dQKV, QKV, T, s.n_q_heads + s.n_kv_heads, D, b.positions, b.cu_seqlens, b.n_seqs,
+                         s.rope_base, -1.f, st));
+
+    {  // dH1 = dQ Wq + dK Wk + dV Wv
+        GemmDesc d = gemm(dt, T, H, true, false);
+        add_seg(d, p.dQKV, QKV, w.Wq, H, QD);
+        add_seg(d, at(p.dQKV, QD, E), QKV, w.Wk, H, KD);
+        add_seg(d, at(p.dQKV, QD + KD, E), QKV, w.Wv, H, KD);
+        add_out(d, p.dHn, 0, H);
+        ALCH_TRY(launch_gemm(d, st));
+    }
+    if (g.dWq || g.dWk || g.dWv) {  // dW{q,k,v} = d{Q,K,V}^T H1
+        ALCH_TRY(launch_rmsnorm_fwd(dt, sv.X, w.g1, p.Hn, T, H, s.rms_eps, st));
+        if (g.dWq && g.dWk && g.dWv && QD % 256 == 0 && KD % 256 == 0) {
+            GemmDesc d = gemm(dt, QKV, H, false, false);
+            add_seg(d, p.dQKV, QKV, p.Hn, H, T);
+            add_out(d, g.dWq, 0, H);
+            add_out(d, g.dWk, QD, H);
+            add_out(d, g.dWv, QD + KD, H);
+            d.accumulate = acc;
+            ALCH_TRY(launch_gemm(d, st));
+        } else {
+            void* outs[3] = {g.dWq, g.dWk, g.dWv};
+            const int off[3] = {0, QD, QD + KD}, rows[3] = {QD, KD, KD};
+            for (int i = 0; i < 3; ++i) {
+                if (!outs[i]) continue;
+                GemmDesc d = gemm(dt, rows[i], H, false, false);
+                add_seg(d, at(p.dQKV, off[i], E), QKV, p.Hn, H, T);
+                add_out(d, outs[i], 0, H);
+                d.accumulate = acc;
+                ALCH_TRY(launch_gemm(d, st));
+            }
+        }
+    }
+    // dX = dX2 + RMSNorm-1 backward(dH1); dg1
+    ALCH_TRY(launch_rmsnorm_bwd(dt, p.dHn, sv.X, w.g1, p.dX2, nullptr, dX, g.dg1, acc, p.partial, T, H, s.rms_eps, st));
+    return ALCH_OK;
+}
+
+int launch_attn_bwd(const AttnArgs& a, hipStream_t stream) {
+    if (attn_mfma_supported(a)) return launch_attn_bwd_mfma(a, stream);
+    return launch_attn_bwd_generic(a, stream);
+}
+
+}  // namespace alch
+
+using namespace alch;
+
+extern "C" {
+
+const char* alch_last_error(void) { return g_error; }
+const char* alch_version(void) { return "alch 0.1 (gfx950)"; }
+
+int alch_gemm(alch_dtype dtype, int32_t M, int32_t N, int32_t a_kmajor, int32_t b_kmajor, int32_t n_terms,
+              const alch_gemm_term* terms, void* C, int64_t ldc, int32_t accumulate, void* hip_stream) {
+    clear_error();
+    if (dtype != ALCH_F32 && dtype != ALCH_BF16) return fail(ALCH_ERR_INVALID_ARG, "bad dtype %d", (int)dtype);
+    if (M < 0 || N < 0) return fail(ALCH_ERR_SHAPE, "negative M or N");
+    if (n_terms < 1 || n_terms > 3 || !terms) return fail(ALCH_ERR_INVALID_ARG, "n_terms must be 1..3 and terms non-NULL");
+    if (!C || ldc < N) return fail(ALCH_ERR_INVALID_ARG, "C is NULL or ldc < N");
+    GemmDesc d = gemm(dtype, M, N, a_kmajor != 0, b_kmajor != 0);
+    for (int i = 0; i < n_terms; ++i) {
+        const alch_gemm_term& t = terms[i];
+        if (t.K < 0) return fail(ALCH_ERR_SHAPE, "term %d: K < 0", i);
+        if (t.K > 0 && (!t.A || !t.B)) return fail(ALCH_ERR_INVALID_ARG, "term %d: NULL operand", i);
+        if (t.lda < (a_kmajor ? t.K : M) || t.ldb < (b_kmajor ? t.K : N))
+            return fail(ALCH_ERR_SHAPE, "term %d: leading dimension smaller than the row length", i);
+        add_seg(d, t.A, t.lda, t.B, t.ldb, t.K);
+    }
+    add_out(d, C, 0, ldc);
+    d.accumulate = accumulate != 0;
+    return launch_gemm(d, static_cast<hipStream_t>(hip_stream));
+}
+
+size_t alch_capture_pack_workspace_bytes(int32_t total_tokens) { return pack_workspace_bytes(total_tokens); }
+
+int alch_capture_pack(const alch_batch* batch, const uint8_t* keep_mask, int32_t n_streams,
+                      const alch_stream* streams, int64_t dst_capacity_rows, int32_t* kept_index, int32_t* cu_kept,
+                      int32_t* n_kept_and_status, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    clear_error();
+    ALCH_TRY(check_batch(batch));
+    if (batch->total_tokens > 0 && !keep_mask) return fail(ALCH_ERR_INVALID_ARG, "keep_mask is NULL");
+    OPTIONAL_PTR(keep_mask, "keep_mask");
+    if (n_streams < 0) return fail(ALCH_ERR_INVALID_ARG, "n_streams < 0");
+    if (n_streams > 0 && !streams) return fail(ALCH_ERR_INVALID_ARG, "streams is NULL");
+    if (dst_capacity_rows < 0) return fail(ALCH_ERR_INVALID_ARG, "dst_capacity_rows < 0");
+    if (dst_capacity_rows > 0 && !kept_index) return fail(ALCH_ERR_INVALID_ARG, "kept_index is NULL");
+    if (!cu_kept || !n_kept_and_status) return fail(ALCH_ERR_INVALID_ARG, "cu_kept / n_kept_and_status is NULL");
+    for (int k = 0; k < n_streams; ++k) {
+        const alch_stream& s = streams[k];
+        if (s.row_bytes == 0 || s.row_bytes % 4) return fail(ALCH_ERR_SHAPE, "stream %d: row_bytes %zu not a positive multiple of 4", k, s.row_bytes);
+        if (s.src_row_stride_bytes < s.row_bytes || s.src_row_stride_bytes % 4)
+            return fail(ALCH_ERR_SHAPE, "stream %d: src_row_stride_bytes %zu < row_bytes or not a multiple of 4", k, s.src_row_stride_bytes);
+        if ((batch->total_tokens > 0 && !s.src) || (dst_capacity_rows > 0 && !s.dst)) return fail(ALCH_ERR_INVALID_ARG, "stream %d: NULL src or dst", k);
+        if ((reinterpret_cast<uintptr_t>(s.src) | reinterpret_cast<uintptr_t>(s.dst)) & 3u)
+            return fail(ALCH_ERR_INVALID_ARG, "stream %d: src or dst not 4-byte aligned", k);
+    }
+    const size_t need = pack_workspace_bytes(batch->total_tokens);
+    if (!workspace || workspace_bytes < need) return fail(ALCH_ERR_WORKSPACE, "workspace %zu bytes < %zu needed", workspace_bytes, need);
+    return launch_pack(keep_mask, batch->total_tokens, batch->cu_seqlens, batch->n_seqs, n_streams, streams,
+                       dst_capacity_rows, kept_index, cu_kept, n_kept_and_status, workspace,
+                       static_cast<hipStream_t>(hip_stream));
+}
+
+size_t alch_layer_backward_workspace_bytes(const alch_layer_shape* shape, int32_t total_tokens, int32_t max_seqlen) {
+    (void)max_seqlen;
+    if (!shape || check_shape(shape) != ALCH_OK || total_tokens < 0) return 0;
+    return plan_layer_bwd(*shape, total_tokens, nullptr, 0).bytes;
+}
+
+int alch_layer_backward(const alch_layer_shape* shape, const alch_batch* batch, const alch_saved* saved,
+                        const alch_weights* weights, const void* dY, const uint8_t* loss_mask, void* dX,
+                        const alch_wgrads* wgrads, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    clear_error();
+    ALCH_TRY(check_shape(shape));
+    ALCH_TRY(check_batch(batch));
+    ALCH_TRY(check_saved_weights(saved, weights, batch->total_tokens));
+    ALCH_TRY(check_wgrads(wgrads));
+    REQUIRE_ACT(dY, "dY", batch->total_tokens);
+    REQUIRE_ACT(dX, "dX", batch->total_tokens);
+    const size_t need = plan_layer_bwd(*shape, batch->total_tokens, nullptr, 0).bytes;
+    if (!workspace || workspace_bytes < need) return fail(ALCH_ERR_WORKSPACE, "workspace %zu bytes < %zu needed", workspace_bytes, need);
+    if (!aligned16(workspace)) return fail(ALCH_ERR_INVALID_ARG, "workspace is not 16-byte aligned");
+    const LayerBwdPlan p = plan_layer_bwd(*shape, batch->total_tokens, workspace, workspace_bytes);
+    return layer_backward_enqueue(*shape, *batch, *saved, *weights, dY, loss_mask, dX, wgrads, p,
+                                  static_cast<hipStream_t>(hip_stream));
+}
+
+size_t alch_stack_backward_workspace_bytes(const alch_layer_shape* shape, int32_t n_layers, int32_t vocab,
+                                           int32_t total_tokens, int32_t max_seqlen) {
+    (void)max_seqlen; (void)n_layers;
+    if (!shape || check_shape(shape) != ALCH_OK || total_tokens < 0 || vocab <= 0) return 0;
+    return plan_stack(*shape, vocab, total_tokens, nullptr, 0).bytes;
+}
+
+int alch_stack_backward(const alch_layer_shape* shape, int32_t n_layers, int32_t vocab, const alch_batch* batch,
+                        const alch_saved* saved, const alch_weights* weights, const void* X_final,
+                        const void* g_final, const void* W_lm, const int32_t* labels, const uint8_t* loss_mask,
+                        const alch_wgrads* wgrads, void* dg_final, void* dW_lm, void* dX_embed, float* loss_out,
+                        const alch_hooks* hooks, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    clear_error();
+    ALCH_TRY(check_shape(shape));
+    ALCH_TRY(check_batch(batch));
+    if (n_layers < 0) return fail(ALCH_ERR_INVALID_ARG, "n_layers < 0");
+    if (vocab <= 0) return fail(ALCH_ERR_SHAPE, "vocab <= 0");
+    if (n_layers > 0 && (!saved || !weights)) return fail(ALCH_ERR_INVALID_ARG, "saved / weights array is NULL");
+    for (int l = 0; l < n_layers; ++l) {
+        ALCH_TRY(check_saved_weights(&saved[l], &weights[l], batch->total_tokens));
+        if (wgrads) ALCH_TRY(check_wgrads(&wgrads[l]));
+    }
+    REQUIRE_ACT(X_final, "X_final", batch->total_tokens); REQUIRE_PTR(g_final, "g_final"); REQUIRE_PTR(W_lm, "W_lm");
+    REQUIRE_ACT(dX_embed, "dX_embed", batch->total_tokens);
+    if ((batch->total_tokens > 0 && !labels) || !loss_out) return fail(ALCH_ERR_INVALID_ARG, "labels / loss_out is NULL");
+    OPTIONAL_PTR(dg_final, "dg_final"); OPTIONAL_PTR(dW_lm, "dW_lm");
+    const size_t need = plan_stack(*shape, vocab, batch->total_tokens, nullptr, 0).bytes;
+    if (!workspace || workspace_bytes < need) return fail(ALCH_ERR_WORKSPACE, "workspace %zu bytes < %zu needed", workspace_bytes, need);
+    if (!aligned16(workspace)) return fail(ALCH_ERR_INVALID_ARG, "workspace is not 16-byte aligned");
+
+    const alch_layer_shape& s = *shape;
+    const StackPlan p = plan_stack(s, vocab, batch->total_tokens, workspace, workspace_bytes);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const alch_dtype dt = s.dtype;
+    const size_t E = dtype_size(dt);
+    const int T = batch->total_tokens, H = s.hidden;
+    const int acc = wgrads ? (wgrads[0].accumulate != 0) : 0;
+
+    // LM head + cross-entropy in row chunks: logits -> dlogits in place, never stored whole
+    ALCH_TRY(launch_count_labels(labels, loss_mask, T, p.n_counted, p.row_loss, st));
+    ALCH_TRY(launch_rmsnorm_fwd(dt, X_final, g_final, p.Hf, T, H, s.rms_eps, st));
+    bool first = true;
+    for (int r0 = 0; r0 < T; r0 += kHeadChunkRows) {
+        const int rows = T - r0 < kHeadChunkRows ? T - r0 : kHeadChunkRows;
+        const void* hf = at(p.Hf, (size_t)r0 * H, E);
+        {  // logits = Hf W_lm^T
+            GemmDesc d = gemm(dt, rows, vocab, true, true);
+            add_seg(d, hf, H, W_lm, H, H);
+            add_out(d, p.logits, 0, vocab);
+            ALCH_TRY(launch_gemm(d, st));
+        }
+        ALCH_TRY(launch_ce_chunk(dt, p.logits, vocab, rows, vocab, labels + r0, loss_mask ? loss_mask + r0 : nullptr,
+                                 p.n_counted, p.row_loss + r0, st));
+        {  // dHf = dlogits W_lm
+            GemmDesc d = gemm(dt, rows, H, true, false);
+            add_seg(d, p.logits, vocab, W_lm, H, vocab);
+            add_out(d, at(p.dHf, (size_t)r0 * H, E), 0, H);
+            ALCH_TRY(launch_gemm(d, st));
+        }
+        if (dW_lm) {  // dW_lm (+)= dlogits^T Hf
+            GemmDesc d = gemm(dt, vocab, H, false, false);
+            add_seg(d, p.logits, vocab, hf, H, rows);
+            add_out(d, dW_lm, 0, H);
+            d.accumulate = first ? acc : 1;
+            ALCH_TRY(launch_gemm(d, st));
+        }
+        first = false;
+    }
+    if (T == 0 && dW_lm && !acc) {
+        GemmDesc d = gemm(dt, vocab, H, false, false);  // zero rows contracted: writes zeros
+        add_seg(d, p.logits, vocab, p.Hf, H, 0);
+        add_out(d, dW_lm, 0, H);
+        ALCH_TRY(launch_gemm_generic(d, st));
+    }
+    ALCH_TRY(launch_finish_loss(p.row_loss, p.n_counted, loss_out, T, st));
+
+    // final RMSNorm backward -> gradient w.r.t. the last layer's output
+    void* cur = n_layers == 0 ? dX_embed : p.ping;
+    ALCH_TRY(launch_rmsnorm_bwd(dt, p.dHf, X_final, g_final, nullptr, nullptr, cur, dg_final, acc, p.partial, T, H,
+                                s.rms_eps, st));
+
+    const LayerBwdPlan lp = plan_layer_bwd(s, T, p.layer_ws, p.layer_ws_bytes);
+    for (int l = n_layers - 1; l >= 0; --l) {
+        if (hooks && hooks->preempt && hooks->preempt(hooks->user, l) != 0)
+            return fail(ALCH_ERR_ABORTED, "preempt hook stopped the walk before layer %d", l);
+        if (hooks && hooks->layer_ready && hooks->layer_ready(hooks->user, l) != 0)
+            return fail(ALCH_ERR_ABORTED, "layer_ready hook failed for layer %d", l);
+        void* out = l == 0 ? dX_embed : (cur == p.ping ? p.pong : p.ping);
+        ALCH_TRY(layer_backward_enqueue(s, *batch, saved[l], weights[l], cur, nullptr, out,
+                                        wgrads ? &wgrads[l] : nullptr, lp, st));
+        cur = out;
+    }
+    return ALCH_OK;
+}
+
+size_t alch_layer_forward_workspace_bytes(const alch_layer_shape* shape, int32_t total_tokens, int32_t max_seqlen) {
+    (void)max_seqlen;
+    if (!shape || check_shape(shape) != ALCH_OK || total_tokens < 0) return 0;
+    return plan_layer_fwd(*shape, total_tokens, nullptr, 0).bytes;
+}
+
+int alch_layer_forward(const alch_layer_shape* shape, const alch_batch* batch, const void* X,
+                       const alch_weights* w, void* Y, const alch_record_out* rec, void* workspace,
+                       size_t workspace_bytes, void* hip_stream) {
+    clear_error();
+    ALCH_TRY(check_shape(shape));
+    ALCH_TRY(check_batch(batch));
+    if (!w || !rec) return fail(ALCH_ERR_INVALID_ARG, "weights / record_out is NULL");
+    REQUIRE_PTR(X, "X"); REQUIRE_PTR(Y, "Y");
+    REQUIRE_PTR(w->Wq, "weights.Wq"); REQUIRE_PTR(w->Wk, "weights.Wk"); REQUIRE_PTR(w->Wv, "weights.Wv");
+    REQUIRE_PTR(w->Wo, "weights.Wo"); REQUIRE_PTR(w->Wg, "weights.Wg"); REQUIRE_PTR(w->Wu, "weights.Wu");
+    REQUIRE_PTR(w->Wd, "weights.Wd"); REQUIRE_PTR(w->g1, "weights.g1"); REQUIRE_PTR(w->g2, "weights.g2");
+    REQUIRE_PTR(rec->X, "record_out.X"); REQUIRE_PTR(rec->X2, "record_out.X2"); REQUIRE_PTR(rec->Q, "record_out.Q");
+    REQUIRE_PTR(rec->K, "record_out.K"); REQUIRE_PTR(rec->V, "record_out.V"); REQUIRE_PTR(rec->O, "record_out.O");
+    REQUIRE_PTR(rec->G, "record_out.G"); REQUIRE_PTR(rec->U, "record_out.U"); REQUIRE_PTR(rec->LSE, "record_out.LSE");
+    const size_t need = plan_layer_fwd(*shape, batch->total_tokens, nullptr, 0).bytes;
+    if (!workspace || workspace_bytes < need) return fail(ALCH_ERR_WORKSPACE, "workspace %zu bytes < %zu needed", workspace_bytes, need);
+    if (!aligned16(workspace)) return fail(ALCH_ERR_INVALID_ARG, "workspace is not 16-byte aligned");
+
+    const alch_layer_shape& s = *shape;
+    const LayerFwdPlan p = plan_layer_fwd(s, batch->total_tokens, workspace, workspace_bytes);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const alch_dtype dt = s.dtype;
+    const int T = batch->total_tokens, H = s.hidden, F = s.ffn, D = s.head_dim;
+    const int QD = s.n_q_heads * D, KD = s.n_kv_heads * D;
+
+    if (rec->X != X) ALCH_TRY(launch_masked_copy(dt, X, nullptr, rec->X, T, H, st));
+    ALCH_TRY(launch_rmsnorm_fwd(dt, X, w->g1, p.Hn, T, H, s.rms_eps, st));
+    const void* Ws[3] = {w->Wq, w->Wk, w->Wv};
+    void* outs[3] = {rec->Q, rec->K, rec->V};
+    const int widths[3] = {QD, KD, KD};
+    for (int i = 0; i < 3; ++i) {
+        GemmDesc d = gemm(dt, T, widths[i], true, true);
+        add_seg(d, p.Hn, H, Ws[i], H, H);
+        add_out(d, outs[i], 0, widths[i]);
+        ALCH_TRY(launch_gemm(d, st));
+    }
+    ALCH_TRY(launch_rope(dt, rec->Q, QD, T, s.n_q_heads, D, batch->positions, batch->cu_seqlens, batch->n_seqs, s.rope_base, 1.f, st));
+    ALCH_TRY(launch_rope(dt, rec->K, KD, T, s.n_kv_heads, D, batch->positions, batch->cu_seqlens, batch->n_seqs, s.rope_base, 1.f, st));
+    ALCH_TRY(launch_attn_fwd(dt, rec->Q, rec->K, rec->V, rec->O, rec->LSE, T, batch->n_seqs, batch->max_seqlen,
+                             batch->cu_seqlens, batch->cu_seqlens_host, s.n_q_heads, s.n_kv_heads, D, st));
+    {  // X2 = X + O Wo^T
+        ALCH_TRY(launch_masked_copy(dt, X, nullptr, rec->X2, T, H, st));
+        GemmDesc d = gemm(dt, T, H, true, true);
+        add_seg(d, rec->O, QD, w->Wo, QD, QD);
+        add_out(d, rec->X2, 0, H);
+        d.accumulate = 1;
+        ALCH_TRY(launch_gemm(d, st));
+    }
+    ALCH_TRY(launch_rmsnorm_fwd(dt, rec->X2, w->g2, p.Hn, T, H, s.rms_eps, st));
+    const void* Wm[2] = {w->Wg, w->Wu};
+    void* om[2] = {rec->G, rec->U};
+    for (int i = 0; i < 2; ++i) {
+        GemmDesc d = gemm(dt, T, F, true, true);
+        add_seg(d, p.Hn, H, Wm[i], H, H);
+        add_out(d, om[i], 0, F);
+        ALCH_TRY(launch_gemm(d, st));
+    }
+    ALCH_TRY(launch_swiglu_act(dt, rec->G, rec->U, p.Act, (long long)T * F, st));
+    {  // Y = X2 + Act Wd^T
+        ALCH_TRY(launch_masked_copy(dt, rec->X2, nullptr, Y, T, H, st));
+        GemmDesc d = gemm(dt, T, H, true, true);
+        add_seg(d, p.Act, F, w->Wd, F, F);
+        add_out(d, Y, 0, H);
+        d.accumulate = 1;
+        ALCH_TRY(launch_gemm(d, st));
+    }
+    return ALCH_OK;
+}
+
+}  // extern "C"

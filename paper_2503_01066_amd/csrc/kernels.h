@@ -1,0 +1,119 @@
+// Internal launch interfaces between the translation units of libalch.
+#pragma once
+#include "common.h"
+
+namespace alch {
+
+// ---- capture/pack ----------------------------------------------------------------------
+static constexpr int kMaxStreamsPerLaunch = 16;
+static constexpr int kGatherGrid = 256 * 8;  // persistent work-groups: 8 per compute unit
+size_t pack_workspace_bytes(int total_tokens);
+int launch_pack(const uint8_t* mask, int T, const int* cu_seqlens, int n_seqs, int n_streams,
+                const alch_stream* streams, long long capacity, int* kept_index, int* cu_kept,
+                int* n_kept_and_status, void* workspace, hipStream_t stream);
+
+// ---- GEMM ------------------------------------------------------------------------------
+// C[M,N] (+)= sum over segments of A_s(M,K_s) * B_s(K_s,N), fp32 accumulation.
+//   a_kmajor: A(m,k) = A[m*lda + k]   else A(m,k) = A[k*lda + m]
+//   b_kmajor: B(k,n) = B[n*ldb + k]   else B(k,n) = B[k*ldb + n]
+// The output may be split along M into up to three row ranges with their own base
+// pointers (rows [m_begin_i, m_begin_{i+1}) go to out[i].C, row index relative to
+// m_begin_i, leading dimension ldc).
+struct GemmSeg {
+    const void* A;
+    const void* B;
+    int K;
+    long long lda, ldb;
+};
+struct GemmOut {
+    void* C;
+    int m_begin;
+    long long ldc;
+};
+enum GemmEpilogue { kEpiNone = 0, kEpiSwigluBwd = 1 };
+struct GemmDesc {
+    int M = 0, N = 0;
+    bool a_kmajor = true, b_kmajor = true;
+    int n_seg = 0;
+    GemmSeg seg[3];
+    int n_out = 0;
+    GemmOut out[3];
+    int accumulate = 0;
+    alch_dtype dtype = ALCH_BF16;
+    // kEpiSwigluBwd: the product is dAct [M, N]; with G, U [M, N] (ld = ldgu) the kernel writes
+    // dG to out[0].C[:, 0:N], dU to out[0].C[:, N:2N] and Act = silu(G)*U to act_out [M, N].
+    int epilogue = kEpiNone;
+    const void* G = nullptr;
+    const void* U = nullptr;
+    long long ldgu = 0;
+    void* act_out = nullptr;
+    const uint8_t* row_mask = nullptr;  // optional: rows of A whose mask byte is 0 count as zero (A k-major only)
+};
+int launch_gemm(const GemmDesc& d, hipStream_t stream);
+// used by launch_gemm
+bool gemm_mfma_supported(const GemmDesc& d);
+int launch_gemm_mfma(const GemmDesc& d, hipStream_t stream);
+int launch_gemm_generic(const GemmDesc& d, hipStream_t stream);
+
+// ---- row-wise kernels --------------------------------------------------------------------
+// H = X * rsqrt(mean(X^2)+eps) * g   (rows of width `width`)
+int launch_rmsnorm_fwd(alch_dtype dt, const void* X, const void* g, void* H, int T, int width, float eps,
+                       hipStream_t stream);
+// dX = resid + rmsnorm_bwd(dH; X, g)   (resid may be NULL; resid_mask zeroes resid rows where mask==0);
+// dg (+)= sum_t dH*X*r  (dg may be NULL).  partial: fp32 scratch [rmsnorm_bwd_blocks(T), width].
+int rmsnorm_bwd_blocks(int T);
+int launch_rmsnorm_bwd(alch_dtype dt, const void* dH, const void* X, const void* g, const void* resid,
+                       const uint8_t* resid_mask, void* dX, void* dg, int accumulate, float* partial, int T,
+                       int width, float eps, hipStream_t stream);
+// Act = silu(G) * U
+int launch_swiglu_act(alch_dtype dt, const void* G, const void* U, void* Act, long long n, hipStream_t stream);
+// dGU[:, 0:F] = dAct*U*silu'(G), dGU[:, F:2F] = dAct*silu(G); optionally Act = silu(G)*U
+int launch_swiglu_bwd(alch_dtype dt, const void* dAct, const void* G, const void* U, void* dGU, void* Act,
+                      int T, int F, hipStream_t stream);
+// delta[t,h] = sum_d dO[t,h,d] * O[t,h,d]   (fp32 out)
+int launch_attn_delta(alch_dtype dt, const void* dO, const void* O, float* delta, int T, int Hq, int D,
+                      hipStream_t stream);
+// In-place rotary rotation of x [T, n_heads, D] (row stride ld elements) by sign * angle.
+int launch_rope(alch_dtype dt, void* x, long long ld, int T, int n_heads, int D, const int* positions,
+                const int* cu_seqlens, int n_seqs, float base, float sign, hipStream_t stream);
+// out = a with rows zeroed where mask == 0 (mask may be NULL: plain copy)
+int launch_masked_copy(alch_dtype dt, const void* a, const uint8_t* mask, void* out, int T, int width,
+                       hipStream_t stream);
+// y = a + b
+int launch_add(alch_dtype dt, const void* a, const void* b, void* y, long long n, hipStream_t stream);
+
+// ---- attention ---------------------------------------------------------------------------
+struct AttnArgs {
+    alch_dtype dtype;
+    int T, n_seqs, max_seqlen, Hq, Hkv, D;
+    const int* cu_seqlens;       // device
+    const int* cu_seqlens_host;  // host
+    const void *Q, *K, *V, *O, *dO;  // dense [T, heads*D]
+    const float* LSE;                // [T, Hq]
+    const float* delta;              // [T, Hq]
+    void *dQ, *dK, *dV;              // row stride ld_dqkv elements
+    long long ld_dqkv;
+};
+int launch_attn_bwd(const AttnArgs& a, hipStream_t stream);
+int launch_attn_bwd_generic(const AttnArgs& a, hipStream_t stream);
+bool attn_mfma_supported(const AttnArgs& a);
+int launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t stream);
+int launch_attn_fwd_generic(alch_dtype dt, const void* Q, const void* K, const void* V, void* O, float* LSE, int T,
+                            int n_seqs, const int* cu_seqlens, int Hq, int Hkv, int D, hipStream_t stream);
+// forward: writes O [T,Hq*D] and LSE [T,Hq]
+int launch_attn_fwd(alch_dtype dt, const void* Q, const void* K, const void* V, void* O, float* LSE, int T,
+                    int n_seqs, int max_seqlen, const int* cu_seqlens, const int* cu_seqlens_host, int Hq,
+                    int Hkv, int D, hipStream_t stream);
+
+// ---- LM head + cross-entropy ---------------------------------------------------------------
+// n_counted[0] = #{t : labels[t] >= 0 and (mask == NULL or mask[t] != 0)}; row_loss[0..T) = 0
+int launch_count_labels(const int* labels, const uint8_t* loss_mask, int T, int* n_counted, float* row_loss,
+                        hipStream_t stream);
+// One chunk of logits rows [rows, vocab] (row stride ld), in place: logits -> dlogits =
+// (softmax - onehot(label)) / N for counted rows, 0 otherwise; row_loss[r] = -log softmax[label].
+int launch_ce_chunk(alch_dtype dt, void* logits, long long ld, int rows, int vocab, const int* labels,
+                    const uint8_t* loss_mask, const int* n_counted, float* row_loss, hipStream_t stream);
+// loss_out[0] = sum(row_loss) / max(N, 1)   (fixed summation order)
+int launch_finish_loss(const float* row_loss, const int* n_counted, float* loss_out, int T, hipStream_t stream);
+
+}  // namespace alch

@@ -1,0 +1,115 @@
+// Cross-entropy on chunks of LM-head logits (Section 5 of the paper: the continual-pre-training
+// loss is computed from the saved prefill output and the prompt's own tokens as labels).
+// Logits are produced chunk by chunk by the GEMM and turned into their gradient in place, so the
+// [tokens, vocab] matrix is never stored whole.
+#include "kernels.h"
+
+namespace alch {
+
+template <typename T> __device__ __forceinline__ float ldf(const T* p) { return (float)*p; }
+template <typename T> __device__ __forceinline__ void stf(T* p, float v) { *p = (T)v; }
+
+__device__ __forceinline__ float wmax(float v) {
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) v = fmaxf(v, __shfl_xor(v, d, 64));
+    return v;
+}
+__device__ __forceinline__ float wsum2(float v) {
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+
+__global__ __launch_bounds__(256) void k_count_labels(const int* __restrict__ labels, const uint8_t* __restrict__ mask,
+                                                      int T, int* __restrict__ n_counted, float* __restrict__ row_loss) {
+    // single block: deterministic count
+    __shared__ int part[4];
+    int c = 0;
+    for (int t = threadIdx.x; t < T; t += 256) {
+        c += (labels[t] >= 0 && (!mask || mask[t] != 0)) ? 1 : 0;
+        row_loss[t] = 0.f;
+    }
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) c += __shfl_xor(c, d, 64);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = c;
+    __syncthreads();
+    if (threadIdx.x == 0) n_counted[0] = part[0] + part[1] + part[2] + part[3];
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_ce_chunk(T* __restrict__ logits, long long ld, int vocab,
+                                                  const int* __restrict__ labels, const uint8_t* __restrict__ mask,
+                                                  const int* __restrict__ n_counted, float* __restrict__ row_loss) {
+    __shared__ float red[4];
+    const int r = blockIdx.x;
+    T* row = logits + (long long)r * ld;
+    const int label = labels[r];
+    const bool counted = label >= 0 && label < vocab && (!mask || mask[r] != 0);
+    if (!counted) {
+        for (int v = threadIdx.x; v < vocab; v += 256) row[v] = (T)0.f;
+        return;
+    }
+    float m = -INFINITY;
+    for (int v = threadIdx.x; v < vocab; v += 256) m = fmaxf(m, ldf(row + v));
+    m = wmax(m);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    __syncthreads();
+    float s = 0.f;
+    for (int v = threadIdx.x; v < vocab; v += 256) s += __expf(ldf(row + v) - m);
+    s = wsum2(s);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    s = red[0] + red[1] + red[2] + red[3];
+    const float logz = m + __logf(s);
+    const float inv_n = 1.f / (float)n_counted[0];
+    const float x_label = ldf(row + label);
+    __syncthreads();  // everyone has read the label logit before it is overwritten
+    for (int v = threadIdx.x; v < vocab; v += 256) {
+        float p = __expf(ldf(row + v) - logz);
+        if (v == label) p -= 1.f;
+        stf(row + v, p * inv_n);
+    }
+    if (threadIdx.x == 0) row_loss[r] = logz - x_label;
+}
+
+__global__ __launch_bounds__(256) void k_finish_loss(const float* __restrict__ row_loss, const int* __restrict__ n_counted,
+                                                     float* __restrict__ loss_out, int T) {
+    __shared__ float red[4];
+    float s = 0.f;
+    for (int t = threadIdx.x; t < T; t += 256) s += row_loss[t];
+    s = wsum2(s);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int n = n_counted[0];
+        loss_out[0] = n > 0 ? (red[0] + red[1] + red[2] + red[3]) / (float)n : 0.f;
+    }
+}
+
+int launch_count_labels(const int* labels, const uint8_t* loss_mask, int T, int* n_counted, float* row_loss,
+                        hipStream_t stream) {
+    k_count_labels<<<1, 256, 0, stream>>>(labels, loss_mask, T, n_counted, row_loss);
+    ALCH_HIP_TRY(hipGetLastError());
+    return ALCH_OK;
+}
+
+int launch_ce_chunk(alch_dtype dt, void* logits, long long ld, int rows, int vocab, const int* labels,
+                    const uint8_t* loss_mask, const int* n_counted, float* row_loss, hipStream_t stream) {
+    if (rows <= 0) return ALCH_OK;
+    if (dt == ALCH_BF16)
+        k_ce_chunk<__bf16><<<rows, 256, 0, stream>>>((__bf16*)logits, ld, vocab, labels, loss_mask, n_counted, row_loss);
+    else
+        k_ce_chunk<float><<<rows, 256, 0, stream>>>((float*)logits, ld, vocab, labels, loss_mask, n_counted, row_loss);
+    ALCH_HIP_TRY(hipGetLastError());
+    return ALCH_OK;
+}
+
+int launch_finish_loss(const float* row_loss, const int* n_counted, float* loss_out, int T, hipStream_t stream) {
+    k_finish_loss<<<1, 256, 0, stream>>>(row_loss, n_counted, loss_out, T);
+    ALCH_HIP_TRY(hipGetLastError());
+    return ALCH_OK;
+}
+
+}  // namespace alch

@@ -1,0 +1,324 @@
+// Row-wise and elementwise kernels of the decoder-layer backward pass (RMSNorm forward and
+// backward with the residual add, SwiGLU activation and its gradient, the softmax-gradient
+// row term, rotary embedding).  All arithmetic in fp32; storage type T is float or bf16.
+// These are HBM-bound: one pass over each operand, 16-byte accesses where alignment allows.
+#include "kernels.h"
+
+namespace alch {
+
+template <typename T> __device__ __forceinline__ float ldf(const T* p) { return (float)*p; }
+template <typename T> __device__ __forceinline__ void stf(T* p, float v) { *p = (T)v; }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+
+// Sum over a 256-thread block (4 waves); every thread gets the result.
+__device__ __forceinline__ float block_sum(float v, float* smem /*[4]*/) {
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) smem[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return smem[0] + smem[1] + smem[2] + smem[3];
+}
+
+// ---- RMSNorm forward: H = X * rsqrt(mean(X^2) + eps) * g, one block per row
+template <typename T>
+__global__ __launch_bounds__(256) void k_rmsnorm_fwd(const T* __restrict__ X, const T* __restrict__ g,
+                                                     T* __restrict__ H, int width, float eps) {
+    __shared__ float red[4];
+    const long long row = blockIdx.x;
+    const T* x = X + row * width;
+    float ss = 0.f;
+    for (int c = threadIdx.x; c < width; c += 256) {
+        float v = ldf(x + c);
+        ss += v * v;
+    }
+    ss = block_sum(ss, red);
+    const float r = rsqrtf(ss / (float)width + eps);
+    for (int c = threadIdx.x; c < width; c += 256) stf(H + row * width + c, ldf(x + c) * r * ldf(g + c));
+}
+
+int launch_rmsnorm_fwd(alch_dtype dt, const void* X, const void* g, void* H, int T, int width, float eps,
+                       hipStream_t stream) {
+    if (T <= 0) return ALCH_OK;
+    if (dt == ALCH_BF16)
+        k_rmsnorm_fwd<__bf16><<<T, 256, 0, stream>>>((const __bf16*)X, (const __bf16*)g, (__bf16*)H, width, eps);
+    else
+        k_rmsnorm_fwd<float><<<T, 256, 0, stream>>>((const float*)X, (const float*)g, (float*)H, width, eps);
+    ALCH_HIP_TRY(hipGetLastError());
+    return ALCH_OK;
+}
+
+// ---- RMSNorm backward with residual:
+//   dX = resid + r*(g*dH) - X * r^3/width * sum(g*dH*X);   dg partial[blk] = sum over the block's rows of dH*X*r
+static constexpr int kNormBwdBlocks = 1024;
+static constexpr int kNormMaxCols = 32;  // columns per thread: width <= 8192
+
+int rmsnorm_bwd_blocks(int T) { return T < kNormBwdBlocks ? (T > 0 ? T : 1) : kNormBwdBlocks; }
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_rmsnorm_bwd(const T* __restrict__ dH, const T* __restrict__ X,
+                                                     const T* __restrict__ g, const T* __restrict__ resid,
+                                                     const uint8_t* __restrict__ resid_mask, T* __restrict__ dX,
+                                                     float* __restrict__ partial, int Trows, int width, float eps) {
+    __shared__ float red[4];
+    float dgp[kNormMaxCols];
+    float gv[kNormMaxCols];
+#pragma unroll
+    for (int i = 0; i < kNormMaxCols; ++i) {
+        dgp[i] = 0.f;
+        const int c = threadIdx.x + 256 * i;
+        gv[i] = c < width ? ldf(g + c) : 0.f;
+    }
+    for (long long row = blockIdx.x; row < Trows; row += gridDim.x) {
+        float xv[kNormMaxCols], dv[kNormMaxCols];
+        float ss = 0.f, dot = 0.f;
+#pragma unroll
+        for (int i = 0; i < kNormMaxCols; ++i) {
+            const int c = threadIdx.x + 256 * i;
+            xv[i] = c < width ? ldf(X + row * width + c) : 0.f;
+            dv[i] = c < width ? ldf(dH + row * width + c) : 0.f;
+            ss += xv[i] * xv[i];
+            dot += gv[i] * dv[i] * xv[i];
+        }
+        ss = block_sum(ss, red);
+        dot = block_sum(dot, red);
+        const float r = rsqrtf(ss / (float)width + eps);
+        const float coef = r * r * r / (float)width * dot;
+        const bool keep = resid && !(resid_mask && resid_mask[row] == 0);
+#pragma unroll
+        for (int i = 0; i < kNormMaxCols; ++i) {
+            const int c = threadIdx.x + 256 * i;
+            if (c < width) {
+                float v = r * gv[i] * dv[i] - xv[i] * coef;
+                if (keep) v += ldf(resid + row * width + c);
+                stf(dX + row * width + c, v);
+                dgp[i] += dv[i] * xv[i] * r;
+            }
+        }
+    }
+    if (partial) {
+#pragma unroll
+        for (int i = 0; i < kNormMaxCols; ++i) {
+            const int c = threadIdx.x + 256 * i;
+            if (c < width) partial[(long long)blockIdx.x * width + c] = dgp[i];
+        }
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_colsum_finish(const float* __restrict__ partial, int nblk, int width,
+                                                       T* __restrict__ dg, int accumulate) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= width) return;
+    float s = 0.f;
+    for (int b = 0; b < nblk; ++b) s += partial[(long long)b * width + c];
+    if (accumulate) s += ldf(dg + c);
+    stf(dg + c, s);
+}
+
+template <typename T>
+static int rmsnorm_bwd_t(const void* dH, const void* X, const void* g, const void* resid, const uint8_t* resid_mask,
+                         void* dX, void* dg, int accumulate, float* partial, int T_, int width, float eps,
+                         hipStream_t stream) {
+    const int nblk = rmsnorm_bwd_blocks(T_);
+    k_rmsnorm_bwd<T><<<nblk, 256, 0, stream>>>((const T*)dH, (const T*)X, (const T*)g, (const T*)resid, resid_mask,
+                                                (T*)dX, dg ? partial : nullptr, T_, width, eps);
+    if (dg) k_colsum_finish<T><<<ceil_div(width, 256), 256, 0, stream>>>(partial, nblk, width, (T*)dg, accumulate);
+    ALCH_HIP_TRY(hipGetLastError());
+    return ALCH_OK;
+}
+
+int launch_rmsnorm_bwd(alch_dtype dt, const void* dH, const void* X, const void* g, const void* resid,
+                       const uint8_t* resid_mask, void* dX, void* dg, int accumulate, float* partial, int T,
+                       int width, float eps, hipStream_t stream) {
+    if (width > 256 * kNormMaxCols) return fail(ALCH_ERR_UNSUPPORTED, "hidden %d > %d", width, 256 * kNormMaxCols);
+    if (T <= 0) {
+        // no rows: the gain gradient is zero (or unchanged when accumulating)
+        if (dg) {
+            if (dt == ALCH_BF16)
+                k_colsum_finish<__bf16><<<ceil_div(width, 256), 256, 0, stream>>>(partial, 0, width, (__bf16*)dg, accumulate);
+            else
+                k_colsum_finish<float><<<ceil_div(width, 256), 256, 0, stream>>>(partial, 0, width, (float*)dg, accumulate);
+            ALCH_HIP_TRY(hipGetLastError());
+        }
+        return ALCH_OK;
+    }
+    return dt == ALCH_BF16
+               ? rmsnorm_bwd_t<__bf16>(dH, X, g, resid, resid_mask, dX, dg, accumulate, partial, T, width, eps, stream)
+               : rmsnorm_bwd_t<float>(dH, X, g, resid, resid_mask, dX, dg, accumulate, partial, T, width, eps, stream);
+}
+
+// ---- SwiGLU
+template <typename T>
+__global__ __launch_bounds__(256) void k_swiglu_act(const T* __restrict__ G, const T* __restrict__ U,
+                                                    T* __restrict__ Act, long long n) {
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) {
+        const float g = ldf(G + i), u = ldf(U + i);
+        stf(Act + i, g / (1.f + __expf(-g)) * u);
+    }
+}
+
+int launch_swiglu_act(alch_dtype dt, const void* G, const void* U, void* Act, long long n, hipStream_t stream) {
+    if (n <= 0) return ALCH_OK;
+    const int grid = (int)((n + 255) / 256 < 256 * 16 ? (n + 255) / 256 : 256 * 16);
+    if (dt == ALCH_BF16)
+        k_swiglu_act<__bf16><<<grid, 256, 0, stream>>>((const __bf16*)G, (const __bf16*)U, (__bf16*)Act, n);
+    else
+        k_swiglu_act<float><<<grid, 256, 0, stream>>>((const float*)G, (const float*)U, (float*)Act, n);
+    ALCH_HIP_TRY(hipGetLastError());
+    return ALCH_OK;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_swiglu_bwd(const T* __restrict__ dAct, const T* __restrict__ G,
+                                                    const T* __restrict__ U, T* __restrict__ dGU,
+                                                    T* __restrict__ Act, int Trows, int F) {
+    const long long n = (long long)Trows * F;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) {
+        const long long t = i / F;
+        const int f = (int)(i - t * F);
+        const float g = ldf(G + i), u = ldf(U + i), d = ldf(dAct + i);
+        const float sg = 1.f / (1.f + __expf(-g));
+        stf(dGU + t * 2 * F + f, d * u * sg * (1.f + g * (1.f - sg)));
+        stf(dGU + t * 2 * F + F + f, d * g * sg);
+        if (Act) stf(Act + i, g * sg * u);
+    }
+}
+
+int launch_swiglu_bwd(alch_dtype dt, const void* dAct, const void* G, const void* U, void* dGU, void* Act, int T,
+                      int F, hipStream_t stream) {
+    const long long n = (long long)T * F;
+    if (n <= 0) return ALCH_OK;
+    const int grid = (int)((n + 255) / 256 < 256 * 16 ? (n + 255) / 256 : 256 * 16);
+    if (dt == ALCH_BF16)
+        k_swiglu_bwd<__bf16><<<grid, 256, 0, stream>>>((const __bf16*)dAct, (const __bf16*)G, (const __bf16*)U,
+                                                       (__bf16*)dGU, (__bf16*)Act, T, F);
+    else
+        k_swiglu_bwd<float><<<grid, 256, 0, stream>>>((const float*)dAct, (const float*)G, (const float*)U,
+                                                      (float*)dGU, (float*)Act, T, F);
+    ALCH_HIP_TRY(hipGetLastError());
+    return ALCH_OK;
+}
+
+// ---- delta[t,h] = sum_d dO*O : one wave per (t,h)
+template <typename T>
+__global__ __launch_bounds__(256) void k_attn_delta(const T* __restrict__ dO, const T* __restrict__ O,
+                                                    float* __restrict__ delta, long long n_rows, int D) {
+    const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= n_rows) return;
+    const int lane = threadIdx.x & 63;
+    float s = 0.f;
+    for (int d = lane; d < D; d += 64) s += ldf(dO + row * D + d) * ldf(O + row * D + d);
+    s = wave_sum(s);
+    if (lane == 0) delta[row] = s;
+}
+
+int launch_attn_delta(alch_dtype dt, const void* dO, const void* O, float* delta, int T, int Hq, int D,
+                      hipStream_t stream) {
+    const long long n = (long long)T * Hq;
+    if (n <= 0) return ALCH_OK;
+    const int grid = (int)((n + 3) / 4);
+    if (dt == ALCH_BF16)
+        k_attn_delta<__bf16><<<grid, 256, 0, stream>>>((const __bf16*)dO, (const __bf16*)O, delta, n, D);
+    else
+        k_attn_delta<float><<<grid, 256, 0, stream>>>((const float*)dO, (const float*)O, delta, n, D);
+    ALCH_HIP_TRY(hipGetLastError());
+    return ALCH_OK;
+}
+
+// ---- rotary embedding in place: pairs (i, i + D/2), angle = pos * base^(-2i/D), rotation by sign*angle
+template <typename T>
+__global__ __launch_bounds__(256) void k_rope(T* __restrict__ x, long long ld, int Trows, int n_heads, int D,
+                                              const int* __restrict__ positions, const int* __restrict__ cu_seqlens,
+                                              int n_seqs, float log2_base, float sign) {
+    const int half = D >> 1;
+    const long long per_row = (long long)n_heads * half;
+    const long long n = (long long)Trows * per_row;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) {
+        const long long t = i / per_row;
+        const int rem = (int)(i - t * per_row);
+        const int h = rem / half, k = rem - h * half;
+        int pos;
+        if (positions) {
+            pos = positions[t];
+        } else {
+            // binary search for the sequence that holds token t
+            int lo = 0, hi = n_seqs;
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (cu_seqlens[mid] <= t) lo = mid; else hi = mid;
+            }
+            pos = (int)t - cu_seqlens[lo];
+        }
+        const float theta = exp2f(-2.f * (float)k / (float)D * log2_base);
+        float sn, cs;
+        sincosf((float)pos * theta, &sn, &cs);
+        sn *= sign;
+        T* p = x + t * ld + (long long)h * D + k;
+        const float a = ldf(p), b = ldf(p + half);
+        stf(p, a * cs - b * sn);
+        stf(p + half, b * cs + a * sn);
+    }
+}
+
+int launch_rope(alch_dtype dt, void* x, long long ld, int T, int n_heads, int D, const int* positions,
+                const int* cu_seqlens, int n_seqs, float base, float sign, hipStream_t stream) {
+    const long long n = (long long)T * n_heads * (D / 2);
+    if (n <= 0) return ALCH_OK;
+    const int grid = (int)((n + 255) / 256 < 256 * 16 ? (n + 255) / 256 : 256 * 16);
+    const float l2 = log2f(base);
+    if (dt == ALCH_BF16)
+        k_rope<__bf16><<<grid, 256, 0, stream>>>((__bf16*)x, ld, T, n_heads, D, positions, cu_seqlens, n_seqs, l2, sign);
+    else
+        k_rope<float><<<grid, 256, 0, stream>>>((float*)x, ld, T, n_heads, D, positions, cu_seqlens, n_seqs, l2, sign);
+    ALCH_HIP_TRY(hipGetLastError());
+    return ALCH_OK;
+}
+
+// ---- masked copy / add
+template <typename T>
+__global__ __launch_bounds__(256) void k_masked_copy(const T* __restrict__ a, const uint8_t* __restrict__ mask,
+                                                     T* __restrict__ out, int Trows, int width) {
+    const long long n = (long long)Trows * width;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) {
+        const long long t = i / width;
+        out[i] = (mask && mask[t] == 0) ? (T)0.f : a[i];
+    }
+}
+
+int launch_masked_copy(alch_dtype dt, const void* a, const uint8_t* mask, void* out, int T, int width,
+                       hipStream_t stream) {
+    const long long n = (long long)T * width;
+    if (n <= 0) return ALCH_OK;
+    const int grid = (int)((n + 255) / 256 < 256 * 16 ? (n + 255) / 256 : 256 * 16);
+    if (dt == ALCH_BF16)
+        k_masked_copy<__bf16><<<grid, 256, 0, stream>>>((const __bf16*)a, mask, (__bf16*)out, T, width);
+    else
+        k_masked_copy<float><<<grid, 256, 0, stream>>>((const float*)a, mask, (float*)out, T, width);
+    ALCH_HIP_TRY(hipGetLastError());
+    return ALCH_OK;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_add(const T* __restrict__ a, const T* __restrict__ b, T* __restrict__ y,
+                                             long long n) {
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256)
+        stf(y + i, ldf(a + i) + ldf(b + i));
+}
+
+int launch_add(alch_dtype dt, const void* a, const void* b, void* y, long long n, hipStream_t stream) {
+    if (n <= 0) return ALCH_OK;
+    const int grid = (int)((n + 255) / 256 < 256 * 16 ? (n + 255) / 256 : 256 * 16);
+    if (dt == ALCH_BF16)
+        k_add<__bf16><<<grid, 256, 0, stream>>>((const __bf16*)a, (const __bf16*)b, (__bf16*)y, n);
+    else
+        k_add<float><<<grid, 256, 0, stream>>>((const float*)a, (const float*)b, (float*)y, n);
+    ALCH_HIP_TRY(hipGetLastError());
+    return ALCH_OK;
+}
+
+}  // namespace alch

@@ -1,0 +1,51 @@
+"""GPU parity of the contraction primitive in all three operand layouts, against fp64 matmul
+on the same bf16-rounded inputs: ragged M / K, several terms, accumulate."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as synth
+from helpers import to_dev, to_np, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def operands(rng, M, N, K, a_k, b_k, dtype):
+    A = synth.quantize(rng.standard_normal((M, K) if a_k else (K, M)).astype(np.float32), dtype)
+    B = synth.quantize(rng.standard_normal((N, K) if b_k else (K, N)).astype(np.float32), dtype)
+    A64 = A.astype(np.float64) if a_k else A.astype(np.float64).T
+    B64 = B.astype(np.float64).T if b_k else B.astype(np.float64)
+    return A, B, A64 @ B64
+
+
+@pytest.mark.parametrize("a_k,b_k", [(True, False), (False, False), (True, True)])
+@pytest.mark.parametrize("M,N,K", [(256, 256, 64), (700, 512, 192), (1000, 768, 333 * 8), (37, 256, 128)])
+def test_gemm_layouts_bf16(a_k, b_k, M, N, K):
+    import paper_2503_01066_amd as A_
+    if (a_k or b_k) and K % 64:
+        K = (K // 64) * 64
+    if not a_k:
+        M = (M + 7) // 8 * 8
+    rng = np.random.default_rng(M * 7 + N + K)
+    A, B, ref = operands(rng, M, N, K, a_k, b_k, "bf16")
+    C = A_.alch_gemm(M, N, [(to_dev(A, "bf16"), to_dev(B, "bf16"), K)], a_k, b_k)
+    torch.cuda.synchronize()
+    assert rel_err(to_np(C), ref) < 6e-3       # one bf16 rounding of the output
+
+
+def test_gemm_terms_accumulate_and_fp32():
+    import paper_2503_01066_amd as A_
+    rng = np.random.default_rng(0)
+    M, N = 300, 512
+    A1, B1, r1 = operands(rng, M, N, 128, True, False, "bf16")
+    A2, B2, r2 = operands(rng, M, N, 192, True, False, "bf16")
+    C0 = synth.quantize(rng.standard_normal((M, N)).astype(np.float32) * 10, "bf16")
+    C = to_dev(C0, "bf16")
+    A_.alch_gemm(M, N, [(to_dev(A1, "bf16"), to_dev(B1, "bf16"), 128), (to_dev(A2, "bf16"), to_dev(B2, "bf16"), 192)],
+                 True, False, out=C, accumulate=True)
+    torch.cuda.synchronize()
+    assert rel_err(to_np(C), r1 + r2 + C0) < 6e-3
+    A3, B3, r3 = operands(rng, 70, 45, 33, False, False, "f32")
+    C = A_.alch_gemm(70, 45, [(to_dev(A3, "f32"), to_dev(B3, "f32"), 33)], False, False)
+    torch.cuda.synchronize()
+    assert rel_err(to_np(C), r3) < 1e-5

@@ -1,0 +1,120 @@
+"""GPU parity of alch_layer_backward against the fp64 oracle on the same seeded inputs.
+Bar: per output tensor max|gpu - oracle| / max|oracle| <= 2e-2 (bf16) / 1e-4 (f32)."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as synth
+from helpers import TOL, to_dev, to_np, f64, rel_err, cosine, oracle_shape, alch_shape
+from oracle import layer_forward, layer_backward_reuse, attention_lse, WEIGHT_KEYS
+
+pytestmark = pytest.mark.gpu
+REC = ("X", "X2", "Q", "K", "V", "O", "G", "U")
+
+
+def make_case(shape_name, dtype, cu, seed, record, wstd=0.02, dy_std=1.0, gain_std=0.1):
+    shp = synth.shape_dict(shape_name)
+    osh = oracle_shape(shp)
+    T = int(cu[-1])
+    W = synth.layer_weights(shp, seed, dtype, std=wstd, gain_std=gain_std)
+    if record == "forward":
+        X = synth.activations(T, shp["hidden"], seed + 1, dtype)
+        _, rec64 = layer_forward(osh, cu, None, X.astype(np.float64), f64(W))
+        rec = {k: synth.quantize(rec64[k].astype(np.float32), dtype) for k in REC}
+        rec["LSE"] = rec64["LSE"].astype(np.float32)
+    else:
+        rec = synth.drawn_record(shp, T, seed + 1, dtype)
+        rec["LSE"] = attention_lse(osh, cu, rec["Q"].astype(np.float64), rec["K"].astype(np.float64)).astype(np.float32)
+    dY = synth.activations(T, shp["hidden"], seed + 2, dtype, std=dy_std)
+    return shp, osh, W, rec, dY
+
+
+def run_gpu(shp, dtype, cu, W, rec, dY, loss_mask=None, want=WEIGHT_KEYS, positions=None, **kw):
+    import paper_2503_01066_amd as A
+    batch = A.Batch(cu, positions=positions)
+    dW = {k: to_dev(v, dtype) for k, v in W.items()}
+    drec = {k: to_dev(rec[k], dtype) for k in REC}
+    drec["LSE"] = torch.from_numpy(rec["LSE"]).cuda()
+    dm = None if loss_mask is None else torch.from_numpy(loss_mask).cuda()
+    out = A.alch_layer_backward(alch_shape(shp, dtype), batch, drec, dW, to_dev(dY, dtype), loss_mask=dm, want=want, **kw)
+    torch.cuda.synchronize()
+    return {k: to_np(v) for k, v in out.items()}
+
+
+def compare(gpu, ref, dtype, keys=None):
+    worst = {}
+    for k in (keys or gpu.keys()):
+        e = rel_err(gpu[k], ref[k])
+        worst[k] = e
+        assert np.isfinite(gpu[k]).all(), k
+        assert e <= TOL[dtype], (k, e, cosine(gpu[k], ref[k]))
+    return worst
+
+
+def test_config1_fp32_layer_with_loss_mask():
+    # config 1: fp32, hidden 256, 4x64 MHA, FFN 1024, eps 1e-6, base 1e4, B=2 x S=128, record from a forward
+    cu = synth.uniform_cu(2, 128)
+    shp, osh, W, rec, dY = make_case("config1", "f32", cu, 0, "forward", gain_std=0.0)
+    mask = synth.keep_mask(256, 0.5, 0)
+    for lm in (None, mask):
+        ref = layer_backward_reuse(osh, cu, None, f64(rec), f64(W), dY, lm)
+        gpu = run_gpu(shp, "f32", cu, W, rec, dY, loss_mask=lm)
+        compare(gpu, ref, "f32")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_tiny_ragged_gqa(dtype):
+    cu = synth.ragged_cu([1, 5, 0, 8, 3])
+    shp, osh, W, rec, dY = make_case("tiny", dtype, cu, 3, "forward", wstd=0.3)
+    ref = layer_backward_reuse(osh, cu, None, f64(rec), f64(W), dY)
+    compare(run_gpu(shp, dtype, cu, W, rec, dY), ref, dtype)
+
+
+@pytest.mark.parametrize("shape_name,lens", [("medium", [300, 1, 257, 64]), ("medium64", [130, 200, 77])])
+def test_medium_bf16_several_tiles_and_ragged_tail(shape_name, lens):
+    # T is not a multiple of any tile size; several 256-wide tiles in every GEMM dimension
+    cu = synth.ragged_cu(lens)
+    for record in ("drawn", "forward"):
+        shp, osh, W, rec, dY = make_case(shape_name, "bf16", cu, 5, record, dy_std=0.01)
+        ref = layer_backward_reuse(osh, cu, None, f64(rec), f64(W), dY)
+        compare(run_gpu(shp, "bf16", cu, W, rec, dY), ref, "bf16")
+
+
+def test_loss_mask_positions_and_frozen_weights_bf16():
+    cu = synth.ragged_cu([200, 313])
+    T = 513
+    shp, osh, W, rec, dY = make_case("medium", "bf16", cu, 7, "drawn", dy_std=0.01)
+    mask = synth.keep_mask(T, 0.25, 1)
+    pos = np.random.default_rng(2).integers(0, 3000, T).astype(np.int32)
+    ref = layer_backward_reuse(osh, cu, pos, f64(rec), f64(W), dY, mask)
+    gpu = run_gpu(shp, "bf16", cu, W, rec, dY, loss_mask=mask, positions=pos, want=("Wq", "Wd", "g2"))
+    assert set(gpu) == {"dX", "dWq", "dWd", "dg2"}
+    compare(gpu, ref, "bf16")
+
+
+def test_accumulate_adds_to_existing_gradients():
+    cu = synth.ragged_cu([100, 156])
+    shp, osh, W, rec, dY = make_case("medium", "bf16", cu, 9, "drawn", dy_std=0.01)
+    ref = layer_backward_reuse(osh, cu, None, f64(rec), f64(W), dY)
+    base = {"d" + k: synth.quantize(0.5 * np.abs(ref["d" + k]).max() *
+                                    np.random.default_rng(3).standard_normal(W[k].shape).astype(np.float32), "bf16")
+            for k in WEIGHT_KEYS}
+    grads = {k: to_dev(v, "bf16") for k, v in base.items()}
+    gpu = run_gpu(shp, "bf16", cu, W, rec, dY, grads=grads, accumulate=True)
+    want = {k: ref[k] + base[k] for k in base}
+    want["dX"] = ref["dX"]
+    compare(gpu, want, "bf16")
+
+
+def test_empty_batch_and_stale_record():
+    import paper_2503_01066_amd as A
+    cu = np.zeros(1, np.int32)
+    shp, osh, W, rec, dY = make_case("tiny", "f32", cu, 1, "drawn")
+    gpu = run_gpu(shp, "f32", cu, W, rec, dY)
+    for k in WEIGHT_KEYS:
+        assert np.all(gpu["d" + k] == 0), k
+    cu = synth.ragged_cu([4])
+    shp, osh, W, rec, dY = make_case("tiny", "f32", cu, 1, "forward")
+    with pytest.raises(A.AlchError) as e:
+        run_gpu(shp, "f32", cu, W, rec, dY, saved_version=3, weights_version=4)
+    assert e.value.code == -4
