@@ -1,0 +1,266 @@
+#!/usr/bin/env python3
+"""Benchmark of the activation-reuse hot path on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic batch:
+  capture/pack of a layer's saved activations (mask scan + row gather of the 9 record
+  streams, keeping 4 of 16 prefilled prompts) followed by the decoder-layer backward pass
+  driven by the packed record (all data and weight gradients).
+Workload "config2" (default): one Llama-3-8B-shaped layer, bf16, hidden 4096, 32 Q / 8 KV heads
+x 128, FFN 14336; the trained batch is 4 sequences x 2048 tokens.
+Workload "config3": capture/pack only, 32 layers x 32 prompts with lengths in [256, 4096],
+per-token keep mask ~ Bernoulli(0.25), 6 streams per layer out of fused qkv / gate-up buffers.
+
+Prints ONE JSON line (see the keys below).  Inputs are resident in HBM before timing starts.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "backward training tokens/sec from reused activations; capture GB/s; % roofline"
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="config2", choices=["config2", "config3"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
+                    help="measured HBM bytes per launch (from the rocprofv3 --pmc summaries)")
+    return ap.parse_args()
+
+
+def cpu_baseline_config2(seed=0):
+    """The fp64 oracle, as it stands, on one of the workload's four 2048-token sequences."""
+    import synth_inputs as synth
+    from oracle import LayerShape, layer_backward_reuse, attention_lse
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count()
+    shp = synth.shape_dict("llama8b")
+    osh = LayerShape(*[shp[k] for k in synth.SHAPE_FIELDS])
+    S = 2048
+    cu = np.array([0, S])
+    W = {k: v.astype(np.float64) for k, v in synth.layer_weights(shp, seed, "bf16").items()}
+    rec = {k: v.astype(np.float64) for k, v in synth.drawn_record(shp, S, seed + 1, "bf16").items()}
+    dY = synth.activations(S, shp["hidden"], seed + 2, "bf16", std=0.01).astype(np.float64)
+    t0 = time.perf_counter()
+    rec["LSE"] = attention_lse(osh, cu, rec["Q"], rec["K"])
+    layer_backward_reuse(osh, cu, None, rec, W, dY)
+    dt = time.perf_counter() - t0
+    return {"value": S / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": "1 of the 4 sequences (2048 tokens) of the same 8B-shaped layer, fp64 numpy, %.1f s" % dt}
+
+
+def cpu_baseline_config3(seed=0):
+    import synth_inputs as synth
+    from oracle import gather_pack
+    lens = synth.random_lengths(2, 256, 4096, seed)
+    cu = synth.ragged_cu(lens)
+    T = int(cu[-1])
+    mask = synth.keep_mask(T, 0.25, seed + 1)
+    rng = np.random.default_rng(seed)
+    widths = (4096, 4096, 1024, 1024, 14336, 14336)
+    srcs = [rng.integers(0, 65535, size=(T, w), dtype=np.uint16) for w in widths]
+    t0 = time.perf_counter()
+    kept, _, packed = gather_pack(mask, cu, srcs)
+    dt = time.perf_counter() - t0
+    nbytes = 2 * sum(p.nbytes for p in packed)
+    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "one layer, 2 prompts (%d tokens, %d kept), python/numpy row loop, %.1f s" % (T, len(kept), dt)}
+
+
+def load_traffic(path, key):
+    try:
+        with open(path) as f:
+            return json.load(f).get(key)
+    except Exception:
+        return None
+
+
+def run_config2(args, torch, A):
+    import synth_inputs as synth
+    dev = "cuda"
+    shp = synth.shape_dict("llama8b")
+    shape = A.make_shape(*[shp[k] for k in synth.SHAPE_FIELDS], "bf16")
+    H, QD, KD, F = shp["hidden"], shp["n_q_heads"] * shp["head_dim"], shp["n_kv_heads"] * shp["head_dim"], shp["ffn"]
+    n_src, S, n_keep = 16, 2048, 4
+    T_src, T = n_src * S, n_keep * S
+    g = torch.Generator(device=dev).manual_seed(0)
+    bf = torch.bfloat16
+    rnd = lambda shape_, std: (torch.randn(shape_, generator=g, device=dev, dtype=torch.float32) * std).to(bf)
+
+    # prefill-side buffers of 16 prompts (the serving batch), record streams ~ N(0,1)
+    widths = dict(X=H, X2=H, Q=QD, K=KD, V=KD, O=QD, G=F, U=F)
+    src = {k: rnd((T_src, w), 1.0) for k, w in widths.items()}
+    rs = np.random.default_rng(0)
+    keep_seqs = np.sort(rs.choice(n_src, n_keep, replace=False))
+    mask_np = np.zeros(T_src, np.uint8)
+    for s in keep_seqs:
+        mask_np[s * S:(s + 1) * S] = 1
+    mask = torch.from_numpy(mask_np).to(dev)
+    # LSE of the kept prompts from their own Q, K (attention forward of the library)
+    src["LSE"] = torch.zeros((T_src, shp["n_q_heads"]), dtype=torch.float32, device=dev)
+    one = A.Batch(synth.uniform_cu(1, S))
+    for s in keep_seqs:
+        sl = slice(int(s) * S, int(s + 1) * S)
+        _, lse = A.alch_attention_forward(shape, one, src["Q"][sl], src["K"][sl], src["V"][sl])
+        src["LSE"][sl] = lse
+    W = {"Wq": rnd((QD, H), 0.02), "Wk": rnd((KD, H), 0.02), "Wv": rnd((KD, H), 0.02), "Wo": rnd((H, QD), 0.02),
+         "Wg": rnd((F, H), 0.02), "Wu": rnd((F, H), 0.02), "Wd": rnd((H, F), 0.02),
+         "g1": torch.ones(H, device=dev, dtype=bf), "g2": torch.ones(H, device=dev, dtype=bf)}
+    dY = rnd((T, H), 0.01)
+
+    keys = list(widths) + ["LSE"]
+    dst = {k: torch.empty((T, src[k].shape[1]), dtype=src[k].dtype, device=dev) for k in keys}
+    src_batch = A.Batch(synth.uniform_cu(n_src, S))
+    kept_batch = A.Batch(synth.uniform_cu(n_keep, S))
+    grads = {"d" + k: torch.empty_like(v) for k, v in W.items()}
+    dX = torch.empty_like(dY)
+    ws_pack = torch.empty(A.lib().alch_capture_pack_workspace_bytes(T_src), dtype=torch.uint8, device=dev)
+    ws_bwd = torch.empty(A.layer_backward_workspace_bytes(shape, T, S), dtype=torch.uint8, device=dev)
+    streams = [src[k] for k in keys]
+    dsts = [dst[k] for k in keys]
+
+    def step():
+        A.alch_capture_pack(src_batch, mask, streams, capacity=T, dsts=dsts, workspace=ws_pack)
+        A.alch_layer_backward(shape, kept_batch, dst, W, dY, grads=grads, dX=dX, workspace=ws_bwd)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    A.alch_trace_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    A.alch_trace_enable(False)
+    trace = A.alch_trace_collect()
+
+    ms_step = dt / args.steps * 1e3
+    by = {}
+    for kind, flops, nbytes, ms in trace:
+        e = by.setdefault(kind, [0.0, 0.0, 0.0, 0])
+        e[0] += flops; e[1] += nbytes; e[2] += ms; e[3] += 1
+    gm = by.get("gemm_mfma", [0, 0, 1e-9, 1])
+    achieved_tf = gm[0] / (gm[2] * 1e-3) / 1e12
+    pk = by.get("pack_gather", [0, 0, 1e-9, 1])
+    pack_gbps = pk[1] * T / (pk[2] * 1e-3) / 1e9       # traced bytes are per kept row
+    P = 2 * H * QD + 2 * H * KD + 3 * H * F
+    attn_flops = 10.0 * shp["head_dim"] * shp["n_q_heads"] * n_keep * S * (S + 1) / 2
+    out = {
+        "metric": METRIC, "value": T * args.steps / dt, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "config2: one Llama-3-8B-shaped layer, bf16, 4 x 2048 trained tokens "
+                               "(packed out of 16 x 2048 prefilled), capture/pack + full layer backward",
+                   "hidden": H, "q_heads": shp["n_q_heads"], "kv_heads": shp["n_kv_heads"],
+                   "head_dim": shp["head_dim"], "ffn": F, "tokens": T, "seq_len": S},
+        "step_tflops": (4.0 * P * T + attn_flops) / 1e12,
+        "step_mfma_frac": (4.0 * P * T + attn_flops) / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "capture_gbps": pack_gbps,
+        "roofline": {"kernel": "k_gemm_mfma (all contractions of the layer backward)", "bound": "mfma",
+                     "achieved": achieved_tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved_tf / PEAK_BF16_TFLOPS,
+                     "traffic": load_traffic(args.traffic_json, "gemm_mfma_config2_bytes_per_launch"),
+                     "launches_per_step": gm[3] / args.steps, "avg_launch_ms": gm[2] / max(gm[3], 1)},
+        "roofline_pack": {"kernel": "k_pack_gather", "bound": "hbm", "achieved": pack_gbps, "peak": PEAK_HBM_GBPS,
+                          "unit": "GB/s", "frac": pack_gbps / PEAK_HBM_GBPS,
+                          "traffic": load_traffic(args.traffic_json, "pack_gather_config2_bytes_per_launch"),
+                          "avg_launch_ms": pk[2] / max(pk[3], 1)},
+        "kernel_ms_per_step": {k: v[2] / args.steps for k, v in by.items()},
+    }
+    return out
+
+
+def run_config3(args, torch, A):
+    import synth_inputs as synth
+    dev = "cuda"
+    n_layers, n_prompts = 32, 32
+    lens = synth.random_lengths(n_prompts, 256, 4096, 0)
+    cu = synth.ragged_cu(lens)
+    T = int(cu[-1])
+    mask_np = synth.keep_mask(T, 0.25, 1)
+    n_kept = int(mask_np.sum())
+    mask = torch.from_numpy(mask_np).to(dev)
+    batch = A.Batch(cu)
+    # two rotating sets of source buffers so that no layer call finds its source in cache
+    sets = []
+    for i in range(2):
+        hid = torch.empty((T, 4096), dtype=torch.bfloat16, device=dev).normal_()
+        qkv = torch.empty((T, 6144), dtype=torch.bfloat16, device=dev).normal_()
+        gu = torch.empty((T, 28672), dtype=torch.bfloat16, device=dev).normal_()
+        sets.append([hid, qkv[:, :4096], qkv[:, 4096:5120], qkv[:, 5120:], gu[:, :14336], gu[:, 14336:]])
+    cap = n_kept
+    dsts = [[torch.empty((cap, s.shape[1]), dtype=s.dtype, device=dev) for s in sets[0]] for _ in range(2)]
+    ws = torch.empty(A.lib().alch_capture_pack_workspace_bytes(T), dtype=torch.uint8, device=dev)
+
+    def step():
+        for l in range(n_layers):
+            A.alch_capture_pack(batch, mask, sets[l & 1], capacity=cap, dsts=dsts[l & 1], workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    A.alch_trace_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    A.alch_trace_enable(False)
+    trace = A.alch_trace_collect()
+    pk = [r for r in trace if r[0] == "pack_gather"]
+    ms = sum(r[3] for r in pk)
+    row_rw = pk[0][2]
+    gbps = row_rw * n_kept * len(pk) / (ms * 1e-3) / 1e9
+    total_bytes = (row_rw * n_kept + T + 4 * n_kept + 8 * (n_prompts + 1)) * n_layers
+    return {
+        "metric": METRIC, "value": total_bytes * args.steps / dt / 1e9, "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "config3: capture/pack only, 32 layers x 32 prompts (lengths U[256,4096]), keep ~ "
+                               "Bernoulli(0.25), 6 bf16 streams per layer from fused qkv / gate-up buffers",
+                   "tokens": T, "kept": n_kept, "bytes_per_kept_token_per_layer": row_rw / 2},
+        "capture_gbps": gbps,
+        "roofline": {"kernel": "k_pack_gather", "bound": "hbm", "achieved": gbps, "peak": PEAK_HBM_GBPS,
+                     "unit": "GB/s", "frac": gbps / PEAK_HBM_GBPS,
+                     "traffic": load_traffic(args.traffic_json, "pack_gather_config3_bytes_per_launch"),
+                     "avg_launch_ms": ms / len(pk)},
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (--gpus 1); multi-GPU sharding is design-only "
+              "(see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2503_01066_amd as A
+    A.lib()  # fails loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    out = run_config2(args, torch, A) if args.workload == "config2" else run_config3(args, torch, A)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_config2() if args.workload == "config2" else cpu_baseline_config3()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

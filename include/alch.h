@@ -252,6 +252,35 @@ typedef struct {
 int alch_gemm(alch_dtype dtype, int32_t M, int32_t N, int32_t a_kmajor, int32_t b_kmajor, int32_t n_terms,
               const alch_gemm_term* terms, void* C, int64_t ldc, int32_t accumulate, void* hip_stream);
 
+/*
+ * alch_attention_forward: causal grouped-query attention over saved (post-RoPE) Q, K and V,
+ * writing O [T,Hq*D] and LSE fp32 [T,Hq].  It is the step of the prefill that defines the LSE
+ * and O members of the record (Section 4.1); exposed so that a record can be completed from
+ * its Q, K, V alone.
+ */
+int alch_attention_forward(const alch_layer_shape* shape, const alch_batch* batch, const void* Q,
+                           const void* K, const void* V, void* O, float* LSE, void* hip_stream);
+
+/*
+ * Launch timing for benchmarks.  While enabled, the library brackets its main kernels with two
+ * HIP events on the caller's stream; alch_trace_collect waits for them, writes up to max_records
+ * records (HOST array) in launch order, and forgets them.  flops / bytes are the algorithmic
+ * work of the launch (2*M*N*K for a contraction; rows read once + written once for the gather).
+ * The trace is process-wide; enable it from one thread.
+ */
+typedef enum {
+    ALCH_TRACE_GEMM_MFMA = 0, ALCH_TRACE_GEMM_GENERIC = 1, ALCH_TRACE_PACK_SCAN = 2,
+    ALCH_TRACE_PACK_GATHER = 3, ALCH_TRACE_ATTN_BWD = 4, ALCH_TRACE_ATTN_FWD = 5,
+    ALCH_TRACE_ROW_OPS = 6, ALCH_TRACE_CROSS_ENTROPY = 7
+} alch_trace_kind;
+typedef struct {
+    int32_t kind; /* alch_trace_kind */
+    double flops, bytes;
+    float ms;
+} alch_trace_record;
+int alch_trace_enable(int32_t enable);
+int alch_trace_collect(alch_trace_record* out, int32_t max_records, int32_t* n_out);
+
 /* Message describing the last error on the calling thread ("" if none). */
 const char* alch_last_error(void);
 

@@ -60,6 +60,13 @@ class CGemmTerm(C.Structure):
     _fields_ = [("A", C.c_void_p), ("B", C.c_void_p), ("K", C.c_int32), ("lda", C.c_int64), ("ldb", C.c_int64)]
 
 
+class CTraceRecord(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("flops", C.c_double), ("bytes", C.c_double), ("ms", C.c_float)]
+
+
+TRACE_KINDS = ("gemm_mfma", "gemm_generic", "pack_scan", "pack_gather", "attn_bwd", "attn_fwd", "row_ops",
+               "cross_entropy")
+
 HOOK_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.c_int)
 
 
@@ -111,6 +118,11 @@ def lib():
     L.alch_gemm.restype = C.c_int
     L.alch_gemm.argtypes = [C.c_int, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(CGemmTerm),
                             C.c_void_p, C.c_int64, C.c_int32, C.c_void_p]
+    L.alch_attention_forward.restype = C.c_int
+    L.alch_attention_forward.argtypes = [C.POINTER(LayerShape), C.POINTER(CBatch), C.c_void_p, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_void_p, C.c_void_p]
+    L.alch_trace_enable.argtypes = [C.c_int32]
+    L.alch_trace_collect.argtypes = [C.POINTER(CTraceRecord), C.c_int32, C.POINTER(C.c_int32)]
     _LIB = L
     return L
 
@@ -282,3 +294,25 @@ def alch_gemm(M, N, terms, a_kmajor, b_kmajor, out=None, accumulate=False, strea
     _check(L.alch_gemm(code, M, N, 1 if a_kmajor else 0, 1 if b_kmajor else 0, len(terms), arr, _ptr(out),
                        out.stride(0), 1 if accumulate else 0, _stream_handle(stream)))
     return out
+
+
+def alch_attention_forward(shape, batch, Q, K, V, stream=None):
+    """Returns (O, LSE) of causal grouped-query attention over post-RoPE Q, K and V."""
+    L = lib()
+    O = torch.empty_like(Q)
+    LSE = torch.empty((Q.shape[0], shape.n_q_heads), dtype=torch.float32, device=Q.device)
+    _check(L.alch_attention_forward(C.byref(shape), C.byref(batch.c), _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE),
+                                    _stream_handle(stream)))
+    return O, LSE
+
+
+def alch_trace_enable(on):
+    _check(lib().alch_trace_enable(1 if on else 0))
+
+
+def alch_trace_collect(max_records=65536):
+    """Returns a list of (kind name, flops, bytes, ms) in launch order (waits for the launches)."""
+    buf = (CTraceRecord * max_records)()
+    n = C.c_int32(0)
+    _check(lib().alch_trace_collect(buf, max_records, C.byref(n)))
+    return [(TRACE_KINDS[buf[i].kind], buf[i].flops, buf[i].bytes, buf[i].ms) for i in range(n.value)]

@@ -5,6 +5,9 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
+#include <vector>
+
 #include "kernels.h"
 
 namespace alch {
@@ -19,6 +22,34 @@ int fail(int code, const char* fmt, ...) {
     return code;
 }
 void clear_error() { g_error[0] = 0; }
+
+// ---- launch tracing --------------------------------------------------------------------------
+struct TraceRec {
+    int kind;
+    double flops, bytes;
+    hipEvent_t e0, e1;
+};
+static std::mutex g_trace_mu;
+static bool g_trace_on = false;
+static std::vector<TraceRec*> g_trace;
+static constexpr size_t kTraceMax = 1 << 16;
+
+TraceScope::TraceScope(int kind, double flops, double bytes, hipStream_t s) : rec(nullptr), stream(s) {
+    if (!g_trace_on) return;
+    std::lock_guard<std::mutex> lk(g_trace_mu);
+    if (g_trace.size() >= kTraceMax) return;
+    TraceRec* r = new TraceRec{kind, flops, bytes, nullptr, nullptr};
+    if (hipEventCreate(&r->e0) != hipSuccess || hipEventCreate(&r->e1) != hipSuccess) {
+        delete r;
+        return;
+    }
+    (void)hipEventRecord(r->e0, s);
+    g_trace.push_back(r);
+    rec = r;
+}
+TraceScope::~TraceScope() {
+    if (rec) (void)hipEventRecord(static_cast<TraceRec*>(rec)->e1, stream);
+}
 
 static int check_shape(const alch_layer_shape* s) {
     if (!s) return fail(ALCH_ERR_INVALID_ARG, "shape is NULL");
@@ -308,6 +339,12 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
 }
 
 int launch_attn_bwd(const AttnArgs& a, hipStream_t stream) {
+    double pairs = 0;  // causal (query, key) pairs per query head
+    for (int s = 0; s < a.n_seqs; ++s) {
+        const double n = a.cu_seqlens_host[s + 1] - a.cu_seqlens_host[s];
+        pairs += n * (n + 1) / 2;
+    }
+    TraceScope ts(kTraceAttnBwd, 10.0 * a.D * a.Hq * pairs, 0.0, stream);
     if (attn_mfma_supported(a)) return launch_attn_bwd_mfma(a, stream);
     return launch_attn_bwd_generic(a, stream);
 }
@@ -317,6 +354,33 @@ int launch_attn_bwd(const AttnArgs& a, hipStream_t stream) {
 using namespace alch;
 
 extern "C" {
+
+int alch_trace_enable(int32_t enable) {
+    std::lock_guard<std::mutex> lk(g_trace_mu);
+    g_trace_on = enable != 0;
+    return ALCH_OK;
+}
+
+int alch_trace_collect(alch_trace_record* out, int32_t max_records, int32_t* n_out) {
+    clear_error();
+    if (!n_out || (max_records > 0 && !out) || max_records < 0) return fail(ALCH_ERR_INVALID_ARG, "bad trace buffer");
+    std::lock_guard<std::mutex> lk(g_trace_mu);
+    int n = 0;
+    int rc = ALCH_OK;
+    for (TraceRec* r : g_trace) {
+        float ms = 0.f;
+        hipError_t e = hipEventSynchronize(r->e1);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, r->e0, r->e1);
+        if (e != hipSuccess) rc = fail(ALCH_ERR_HIP, "trace event: %s", hipGetErrorString(e));
+        if (n < max_records && e == hipSuccess) out[n++] = alch_trace_record{r->kind, r->flops, r->bytes, ms};
+        (void)hipEventDestroy(r->e0);
+        (void)hipEventDestroy(r->e1);
+        delete r;
+    }
+    g_trace.clear();
+    *n_out = n;
+    return rc;
+}
 
 const char* alch_last_error(void) { return g_error; }
 const char* alch_version(void) { return "alch 0.1 (gfx950)"; }
@@ -489,6 +553,19 @@ int alch_stack_backward(const alch_layer_shape* shape, int32_t n_layers, int32_t
         cur = out;
     }
     return ALCH_OK;
+}
+
+int alch_attention_forward(const alch_layer_shape* shape, const alch_batch* batch, const void* Q, const void* K,
+                           const void* V, void* O, float* LSE, void* hip_stream) {
+    clear_error();
+    ALCH_TRY(check_shape(shape));
+    ALCH_TRY(check_batch(batch));
+    const int T = batch->total_tokens;
+    REQUIRE_ACT(Q, "Q", T); REQUIRE_ACT(K, "K", T); REQUIRE_ACT(V, "V", T); REQUIRE_ACT(O, "O", T);
+    REQUIRE_ACT(LSE, "LSE", T);
+    return launch_attn_fwd(shape->dtype, Q, K, V, O, LSE, T, batch->n_seqs, batch->max_seqlen, batch->cu_seqlens,
+                           batch->cu_seqlens_host, shape->n_q_heads, shape->n_kv_heads, shape->head_dim,
+                           static_cast<hipStream_t>(hip_stream));
 }
 
 size_t alch_layer_forward_workspace_bytes(const alch_layer_shape* shape, int32_t total_tokens, int32_t max_seqlen) {

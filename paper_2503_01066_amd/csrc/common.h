@@ -42,4 +42,15 @@ struct Arena {
     bool ok() const { return used <= size; }
 };
 
+// Optional per-launch timing (alch_trace_enable): when on, a TraceScope brackets the kernels
+// launched inside it with two HIP events on their stream.
+enum TraceKind { kTraceGemmMfma = 0, kTraceGemmGeneric = 1, kTracePackScan = 2, kTracePackGather = 3,
+                 kTraceAttnBwd = 4, kTraceAttnFwd = 5, kTraceRowOps = 6, kTraceCrossEntropy = 7 };
+struct TraceScope {
+    void* rec;
+    hipStream_t stream;
+    TraceScope(int kind, double flops, double bytes, hipStream_t s);
+    ~TraceScope();
+};
+
 }  // namespace alch

@@ -134,7 +134,16 @@ int launch_gemm_generic(const GemmDesc& d, hipStream_t stream) {
 
 int launch_gemm(const GemmDesc& d, hipStream_t stream) {
     if (d.M <= 0 || d.N <= 0) return ALCH_OK;
-    if (gemm_mfma_supported(d)) return launch_gemm_mfma(d, stream);
+    double k_total = 0;
+    for (int s = 0; s < d.n_seg; ++s) k_total += d.seg[s].K;
+    const double flops = 2.0 * d.M * d.N * k_total;
+    const size_t E = dtype_size(d.dtype);
+    const double bytes = ((double)d.M * k_total + (double)d.N * k_total + (double)d.M * d.N) * E;
+    if (gemm_mfma_supported(d)) {
+        TraceScope ts(kTraceGemmMfma, flops, bytes, stream);
+        return launch_gemm_mfma(d, stream);
+    }
+    TraceScope ts(kTraceGemmGeneric, flops, bytes, stream);
     return launch_gemm_generic(d, stream);
 }
 

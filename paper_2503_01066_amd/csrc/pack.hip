@@ -177,13 +177,21 @@ int launch_pack(const uint8_t* mask, int T, const int* cu_seqlens, int n_seqs, i
                 int* n_kept_and_status, void* workspace, hipStream_t stream) {
     int* block_offsets = static_cast<int*>(workspace);
     const int nblocks = T > 0 ? ceil_div(T, kTokPerBlock) : 0;
+    {
+    TraceScope ts(kTracePackScan, 0.0, (double)T + 4.0 * (n_seqs + 1), stream);
     if (nblocks > 0) k_pack_count<<<nblocks, kScanThreads, 0, stream>>>(mask, T, block_offsets);
     k_pack_scan_blocks<<<1, kScanThreads, 0, stream>>>(block_offsets, nblocks, n_kept_and_status, capacity);
     if (nblocks > 0) k_pack_fill<<<nblocks, kScanThreads, 0, stream>>>(mask, T, block_offsets, kept_index, capacity);
     k_pack_cu<<<n_seqs + 1, 64, 0, stream>>>(mask, cu_seqlens, n_seqs + 1, block_offsets, nblocks,
                                               n_kept_and_status, cu_kept);
+    }
     ALCH_HIP_TRY(hipGetLastError());
     if (T == 0 || capacity == 0) return ALCH_OK;
+
+    // traced bytes of the gather: per kept row (read once + written once); the row count is on the device
+    double row_bytes_rw = 0;
+    for (int k = 0; k < n_streams; ++k) row_bytes_rw += 2.0 * (double)streams[k].row_bytes;
+    TraceScope ts(kTracePackGather, 0.0, row_bytes_rw, stream);
 
     long long max_rows = (long long)T < capacity ? (long long)T : capacity;
     int grid = (int)(max_rows < (long long)kGatherGrid ? max_rows : (long long)kGatherGrid);
