@@ -1,10 +1,352 @@
-// Matrix-core attention kernels (placeholder dispatch until the MFMA kernels land).
+// Causal grouped-query attention on the gfx950 matrix cores, head_dim 128, bf16.
+//
+// Backward from the saved record (Section 4.1 of the paper: the prompt's Q, K, V stay on the
+// GPU after prefill; Section 4.2: the layer's backward consumes them).  Probabilities are
+// rebuilt from saved Q, K and LSE, never stored: p_ij = exp(q_i.k_j/sqrt(D) - LSE_i), j <= i.
+//
+// Two kernels, no atomics, deterministic:
+//   dK/dV kernel: a work-group owns 128 keys of one (sequence, kv head) -- 32 per wavefront,
+//     their K and V fragments held in registers -- and streams 64-query tiles of Q and dO of
+//     every query head of the group through LDS (direct-to-LDS loads, double buffered).
+//       S = Q K^T, dP = dO V^T            (tile rows from LDS with ds_read_b128)
+//       P, dS in the accumulator layout feed straight back as the left operand of
+//       dV += P^T dO, dK += dS^T Q        (dO, Q rows read with the transposing LDS read)
+//   dQ kernel: a work-group owns 128 queries of one (sequence, query head) and streams 64-key
+//     tiles of K and V:  S^T = K Q^T, dP^T = V dO^T, dQ += dS K.
+// The LDS tile is [rows][128] bf16 with the 16-byte chunk index XOR-ed by a function of the row
+// that makes both the row-major and the transposing reads bank-conflict free.
 #include "kernels.h"
 
 namespace alch {
 
-bool attn_mfma_supported(const AttnArgs&) { return false; }
-int launch_attn_bwd_mfma(const AttnArgs&, hipStream_t) { return fail(ALCH_ERR_UNSUPPORTED, "no matrix-core attention kernel for this shape"); }
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+
+#define ALCH_LDS(p) ((__attribute__((address_space(3))) void*)(p))
+
+static constexpr int kD = 128;
+static constexpr int kTileRows = 64;                       // rows of a streamed tile
+static constexpr int kTileBytes = kTileRows * kD * 2;      // 16 KB
+static constexpr int kStageBytes = 2 * kTileBytes + 1024;  // two tiles + two 64-float vectors (padded)
+static constexpr float kLog2e = 1.4426950408889634f;
+
+struct AttnMfmaParams {
+    const __bf16 *Q, *K, *V, *dO;
+    const float *LSE, *delta;
+    __bf16 *dQ, *dK, *dV;
+    const int* cu;
+    int Hq, Hkv;
+    long long ldq, ldk, ldo;  // row strides (elements) of Q/dO, K/V, and of the outputs
+    float scale;
+};
+
+__device__ __forceinline__ i32x4 rsrc_of(const void* p, long long bytes) {
+    const uint32_t n = bytes <= 0 ? 0u : (bytes > 0x7fffffffLL ? 0x7fffffffu : (uint32_t)bytes);
+    const uint64_t a = reinterpret_cast<uint64_t>(p);
+    i32x4 r;
+    r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+    r[1] = __builtin_amdgcn_readfirstlane((int)((uint32_t)(a >> 32) & 0xffffu));
+    r[2] = __builtin_amdgcn_readfirstlane((int)n);
+    r[3] = 0x00020000;
+    return r;
+}
+__device__ __forceinline__ void dma16(i32x4 r, uint32_t lds_addr, uint32_t voff) {
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_addr), "v"(voff), "s"(r)
+                 : "memory", "m0");
+}
+__device__ __forceinline__ void dma4(i32x4 r, uint32_t lds_addr, uint32_t voff) {
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, 0 offen lds" ::"s"(lds_addr), "v"(voff), "s"(r)
+                 : "memory", "m0");
+}
+
+// chunk swizzle of the [rows][128] tile: 16 chunks of 16 bytes per row
+__device__ __forceinline__ int swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+
+// One wave's share (4 of 16 loads) of a 64-row tile: rows of `ld` elements starting at `base`,
+// `rows_valid` rows exist (the rest read as zero).
+__device__ __forceinline__ void issue_rows_tile(const __bf16* base, long long ld, int rows_valid, uint32_t lds_addr,
+                                                int wave, int lane) {
+    const i32x4 r = rsrc_of(base, rows_valid > 0 ? ((long long)(rows_valid - 1) * ld + kD) * 2 : 0);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int slot = (wave * 4 + j) * 64 + lane;
+        const int row = slot >> 4, c = (slot & 15) ^ swz(row);
+        dma16(r, lds_addr + (uint32_t)(wave * 4 + j) * 1024u, (uint32_t)((row * ld + c * 8) * 2));
+    }
+}
+// 64 floats with stride `stride` elements (one per tile row) -> LDS, by one wave
+__device__ __forceinline__ void issue_row_scalars(const float* base, long long stride, int rows_valid, uint32_t lds_addr,
+                                                  int lane) {
+    const i32x4 r = rsrc_of(base, rows_valid > 0 ? ((long long)(rows_valid - 1) * stride + 1) * 4 : 0);
+    dma4(r, lds_addr, (uint32_t)(lane * stride * 4));
+}
+
+// operand fragment along the 128-wide dimension (k = d): rows row0 + (lane&31), d = kk*16 + 8*(lane>>5) ..+7
+__device__ __forceinline__ bf16x8 tile_frag_d(const char* tile, int row0, int kk, int lane) {
+    const int row = row0 + (lane & 31);
+    const int c = (kk * 2 + (lane >> 5)) ^ swz(row);
+    return *reinterpret_cast<const bf16x8*>(tile + row * 256 + c * 16);
+}
+// operand fragment along the row dimension (k = tile row) for the column block nb (32 columns):
+// k index (half = lane>>5, e) <-> tile row row0 + 16*ks + 8*(e>>2) + 4*half + (e&3), matching the
+// accumulator layout of a 32x32 MFMA whose rows are these tile rows.
+__device__ __forceinline__ bf16x8 tile_frag_rows(const char* tile, int row0, int ks, int nb, int lane) {
+    const int g = lane >> 4, i = lane & 15;
+    const int col = nb * 32 + (g & 1) * 16 + 4 * (i & 3);
+    const int r0 = row0 + 16 * ks + 4 * (g >> 1) + (i >> 2);
+    const int r1 = r0 + 8;
+    const char* p0 = tile + r0 * 256 + (((col >> 3) ^ swz(r0)) << 4) + (col & 7) * 2;
+    const char* p1 = tile + r1 * 256 + (((col >> 3) ^ swz(r1)) << 4) + (col & 7) * 2;
+    bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4*)(p0));
+    bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4*)(p1));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+__device__ __forceinline__ bf16x8 pack8(const f32x16& v, int ks) {
+    bf16x8 o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = (__bf16)v[8 * ks + e];
+    return o;
+}
+
+// 16-byte global load of an operand fragment held in registers for the whole kernel:
+// rows row0 + (lane&31) of a [rows, ld] matrix (column offset already in base), zero beyond rows_valid
+__device__ __forceinline__ bf16x8 global_frag_d(const __bf16* base, long long ld, int row0, int rows_valid, int kk, int lane) {
+    const int row = row0 + (lane & 31);
+    bf16x8 z;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) z[e] = (__bf16)0.f;
+    if (row >= rows_valid) return z;
+    return *reinterpret_cast<const bf16x8*>(base + (long long)row * ld + kk * 16 + 8 * (lane >> 5));
+}
+
+// ---------------------------------------------------------------------------------------------
+// dK / dV
+__global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
+    __shared__ __attribute__((aligned(1024))) char smem[2 * kStageBytes];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)ALCH_LDS(smem);
+    const int seq = blockIdx.z, kv = blockIdx.y, kb = blockIdx.x;
+    const int seq_start = p.cu[seq], len = p.cu[seq + 1] - seq_start;
+    if (kb * 128 >= len) return;
+    const int lane = threadIdx.x & 63, half = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int G = p.Hq / p.Hkv;
+    const int j0 = kb * 128 + wave * 32;  // this wave's first key (index inside the sequence)
+
+    // K, V fragments of the wave's 32 keys stay in registers
+    const __bf16* Kb = p.K + (long long)seq_start * p.ldk + kv * kD;
+    const __bf16* Vb = p.V + (long long)seq_start * p.ldk + kv * kD;
+    bf16x8 kf[8], vf[8];
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+        kf[kk] = global_frag_d(Kb, p.ldk, j0, len, kk, lane);
+        vf[kk] = global_frag_d(Vb, p.ldk, j0, len, kk, lane);
+    }
+    f32x16 dK[4], dV[4];
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) dK[n][e] = dV[n][e] = 0.f;
+
+    const int qt0 = (kb * 128) / kTileRows;
+    const int nqt = (len + kTileRows - 1) / kTileRows - qt0;
+    const int n_it = G * nqt;
+    const float sl2 = p.scale * kLog2e;
+
+    auto issue = [&](int it) {
+        const int h = kv * G + it / nqt, qt = qt0 + it % nqt;
+        const int row_first = qt * kTileRows, rows_valid = len - row_first;
+        const uint32_t st = lds0 + (uint32_t)(it & 1) * kStageBytes;
+        issue_rows_tile(p.Q + (long long)(seq_start + row_first) * p.ldq + h * kD, p.ldq, rows_valid, st, wave, lane);
+        issue_rows_tile(p.dO + (long long)(seq_start + row_first) * p.ldq + h * kD, p.ldq, rows_valid, st + kTileBytes, wave, lane);
+        if (wave == 0) issue_row_scalars(p.LSE + (long long)(seq_start + row_first) * p.Hq + h, p.Hq, rows_valid, st + 2 * kTileBytes, lane);
+        if (wave == 1) issue_row_scalars(p.delta + (long long)(seq_start + row_first) * p.Hq + h, p.Hq, rows_valid, st + 2 * kTileBytes + 256, lane);
+    };
+
+    issue(0);
+    for (int it = 0; it < n_it; ++it) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (it + 1 < n_it) issue(it + 1);
+        const int qt = qt0 + it % nqt;
+        const char* tq = smem + (it & 1) * kStageBytes;
+        const char* tdo = tq + kTileBytes;
+        const float* lse_s = reinterpret_cast<const float*>(tq + 2 * kTileBytes);
+        const float* del_s = lse_s + 64;
+#pragma unroll
+        for (int ib = 0; ib < 2; ++ib) {
+            const int i0 = qt * kTileRows + ib * 32;  // first query of the block (inside the sequence)
+            if (i0 + 31 < j0 || i0 >= len) continue;  // wholly above the diagonal / beyond the sequence
+            f32x16 S, dP;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) S[e] = dP[e] = 0.f;
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) {
+                S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tile_frag_d(tq, ib * 32, kk, lane), kf[kk], S, 0, 0, 0);
+                dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tile_frag_d(tdo, ib * 32, kk, lane), vf[kk], dP, 0, 0, 0);
+            }
+            // accumulator element e: query row i0 + 8*(e>>2) + 4*half + (e&3), key column j0 + (lane&31)
+            const bool need_mask = (i0 < j0 + 31) || (i0 + 32 > len);
+            const int j = j0 + (lane & 31);
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_s + ib * 32 + 8 * b + 4 * half);
+                const f32x4 d4 = *reinterpret_cast<const f32x4*>(del_s + ib * 32 + 8 * b + 4 * half);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int e = 4 * b + r;
+                    const int i = i0 + 8 * b + 4 * half + r;
+                    float pr = exp2f(S[e] * sl2 - l4[r] * kLog2e);
+                    if (need_mask && (j > i || i >= len)) pr = 0.f;
+                    S[e] = pr;
+                    dP[e] = pr * (dP[e] - d4[r]);
+                }
+            }
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                const bf16x8 pf = pack8(S, ks), dsf = pack8(dP, ks);
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb) {
+                    dV[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, tile_frag_rows(tdo, ib * 32, ks, nb, lane), dV[nb], 0, 0, 0);
+                    dK[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf, tile_frag_rows(tq, ib * 32, ks, nb, lane), dK[nb], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    // accumulator element e of block nb: key row j0 + 8*(e>>2) + 4*half + (e&3), column nb*32 + (lane&31)
+    __bf16* dKb = p.dK + (long long)seq_start * p.ldo + kv * kD;
+    __bf16* dVb = p.dV + (long long)seq_start * p.ldo + kv * kD;
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int j = j0 + 8 * (e >> 2) + 4 * half + (e & 3);
+            if (j < len) {
+                const long long off = (long long)j * p.ldo + nb * 32 + (lane & 31);
+                dKb[off] = (__bf16)(dK[nb][e] * p.scale);
+                dVb[off] = (__bf16)dV[nb][e];
+            }
+        }
+}
+
+// ---------------------------------------------------------------------------------------------
+// dQ
+__global__ __launch_bounds__(256) void k_attn_bwd_dq_mfma(AttnMfmaParams p) {
+    __shared__ __attribute__((aligned(1024))) char smem[2 * kStageBytes];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)ALCH_LDS(smem);
+    const int seq = blockIdx.z, h = blockIdx.y;
+    const int seq_start = p.cu[seq], len = p.cu[seq + 1] - seq_start;
+    // heaviest (last) query blocks first
+    const int nqb = (len + 127) / 128;
+    if ((int)blockIdx.x >= nqb) return;
+    const int qb = nqb - 1 - blockIdx.x;
+    const int lane = threadIdx.x & 63, half = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int kv = h / (p.Hq / p.Hkv);
+    const int i0 = qb * 128 + wave * 32;  // this wave's first query
+
+    const __bf16* Qb = p.Q + (long long)seq_start * p.ldq + h * kD;
+    const __bf16* dOb = p.dO + (long long)seq_start * p.ldq + h * kD;
+    bf16x8 qf[8], gf[8];
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+        qf[kk] = global_frag_d(Qb, p.ldq, i0, len, kk, lane);
+        gf[kk] = global_frag_d(dOb, p.ldq, i0, len, kk, lane);
+    }
+    const int i = i0 + (lane & 31);  // this lane's query (accumulator column)
+    const bool i_ok = i < len;
+    const float lse2 = i_ok ? p.LSE[(long long)(seq_start + i) * p.Hq + h] * kLog2e : 0.f;
+    const float del = i_ok ? p.delta[(long long)(seq_start + i) * p.Hq + h] : 0.f;
+    f32x16 dQ[4];
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) dQ[n][e] = 0.f;
+
+    // key tiles 0 .. last tile that holds a key <= the work-group's last query
+    const int last_q = min(qb * 128 + 127, len - 1);
+    const int n_it = last_q / kTileRows + 1;
+    const float sl2 = p.scale * kLog2e;
+
+    auto issue = [&](int it) {
+        const int row_first = it * kTileRows, rows_valid = len - row_first;
+        const uint32_t st = lds0 + (uint32_t)(it & 1) * kStageBytes;
+        issue_rows_tile(p.K + (long long)(seq_start + row_first) * p.ldk + kv * kD, p.ldk, rows_valid, st, wave, lane);
+        issue_rows_tile(p.V + (long long)(seq_start + row_first) * p.ldk + kv * kD, p.ldk, rows_valid, st + kTileBytes, wave, lane);
+    };
+
+    issue(0);
+    for (int it = 0; it < n_it; ++it) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (it + 1 < n_it) issue(it + 1);
+        const char* tk = smem + (it & 1) * kStageBytes;
+        const char* tv = tk + kTileBytes;
+#pragma unroll
+        for (int jb = 0; jb < 2; ++jb) {
+            const int j0 = it * kTileRows + jb * 32;
+            if (j0 > i0 + 31 || j0 >= len) continue;  // wholly above the diagonal
+            f32x16 St, dPt;  // transposed: rows = keys, columns = queries
+#pragma unroll
+            for (int e = 0; e < 16; ++e) St[e] = dPt[e] = 0.f;
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) {
+                St = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tile_frag_d(tk, jb * 32, kk, lane), qf[kk], St, 0, 0, 0);
+                dPt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tile_frag_d(tv, jb * 32, kk, lane), gf[kk], dPt, 0, 0, 0);
+            }
+            const bool need_mask = (j0 + 31 > i0);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int j = j0 + 8 * (e >> 2) + 4 * half + (e & 3);
+                float pr = exp2f(St[e] * sl2 - lse2);
+                if (!i_ok || (need_mask && j > i)) pr = 0.f;
+                dPt[e] = pr * (dPt[e] - del);
+            }
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                // left operand dS[i][j]: row i = lane&31 (this lane's query), k <-> key rows of the accumulator
+                const bf16x8 dsf = pack8(dPt, ks);
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb)
+                    dQ[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf, tile_frag_rows(tk, jb * 32, ks, nb, lane), dQ[nb], 0, 0, 0);
+            }
+        }
+    }
+
+    __bf16* dQb = p.dQ + (long long)seq_start * p.ldo + h * kD;
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int ii = i0 + 8 * (e >> 2) + 4 * half + (e & 3);
+            if (ii < len) dQb[(long long)ii * p.ldo + nb * 32 + (lane & 31)] = (__bf16)(dQ[nb][e] * p.scale);
+        }
+}
+
+bool attn_mfma_supported(const AttnArgs& a) {
+    return a.dtype == ALCH_BF16 && a.D == kD && a.T > 0 && a.ld_dqkv % 8 == 0 && aligned16(a.Q) && aligned16(a.K) &&
+           aligned16(a.V) && aligned16(a.dO);
+}
+
+int launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t stream) {
+    AttnMfmaParams p;
+    p.Q = (const __bf16*)a.Q; p.K = (const __bf16*)a.K; p.V = (const __bf16*)a.V; p.dO = (const __bf16*)a.dO;
+    p.LSE = a.LSE; p.delta = a.delta;
+    p.dQ = (__bf16*)a.dQ; p.dK = (__bf16*)a.dK; p.dV = (__bf16*)a.dV;
+    p.cu = a.cu_seqlens; p.Hq = a.Hq; p.Hkv = a.Hkv;
+    p.ldq = (long long)a.Hq * a.D; p.ldk = (long long)a.Hkv * a.D; p.ldo = a.ld_dqkv;
+    p.scale = 1.0f / sqrtf((float)a.D);
+    const int nb = ceil_div(a.max_seqlen, 128);
+    if (nb <= 0 || a.n_seqs <= 0) return ALCH_OK;
+    k_attn_bwd_dkv_mfma<<<dim3(nb, a.Hkv, a.n_seqs), 256, 0, stream>>>(p);
+    k_attn_bwd_dq_mfma<<<dim3(nb, a.Hq, a.n_seqs), 256, 0, stream>>>(p);
+    ALCH_HIP_TRY(hipGetLastError());
+    return ALCH_OK;
+}
 
 int launch_attn_fwd(alch_dtype dt, const void* Q, const void* K, const void* V, void* O, float* LSE, int T,
                     int n_seqs, int max_seqlen, const int* cu_seqlens, const int* cu_seqlens_host, int Hq,

@@ -70,7 +70,8 @@ def test_tiny_ragged_gqa(dtype):
     compare(run_gpu(shp, dtype, cu, W, rec, dY), ref, dtype)
 
 
-@pytest.mark.parametrize("shape_name,lens", [("medium", [300, 1, 257, 64]), ("medium64", [130, 200, 77])])
+@pytest.mark.parametrize("shape_name,lens", [("medium", [300, 1, 257, 64]), ("medium64", [130, 200, 77]),
+                                             ("medium", [715, 128, 33])])
 def test_medium_bf16_several_tiles_and_ragged_tail(shape_name, lens):
     # T is not a multiple of any tile size; several 256-wide tiles in every GEMM dimension
     cu = synth.ragged_cu(lens)
