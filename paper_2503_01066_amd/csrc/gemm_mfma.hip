@@ -30,8 +30,10 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 #define ALCH_LDS(p) ((__attribute__((address_space(3))) void*)(p))
 
-static constexpr int BM = 256, BN = 256, BK = 64;
-static constexpr int kOperandStageBytes = 256 * BK * 2;  // 32 KB
+static constexpr int BM = 256, BN = 256, BK = 32;
+static constexpr int kStages = 5;                        // 5 x 32 KB = the whole 160 KB LDS
+static constexpr int kOperandStageBytes = 256 * BK * 2;  // 16 KB per operand per stage
+static constexpr int kLoadsPerTile = 8;                  // direct-to-LDS instructions per wave per k-tile (A + B)
 static constexpr uint32_t kOobOffset = 0x80000000u;      // >= any num_records we set
 static constexpr uint32_t kMaxRecords = 0x80000000u;
 static constexpr int kGroupM = 4;                        // tile rows per raster band
@@ -77,29 +79,28 @@ __device__ __forceinline__ void dma16(i32x4 r, uint32_t lds_addr, uint32_t voff)
                  : "memory", "m0");
 }
 
-// Per-lane byte offsets (relative to the tile origin) of the 8 direct-to-LDS loads a wave
-// issues for one operand tile.  LDS slot s (16-byte units) = (wave*8 + j)*64 + lane.
-//   k-major tile [256 rows][64 k]: slot = row*8 + (c ^ ((row>>1)&7)), c = 16-byte chunk in the row
-//   mn-major tile [64 k][256 cols]: slot = k*32 + (c ^ (4*(k&3)))
+// Per-lane byte offsets (relative to the tile origin) of the 4 direct-to-LDS loads a wave
+// issues for one operand tile.  LDS slot s (16-byte units) = (wave*4 + j)*64 + lane.
+//   k-major tile [256 rows][32 k]: slot = row*4 + (c ^ ((row>>2)&3)), c = 16-byte chunk in the row
+//   mn-major tile [32 k][256 cols]: slot = k*32 + (c ^ (4*(k&3)))
 template <bool KMAJOR>
-__device__ __forceinline__ void tile_offsets(uint32_t (&voff)[8], int wave, int lane, long long ld,
-                                             int rows_valid /*k-major: valid rows*/, int cols_valid /*mn-major: valid cols*/) {
+__device__ __forceinline__ void tile_offsets(uint32_t (&voff)[4], int wave, int lane, long long ld, int valid) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int s = (wave * 8 + j) * 64 + lane;
+    for (int j = 0; j < 4; ++j) {
+        const int s = (wave * 4 + j) * 64 + lane;
         if (KMAJOR) {
-            const int row = s >> 3, c = (s & 7) ^ ((row >> 1) & 7);
-            voff[j] = row < rows_valid ? (uint32_t)((row * ld + c * 8) * 2) : kOobOffset;
+            const int row = s >> 2, c = (s & 3) ^ ((row >> 2) & 3);
+            voff[j] = row < valid ? (uint32_t)((row * ld + c * 8) * 2) : kOobOffset;
         } else {
             const int k = s >> 5, c = (s & 31) ^ (4 * (k & 3));
-            voff[j] = c * 8 < cols_valid ? (uint32_t)((k * ld + c * 8) * 2) : kOobOffset;
+            voff[j] = c * 8 < valid ? (uint32_t)((k * ld + c * 8) * 2) : kOobOffset;
         }
     }
 }
 
-__device__ __forceinline__ void issue_tile(i32x4 r, uint32_t stage_addr, int wave, const uint32_t (&voff)[8]) {
+__device__ __forceinline__ void issue_tile(i32x4 r, uint32_t stage_addr, int wave, const uint32_t (&voff)[4]) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) dma16(r, stage_addr + (uint32_t)(wave * 8 + j) * 1024u, voff[j]);
+    for (int j = 0; j < 4; ++j) dma16(r, stage_addr + (uint32_t)(wave * 4 + j) * 1024u, voff[j]);
 }
 
 // Fragment (8 consecutive-k bf16 per lane for one 32-wide block of rows/cols) from an LDS tile.
@@ -107,8 +108,8 @@ template <bool KMAJOR>
 __device__ __forceinline__ bf16x8 read_frag(const char* stage, int idx0 /*first row/col of the 32-block*/, int kk, int lane) {
     if (KMAJOR) {
         const int row = idx0 + (lane & 31);
-        const int c = (kk * 2 + (lane >> 5)) ^ ((row >> 1) & 7);
-        return *reinterpret_cast<const bf16x8*>(stage + row * 128 + c * 16);
+        const int c = (kk * 2 + (lane >> 5)) ^ ((row >> 2) & 3);
+        return *reinterpret_cast<const bf16x8*>(stage + row * 64 + c * 16);
     } else {
         const int g = lane >> 4, i = lane & 15;
         const int col = idx0 + (g & 1) * 16 + 4 * (i & 3);
@@ -122,21 +123,24 @@ __device__ __forceinline__ bf16x8 read_frag(const char* stage, int idx0 /*first 
     }
 }
 
+struct Frags {
+    bf16x8 a[4], b[4];
+};
+
 template <bool AK, bool BKM>
-__device__ __forceinline__ void compute_stage(const char* sa, const char* sb, int wm, int wn, int lane, f32x16 (&acc)[4][4]) {
+__device__ __forceinline__ void read_frags(Frags& f, const char* sa, const char* sb, int wm, int wn, int kk, int lane) {
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-        bf16x8 af[4], bfr[4];
+    for (int i = 0; i < 4; ++i) f.a[i] = read_frag<AK>(sa, wm * 128 + i * 32, kk, lane);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) af[i] = read_frag<AK>(sa, wm * 128 + i * 32, kk, lane);
+    for (int i = 0; i < 4; ++i) f.b[i] = read_frag<BKM>(sb, wn * 128 + i * 32, kk, lane);
+}
+
+__device__ __forceinline__ void mfma_block(const Frags& f, f32x16 (&acc)[4][4]) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) bfr[i] = read_frag<BKM>(sb, wn * 128 + i * 32, kk, lane);
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-    }
+        for (int j = 0; j < 4; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
 }
 
 __device__ __forceinline__ float bf2f(__bf16 v) { return (float)v; }
@@ -151,26 +155,28 @@ template <typename F> __device__ __forceinline__ void static_for4(F&& f) {
 
 template <bool AK, bool BKM>
 __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
-    // [A stage 0 | A stage 1 | B stage 0 | B stage 1], 32 KB each: the stage is an immediate offset
-    __shared__ __attribute__((aligned(1024))) char smem[4 * kOperandStageBytes];
+    // kStages pipeline stages of [A tile 16 KB | B tile 16 KB]
+    __shared__ __attribute__((aligned(1024))) char smem[kStages * 2 * kOperandStageBytes];
     const uint32_t lds0 = (uint32_t)(uintptr_t)ALCH_LDS(smem);
-    constexpr int kAOff = 0, kBOff = 2 * kOperandStageBytes, kStage = kOperandStageBytes;
+    constexpr int kStage = 2 * kOperandStageBytes;
 
     // ---- work-group -> output tile: XCD-contiguous chunks, banded raster inside a chunk
+    // The grid is persistent (one work-group per compute unit): each work-group walks its share of
+    // the tiles, so the stores of one tile drain while the next tile's loads are already in flight.
     const int nt = p.tiles_m * p.tiles_n;
     const int per_xcd = (nt + 7) / 8;
-    const int t = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-    if (t >= nt) return;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    for (int q = blockIdx.x / 8; q < per_xcd; q += gridDim.x / 8) {
+    const int t = (blockIdx.x % 8) * per_xcd + q;
+    if (t >= nt) break;
     const int band_tiles = kGroupM * p.tiles_n;
     const int band = t / band_tiles, in_band = t % band_tiles;
     const int band_rows = min(kGroupM, p.tiles_m - band * kGroupM);
     const int tm = band * kGroupM + in_band % band_rows;
     const int tn = in_band / band_rows;
     const int m0 = tm * BM, n0 = tn * BN;
-
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
 
     f32x16 acc[4][4];
 #pragma unroll
@@ -179,6 +185,9 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+#ifdef ALCH_GEMM_TIMING
+    if (blockIdx.x == 8 && threadIdx.x == 0 && q == blockIdx.x / 8) g_stamps[0] = __builtin_readcyclecounter();
+#endif
 
     for (int seg = 0; seg < p.n_seg; ++seg) {
         const long long lda = p.lda[seg], ldb = p.ldb[seg];
@@ -204,38 +213,93 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
             endb = (const char*)(p.B[seg] + (long long)(K - 1) * ldb + p.N);
             stepb = (long long)BK * ldb * 2;
         }
-        uint32_t va[8], vb[8];
-        tile_offsets<AK>(va, wave, lane, lda, p.M - m0, p.M - m0);
-        tile_offsets<BKM>(vb, wave, lane, ldb, p.N - n0, p.N - n0);
+        uint32_t va[4], vb[4];
+        tile_offsets<AK>(va, wave, lane, lda, p.M - m0);
+        tile_offsets<BKM>(vb, wave, lane, ldb, p.N - n0);
 
-        // all waves are done reading the previous segment's last stage before it is refilled
+        // Loads of the next k-tile go out one instruction at a time between MFMAs (a burst of
+        // eight would hold the wave at the issue stage while the texture path drains).  Past the
+        // last tile the same loads are issued against an empty buffer (they fetch nothing and
+        // write zeros nobody reads), so the outstanding-load count is the same in every iteration.
+        int next_tile = 0;
+        i32x4 ra, rb;
+        auto open_next = [&]() {
+            const bool live = next_tile < nk;
+            ra = make_rsrc(pa, live ? enda - pa : 0);
+            rb = make_rsrc(pb, live ? endb - pb : 0);
+            pa += stepa;
+            pb += stepb;
+            ++next_tile;
+        };
+#define ALCH_DMA_A(stage, j) dma16(ra, lds0 + (stage) * kStage + (uint32_t)(wave * 4 + (j)) * 1024u, va[j])
+#define ALCH_DMA_B(stage, j) dma16(rb, lds0 + (stage) * kStage + kOperandStageBytes + (uint32_t)(wave * 4 + (j)) * 1024u, vb[j])
+#define ALCH_MFMA(F, i, j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(F.b[j], F.a[i], acc[i][j], 0, 0, 0)
+#define ALCH_SB() __builtin_amdgcn_sched_barrier(0)
+#define ALCH_RA(F, st, kk, i) F.a[i] = read_frag<AK>(st, wm * 128 + (i) * 32, kk, lane)
+#define ALCH_RB(F, st, kk, i) F.b[i] = read_frag<BKM>((st) + kOperandStageBytes, wn * 128 + (i) * 32, kk, lane)
+
+        // all waves are done with the previous segment's stages before they are refilled
         __syncthreads();
-        issue_tile(make_rsrc(pa, enda - pa), lds0 + kAOff, wave, va);
-        issue_tile(make_rsrc(pb, endb - pb), lds0 + kBOff, wave, vb);
-        for (int kt = 0; kt < nk; kt += 2) {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-            if (kt + 1 < nk) {
-                pa += stepa;
-                pb += stepb;
-                issue_tile(make_rsrc(pa, enda - pa), lds0 + kAOff + kStage, wave, va);
-                issue_tile(make_rsrc(pb, endb - pb), lds0 + kBOff + kStage, wave, vb);
-            }
-            compute_stage<AK, BKM>(smem + kAOff, smem + kBOff, wm, wn, lane, acc);
-            if (kt + 1 >= nk) break;
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-            if (kt + 2 < nk) {
-                pa += stepa;
-                pb += stepb;
-                issue_tile(make_rsrc(pa, enda - pa), lds0 + kAOff, wave, va);
-                issue_tile(make_rsrc(pb, endb - pb), lds0 + kBOff, wave, vb);
-            }
-            compute_stage<AK, BKM>(smem + kAOff + kStage, smem + kBOff + kStage, wm, wn, lane, acc);
+#pragma unroll
+        for (int s = 0; s < kStages; ++s) {
+            open_next();
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { ALCH_DMA_A(s, j); ALCH_DMA_B(s, j); }
         }
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoadsPerTile * (kStages - 1)) : "memory");
+        __syncthreads();
+        Frags f0, f1;
+        read_frags<AK, BKM>(f0, smem, smem + kOperandStageBytes, wm, wn, 0, lane);
+#ifdef ALCH_GEMM_TIMING
+        if (blockIdx.x == 8 && threadIdx.x == 0 && q == blockIdx.x / 8) g_stamps[1] = __builtin_readcyclecounter();
+#endif
+        for (int kt = 0; kt < nk; kt += kStages) {
+#pragma unroll
+            for (int s = 0; s < kStages; ++s) {
+                if (kt + s < nk) {
+                    const char* st = smem + s * kStage;
+                    const char* stn = smem + ((s + 1) % kStages) * kStage;
+                    // ---- first half: MFMAs on k 0..15 of this stage, fragment reads for k 16..31
+                    ALCH_SB();
+                    ALCH_RA(f1, st, 1, 0); ALCH_RA(f1, st, 1, 1); ALCH_MFMA(f0, 0, 0); ALCH_MFMA(f0, 0, 1); ALCH_SB();
+                    ALCH_RA(f1, st, 1, 2); ALCH_RA(f1, st, 1, 3); ALCH_MFMA(f0, 0, 2); ALCH_MFMA(f0, 0, 3); ALCH_SB();
+                    ALCH_RB(f1, st, 1, 0); ALCH_RB(f1, st, 1, 1); ALCH_MFMA(f0, 1, 0); ALCH_MFMA(f0, 1, 1); ALCH_SB();
+                    ALCH_RB(f1, st, 1, 2); ALCH_RB(f1, st, 1, 3); ALCH_MFMA(f0, 1, 2); ALCH_MFMA(f0, 1, 3); ALCH_SB();
+                    ALCH_MFMA(f0, 2, 0); ALCH_MFMA(f0, 2, 1); ALCH_MFMA(f0, 2, 2); ALCH_MFMA(f0, 2, 3);
+                    ALCH_MFMA(f0, 3, 0); ALCH_MFMA(f0, 3, 1); ALCH_MFMA(f0, 3, 2); ALCH_MFMA(f0, 3, 3);
+                    ALCH_SB();
+                    // k-tile kt+s+1 has landed (this wave's share), and this wave's reads of stage s are done
+                    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(kLoadsPerTile * (kStages - 2)) : "memory");
+                    __syncthreads();
+                    // ---- second half: MFMAs on k 16..31, refill of stage s, fragment reads of the next stage
+                    open_next();
+                    ALCH_SB();
+                    ALCH_DMA_A(s, 0); ALCH_RA(f0, stn, 0, 0); ALCH_RA(f0, stn, 0, 1); ALCH_MFMA(f1, 0, 0); ALCH_MFMA(f1, 0, 1); ALCH_SB();
+                    ALCH_DMA_A(s, 1); ALCH_RA(f0, stn, 0, 2); ALCH_RA(f0, stn, 0, 3); ALCH_MFMA(f1, 0, 2); ALCH_MFMA(f1, 0, 3); ALCH_SB();
+                    ALCH_DMA_A(s, 2); ALCH_RB(f0, stn, 0, 0); ALCH_MFMA(f1, 1, 0); ALCH_MFMA(f1, 1, 1); ALCH_SB();
+                    ALCH_DMA_A(s, 3); ALCH_RB(f0, stn, 0, 1); ALCH_MFMA(f1, 1, 2); ALCH_MFMA(f1, 1, 3); ALCH_SB();
+                    ALCH_DMA_B(s, 0); ALCH_RB(f0, stn, 0, 2); ALCH_MFMA(f1, 2, 0); ALCH_MFMA(f1, 2, 1); ALCH_SB();
+                    ALCH_DMA_B(s, 1); ALCH_RB(f0, stn, 0, 3); ALCH_MFMA(f1, 2, 2); ALCH_MFMA(f1, 2, 3); ALCH_SB();
+                    ALCH_DMA_B(s, 2); ALCH_MFMA(f1, 3, 0); ALCH_MFMA(f1, 3, 1); ALCH_SB();
+                    ALCH_DMA_B(s, 3); ALCH_MFMA(f1, 3, 2); ALCH_MFMA(f1, 3, 3); ALCH_SB();
+                }
+            }
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#undef ALCH_DMA_A
+#undef ALCH_DMA_B
+#undef ALCH_MFMA
+#undef ALCH_SB
+#undef ALCH_RA
+#undef ALCH_RB
     }
+#ifdef ALCH_GEMM_TIMING
+    if (blockIdx.x == 8 && threadIdx.x == 0 && q == blockIdx.x / 8) g_stamps[2] = __builtin_readcyclecounter();
+#endif
 
-    // ---- epilogue: lane holds column n = n0 + wn*128 + j*32 + (lane&31), rows 8b + 4(lane>>5) + r
+    // ---- epilogue.  The MFMAs were issued with the operand roles swapped, so block (i, j) holds
+    // the transposed 32x32 result: this lane owns output row m = .. + i*32 + (lane&31) and, in
+    // registers 4b..4b+3, the four consecutive columns n = .. + j*32 + 8b + 4*(lane>>5) + 0..3.
     int oseg = 0;
 #pragma unroll
     for (int s = 1; s < 3; ++s)
@@ -244,51 +308,92 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
     const long long ldc = p.ldc[oseg];
     const int mrel0 = m0 - p.m_begin[oseg];
     const int m_end = (oseg + 1 < p.n_out ? p.m_begin[oseg + 1] : p.M);
+    const int half = lane >> 5;
 
-    // (the row-block loop is expanded through a template so that every accumulator index is a
-    // compile-time constant and the accumulators stay in registers)
-    if (p.epilogue == kEpiSwigluBwd) {
+    if (!p.accumulate) {
+        // Stage the wave's 128x128 bf16 result through the (now idle) pipeline LDS so that it leaves
+        // as whole 256-byte row segments: 8-byte LDS writes, 16-byte LDS reads, 16-byte global stores.
+        constexpr int kRowStride = 272;  // 256 + 16: rows stay 16-byte aligned, reads conflict-free
+        char* stage = smem + wave * (128 * kRowStride);
+        __syncthreads();  // every wave's loads have landed and every wave is done reading the pipeline
         static_for4([&](auto ic) {
             constexpr int i = decltype(ic)::value;
+            char* row = stage + (i * 32 + (lane & 31)) * kRowStride;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int n = n0 + wn * 128 + j * 32 + (lane & 31);
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int m = m0 + wm * 128 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                    if (m < p.M && n < p.N) {
-                        const float g = bf2f(p.G[(long long)m * p.ldgu + n]);
-                        const float u = bf2f(p.U[(long long)m * p.ldgu + n]);
-                        const float d = bf2f((__bf16)acc[i][j][e]);  // dAct is a bf16 tensor of the method
+                for (int b = 0; b < 4; ++b) {
+                    bf16x4 o;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) o[r] = (__bf16)acc[i][j][4 * b + r];
+                    *reinterpret_cast<bf16x4*>(row + (j * 32 + 8 * b + 4 * half) * 2) = o;
+                }
+        });
+        // (a wave reads back only what it wrote itself: no barrier needed in between)
+        const int n = n0 + wn * 128 + (lane & 15) * 8;
+        if (p.epilogue == kEpiSwigluBwd) {
+#pragma unroll 4
+            for (int qq = 0; qq < 32; ++qq) {
+                const int rl = 4 * qq + (lane >> 4);
+                const int m = m0 + wm * 128 + rl;
+                const bf16x8 d8 = *reinterpret_cast<const bf16x8*>(stage + rl * kRowStride + (lane & 15) * 16);
+                if (m < p.M && n < p.N) {
+                    const bf16x8 g8 = *reinterpret_cast<const bf16x8*>(p.G + (long long)m * p.ldgu + n);
+                    const bf16x8 u8 = *reinterpret_cast<const bf16x8*>(p.U + (long long)m * p.ldgu + n);
+                    bf16x8 dg8, du8, a8;
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) {
+                        const float g = bf2f(g8[r]), u = bf2f(u8[r]), d = bf2f(d8[r]);
                         const float sg = 1.f / (1.f + __expf(-g));
                         const float silu = g * sg;
-                        C[(long long)m * ldc + n] = (__bf16)(d * u * sg * (1.f + g * (1.f - sg)));
-                        C[(long long)m * ldc + p.N + n] = (__bf16)(d * silu);
-                        if (p.act_out) p.act_out[(long long)m * p.N + n] = (__bf16)(silu * u);
+                        dg8[r] = (__bf16)(d * u * sg * (1.f + g * (1.f - sg)));
+                        du8[r] = (__bf16)(d * silu);
+                        a8[r] = (__bf16)(silu * u);
                     }
+                    *reinterpret_cast<bf16x8*>(C + (long long)m * ldc + n) = dg8;
+                    *reinterpret_cast<bf16x8*>(C + (long long)m * ldc + p.N + n) = du8;
+                    if (p.act_out) *reinterpret_cast<bf16x8*>(p.act_out + (long long)m * p.N + n) = a8;
                 }
             }
-        });
-        return;
-    }
-
-    static_for4([&](auto ic) {
-        constexpr int i = decltype(ic)::value;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int n = n0 + wn * 128 + j * 32 + (lane & 31);
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int ml = wm * 128 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                if (m0 + ml < m_end && n < p.N) {
-                    __bf16* dst = C + (long long)(mrel0 + ml) * ldc + n;
-                    float v = acc[i][j][e];
-                    if (p.accumulate) v += bf2f(*dst);
-                    *dst = (__bf16)v;
-                }
+        } else {
+#pragma unroll 8
+            for (int qq = 0; qq < 32; ++qq) {
+                const int rl = 4 * qq + (lane >> 4);
+                const int ml = wm * 128 + rl;
+                const bf16x8 d8 = *reinterpret_cast<const bf16x8*>(stage + rl * kRowStride + (lane & 15) * 16);
+                if (m0 + ml < m_end && n < p.N) *reinterpret_cast<bf16x8*>(C + (long long)(mrel0 + ml) * ldc + n) = d8;
             }
         }
-    });
+    } else {
+        // accumulate: C = round(acc + C) with the sum in fp32, straight from the accumulators
+        static_for4([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            const int ml = wm * 128 + i * 32 + (lane & 31);
+            if (m0 + ml < m_end) {
+                __bf16* row = C + (long long)(mrel0 + ml) * ldc;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const int nn = n0 + wn * 128 + j * 32 + 8 * b + 4 * half;
+                        if (nn < p.N) {
+                            const bf16x4 old = *reinterpret_cast<const bf16x4*>(row + nn);
+                            bf16x4 o;
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) o[r] = (__bf16)(acc[i][j][4 * b + r] + bf2f(old[r]));
+                            *reinterpret_cast<bf16x4*>(row + nn) = o;
+                        }
+                    }
+            }
+        });
+    }
+#ifdef ALCH_GEMM_TIMING
+    if (blockIdx.x == 8 && threadIdx.x == 0 && q == blockIdx.x / 8) g_stamps[3] = __builtin_readcyclecounter();
+#endif
+    }  // tiles of this work-group
+#ifdef ALCH_GEMM_TIMING
+    if (blockIdx.x == 8 && threadIdx.x == 0) g_stamps[4] = __builtin_readcyclecounter();
+#endif
 }
 
 bool gemm_mfma_supported(const GemmDesc& d) {
@@ -298,17 +403,19 @@ bool gemm_mfma_supported(const GemmDesc& d) {
     for (int s = 0; s < d.n_seg; ++s) {
         const GemmSeg& g = d.seg[s];
         if (g.K <= 0 || !aligned16(g.A) || !aligned16(g.B) || g.lda % 8 || g.ldb % 8) return false;
-        if ((d.a_kmajor || d.b_kmajor) && g.K % BK) return false;  // no k tail on k-major operands
+        if ((d.a_kmajor || d.b_kmajor) && g.K % 64) return false;  // no k tail on k-major operands
         if (!d.a_kmajor && d.M % 8) return false;
         if (!d.b_kmajor && d.N % 8) return false;
+        if (d.N % 8) return false;  // 16-byte output stores
         if (g.lda > (1 << 21) || g.ldb > (1 << 21)) return false;  // tile extent must stay below 2 GiB
     }
     for (int o = 0; o < d.n_out; ++o) {
+        if (d.out[o].ldc % 8 || !aligned16(d.out[o].C)) return false;
         if (d.out[o].m_begin % BM) return false;
         if (o == 0 && d.out[o].m_begin != 0) return false;
         if (o > 0 && d.out[o].m_begin <= d.out[o - 1].m_begin) return false;
     }
-    if (d.epilogue == kEpiSwigluBwd && (d.n_out != 1 || d.accumulate)) return false;
+    if (d.epilogue == kEpiSwigluBwd && (d.n_out != 1 || d.accumulate || d.ldgu % 8 || (d.act_out && !aligned16(d.act_out)) || !aligned16(d.G) || !aligned16(d.U))) return false;
     return true;
 }
 
@@ -339,7 +446,14 @@ int launch_gemm_mfma(const GemmDesc& d, hipStream_t stream) {
     p.ldgu = d.ldgu;
     p.act_out = static_cast<__bf16*>(d.act_out);
     const int nt = p.tiles_m * p.tiles_n;
-    const int grid = ceil_div(nt, 8) * 8;
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0, v = 0;
+        ALCH_HIP_TRY(hipGetDevice(&dev));
+        ALCH_HIP_TRY(hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev));
+        n_cu = v > 8 ? v / 8 * 8 : 8;
+    }
+    const int grid = ceil_div(nt, 8) * 8 < n_cu ? ceil_div(nt, 8) * 8 : n_cu;
     if (d.a_kmajor && d.b_kmajor)
         k_gemm_mfma<true, true><<<grid, 256, 0, stream>>>(p);
     else if (d.a_kmajor && !d.b_kmajor)

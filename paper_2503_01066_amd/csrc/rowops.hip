@@ -57,7 +57,7 @@ int launch_rmsnorm_fwd(alch_dtype dt, const void* X, const void* g, void* H, int
 static constexpr int kNormBwdBlocks = 1024;
 static constexpr int kNormMaxCols = 32;  // columns per thread: width <= 8192
 
-int rmsnorm_bwd_blocks(int T) { return T < kNormBwdBlocks ? (T > 0 ? T : 1) : kNormBwdBlocks; }
+int rmsnorm_bwd_blocks(int T);
 
 template <typename T>
 __global__ __launch_bounds__(256) void k_rmsnorm_bwd(const T* __restrict__ dH, const T* __restrict__ X,
@@ -109,25 +109,150 @@ __global__ __launch_bounds__(256) void k_rmsnorm_bwd(const T* __restrict__ dH, c
     }
 }
 
+// bf16 fast path: one wavefront per row, 16-byte accesses, no barrier inside the row loop.
+// Lane l owns the 8-column chunks (k*64 + l), k < NC.
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+static constexpr int kNormFastBlocks = 512;
+
+template <int NC>
+__global__ __launch_bounds__(256) void k_rmsnorm_bwd_bf16(const __bf16* __restrict__ dH, const __bf16* __restrict__ X,
+                                                          const __bf16* __restrict__ g, const __bf16* __restrict__ resid,
+                                                          const uint8_t* __restrict__ resid_mask, __bf16* __restrict__ dX,
+                                                          float* __restrict__ partial, int Trows, int width, float eps) {
+    __shared__ float sred[NC * 512];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    bf16x8_t gv[NC];
+    float dgp[NC][8];
+#pragma unroll
+    for (int k = 0; k < NC; ++k) {
+        const int col = (k * 64 + lane) * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { gv[k][e] = (__bf16)0.f; dgp[k][e] = 0.f; }
+        if (col < width) gv[k] = *reinterpret_cast<const bf16x8_t*>(g + col);
+    }
+    const float inv_w = 1.f / (float)width;
+    for (long long row = (long long)blockIdx.x * 4 + wave; row < Trows; row += (long long)gridDim.x * 4) {
+        bf16x8_t xv[NC], dv[NC];
+#pragma unroll
+        for (int k = 0; k < NC; ++k) {
+            const int col = (k * 64 + lane) * 8;
+            if (col < width) {
+                xv[k] = *reinterpret_cast<const bf16x8_t*>(X + row * width + col);
+                dv[k] = *reinterpret_cast<const bf16x8_t*>(dH + row * width + col);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) { xv[k][e] = (__bf16)0.f; dv[k][e] = (__bf16)0.f; }
+            }
+        }
+        float ss = 0.f, dot = 0.f;
+#pragma unroll
+        for (int k = 0; k < NC; ++k)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float x = (float)xv[k][e];
+                ss += x * x;
+                dot += (float)gv[k][e] * (float)dv[k][e] * x;
+            }
+        ss = wave_sum(ss);
+        dot = wave_sum(dot);
+        const float r = rsqrtf(ss * inv_w + eps);
+        const float coef = r * r * r * inv_w * dot;
+        const bool keep = resid && !(resid_mask && resid_mask[row] == 0);
+#pragma unroll
+        for (int k = 0; k < NC; ++k) {
+            const int col = (k * 64 + lane) * 8;
+            if (col < width) {
+                bf16x8_t rv, ov;
+                if (keep) rv = *reinterpret_cast<const bf16x8_t*>(resid + row * width + col);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float x = (float)xv[k][e], d = (float)dv[k][e];
+                    float v = r * (float)gv[k][e] * d - x * coef;
+                    if (keep) v += (float)rv[e];
+                    ov[e] = (__bf16)v;
+                    dgp[k][e] += d * x * r;
+                }
+                *reinterpret_cast<bf16x8_t*>(dX + row * width + col) = ov;
+            }
+        }
+    }
+    if (!partial) return;
+    // fold the four waves' column sums in a fixed order, then one row of partials per block
+    for (int w = 1; w < 4; ++w) {
+        __syncthreads();
+        if (wave == w)
+#pragma unroll
+            for (int k = 0; k < NC; ++k)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) sred[(k * 8 + e) * 64 + lane] = dgp[k][e];
+        __syncthreads();
+        if (wave == 0)
+#pragma unroll
+            for (int k = 0; k < NC; ++k)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dgp[k][e] += sred[(k * 8 + e) * 64 + lane];
+    }
+    if (wave == 0)
+#pragma unroll
+        for (int k = 0; k < NC; ++k) {
+            const int col = (k * 64 + lane) * 8;
+            if (col < width)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) partial[(long long)blockIdx.x * width + col + e] = dgp[k][e];
+        }
+}
+
+// dg[c] (+)= sum over nblk partial rows; 64 columns per block, 16 row groups folded through LDS
 template <typename T>
-__global__ __launch_bounds__(256) void k_colsum_finish(const float* __restrict__ partial, int nblk, int width,
-                                                       T* __restrict__ dg, int accumulate) {
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= width) return;
+__global__ __launch_bounds__(1024) void k_colsum_finish_wide(const float* __restrict__ partial, int nblk, int width,
+                                                             T* __restrict__ dg, int accumulate) {
+    __shared__ float red[16][64];
+    const int c = blockIdx.x * 64 + (threadIdx.x & 63), rg = threadIdx.x >> 6;
     float s = 0.f;
-    for (int b = 0; b < nblk; ++b) s += partial[(long long)b * width + c];
-    if (accumulate) s += ldf(dg + c);
-    stf(dg + c, s);
+    if (c < width)
+        for (int b = rg; b < nblk; b += 16) s += partial[(long long)b * width + c];
+    red[rg][threadIdx.x & 63] = s;
+    __syncthreads();
+    if (rg == 0 && c < width) {
+        float t = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) t += red[i][threadIdx.x & 63];
+        if (accumulate) t += ldf(dg + c);
+        stf(dg + c, t);
+    }
+}
+
+int rmsnorm_bwd_blocks(int T) {
+    const int n = T < kNormBwdBlocks ? (T > 0 ? T : 1) : kNormBwdBlocks;
+    return n > kNormFastBlocks ? n : kNormFastBlocks;  // scratch rows: enough for either kernel
 }
 
 template <typename T>
 static int rmsnorm_bwd_t(const void* dH, const void* X, const void* g, const void* resid, const uint8_t* resid_mask,
                          void* dX, void* dg, int accumulate, float* partial, int T_, int width, float eps,
                          hipStream_t stream) {
-    const int nblk = rmsnorm_bwd_blocks(T_);
+    const int nblk = T_ < kNormBwdBlocks ? T_ : kNormBwdBlocks;
     k_rmsnorm_bwd<T><<<nblk, 256, 0, stream>>>((const T*)dH, (const T*)X, (const T*)g, (const T*)resid, resid_mask,
                                                 (T*)dX, dg ? partial : nullptr, T_, width, eps);
-    if (dg) k_colsum_finish<T><<<ceil_div(width, 256), 256, 0, stream>>>(partial, nblk, width, (T*)dg, accumulate);
+    if (dg) k_colsum_finish_wide<T><<<ceil_div(width, 64), 1024, 0, stream>>>(partial, nblk, width, (T*)dg, accumulate);
+    ALCH_HIP_TRY(hipGetLastError());
+    return ALCH_OK;
+}
+
+static int rmsnorm_bwd_bf16_fast(const void* dH, const void* X, const void* g, const void* resid,
+                                 const uint8_t* resid_mask, void* dX, void* dg, int accumulate, float* partial, int T_,
+                                 int width, float eps, hipStream_t stream) {
+    const int nblk = ceil_div(T_, 4) < kNormFastBlocks ? ceil_div(T_, 4) : kNormFastBlocks;
+    float* part = dg ? partial : nullptr;
+#define ALCH_NORM_BWD(NC)                                                                                          \
+    k_rmsnorm_bwd_bf16<NC><<<nblk, 256, 0, stream>>>((const __bf16*)dH, (const __bf16*)X, (const __bf16*)g,         \
+                                                     (const __bf16*)resid, resid_mask, (__bf16*)dX, part, T_, width, eps)
+    if (width <= 1024) ALCH_NORM_BWD(2);
+    else if (width <= 2048) ALCH_NORM_BWD(4);
+    else if (width <= 4096) ALCH_NORM_BWD(8);
+    else ALCH_NORM_BWD(16);
+#undef ALCH_NORM_BWD
+    if (dg) k_colsum_finish_wide<__bf16><<<ceil_div(width, 64), 1024, 0, stream>>>(partial, nblk, width, (__bf16*)dg, accumulate);
     ALCH_HIP_TRY(hipGetLastError());
     return ALCH_OK;
 }
@@ -140,13 +265,16 @@ int launch_rmsnorm_bwd(alch_dtype dt, const void* dH, const void* X, const void*
         // no rows: the gain gradient is zero (or unchanged when accumulating)
         if (dg) {
             if (dt == ALCH_BF16)
-                k_colsum_finish<__bf16><<<ceil_div(width, 256), 256, 0, stream>>>(partial, 0, width, (__bf16*)dg, accumulate);
+                k_colsum_finish_wide<__bf16><<<ceil_div(width, 64), 1024, 0, stream>>>(partial, 0, width, (__bf16*)dg, accumulate);
             else
-                k_colsum_finish<float><<<ceil_div(width, 256), 256, 0, stream>>>(partial, 0, width, (float*)dg, accumulate);
+                k_colsum_finish_wide<float><<<ceil_div(width, 64), 1024, 0, stream>>>(partial, 0, width, (float*)dg, accumulate);
             ALCH_HIP_TRY(hipGetLastError());
         }
         return ALCH_OK;
     }
+    if (dt == ALCH_BF16 && width % 8 == 0 && aligned16(dH) && aligned16(X) && aligned16(g) && aligned16(dX) &&
+        (!resid || aligned16(resid)))
+        return rmsnorm_bwd_bf16_fast(dH, X, g, resid, resid_mask, dX, dg, accumulate, partial, T, width, eps, stream);
     return dt == ALCH_BF16
                ? rmsnorm_bwd_t<__bf16>(dH, X, g, resid, resid_mask, dX, dg, accumulate, partial, T, width, eps, stream)
                : rmsnorm_bwd_t<float>(dH, X, g, resid, resid_mask, dX, dg, accumulate, partial, T, width, eps, stream);
