@@ -232,3 +232,59 @@ def layer_backward_recompute(shape, cu_seqlens, positions, X, W, dY, loss_mask=N
     forward from X and the weights, then back-propagate through what it produced."""
     _, rec = layer_forward(shape, cu_seqlens, positions, X, W)
     return layer_backward_reuse(shape, cu_seqlens, positions, rec, W, dY, loss_mask)
+
+
+def layer_backward_reuse_tail_rows(shape, positions_seq, rec_seq, W, dY_tail):
+    """dX rows of the last m tokens of ONE sequence, from the dY rows of those tokens alone.
+
+    Causality makes this exact: the input gradient of token t depends only on output gradients of
+    tokens i >= t of the same sequence, so the last m rows of dX need the last m rows of dY and
+    nothing else (K and V of all earlier tokens enter through the saved record).  Used to check
+    full-size GPU runs on sampled rows; pinned against layer_backward_reuse on small cases.
+
+    rec_seq: record tensors of the one sequence (n tokens); dY_tail: [m, H]; positions_seq: [n] or
+    None (0..n-1).  Returns dX_tail [m, H].
+    """
+    X, X2, Q, K, V, O, LSE, Gt, U = (np.asarray(rec_seq[k], dtype=np.float64) for k in RECORD_KEYS)
+    n, H = X.shape
+    m = dY_tail.shape[0]
+    a = n - m
+    Hq, Hkv, D = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
+    G = Hq // Hkv
+    pos = np.arange(n, dtype=np.float64) if positions_seq is None else np.asarray(positions_seq, dtype=np.float64)
+    dY = np.asarray(dY_tail, dtype=np.float64)
+
+    sig = _sigmoid(Gt[a:])
+    dAct = dY @ W["Wd"]
+    dG = dAct * U[a:] * sig * (1.0 + Gt[a:] * (1.0 - sig))
+    dU = dAct * Gt[a:] * sig
+    dH2 = dG @ W["Wg"] + dU @ W["Wu"]
+    _, r2 = _rms_norm(X2[a:], W["g2"], shape.rms_eps)
+    dX2n, _ = _rms_norm_backward(dH2, X2[a:], W["g2"], r2)
+    dX2 = dY + dX2n
+    dO = (dX2 @ W["Wo"]).reshape(m, Hq, D)
+
+    Qh, Kh, Vh, Oh = Q.reshape(n, Hq, D), K.reshape(n, Hkv, D), V.reshape(n, Hkv, D), O.reshape(n, Hq, D)
+    delta = np.sum(dO * Oh[a:], axis=-1)
+    dQ = np.zeros((m, Hq, D))
+    dK = np.zeros((m, Hkv, D))
+    dV = np.zeros((m, Hkv, D))
+    scale = 1.0 / np.sqrt(D)
+    # query rows a..n-1 against all keys 0..n-1; key j is visible to query i iff j <= i
+    allowed = np.arange(n)[None, :] <= (a + np.arange(m))[:, None]
+    for h in range(Hq):
+        kv = h // G
+        sc = Qh[a:, h] @ Kh[:, kv].T * scale
+        P = np.where(allowed, np.exp(sc - LSE[a:, h][:, None]), 0.0)
+        dP = dO[:, h] @ Vh[:, kv].T
+        dS = P * (dP - delta[:, h][:, None])
+        dQ[:, h] = dS @ Kh[:, kv] * scale
+        # keys in the tail receive gradient only from tail queries
+        dK[:, kv] += dS[:, a:].T @ Qh[a:, h] * scale
+        dV[:, kv] += P[:, a:].T @ dO[:, h]
+    dQp = _rope(dQ, pos[a:], shape.rope_base, -1).reshape(m, Hq * D)
+    dKp = _rope(dK, pos[a:], shape.rope_base, -1).reshape(m, Hkv * D)
+    dH1 = dQp @ W["Wq"] + dKp @ W["Wk"] + dV.reshape(m, Hkv * D) @ W["Wv"]
+    _, r1 = _rms_norm(X[a:], W["g1"], shape.rms_eps)
+    dXn, _ = _rms_norm_backward(dH1, X[a:], W["g1"], r1)
+    return dX2 + dXn

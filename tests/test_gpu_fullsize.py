@@ -1,0 +1,126 @@
+"""Full-size parity in the launch configuration bench.py times (config 2: one Llama-3-8B-shaped
+layer, bf16, 4 x 2048 tokens), on sampled outputs the oracle can compute one by one, plus a
+full-width / short-batch case checked element by element, plus config-3-sized capture/pack."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as synth
+from helpers import to_dev, to_np, f64, rel_err, oracle_shape, alch_shape
+from oracle import layer_backward_reuse, attention_lse, gather_pack, WEIGHT_KEYS
+from oracle.layer import layer_backward_reuse_tail_rows, _rms_norm, _sigmoid
+
+pytestmark = pytest.mark.gpu
+REC = ("X", "X2", "Q", "K", "V", "O", "G", "U")
+
+
+def gpu_layer(shp, cu, W, rec, dY):
+    import paper_2503_01066_amd as A
+    dW = {k: to_dev(v, "bf16") for k, v in W.items()}
+    drec = {k: to_dev(rec[k], "bf16") for k in REC}
+    drec["LSE"] = torch.from_numpy(rec["LSE"]).cuda()
+    out = A.alch_layer_backward(alch_shape(shp, "bf16"), A.Batch(cu), drec, dW, to_dev(dY, "bf16"))
+    torch.cuda.synchronize()
+    return out
+
+
+def test_llama8b_width_short_batch_elementwise():
+    # every GEMM dimension at its real width (hidden 4096, ffn 14336, 32/8 heads x 128), ragged short batch
+    shp = synth.shape_dict("llama8b")
+    osh = oracle_shape(shp)
+    cu = synth.ragged_cu([150, 41, 129])
+    T = int(cu[-1])
+    W = synth.layer_weights(shp, 0, "bf16")
+    rec = synth.drawn_record(shp, T, 1, "bf16")
+    rec["LSE"] = attention_lse(osh, cu, rec["Q"].astype(np.float64), rec["K"].astype(np.float64)).astype(np.float32)
+    dY = synth.activations(T, shp["hidden"], 2, "bf16", std=0.01)
+    print("oracle ...", flush=True)
+    ref = layer_backward_reuse(osh, cu, None, f64(rec), f64(W), dY.astype(np.float64))
+    print("gpu ...", flush=True)
+    out = gpu_layer(shp, cu, W, rec, dY)
+    for k, v in out.items():
+        e = rel_err(to_np(v), ref[k])
+        assert e <= 2e-2, (k, e)
+
+
+def test_config2_full_size_sampled_outputs():
+    shp = synth.shape_dict("llama8b")
+    osh = oracle_shape(shp)
+    S, B = 2048, 4
+    cu = synth.uniform_cu(B, S)
+    T = B * S
+    H, F = shp["hidden"], shp["ffn"]
+    W = synth.layer_weights(shp, 0, "bf16")
+    rec = synth.drawn_record(shp, T, 1, "bf16")
+    print("lse ...", flush=True)
+    rec["LSE"] = attention_lse(osh, cu, rec["Q"].astype(np.float64), rec["K"].astype(np.float64)).astype(np.float32)
+    dY = synth.activations(T, H, 2, "bf16", std=0.01)
+    print("gpu ...", flush=True)
+    out = gpu_layer(shp, cu, W, rec, dY)
+    W64 = f64(W)
+    rng = np.random.default_rng(3)
+
+    # (a) dX rows of the last tokens of two sequences (exact by causality)
+    m = 24
+    dX = to_np(out["dX"])
+    for s in (0, 3):
+        a, b = s * S, (s + 1) * S
+        seq = {k: rec[k][a:b].astype(np.float64) for k in REC + ("LSE",)}
+        tail = layer_backward_reuse_tail_rows(osh, None, seq, W64, dY[b - m:b].astype(np.float64))
+        e = np.abs(dX[b - m:b] - tail).max() / np.abs(tail).max()
+        assert e <= 2e-2, ("dX tail", s, e)
+
+    # (b) sampled entries of dWd = dY^T (silu(G) * U)
+    dWd = to_np(out["dWd"])
+    G64, U64, dY64 = rec["G"].astype(np.float64), rec["U"].astype(np.float64), dY.astype(np.float64)
+    oo, ii = rng.integers(0, H, 48), rng.integers(0, F, 48)
+    want = np.array([np.sum(dY64[:, o] * (G64[:, i] * _sigmoid(G64[:, i]) * U64[:, i])) for o, i in zip(oo, ii)])
+    scale = np.abs(want).max()
+    assert np.abs(dWd[oo, ii] - want).max() <= 2e-2 * scale
+
+    # (c) sampled entries of dWg, dWu = dG^T H2, dU^T H2 with dAct[:, f] = dY Wd[:, f]
+    X2 = rec["X2"].astype(np.float64)
+    H2, _ = _rms_norm(X2, W64["g2"], osh.rms_eps)
+    dWg, dWu = to_np(out["dWg"]), to_np(out["dWu"])
+    ff, hh = rng.integers(0, F, 12), rng.integers(0, H, 12)
+    wg, wu = [], []
+    for f, h in zip(ff, hh):
+        dAct = dY64 @ W64["Wd"][:, f]
+        sg = _sigmoid(G64[:, f])
+        wg.append(np.sum(dAct * U64[:, f] * sg * (1 + G64[:, f] * (1 - sg)) * H2[:, h]))
+        wu.append(np.sum(dAct * G64[:, f] * sg * H2[:, h]))
+    wg, wu = np.array(wg), np.array(wu)
+    # the bar is relative to the largest entry of the tensor; the samples give a lower bound of it
+    assert np.abs(dWg[ff, hh] - wg).max() <= 2e-2 * max(np.abs(wg).max(), np.abs(dWg).max())
+    assert np.abs(dWu[ff, hh] - wu).max() <= 2e-2 * max(np.abs(wu).max(), np.abs(dWu).max())
+    for k, v in out.items():
+        assert torch.isfinite(v.float()).all(), k
+
+
+def test_config3_sized_capture_pack_one_layer():
+    # 32 prompts with lengths U[256,4096], Bernoulli(0.25) keep mask, 6 streams out of fused buffers
+    import paper_2503_01066_amd as A
+    lens = synth.random_lengths(32, 256, 4096, 0)
+    cu = synth.ragged_cu(lens)
+    T = int(cu[-1])
+    mask = synth.keep_mask(T, 0.25, 1)
+    g = torch.Generator(device="cuda").manual_seed(0)
+    hid = torch.randint(-2 ** 15, 2 ** 15, (T, 4096), generator=g, device="cuda", dtype=torch.int16)
+    qkv = torch.randint(-2 ** 15, 2 ** 15, (T, 6144), generator=g, device="cuda", dtype=torch.int16)
+    gu = torch.randint(-2 ** 15, 2 ** 15, (T, 28672), generator=g, device="cuda", dtype=torch.int16)
+    streams = [hid, qkv[:, :4096], qkv[:, 4096:5120], qkv[:, 5120:], gu[:, :14336], gu[:, 14336:]]
+    kept, cu_kept, status, dsts = A.alch_capture_pack(A.Batch(cu), torch.from_numpy(mask).cuda(), streams)
+    torch.cuda.synchronize()
+    ok, ocu, _ = gather_pack(mask, cu, [])
+    n = len(ok)
+    assert status.cpu().tolist() == [n, 0]
+    assert np.array_equal(kept.cpu().numpy()[:n], ok) and np.array_equal(cu_kept.cpu().numpy(), ocu)
+    # rows: sampled kept rows, each stream compared bit for bit with the source row the oracle index names
+    rows = np.random.default_rng(2).choice(n, 64, replace=False)
+    for s, d in zip(streams, dsts):
+        src_rows = s[torch.from_numpy(ok[rows].astype(np.int64)).cuda()].cpu().numpy()
+        assert np.array_equal(d[torch.from_numpy(rows).cuda()].cpu().numpy(), src_rows)
+    # and every packed row equals its source row (checksum over all rows, on the device)
+    idx = torch.from_numpy(ok.astype(np.int64)).cuda()
+    for s, d in zip(streams, dsts):
+        assert torch.equal(d[:n], s[idx])

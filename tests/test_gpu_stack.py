@@ -1,0 +1,128 @@
+"""GPU parity of alch_stack_backward (cross-entropy head + layer walk) and alch_layer_forward
+against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as synth
+from helpers import TOL, to_dev, to_np, f64, rel_err, oracle_shape, alch_shape
+from oracle import stack_forward, stack_backward_reuse, layer_forward, layer_backward_recompute, WEIGHT_KEYS
+
+pytestmark = pytest.mark.gpu
+REC = ("X", "X2", "Q", "K", "V", "O", "G", "U")
+
+
+def make_stack(shape_name, dtype, cu, L, V, seed, wstd):
+    shp = synth.shape_dict(shape_name)
+    osh = oracle_shape(shp)
+    T = int(cu[-1])
+    Ws = [synth.layer_weights(shp, seed + 10 * l, dtype, std=wstd, gain_std=0.1) for l in range(L)]
+    rng = np.random.default_rng(seed + 1000)
+    X0 = synth.normal(rng, (T, shp["hidden"]), 1.0, dtype)
+    gf = synth.quantize(1.0 + 0.1 * rng.standard_normal(shp["hidden"]).astype(np.float32), dtype)
+    Wlm = synth.normal(rng, (V, shp["hidden"]), wstd, dtype)
+    ids = rng.integers(0, V, T)
+    labels = np.full(T, -1, dtype=np.int32)
+    for s in range(len(cu) - 1):
+        a, b = int(cu[s]), int(cu[s + 1])
+        if b - a > 1:
+            labels[a:b - 1] = ids[a + 1:b]
+    # records: oracle forward in fp64, then rounded to the storage type (what a serving pass would hold)
+    Xf64, recs64 = stack_forward(osh, cu, None, X0.astype(np.float64), [f64(W) for W in Ws])
+    recs = []
+    for r in recs64:
+        q = {k: synth.quantize(r[k].astype(np.float32), dtype) for k in REC}
+        q["LSE"] = r["LSE"].astype(np.float32)
+        recs.append(q)
+    Xf = synth.quantize(Xf64.astype(np.float32), dtype)
+    return shp, osh, Ws, recs, Xf, gf, Wlm, labels
+
+
+def run_stack(shp, dtype, cu, Ws, recs, Xf, gf, Wlm, labels, mask=None, hooks=None):
+    import paper_2503_01066_amd as A
+    batch = A.Batch(cu)
+    dWs = [{k: to_dev(v, dtype) for k, v in W.items()} for W in Ws]
+    drecs = []
+    for r in recs:
+        d = {k: to_dev(r[k], dtype) for k in REC}
+        d["LSE"] = torch.from_numpy(r["LSE"]).cuda()
+        drecs.append(d)
+    out = A.alch_stack_backward(alch_shape(shp, dtype), batch, drecs, dWs, to_dev(Xf, dtype), to_dev(gf, dtype),
+                                to_dev(Wlm, dtype), torch.from_numpy(labels).cuda(),
+                                loss_mask=None if mask is None else torch.from_numpy(mask).cuda(), hooks=hooks)
+    torch.cuda.synchronize()
+    return out
+
+
+def check_stack(out, ref, dtype, L):
+    tol = TOL[dtype]
+    assert abs(out["loss"].item() - ref["loss"]) <= tol * max(1.0, abs(ref["loss"]))
+    for k in ("dX_embed", "dg_final", "dW_lm"):
+        assert rel_err(to_np(out[k]), ref[k]) <= tol, k
+    for l in range(L):
+        for k in WEIGHT_KEYS:
+            assert rel_err(to_np(out["layers"][l]["d" + k]), ref["layers"][l]["d" + k]) <= tol, (l, k)
+
+
+@pytest.mark.parametrize("dtype,shape_name,lens,V,wstd", [("f32", "tiny", [5, 1, 8], 53, 0.3),
+                                                           ("bf16", "medium", [200, 150], 1024, 0.05)])
+def test_stack_backward_matches_oracle(dtype, shape_name, lens, V, wstd):
+    cu = synth.ragged_cu(lens)
+    L = 2
+    shp, osh, Ws, recs, Xf, gf, Wlm, labels = make_stack(shape_name, dtype, cu, L, V, 3, wstd)
+    T = int(cu[-1])
+    mask = np.ones(T, np.uint8)
+    mask[::7] = 0
+    for m in (None, mask):
+        ref = stack_backward_reuse(osh, cu, None, [f64(r) for r in recs], [f64(W) for W in Ws], Xf.astype(np.float64),
+                                   gf.astype(np.float64), Wlm.astype(np.float64), labels, m)
+        out = run_stack(shp, dtype, cu, Ws, recs, Xf, gf, Wlm, labels, m)
+        check_stack(out, ref, dtype, L)
+
+
+def test_stack_nothing_counted_and_hooks():
+    import paper_2503_01066_amd as A
+    cu = synth.ragged_cu([6, 3])
+    shp, osh, Ws, recs, Xf, gf, Wlm, labels = make_stack("tiny", "f32", cu, 3, 31, 5, 0.3)
+    out = run_stack(shp, "f32", cu, Ws, recs, Xf, gf, Wlm, np.full(9, -1, np.int32))
+    assert out["loss"].item() == 0.0
+    assert float(out["dX_embed"].abs().max()) == 0.0 and float(out["dW_lm"].abs().max()) == 0.0
+    # layers are walked output -> input; the preempt hook stops the walk
+    seen = []
+    out = run_stack(shp, "f32", cu, Ws, recs, Xf, gf, Wlm, labels, hooks=(lambda u, l: seen.append(l) or 0, None))
+    assert seen == [2, 1, 0]
+    with pytest.raises(A.AlchError) as e:
+        run_stack(shp, "f32", cu, Ws, recs, Xf, gf, Wlm, labels, hooks=(None, lambda u, l: 1 if l == 1 else 0))
+    assert e.value.code == -7
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("dtype,shape_name,lens,wstd", [("f32", "config1", [128, 128], 0.02),
+                                                         ("bf16", "medium", [300, 77, 1], 0.02),
+                                                         ("bf16", "medium64", [90, 60], 0.05)])
+def test_layer_forward_and_reuse_equals_recompute(dtype, shape_name, lens, wstd):
+    import paper_2503_01066_amd as A
+    cu = synth.ragged_cu(lens)
+    T = int(cu[-1])
+    shp = synth.shape_dict(shape_name)
+    osh = oracle_shape(shp)
+    W = synth.layer_weights(shp, 11, dtype, std=wstd, gain_std=0.1)
+    X = synth.activations(T, shp["hidden"], 12, dtype)
+    dY = synth.activations(T, shp["hidden"], 13, dtype, std=0.5)
+    Yref, rec_ref = layer_forward(osh, cu, None, X.astype(np.float64), f64(W))
+    batch = A.Batch(cu)
+    shape = alch_shape(shp, dtype)
+    dW = {k: to_dev(v, dtype) for k, v in W.items()}
+    Y, rec = A.alch_layer_forward(shape, batch, to_dev(X, dtype), dW)
+    torch.cuda.synchronize()
+    tol = TOL[dtype]
+    assert rel_err(to_np(Y), Yref) <= tol
+    for k in REC + ("LSE",):
+        assert rel_err(to_np(rec[k]), rec_ref[k]) <= tol, k
+    # the paper's central claim on the device: gradients from the record the forward just produced
+    # equal the gradients of a recomputed forward (oracle) under unchanged weights
+    ref = layer_backward_recompute(osh, cu, None, X.astype(np.float64), f64(W), dY.astype(np.float64))
+    out = A.alch_layer_backward(shape, batch, rec, dW, to_dev(dY, dtype))
+    torch.cuda.synchronize()
+    for k, v in out.items():
+        assert rel_err(to_np(v), ref[k]) <= (tol if dtype == "f32" else 3e-2), k

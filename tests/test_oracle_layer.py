@@ -7,7 +7,7 @@ import torch
 
 from oracle import (LayerShape, layer_forward, layer_backward_reuse, layer_backward_recompute,
                     attention_lse, RECORD_KEYS, WEIGHT_KEYS)
-from oracle.layer import attention_backward, _rope, _rms_norm, _rms_norm_backward
+from oracle.layer import attention_backward, layer_backward_reuse_tail_rows, _rope, _rms_norm, _rms_norm_backward
 
 GRADS = ("dX",) + tuple("d" + k for k in WEIGHT_KEYS)
 
@@ -236,3 +236,18 @@ def test_identical_query_heads_in_a_group_scale_key_gradient():
     dQG, dKG, dVG = attention_backward(sG, cu, rep(q1), K, V, rep(O1), np.tile(lse1, (1, G)), rep(dO1))
     assert np.allclose(dKG, G * dK1, rtol=1e-12) and np.allclose(dVG, G * dV1, rtol=1e-12)
     assert np.allclose(dQG, rep(dQ1), rtol=1e-12)
+
+
+@pytest.mark.parametrize("m", [1, 3, 8])
+def test_tail_rows_shortcut_equals_full_backward(m):
+    # the sampled-row helper used at full size is the same function as the full oracle
+    shape, cu, T, W, X, R = make(31, lens=(4, 9))
+    _, rec = layer_forward(shape, cu, None, X, W)
+    rec = {k: v + 0.01 * np.random.default_rng(1).normal(0, 1, v.shape) for k, v in rec.items()}  # any record
+    full = layer_backward_reuse(shape, cu, None, rec, W, R)["dX"]
+    for s in range(2):
+        a, b = int(cu[s]), int(cu[s + 1])
+        mm = min(m, b - a)
+        seq = {k: rec[k][a:b] for k in RECORD_KEYS}
+        tail = layer_backward_reuse_tail_rows(shape, None, seq, W, R[b - mm:b])
+        assert np.max(np.abs(tail - full[b - mm:b])) <= 1e-12 * np.abs(full).max()
