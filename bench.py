@@ -33,7 +33,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config2", choices=["config2", "config3"])
+    ap.add_argument("--workload", default="config2", choices=["config2", "config3", "copy"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
                     help="measured HBM bytes per launch (from the rocprofv3 --pmc summaries)")
@@ -243,6 +243,28 @@ def run_config3(args, torch, A):
     }
 
 
+def run_copy(args, torch, A):
+    """Calibration workload for the HBM byte counters: a plain device-to-device copy of known size."""
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255)
+    dst = torch.empty_like(src)
+    for _ in range(args.warmup):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    gbps = 2.0 * n * args.steps / dt / 1e9
+    return {"metric": "plain copy GB/s (counter calibration)", "value": gbps, "unit": "GB/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+            "config": {"workload": "copy: 1 GiB read + 1 GiB written per step", "bytes_read": n, "bytes_written": n},
+            "roofline": {"kernel": "device copy", "bound": "hbm", "achieved": gbps, "peak": PEAK_HBM_GBPS,
+                         "unit": "GB/s", "frac": gbps / PEAK_HBM_GBPS, "traffic": None}}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -256,8 +278,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
-    out = run_config2(args, torch, A) if args.workload == "config2" else run_config3(args, torch, A)
-    if not args.no_cpu_baseline:
+    out = {"config2": run_config2, "config3": run_config3, "copy": run_copy}[args.workload](args, torch, A)
+    if not args.no_cpu_baseline and args.workload != "copy":
         out["cpu_baseline"] = cpu_baseline_config2() if args.workload == "config2" else cpu_baseline_config3()
     print(json.dumps(out))
 
