@@ -65,17 +65,21 @@ __device__ __forceinline__ void dma4(i32x4 r, uint32_t lds_addr, uint32_t voff) 
 // chunk swizzle of the [rows][128] tile: 16 chunks of 16 bytes per row
 __device__ __forceinline__ int swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
 
-// One wave's share (4 of 16 loads) of a 64-row tile: rows of `ld` elements starting at `base`,
-// `rows_valid` rows exist (the rest read as zero).
-__device__ __forceinline__ void issue_rows_tile(const __bf16* base, long long ld, int rows_valid, uint32_t lds_addr,
-                                                int wave, int lane) {
-    const i32x4 r = rsrc_of(base, rows_valid > 0 ? ((long long)(rows_valid - 1) * ld + kD) * 2 : 0);
+// Per-lane byte offsets of one wave's share (4 of 16 loads) of a 64-row tile of rows `ld` elements apart.
+__device__ __forceinline__ void tile_voffsets(uint32_t (&voff)[4], long long ld, int wave, int lane) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int slot = (wave * 4 + j) * 64 + lane;
         const int row = slot >> 4, c = (slot & 15) ^ swz(row);
-        dma16(r, lds_addr + (uint32_t)(wave * 4 + j) * 1024u, (uint32_t)((row * ld + c * 8) * 2));
+        voff[j] = (uint32_t)((row * ld + c * 8) * 2);
     }
+}
+// The loads themselves: tile rows start at `base`, `rows_valid` rows exist (the rest read as zero).
+__device__ __forceinline__ void issue_rows_tile(const __bf16* base, long long ld, int rows_valid, uint32_t lds_addr,
+                                                int wave, const uint32_t (&voff)[4]) {
+    const i32x4 r = rsrc_of(base, rows_valid > 0 ? ((long long)(rows_valid - 1) * ld + kD) * 2 : 0);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) dma16(r, lds_addr + (uint32_t)(wave * 4 + j) * 1024u, voff[j]);
 }
 // 64 floats with stride `stride` elements (one per tile row) -> LDS, by one wave
 __device__ __forceinline__ void issue_row_scalars(const float* base, long long stride, int rows_valid, uint32_t lds_addr,
@@ -84,24 +88,29 @@ __device__ __forceinline__ void issue_row_scalars(const float* base, long long s
     dma4(r, lds_addr, (uint32_t)(lane * stride * 4));
 }
 
-// operand fragment along the 128-wide dimension (k = d): rows row0 + (lane&31), d = kk*16 + 8*(lane>>5) ..+7
-__device__ __forceinline__ bf16x8 tile_frag_d(const char* tile, int row0, int kk, int lane) {
-    const int row = row0 + (lane & 31);
-    const int c = (kk * 2 + (lane >> 5)) ^ swz(row);
-    return *reinterpret_cast<const bf16x8*>(tile + row * 256 + c * 16);
+// LDS read addresses.  Every fragment address of a [rows][128] tile is a per-lane constant combined
+// with compile-time terms, so the lane parts are computed once per kernel:
+//   d-fragments (k = d):   byte = row0*256 + (lane_d ^ (kk << 5)),       lane_d from frag_d_lane()
+//   row-fragments (k = row): byte = (row0 + 16*ks)*256 + (lane_r ^ (nb << 6)), lane_r from frag_rows_lane()
+// where row0 is a multiple of 32 (XOR and ADD commute with it).
+__device__ __forceinline__ uint32_t frag_d_lane(int lane) {
+    const int row = lane & 31;
+    return (uint32_t)(row * 256 + (((lane >> 5) ^ swz(row)) << 4));
 }
-// operand fragment along the row dimension (k = tile row) for the column block nb (32 columns):
-// k index (half = lane>>5, e) <-> tile row row0 + 16*ks + 8*(e>>2) + 4*half + (e&3), matching the
-// accumulator layout of a 32x32 MFMA whose rows are these tile rows.
-__device__ __forceinline__ bf16x8 tile_frag_rows(const char* tile, int row0, int ks, int nb, int lane) {
+// second = 0: tile rows 4*(g>>1) + (i>>2); second = 1: eight rows further down
+__device__ __forceinline__ uint32_t frag_rows_lane(int lane, int second) {
     const int g = lane >> 4, i = lane & 15;
-    const int col = nb * 32 + (g & 1) * 16 + 4 * (i & 3);
-    const int r0 = row0 + 16 * ks + 4 * (g >> 1) + (i >> 2);
-    const int r1 = r0 + 8;
-    const char* p0 = tile + r0 * 256 + (((col >> 3) ^ swz(r0)) << 4) + (col & 7) * 2;
-    const char* p1 = tile + r1 * 256 + (((col >> 3) ^ swz(r1)) << 4) + (col & 7) * 2;
-    bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4*)(p0));
-    bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4*)(p1));
+    const int col = (g & 1) * 16 + 4 * (i & 3);
+    const int r = 4 * (g >> 1) + (i >> 2) + 8 * second;
+    return (uint32_t)(r * 256 + (((col >> 3) ^ swz(r)) << 4) + (col & 7) * 2);
+}
+__device__ __forceinline__ bf16x8 lds_frag_d(const char* tile, uint32_t lane_d, int kk) {
+    return *reinterpret_cast<const bf16x8*>(tile + (lane_d ^ (uint32_t)(kk << 5)));
+}
+__device__ __forceinline__ bf16x8 lds_frag_rows(const char* tile, uint32_t lane_r0, uint32_t lane_r1, int ks, int nb) {
+    const char* t = tile + ks * 16 * 256;
+    bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4*)(t + (lane_r0 ^ (uint32_t)(nb << 6))));
+    bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((__attribute__((address_space(3))) bf16x4*)(t + (lane_r1 ^ (uint32_t)(nb << 6))));
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
@@ -151,6 +160,9 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) dK[n][e] = dV[n][e] = 0.f;
 
+    const uint32_t lane_d = frag_d_lane(lane), lane_r0 = frag_rows_lane(lane, 0), lane_r1 = frag_rows_lane(lane, 1);
+    uint32_t voff[4];
+    tile_voffsets(voff, p.ldq, wave, lane);
     const int qt0 = (kb * 128) / kTileRows;
     const int nqt = (len + kTileRows - 1) / kTileRows - qt0;
     const int n_it = G * nqt;
@@ -160,17 +172,28 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
         const int h = kv * G + it / nqt, qt = qt0 + it % nqt;
         const int row_first = qt * kTileRows, rows_valid = len - row_first;
         const uint32_t st = lds0 + (uint32_t)(it & 1) * kStageBytes;
-        issue_rows_tile(p.Q + (long long)(seq_start + row_first) * p.ldq + h * kD, p.ldq, rows_valid, st, wave, lane);
-        issue_rows_tile(p.dO + (long long)(seq_start + row_first) * p.ldq + h * kD, p.ldq, rows_valid, st + kTileBytes, wave, lane);
+        issue_rows_tile(p.Q + (long long)(seq_start + row_first) * p.ldq + h * kD, p.ldq, rows_valid, st, wave, voff);
+        issue_rows_tile(p.dO + (long long)(seq_start + row_first) * p.ldq + h * kD, p.ldq, rows_valid, st + kTileBytes, wave, voff);
         if (wave == 0) issue_row_scalars(p.LSE + (long long)(seq_start + row_first) * p.Hq + h, p.Hq, rows_valid, st + 2 * kTileBytes, lane);
         if (wave == 1) issue_row_scalars(p.delta + (long long)(seq_start + row_first) * p.Hq + h, p.Hq, rows_valid, st + 2 * kTileBytes + 256, lane);
     };
 
+#ifdef ALCH_ATTN_TIMING
+    long long tph[6] = {0, 0, 0, 0, 0, 0}, tt0, tt1;
+#define ALCH_T0() tt0 = __builtin_readcyclecounter()
+#define ALCH_T(i) tt1 = __builtin_readcyclecounter(); tph[i] += tt1 - tt0; tt0 = tt1
+#else
+#define ALCH_T0()
+#define ALCH_T(i)
+#endif
     issue(0);
     for (int it = 0; it < n_it; ++it) {
+        ALCH_T0();
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
+        ALCH_T(0);
         if (it + 1 < n_it) issue(it + 1);
+        ALCH_T(1);
         const int qt = qt0 + it % nqt;
         const char* tq = smem + (it & 1) * kStageBytes;
         const char* tdo = tq + kTileBytes;
@@ -179,18 +202,24 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
 #pragma unroll
         for (int ib = 0; ib < 2; ++ib) {
             const int i0 = qt * kTileRows + ib * 32;  // first query of the block (inside the sequence)
-            if (i0 + 31 < j0 || i0 >= len) continue;  // wholly above the diagonal / beyond the sequence
+            // (blocks wholly above the diagonal are computed too and masked to zero: a branch around
+            //  the block would make the compiler shuffle the 128 accumulator registers at the join)
+            const char* bq = tq + ib * 32 * 256;
+            const char* bdo = tdo + ib * 32 * 256;
             f32x16 S, dP;
 #pragma unroll
             for (int e = 0; e < 16; ++e) S[e] = dP[e] = 0.f;
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk) {
-                S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tile_frag_d(tq, ib * 32, kk, lane), kf[kk], S, 0, 0, 0);
-                dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tile_frag_d(tdo, ib * 32, kk, lane), vf[kk], dP, 0, 0, 0);
+                S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_d(bq, lane_d, kk), kf[kk], S, 0, 0, 0);
+                dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_d(bdo, lane_d, kk), vf[kk], dP, 0, 0, 0);
             }
+#ifdef ALCH_ATTN_TIMING
+            asm volatile("s_nop 0" :: "v"(S[0]), "v"(dP[0]));
+#endif
+            ALCH_T(2);
             // accumulator element e: query row i0 + 8*(e>>2) + 4*half + (e&3), key column j0 + (lane&31)
             const bool need_mask = (i0 < j0 + 31) || (i0 + 32 > len);
-            const int j = j0 + (lane & 31);
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_s + ib * 32 + 8 * b + 4 * half);
@@ -198,24 +227,41 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int e = 4 * b + r;
-                    const int i = i0 + 8 * b + 4 * half + r;
-                    float pr = exp2f(S[e] * sl2 - l4[r] * kLog2e);
-                    if (need_mask && (j > i || i >= len)) pr = 0.f;
+                    const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(S[e], sl2, -l4[r] * kLog2e));
                     S[e] = pr;
                     dP[e] = pr * (dP[e] - d4[r]);
                 }
             }
+            if (need_mask) {
+                const int j = j0 + (lane & 31);
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int i = i0 + 8 * (e >> 2) + 4 * half + (e & 3);
+                    if (j > i || i >= len) S[e] = dP[e] = 0.f;
+                }
+            }
+            ALCH_T(3);
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
                 const bf16x8 pf = pack8(S, ks), dsf = pack8(dP, ks);
 #pragma unroll
                 for (int nb = 0; nb < 4; ++nb) {
-                    dV[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, tile_frag_rows(tdo, ib * 32, ks, nb, lane), dV[nb], 0, 0, 0);
-                    dK[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf, tile_frag_rows(tq, ib * 32, ks, nb, lane), dK[nb], 0, 0, 0);
+                    dV[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, lds_frag_rows(bdo, lane_r0, lane_r1, ks, nb), dV[nb], 0, 0, 0);
+                    dK[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf, lds_frag_rows(bq, lane_r0, lane_r1, ks, nb), dK[nb], 0, 0, 0);
                 }
             }
+#ifdef ALCH_ATTN_TIMING
+            asm volatile("s_nop 0" :: "v"(dK[3][0]), "v"(dV[3][0]));
+#endif
+            ALCH_T(4);
         }
     }
+#ifdef ALCH_ATTN_TIMING
+    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) {
+        for (int i = 0; i < 5; ++i) g_attn_stamps[i] = tph[i];
+        g_attn_stamps[5] = n_it;
+    }
+#endif
 
     // accumulator element e of block nb: key row j0 + 8*(e>>2) + 4*half + (e&3), column nb*32 + (lane&31)
     __bf16* dKb = p.dK + (long long)seq_start * p.ldo + kv * kD;
@@ -235,7 +281,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
 
 // ---------------------------------------------------------------------------------------------
 // dQ
-__global__ __launch_bounds__(256) void k_attn_bwd_dq_mfma(AttnMfmaParams p) {
+__global__ __launch_bounds__(256, 2) void k_attn_bwd_dq_mfma(AttnMfmaParams p) {
     __shared__ __attribute__((aligned(1024))) char smem[2 * kStageBytes];
     const uint32_t lds0 = (uint32_t)(uintptr_t)ALCH_LDS(smem);
     const int seq = blockIdx.z, h = blockIdx.y;
@@ -267,6 +313,9 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dq_mfma(AttnMfmaParams p) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) dQ[n][e] = 0.f;
 
+    const uint32_t lane_d = frag_d_lane(lane), lane_r0 = frag_rows_lane(lane, 0), lane_r1 = frag_rows_lane(lane, 1);
+    uint32_t voff[4];
+    tile_voffsets(voff, p.ldk, wave, lane);
     // key tiles 0 .. last tile that holds a key <= the work-group's last query
     const int last_q = min(qb * 128 + 127, len - 1);
     const int n_it = last_q / kTileRows + 1;
@@ -275,8 +324,8 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dq_mfma(AttnMfmaParams p) {
     auto issue = [&](int it) {
         const int row_first = it * kTileRows, rows_valid = len - row_first;
         const uint32_t st = lds0 + (uint32_t)(it & 1) * kStageBytes;
-        issue_rows_tile(p.K + (long long)(seq_start + row_first) * p.ldk + kv * kD, p.ldk, rows_valid, st, wave, lane);
-        issue_rows_tile(p.V + (long long)(seq_start + row_first) * p.ldk + kv * kD, p.ldk, rows_valid, st + kTileBytes, wave, lane);
+        issue_rows_tile(p.K + (long long)(seq_start + row_first) * p.ldk + kv * kD, p.ldk, rows_valid, st, wave, voff);
+        issue_rows_tile(p.V + (long long)(seq_start + row_first) * p.ldk + kv * kD, p.ldk, rows_valid, st + kTileBytes, wave, voff);
     };
 
     issue(0);
@@ -289,22 +338,28 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dq_mfma(AttnMfmaParams p) {
 #pragma unroll
         for (int jb = 0; jb < 2; ++jb) {
             const int j0 = it * kTileRows + jb * 32;
-            if (j0 > i0 + 31 || j0 >= len) continue;  // wholly above the diagonal
+            // (blocks wholly above the diagonal are computed and masked to zero, see the dK/dV kernel)
+            const char* bk = tk + jb * 32 * 256;
+            const char* bv = tv + jb * 32 * 256;
             f32x16 St, dPt;  // transposed: rows = keys, columns = queries
 #pragma unroll
             for (int e = 0; e < 16; ++e) St[e] = dPt[e] = 0.f;
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk) {
-                St = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tile_frag_d(tk, jb * 32, kk, lane), qf[kk], St, 0, 0, 0);
-                dPt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tile_frag_d(tv, jb * 32, kk, lane), gf[kk], dPt, 0, 0, 0);
+                St = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_d(bk, lane_d, kk), qf[kk], St, 0, 0, 0);
+                dPt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_d(bv, lane_d, kk), gf[kk], dPt, 0, 0, 0);
             }
-            const bool need_mask = (j0 + 31 > i0);
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const int j = j0 + 8 * (e >> 2) + 4 * half + (e & 3);
-                float pr = exp2f(St[e] * sl2 - lse2);
-                if (!i_ok || (need_mask && j > i)) pr = 0.f;
+                const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(St[e], sl2, -lse2));
                 dPt[e] = pr * (dPt[e] - del);
+            }
+            if (!i_ok || j0 + 31 > i0) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int j = j0 + 8 * (e >> 2) + 4 * half + (e & 3);
+                    if (!i_ok || j > i) dPt[e] = 0.f;
+                }
             }
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
@@ -312,7 +367,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dq_mfma(AttnMfmaParams p) {
                 const bf16x8 dsf = pack8(dPt, ks);
 #pragma unroll
                 for (int nb = 0; nb < 4; ++nb)
-                    dQ[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf, tile_frag_rows(tk, jb * 32, ks, nb, lane), dQ[nb], 0, 0, 0);
+                    dQ[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf, lds_frag_rows(bk, lane_r0, lane_r1, ks, nb), dQ[nb], 0, 0, 0);
             }
         }
     }

@@ -221,15 +221,39 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
         // eight would hold the wave at the issue stage while the texture path drains).  Past the
         // last tile the same loads are issued against an empty buffer (they fetch nothing and
         // write zeros nobody reads), so the outstanding-load count is the same in every iteration.
-        int next_tile = 0;
+        // The stream state (tile base address, bytes left in the operand) is kept in scalar registers
+        // and advanced with scalar instructions, off the vector pipeline that feeds the MFMAs.
+        int tiles_left = nk;
+        uint32_t a_lo, a_hi, b_lo, b_hi;
+        int a_rem, b_rem;
+        {
+            const uint64_t ua = (uint64_t)pa, ub = (uint64_t)pb;
+            const long long la = enda - pa, lb = endb - pb;
+            a_lo = __builtin_amdgcn_readfirstlane((uint32_t)ua);
+            a_hi = __builtin_amdgcn_readfirstlane((uint32_t)(ua >> 32) & 0xffffu);
+            a_rem = __builtin_amdgcn_readfirstlane((int)(la < 0 ? 0 : (la > 0x7fffffffLL ? 0x7fffffffLL : la)));
+            b_lo = __builtin_amdgcn_readfirstlane((uint32_t)ub);
+            b_hi = __builtin_amdgcn_readfirstlane((uint32_t)(ub >> 32) & 0xffffu);
+            b_rem = __builtin_amdgcn_readfirstlane((int)(lb < 0 ? 0 : (lb > 0x7fffffffLL ? 0x7fffffffLL : lb)));
+        }
+        const int sa_step = __builtin_amdgcn_readfirstlane((int)stepa);
+        const int sb_step = __builtin_amdgcn_readfirstlane((int)stepb);
         i32x4 ra, rb;
         auto open_next = [&]() {
-            const bool live = next_tile < nk;
-            ra = make_rsrc(pa, live ? enda - pa : 0);
-            rb = make_rsrc(pb, live ? endb - pb : 0);
-            pa += stepa;
-            pb += stepb;
-            ++next_tile;
+            // resources of the next k-tile (an exhausted stream gets an empty buffer), then advance
+            int na, nbb;
+            asm volatile("s_cmp_gt_i32 %2, 0\n\ts_cselect_b32 %0, %3, 0\n\ts_cselect_b32 %1, %4, 0"
+                         : "=&s"(na), "=&s"(nbb)
+                         : "s"(tiles_left), "s"(a_rem), "s"(b_rem)
+                         : "scc");
+            ra[0] = (int)a_lo; ra[1] = (int)a_hi; ra[2] = na; ra[3] = 0x00020000;
+            rb[0] = (int)b_lo; rb[1] = (int)b_hi; rb[2] = nbb; rb[3] = 0x00020000;
+            asm volatile("s_add_u32 %0, %0, %7\n\ts_addc_u32 %1, %1, 0\n\ts_sub_i32 %2, %2, %7\n\ts_max_i32 %2, %2, 0\n\t"
+                         "s_add_u32 %3, %3, %8\n\ts_addc_u32 %4, %4, 0\n\ts_sub_i32 %5, %5, %8\n\ts_max_i32 %5, %5, 0\n\t"
+                         "s_sub_i32 %6, %6, 1"
+                         : "+s"(a_lo), "+s"(a_hi), "+s"(a_rem), "+s"(b_lo), "+s"(b_hi), "+s"(b_rem), "+s"(tiles_left)
+                         : "s"(sa_step), "s"(sb_step)
+                         : "scc");
         };
 #define ALCH_DMA_A(stage, j) dma16(ra, lds0 + (stage) * kStage + (uint32_t)(wave * 4 + (j)) * 1024u, va[j])
 #define ALCH_DMA_B(stage, j) dma16(rb, lds0 + (stage) * kStage + kOperandStageBytes + (uint32_t)(wave * 4 + (j)) * 1024u, vb[j])
@@ -408,6 +432,9 @@ bool gemm_mfma_supported(const GemmDesc& d) {
         if (!d.b_kmajor && d.N % 8) return false;
         if (d.N % 8) return false;  // 16-byte output stores
         if (g.lda > (1 << 21) || g.ldb > (1 << 21)) return false;  // tile extent must stay below 2 GiB
+        // the kernel tracks the bytes left in an operand in a signed 32-bit scalar
+        const long long a_rows = d.a_kmajor ? d.M : g.K, b_rows = d.b_kmajor ? d.N : g.K;
+        if (a_rows * g.lda * 2 >= (1LL << 31) || b_rows * g.ldb * 2 >= (1LL << 31)) return false;
     }
     for (int o = 0; o < d.n_out; ++o) {
         if (d.out[o].ldc % 8 || !aligned16(d.out[o].C)) return false;
