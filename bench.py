@@ -33,25 +33,27 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config2", choices=["config2", "config3", "copy"])
+    ap.add_argument("--workload", default="config2", choices=["config2", "config3", "config5", "copy"])
+    ap.add_argument("--loss-mask", action="store_true", help="config5: zero dY rows with a Bernoulli(0.25) loss mask")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
                     help="measured HBM bytes per launch (from the rocprofv3 --pmc summaries)")
     return ap.parse_args()
 
 
-def cpu_baseline_config2(seed=0):
-    """The fp64 oracle, as it stands, on one of the workload's four 2048-token sequences."""
+def cpu_baseline_layer(workload, seed=0):
+    """The fp64 oracle, as it stands, on a bounded sample of the layer workload."""
     import synth_inputs as synth
     from oracle import LayerShape, layer_backward_reuse, attention_lse
+    shape_name = LAYER_WORKLOADS[workload][0]
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count()
-    shp = synth.shape_dict("llama8b")
+    shp = synth.shape_dict(shape_name)
     osh = LayerShape(*[shp[k] for k in synth.SHAPE_FIELDS])
-    S = 2048
+    S = 2048 if workload == "config2" else 512
     cu = np.array([0, S])
     W = {k: v.astype(np.float64) for k, v in synth.layer_weights(shp, seed, "bf16").items()}
     rec = {k: v.astype(np.float64) for k, v in synth.drawn_record(shp, S, seed + 1, "bf16").items()}
@@ -61,7 +63,8 @@ def cpu_baseline_config2(seed=0):
     layer_backward_reuse(osh, cu, None, rec, W, dY)
     dt = time.perf_counter() - t0
     return {"value": S / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": "1 of the 4 sequences (2048 tokens) of the same 8B-shaped layer, fp64 numpy, %.1f s" % dt}
+            "sample": "one sequence of %d tokens of the same %s-shaped layer (all nine gradients), fp64 numpy, %.1f s"
+                      % (S, shape_name, dt)}
 
 
 def cpu_baseline_config3(seed=0):
@@ -90,13 +93,22 @@ def load_traffic(path, key):
         return None
 
 
-def run_config2(args, torch, A):
+LAYER_WORKLOADS = {
+    # name: (shape, prefilled prompts, tokens per prompt, prompts kept for training, description)
+    "config2": ("llama8b", 16, 2048, 4, "config2: one Llama-3-8B-shaped layer, bf16, 4 x 2048 trained tokens "
+                "(packed out of 16 x 2048 prefilled), capture/pack + full layer backward"),
+    "config5": ("llama70b", 8, 4096, 2, "config5: one Llama-3-70B-shaped layer, bf16, 2 x 4096 trained tokens "
+                "(packed out of 8 x 4096 prefilled), capture/pack + full layer backward"),
+}
+
+
+def run_layer(args, torch, A):
     import synth_inputs as synth
     dev = "cuda"
-    shp = synth.shape_dict("llama8b")
+    shape_name, n_src, S, n_keep, descr = LAYER_WORKLOADS[args.workload]
+    shp = synth.shape_dict(shape_name)
     shape = A.make_shape(*[shp[k] for k in synth.SHAPE_FIELDS], "bf16")
     H, QD, KD, F = shp["hidden"], shp["n_q_heads"] * shp["head_dim"], shp["n_kv_heads"] * shp["head_dim"], shp["ffn"]
-    n_src, S, n_keep = 16, 2048, 4
     T_src, T = n_src * S, n_keep * S
     g = torch.Generator(device=dev).manual_seed(0)
     bf = torch.bfloat16
@@ -122,6 +134,10 @@ def run_config2(args, torch, A):
          "Wg": rnd((F, H), 0.02), "Wu": rnd((F, H), 0.02), "Wd": rnd((H, F), 0.02),
          "g1": torch.ones(H, device=dev, dtype=bf), "g2": torch.ones(H, device=dev, dtype=bf)}
     dY = rnd((T, H), 0.01)
+    loss_mask = None
+    if args.loss_mask:
+        loss_mask = torch.from_numpy(synth.keep_mask(T, 0.25, 7)).to(dev)
+        descr += ", dY rows zeroed by a Bernoulli(0.25) loss mask (dense kernels)"
 
     keys = list(widths) + ["LSE"]
     dst = {k: torch.empty((T, src[k].shape[1]), dtype=src[k].dtype, device=dev) for k in keys}
@@ -136,7 +152,7 @@ def run_config2(args, torch, A):
 
     def step():
         A.alch_capture_pack(src_batch, mask, streams, capacity=T, dsts=dsts, workspace=ws_pack)
-        A.alch_layer_backward(shape, kept_batch, dst, W, dY, grads=grads, dX=dX, workspace=ws_bwd)
+        A.alch_layer_backward(shape, kept_batch, dst, W, dY, loss_mask=loss_mask, grads=grads, dX=dX, workspace=ws_bwd)
 
     for _ in range(args.warmup):
         step()
@@ -165,8 +181,7 @@ def run_config2(args, torch, A):
         "metric": METRIC, "value": T * args.steps / dt, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "config2: one Llama-3-8B-shaped layer, bf16, 4 x 2048 trained tokens "
-                               "(packed out of 16 x 2048 prefilled), capture/pack + full layer backward",
+        "config": {"workload": descr,
                    "hidden": H, "q_heads": shp["n_q_heads"], "kv_heads": shp["n_kv_heads"],
                    "head_dim": shp["head_dim"], "ffn": F, "tokens": T, "seq_len": S},
         "step_tflops": (4.0 * P * T + attn_flops) / 1e12,
@@ -175,11 +190,11 @@ def run_config2(args, torch, A):
         "roofline": {"kernel": "k_gemm_mfma (all contractions of the layer backward)", "bound": "mfma",
                      "achieved": achieved_tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved_tf / PEAK_BF16_TFLOPS,
-                     "traffic": load_traffic(args.traffic_json, "gemm_mfma_config2_bytes_per_launch"),
+                     "traffic": load_traffic(args.traffic_json, "gemm_mfma_%s_bytes_per_launch" % args.workload),
                      "launches_per_step": gm[3] / args.steps, "avg_launch_ms": gm[2] / max(gm[3], 1)},
         "roofline_pack": {"kernel": "k_pack_gather", "bound": "hbm", "achieved": pack_gbps, "peak": PEAK_HBM_GBPS,
                           "unit": "GB/s", "frac": pack_gbps / PEAK_HBM_GBPS,
-                          "traffic": load_traffic(args.traffic_json, "pack_gather_config2_bytes_per_launch"),
+                          "traffic": load_traffic(args.traffic_json, "pack_gather_%s_bytes_per_launch" % args.workload),
                           "avg_launch_ms": pk[2] / max(pk[3], 1)},
         "kernel_ms_per_step": {k: v[2] / args.steps for k, v in by.items()},
     }
@@ -278,9 +293,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
-    out = {"config2": run_config2, "config3": run_config3, "copy": run_copy}[args.workload](args, torch, A)
+    out = {"config2": run_layer, "config5": run_layer, "config3": run_config3, "copy": run_copy}[args.workload](args, torch, A)
     if not args.no_cpu_baseline and args.workload != "copy":
-        out["cpu_baseline"] = cpu_baseline_config2() if args.workload == "config2" else cpu_baseline_config3()
+        out["cpu_baseline"] = cpu_baseline_config3() if args.workload == "config3" else cpu_baseline_layer(args.workload)
     print(json.dumps(out))
 
 

@@ -36,7 +36,10 @@ static constexpr int kOperandStageBytes = 256 * BK * 2;  // 16 KB per operand pe
 static constexpr int kLoadsPerTile = 8;                  // direct-to-LDS instructions per wave per k-tile (A + B)
 static constexpr uint32_t kOobOffset = 0x80000000u;      // >= any num_records we set
 static constexpr uint32_t kMaxRecords = 0x80000000u;
-static constexpr int kGroupM = 4;                        // tile rows per raster band
+#ifndef ALCH_GROUP_M
+#define ALCH_GROUP_M 4
+#endif
+static constexpr int kGroupM = ALCH_GROUP_M;             // tile rows per raster band
 
 struct MfmaGemmParams {
     int M, N, n_seg, n_out, accumulate, tiles_m, tiles_n;

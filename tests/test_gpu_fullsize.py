@@ -124,3 +124,29 @@ def test_config3_sized_capture_pack_one_layer():
     idx = torch.from_numpy(ok.astype(np.int64)).cuda()
     for s, d in zip(streams, dsts):
         assert torch.equal(d[:n], s[idx])
+
+
+def test_llama70b_width_short_batch_elementwise_with_loss_mask():
+    # config-5 widths (hidden 8192, 64/8 heads x 128, ffn 28672), Bernoulli(0.25) loss mask, short ragged batch
+    shp = synth.shape_dict("llama70b")
+    osh = oracle_shape(shp)
+    cu = synth.ragged_cu([70, 131])
+    T = int(cu[-1])
+    W = synth.layer_weights(shp, 0, "bf16")
+    rec = synth.drawn_record(shp, T, 1, "bf16")
+    rec["LSE"] = attention_lse(osh, cu, rec["Q"].astype(np.float64), rec["K"].astype(np.float64)).astype(np.float32)
+    dY = synth.activations(T, shp["hidden"], 2, "bf16", std=0.01)
+    mask = synth.keep_mask(T, 0.25, 3)
+    print("oracle ...", flush=True)
+    ref = layer_backward_reuse(osh, cu, None, f64(rec), f64(W), dY.astype(np.float64), mask)
+    print("gpu ...", flush=True)
+    import paper_2503_01066_amd as A
+    dW = {k: to_dev(v, "bf16") for k, v in W.items()}
+    drec = {k: to_dev(rec[k], "bf16") for k in REC}
+    drec["LSE"] = torch.from_numpy(rec["LSE"]).cuda()
+    out = A.alch_layer_backward(alch_shape(shp, "bf16"), A.Batch(cu), drec, dW, to_dev(dY, "bf16"),
+                                loss_mask=torch.from_numpy(mask).cuda())
+    torch.cuda.synchronize()
+    for k, v in out.items():
+        e = rel_err(to_np(v), ref[k])
+        assert e <= 2e-2, (k, e)
