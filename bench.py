@@ -33,7 +33,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config2", choices=["config2", "config3", "config5", "copy"])
+    ap.add_argument("--workload", default="config2", choices=["config2", "config3", "config4", "config5", "copy"])
+    ap.add_argument("--layers", type=int, default=32, help="config4: number of layers")
     ap.add_argument("--loss-mask", action="store_true", help="config5: zero dY rows with a Bernoulli(0.25) loss mask")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
@@ -201,6 +202,96 @@ def run_layer(args, torch, A):
     return out
 
 
+def run_config4(args, torch, A):
+    """32-layer 8B-shaped stack, 8 x 4096 tokens, vocab 128256: loss + backward from reused records
+    (Section 1 of the paper) against forward recompute + the same backward (its separate-cluster baseline)."""
+    import synth_inputs as synth
+    dev, bf = "cuda", torch.bfloat16
+    shp = synth.shape_dict("llama8b")
+    shape = A.make_shape(*[shp[k] for k in synth.SHAPE_FIELDS], "bf16")
+    H, QD, KD, F = shp["hidden"], shp["n_q_heads"] * shp["head_dim"], shp["n_kv_heads"] * shp["head_dim"], shp["ffn"]
+    L, B, S, V = args.layers, 8, 4096, 128256
+    T = B * S
+    g = torch.Generator(device=dev).manual_seed(0)
+    rnd = lambda shape_, std: (torch.randn(shape_, generator=g, device=dev, dtype=torch.float32) * std).to(bf)
+    Ws = [{"Wq": rnd((QD, H), 0.02), "Wk": rnd((KD, H), 0.02), "Wv": rnd((KD, H), 0.02), "Wo": rnd((H, QD), 0.02),
+           "Wg": rnd((F, H), 0.02), "Wu": rnd((F, H), 0.02), "Wd": rnd((H, F), 0.02),
+           "g1": torch.ones(H, device=dev, dtype=bf), "g2": torch.ones(H, device=dev, dtype=bf)} for _ in range(L)]
+    W_lm, g_final = rnd((V, H), 0.02), torch.ones(H, device=dev, dtype=bf)
+    ids = torch.randint(0, V, (T,), generator=g, device=dev)
+    emb = rnd((V, H), 0.02)
+    X0 = emb[ids]
+    del emb
+    labels = torch.full((T,), -1, dtype=torch.int32, device=dev)
+    lab2 = labels.view(B, S)
+    lab2[:, :-1] = ids.view(B, S)[:, 1:].to(torch.int32)
+    batch = A.Batch(synth.uniform_cu(B, S))
+    ws_fwd = torch.empty(A.lib().alch_layer_forward_workspace_bytes(__import__("ctypes").byref(shape), T, S),
+                         dtype=torch.uint8, device=dev)
+
+    def forward():
+        X, recs = X0, []
+        for l in range(L):
+            X, rec = A.alch_layer_forward(shape, batch, X, Ws[l], workspace=ws_fwd)
+            recs.append(rec)
+        return X, recs
+
+    X_final, recs = forward()          # the records a serving prefill would have left behind
+    grads = [{"d" + k: torch.empty_like(v) for k, v in W.items()} for W in Ws]
+    ws = torch.empty(A.stack_backward_workspace_bytes(shape, L, V, T, S), dtype=torch.uint8, device=dev)
+
+    def backward(xf, rs):
+        return A.alch_stack_backward(shape, batch, rs, Ws, xf, g_final, W_lm, labels, grads_layers=grads, workspace=ws)
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            out = fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps, out
+
+    A.alch_trace_enable(True)
+    t_reuse, out = timed(lambda: backward(X_final, recs), args.steps, args.warmup)
+    A.alch_trace_enable(False)
+    trace = A.alch_trace_collect()
+    loss = float(out["loss"].item())
+    del recs
+
+    def recompute_step():
+        xf, rs = forward()
+        return backward(xf, rs)
+    t_rec, _ = timed(recompute_step, max(1, args.steps // 2), 1)
+
+    gm = [r for r in trace if r[0] == "gemm_mfma"]
+    gm_ms = sum(r[3] for r in gm)
+    achieved_tf = sum(r[1] for r in gm) / (gm_ms * 1e-3) / 1e12
+    P = 2 * H * QD + 2 * H * KD + 3 * H * F
+    flops = T * (L * 4.0 * P + 6.0 * V * H) + L * 10.0 * shp["head_dim"] * shp["n_q_heads"] * B * S * (S + 1) / 2
+    by = {}
+    for kind, fl, nb, ms in trace:
+        by[kind] = by.get(kind, 0.0) + ms
+    n_traced = args.steps + args.warmup
+    return {
+        "metric": METRIC, "value": T / t_reuse, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": t_reuse * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "config4: %d-layer Llama-3-8B-shaped stack, bf16, 8 x 4096 tokens, vocab 128256, "
+                               "cross-entropy + full backward from reused records" % L,
+                   "layers": L, "tokens": T, "seq_len": S, "vocab": V},
+        "loss": loss, "loss_expected_random_init": float(np.log(V) + 0.5 * 0.02 ** 2 * H),
+        "step_tflops": flops / 1e12, "step_mfma_frac": flops / t_reuse / 1e12 / PEAK_BF16_TFLOPS,
+        "recompute_tokens_per_s": T / t_rec, "reuse_speedup_over_recompute": t_rec / t_reuse,
+        "roofline": {"kernel": "k_gemm_mfma (all contractions of the stack backward)", "bound": "mfma",
+                     "achieved": achieved_tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved_tf / PEAK_BF16_TFLOPS, "traffic": None,
+                     "launches_per_step": len(gm) / n_traced, "avg_launch_ms": gm_ms / max(len(gm), 1)},
+        "kernel_ms_per_step": {k: v / n_traced for k, v in by.items()},
+    }
+
+
 def run_config3(args, torch, A):
     import synth_inputs as synth
     dev = "cuda"
@@ -293,8 +384,17 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
-    out = {"config2": run_layer, "config5": run_layer, "config3": run_config3, "copy": run_copy}[args.workload](args, torch, A)
-    if not args.no_cpu_baseline and args.workload != "copy":
+    out = {"config2": run_layer, "config5": run_layer, "config3": run_config3, "config4": run_config4,
+           "copy": run_copy}[args.workload](args, torch, A)
+    if not args.no_cpu_baseline and args.workload == "config4":
+        # extrapolated, and labelled so: one 2048-token sequence of one layer, scaled by flops
+        b = cpu_baseline_layer("config2")
+        per_tok = out["step_tflops"] * 1e12 / out["config"]["tokens"]
+        P_tok = 4.0 * (2 * 4096 * 4096 + 2 * 4096 * 1024 + 3 * 4096 * 14336) + 10.0 * 128 * 32 * 2049 / 2
+        b["value"] = b["value"] * P_tok / per_tok
+        b["sample"] = "EXTRAPOLATED by flop count from: " + b["sample"]
+        out["cpu_baseline"] = b
+    elif not args.no_cpu_baseline and args.workload != "copy":
         out["cpu_baseline"] = cpu_baseline_config3() if args.workload == "config3" else cpu_baseline_layer(args.workload)
     print(json.dumps(out))
 

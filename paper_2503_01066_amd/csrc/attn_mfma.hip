@@ -382,6 +382,139 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_dq_mfma(AttnMfmaParams p) {
         }
 }
 
+// ---------------------------------------------------------------------------------------------
+// forward: O = softmax_causal(Q K^T / sqrt(D)) V and LSE, the step of the prefill that produces the
+// O and LSE members of the record.  A work-group owns 128 queries of one (sequence, head), 32 per
+// wavefront with their Q fragments in registers, and streams 64-key tiles of K and V through LDS.
+// Scores are formed transposed (rows = keys, columns = queries) so that a lane owns one query: its
+// running maximum, normaliser and the rescaling of its output column are per-lane scalars, and P
+// in the accumulator layout is directly the right operand of O^T += V^T P^T.
+struct AttnFwdParams {
+    const __bf16 *Q, *K, *V;
+    __bf16* O;
+    float* LSE;
+    const int* cu;
+    int Hq, Hkv;
+    long long ldq, ldk;
+    float scale;
+};
+
+__global__ __launch_bounds__(256, 2) void k_attn_fwd_mfma(AttnFwdParams p) {
+    __shared__ __attribute__((aligned(1024))) char smem[2 * kStageBytes];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)ALCH_LDS(smem);
+    const int seq = blockIdx.z, h = blockIdx.y;
+    const int seq_start = p.cu[seq], len = p.cu[seq + 1] - seq_start;
+    const int nqb = (len + 127) / 128;
+    if ((int)blockIdx.x >= nqb) return;
+    const int qb = nqb - 1 - blockIdx.x;  // heaviest (last) query blocks first
+    const int lane = threadIdx.x & 63, half = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int kv = h / (p.Hq / p.Hkv);
+    const int i0 = qb * 128 + wave * 32;
+
+    const __bf16* Qb = p.Q + (long long)seq_start * p.ldq + h * kD;
+    bf16x8 qf[8];
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) qf[kk] = global_frag_d(Qb, p.ldq, i0, len, kk, lane);
+    const int i = i0 + (lane & 31);
+    f32x16 Ot[4];  // O^T: block nb holds d = nb*32 + 8b + 4*half + r (register 4b+r) of query i
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) Ot[n][e] = 0.f;
+    float m2 = -INFINITY, l = 0.f;  // running max (log2 domain) and normaliser of this lane's half of the keys
+
+    const uint32_t lane_d = frag_d_lane(lane), lane_r0 = frag_rows_lane(lane, 0), lane_r1 = frag_rows_lane(lane, 1);
+    uint32_t voff[4];
+    tile_voffsets(voff, p.ldk, wave, lane);
+    const int last_q = min(qb * 128 + 127, len - 1);
+    const int n_it = last_q / kTileRows + 1;
+    const float sl2 = p.scale * kLog2e;
+
+    auto issue = [&](int it) {
+        const int row_first = it * kTileRows, rows_valid = len - row_first;
+        const uint32_t st = lds0 + (uint32_t)(it & 1) * kStageBytes;
+        issue_rows_tile(p.K + (long long)(seq_start + row_first) * p.ldk + kv * kD, p.ldk, rows_valid, st, wave, voff);
+        issue_rows_tile(p.V + (long long)(seq_start + row_first) * p.ldk + kv * kD, p.ldk, rows_valid, st + kTileBytes, wave, voff);
+    };
+
+    issue(0);
+    for (int it = 0; it < n_it; ++it) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (it + 1 < n_it) issue(it + 1);
+        const char* tk = smem + (it & 1) * kStageBytes;
+        const char* tv = tk + kTileBytes;
+        const int jt = it * kTileRows;
+        // (a tile wholly above this wave's diagonal is computed and fully masked: p = 0, alpha = 1)
+        f32x16 St[2];
+#pragma unroll
+        for (int jb = 0; jb < 2; ++jb) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) St[jb][e] = 0.f;
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk)
+                St[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_d(tk + jb * 32 * 256, lane_d, kk), qf[kk], St[jb], 0, 0, 0);
+        }
+        // scores in the log2 domain, masked (key j = jt + jb*32 + 8b + 4*half + r must satisfy j <= i)
+        const bool need_mask = jt + 63 > i0;
+        float mx = m2;
+#pragma unroll
+        for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                float sv = St[jb][e] * sl2;
+                if (need_mask) {
+                    const int j = jt + jb * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+                    if (j > i) sv = -INFINITY;
+                }
+                St[jb][e] = sv;
+                mx = fmaxf(mx, sv);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));  // both halves of the wave share the query
+        const float alpha = __builtin_amdgcn_exp2f(m2 - mx);  // 0 on the first tile (m2 = -inf), keys 0.. always valid
+        m2 = mx;
+        float sum = 0.f;
+#pragma unroll
+        for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const float pr = __builtin_amdgcn_exp2f(St[jb][e] - mx);
+                St[jb][e] = pr;
+                sum += pr;
+            }
+        l = l * alpha + sum;
+#pragma unroll
+        for (int n = 0; n < 4; ++n)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) Ot[n][e] *= alpha;
+#pragma unroll
+        for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                const bf16x8 pf = pack8(St[jb], ks);  // right operand P^T: column = this lane's query, k <-> key rows
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb)
+                    Ot[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_rows(tv + jb * 32 * 256, lane_r0, lane_r1, ks, nb), pf, Ot[nb], 0, 0, 0);
+            }
+    }
+    l += __shfl_xor(l, 32, 64);
+    if (i < len) {
+        const float inv = 1.f / l;
+        __bf16* orow = p.O + (long long)(seq_start + i) * p.ldq + h * kD;
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                bf16x4 o;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) o[r] = (__bf16)(Ot[nb][4 * b + r] * inv);
+                *reinterpret_cast<bf16x4*>(orow + nb * 32 + 8 * b + 4 * half) = o;
+            }
+        if (half == 0) p.LSE[(long long)(seq_start + i) * p.Hq + h] = (m2 + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+    }
+}
+
 bool attn_mfma_supported(const AttnArgs& a) {
     return a.dtype == ALCH_BF16 && a.D == kD && a.T > 0 && a.ld_dqkv % 8 == 0 && aligned16(a.Q) && aligned16(a.K) &&
            aligned16(a.V) && aligned16(a.dO);
@@ -406,7 +539,23 @@ int launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t stream) {
 int launch_attn_fwd(alch_dtype dt, const void* Q, const void* K, const void* V, void* O, float* LSE, int T,
                     int n_seqs, int max_seqlen, const int* cu_seqlens, const int* cu_seqlens_host, int Hq,
                     int Hkv, int D, hipStream_t stream) {
-    (void)max_seqlen; (void)cu_seqlens_host;
+    double pairs = 0;
+    for (int s = 0; s < n_seqs; ++s) {
+        const double n = cu_seqlens_host[s + 1] - cu_seqlens_host[s];
+        pairs += n * (n + 1) / 2;
+    }
+    TraceScope ts(kTraceAttnFwd, 4.0 * D * Hq * pairs, 0.0, stream);
+    if (dt == ALCH_BF16 && D == kD && T > 0 && aligned16(Q) && aligned16(K) && aligned16(V) && aligned16(O)) {
+        AttnFwdParams p;
+        p.Q = (const __bf16*)Q; p.K = (const __bf16*)K; p.V = (const __bf16*)V; p.O = (__bf16*)O; p.LSE = LSE;
+        p.cu = cu_seqlens; p.Hq = Hq; p.Hkv = Hkv; p.ldq = (long long)Hq * D; p.ldk = (long long)Hkv * D;
+        p.scale = 1.0f / sqrtf((float)D);
+        const int nb = ceil_div(max_seqlen, 128);
+        if (nb <= 0 || n_seqs <= 0) return ALCH_OK;
+        k_attn_fwd_mfma<<<dim3(nb, Hq, n_seqs), 256, 0, stream>>>(p);
+        ALCH_HIP_TRY(hipGetLastError());
+        return ALCH_OK;
+    }
     return launch_attn_fwd_generic(dt, Q, K, V, O, LSE, T, n_seqs, cu_seqlens, Hq, Hkv, D, stream);
 }
 
