@@ -178,48 +178,48 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
         if (wave == 1) issue_row_scalars(p.delta + (long long)(seq_start + row_first) * p.Hq + h, p.Hq, rows_valid, st + 2 * kTileBytes + 256, lane);
     };
 
-#ifdef ALCH_ATTN_TIMING
-    long long tph[6] = {0, 0, 0, 0, 0, 0}, tt0, tt1;
-#define ALCH_T0() tt0 = __builtin_readcyclecounter()
-#define ALCH_T(i) tt1 = __builtin_readcyclecounter(); tph[i] += tt1 - tt0; tt0 = tt1
-#else
-#define ALCH_T0()
-#define ALCH_T(i)
-#endif
+    // One iteration = one 64-query tile = two 32-query blocks.  The two blocks are interleaved by hand
+    // so that independent work sits next to each other in program order (the wave issues in order):
+    //   LDS reads(0), LDS reads(1) | S/dP MFMAs(0) | S/dP MFMAs(1) | softmax(0) under the MFMAs of (1)
+    //   | dV/dK MFMAs(0) | softmax(1) under them | dV/dK MFMAs(1); the next tile's loads go out in between.
     issue(0);
     for (int it = 0; it < n_it; ++it) {
-        ALCH_T0();
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        ALCH_T(0);
-        if (it + 1 < n_it) issue(it + 1);
-        ALCH_T(1);
         const int qt = qt0 + it % nqt;
         const char* tq = smem + (it & 1) * kStageBytes;
         const char* tdo = tq + kTileBytes;
         const float* lse_s = reinterpret_cast<const float*>(tq + 2 * kTileBytes);
         const float* del_s = lse_s + 64;
+        const int i00 = qt * kTileRows;
+
+        bf16x8 fq[2][8], fdo[2][8];
 #pragma unroll
-        for (int ib = 0; ib < 2; ++ib) {
-            const int i0 = qt * kTileRows + ib * 32;  // first query of the block (inside the sequence)
-            // (blocks wholly above the diagonal are computed too and masked to zero: a branch around
-            //  the block would make the compiler shuffle the 128 accumulator registers at the join)
-            const char* bq = tq + ib * 32 * 256;
-            const char* bdo = tdo + ib * 32 * 256;
-            f32x16 S, dP;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) S[e] = dP[e] = 0.f;
+        for (int ib = 0; ib < 2; ++ib)
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk) {
-                S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_d(bq, lane_d, kk), kf[kk], S, 0, 0, 0);
-                dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_d(bdo, lane_d, kk), vf[kk], dP, 0, 0, 0);
+                fq[ib][kk] = lds_frag_d(tq + ib * 32 * 256, lane_d, kk);
+                fdo[ib][kk] = lds_frag_d(tdo + ib * 32 * 256, lane_d, kk);
             }
-#ifdef ALCH_ATTN_TIMING
-            asm volatile("s_nop 0" :: "v"(S[0]), "v"(dP[0]));
-#endif
-            ALCH_T(2);
+        __builtin_amdgcn_sched_barrier(0);
+        f32x16 S[2], dP[2];
+#pragma unroll
+        for (int ib = 0; ib < 2; ++ib) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) S[ib][e] = dP[ib][e] = 0.f;
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) {
+                S[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[ib][kk], kf[kk], S[ib], 0, 0, 0);
+                dP[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fdo[ib][kk], vf[kk], dP[ib], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (it + 1 < n_it) issue(it + 1);  // the other stage is free since the barrier
+        __builtin_amdgcn_sched_barrier(0);
+
+        auto softmax = [&](int ib) {
             // accumulator element e: query row i0 + 8*(e>>2) + 4*half + (e&3), key column j0 + (lane&31)
-            const bool need_mask = (i0 < j0 + 31) || (i0 + 32 > len);
+            const int i0 = i00 + ib * 32;
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_s + ib * 32 + 8 * b + 4 * half);
@@ -227,41 +227,43 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int e = 4 * b + r;
-                    const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(S[e], sl2, -l4[r] * kLog2e));
-                    S[e] = pr;
-                    dP[e] = pr * (dP[e] - d4[r]);
+                    const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(S[ib][e], sl2, -l4[r] * kLog2e));
+                    S[ib][e] = pr;
+                    dP[ib][e] = pr * (dP[ib][e] - d4[r]);
                 }
             }
-            if (need_mask) {
+            // blocks wholly above the diagonal are computed too and masked to zero (a branch around a
+            // block would make the compiler shuffle the 128 accumulator registers at the join)
+            if ((i0 < j0 + 31) || (i0 + 32 > len)) {
                 const int j = j0 + (lane & 31);
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const int i = i0 + 8 * (e >> 2) + 4 * half + (e & 3);
-                    if (j > i || i >= len) S[e] = dP[e] = 0.f;
+                    if (j > i || i >= len) S[ib][e] = dP[ib][e] = 0.f;
                 }
             }
-            ALCH_T(3);
+        };
+        auto accumulate = [&](int ib) {
+            const char* bq = tq + ib * 32 * 256;
+            const char* bdo = tdo + ib * 32 * 256;
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
-                const bf16x8 pf = pack8(S, ks), dsf = pack8(dP, ks);
+                const bf16x8 pf = pack8(S[ib], ks), dsf = pack8(dP[ib], ks);
 #pragma unroll
                 for (int nb = 0; nb < 4; ++nb) {
                     dV[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, lds_frag_rows(bdo, lane_r0, lane_r1, ks, nb), dV[nb], 0, 0, 0);
                     dK[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf, lds_frag_rows(bq, lane_r0, lane_r1, ks, nb), dK[nb], 0, 0, 0);
                 }
             }
-#ifdef ALCH_ATTN_TIMING
-            asm volatile("s_nop 0" :: "v"(dK[3][0]), "v"(dV[3][0]));
-#endif
-            ALCH_T(4);
-        }
+        };
+        softmax(0);
+        __builtin_amdgcn_sched_barrier(0);
+        accumulate(0);
+        __builtin_amdgcn_sched_barrier(0);
+        softmax(1);
+        __builtin_amdgcn_sched_barrier(0);
+        accumulate(1);
     }
-#ifdef ALCH_ATTN_TIMING
-    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) {
-        for (int i = 0; i < 5; ++i) g_attn_stamps[i] = tph[i];
-        g_attn_stamps[5] = n_it;
-    }
-#endif
 
     // accumulator element e of block nb: key row j0 + 8*(e>>2) + 4*half + (e&3), column nb*32 + (lane&31)
     __bf16* dKb = p.dK + (long long)seq_start * p.ldo + kv * kD;
