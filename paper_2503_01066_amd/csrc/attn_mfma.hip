@@ -180,7 +180,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
 
     // One iteration = one 64-query tile = two 32-query blocks.  The two blocks are interleaved by hand
     // so that independent work sits next to each other in program order (the wave issues in order):
-    //   LDS reads(0), LDS reads(1) | S/dP MFMAs(0) | S/dP MFMAs(1) | softmax(0) under the MFMAs of (1)
+    //   LDS reads + S/dP MFMAs(0) | LDS reads + S/dP MFMAs(1) | softmax(0)
     //   | dV/dK MFMAs(0) | softmax(1) under them | dV/dK MFMAs(1); the next tile's loads go out in between.
     issue(0);
     for (int it = 0; it < n_it; ++it) {
@@ -193,27 +193,24 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
         const float* del_s = lse_s + 64;
         const int i00 = qt * kTileRows;
 
-        bf16x8 fq[2][8], fdo[2][8];
-#pragma unroll
-        for (int ib = 0; ib < 2; ++ib)
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk) {
-                fq[ib][kk] = lds_frag_d(tq + ib * 32 * 256, lane_d, kk);
-                fdo[ib][kk] = lds_frag_d(tdo + ib * 32 * 256, lane_d, kk);
-            }
-        __builtin_amdgcn_sched_barrier(0);
         f32x16 S[2], dP[2];
 #pragma unroll
         for (int ib = 0; ib < 2; ++ib) {
+            bf16x8 fq[8], fdo[8];
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) {
+                fq[kk] = lds_frag_d(tq + ib * 32 * 256, lane_d, kk);
+                fdo[kk] = lds_frag_d(tdo + ib * 32 * 256, lane_d, kk);
+            }
 #pragma unroll
             for (int e = 0; e < 16; ++e) S[ib][e] = dP[ib][e] = 0.f;
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk) {
-                S[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[ib][kk], kf[kk], S[ib], 0, 0, 0);
-                dP[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fdo[ib][kk], vf[kk], dP[ib], 0, 0, 0);
+                S[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[kk], kf[kk], S[ib], 0, 0, 0);
+                dP[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fdo[kk], vf[kk], dP[ib], 0, 0, 0);
             }
-            __builtin_amdgcn_sched_barrier(0);
         }
+        __builtin_amdgcn_sched_barrier(0);
         if (it + 1 < n_it) issue(it + 1);  // the other stage is free since the barrier
         __builtin_amdgcn_sched_barrier(0);
 
