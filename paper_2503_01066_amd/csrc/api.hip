@@ -288,8 +288,7 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
         ALCH_TRY(launch_gemm(d, st));
     }
 
-    // attention backward from saved Q, K, V, O, LSE -> [dQ | dK | dV], then RoPE backward on dQ, dK
-    ALCH_TRY(launch_attn_delta(dt, p.dO, sv.O, p.delta, T, s.n_q_heads, D, st));
+    // attention backward from saved Q, K, V, O, LSE -> [dQ | dK | dV] with RoPE backward applied to dQ, dK
     {
         AttnArgs a;
         a.dtype = dt; a.T = T; a.n_seqs = b.n_seqs; a.max_seqlen = b.max_seqlen;
@@ -297,10 +296,9 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
         a.cu_seqlens = b.cu_seqlens; a.cu_seqlens_host = b.cu_seqlens_host;
         a.Q = sv.Q; a.K = sv.K; a.V = sv.V; a.O = sv.O; a.dO = p.dO; a.LSE = sv.LSE; a.delta = p.delta;
         a.dQ = p.dQKV; a.dK = at(p.dQKV, QD, E); a.dV = at(p.dQKV, QD + KD, E); a.ld_dqkv = QKV;
+        a.positions = b.positions; a.rope_base = s.rope_base;
         ALCH_TRY(launch_attn_bwd(a, st));
     }
-    ALCH_TRY(launch_rope(dt, p.dQKV, QKV, T, s.n_q_heads + s.n_kv_heads, D, b.positions, b.cu_seqlens, b.n_seqs,
-                         s.rope_base, -1.f, st));
 
     {  // dH1 = dQ Wq + dK Wk + dV Wv
         GemmDesc d = gemm(dt, T, H, true, false);
@@ -345,8 +343,13 @@ int launch_attn_bwd(const AttnArgs& a, hipStream_t stream) {
         pairs += n * (n + 1) / 2;
     }
     TraceScope ts(kTraceAttnBwd, 10.0 * a.D * a.Hq * pairs, 0.0, stream);
-    if (attn_mfma_supported(a)) return launch_attn_bwd_mfma(a, stream);
-    return launch_attn_bwd_generic(a, stream);
+    if (attn_mfma_supported(a)) return launch_attn_bwd_mfma(a, stream);  // delta and RoPE backward fused
+    ALCH_TRY(launch_attn_delta(a.dtype, a.dO, a.O, a.delta, a.T, a.Hq, a.D, stream));
+    ALCH_TRY(launch_attn_bwd_generic(a, stream));
+    if (a.rope_base > 0.f)
+        ALCH_TRY(launch_rope(a.dtype, a.dQ, a.ld_dqkv, a.T, a.Hq + a.Hkv, a.D, a.positions, a.cu_seqlens, a.n_seqs,
+                             a.rope_base, -1.f, stream));
+    return ALCH_OK;
 }
 
 }  // namespace alch

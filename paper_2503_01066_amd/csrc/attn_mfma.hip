@@ -34,14 +34,39 @@ static constexpr int kStageBytes = 2 * kTileBytes + 1024;  // two tiles + two 64
 static constexpr float kLog2e = 1.4426950408889634f;
 
 struct AttnMfmaParams {
-    const __bf16 *Q, *K, *V, *dO;
-    const float *LSE, *delta;
+    const __bf16 *Q, *K, *V, *O, *dO;
+    const float* LSE;
+    float* delta;  // written by the dQ kernel (row sums of dO*O), read by the dK/dV kernel
     __bf16 *dQ, *dK, *dV;
     const int* cu;
+    const int* positions;  // RoPE positions per token, or null: index inside the sequence
     int Hq, Hkv;
     long long ldq, ldk, ldo;  // row strides (elements) of Q/dO, K/V, and of the outputs
     float scale;
+    float rope_log2_base;  // > 0: rotate dQ, dK by minus the RoPE angle before they are stored
 };
+
+// RoPE backward on one accumulator set: block nb (< 2) holds element d = nb*32 + (lane&31) of a head,
+// block nb + 2 its partner d + 64; x'[d] = x[d] cos a + x[d+64] sin a, x'[d+64] = x[d+64] cos a - x[d] sin a
+// with a = pos * base^(-2d/128).
+__device__ __forceinline__ void rope_backward_rows(f32x16 (&x)[4], const AttnMfmaParams& p, int seq_start, int row0,
+                                                  int len, int lane) {
+    const int half = lane >> 5;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        const float theta = __builtin_amdgcn_exp2f(-(float)(nb * 32 + (lane & 31)) * (2.0f / kD) * p.rope_log2_base);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int r = row0 + 8 * (e >> 2) + 4 * half + (e & 3);
+            const int pos = (p.positions && r < len) ? p.positions[seq_start + r] : r;
+            float sn, cs;
+            __sincosf((float)pos * theta, &sn, &cs);
+            const float a = x[nb][e], b = x[nb + 2][e];
+            x[nb][e] = a * cs + b * sn;
+            x[nb + 2][e] = b * cs - a * sn;
+        }
+    }
+}
 
 __device__ __forceinline__ i32x4 rsrc_of(const void* p, long long bytes) {
     const uint32_t n = bytes <= 0 ? 0u : (bytes > 0x7fffffffLL ? 0x7fffffffu : (uint32_t)bytes);
@@ -263,6 +288,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
     }
 
     // accumulator element e of block nb: key row j0 + 8*(e>>2) + 4*half + (e&3), column nb*32 + (lane&31)
+    if (p.rope_log2_base > 0.f) rope_backward_rows(dK, p, seq_start, j0, len, lane);
     __bf16* dKb = p.dK + (long long)seq_start * p.ldo + kv * kD;
     __bf16* dVb = p.dV + (long long)seq_start * p.ldo + kv * kD;
 #pragma unroll
@@ -305,7 +331,19 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_dq_mfma(AttnMfmaParams p) {
     const int i = i0 + (lane & 31);  // this lane's query (accumulator column)
     const bool i_ok = i < len;
     const float lse2 = i_ok ? p.LSE[(long long)(seq_start + i) * p.Hq + h] * kLog2e : 0.f;
-    const float del = i_ok ? p.delta[(long long)(seq_start + i) * p.Hq + h] : 0.f;
+    // delta_i = sum_d dO[i,d] O[i,d]: each lane holds 64 of the 128 elements of its query's dO row
+    float del = 0.f;
+    {
+        const __bf16* Ob = p.O + (long long)seq_start * p.ldq + h * kD;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            const bf16x8 of = global_frag_d(Ob, p.ldq, i0, len, kk, lane);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) del += (float)of[e] * (float)gf[kk][e];
+        }
+        del += __shfl_xor(del, 32, 64);
+        if (i_ok && half == 0) p.delta[(long long)(seq_start + i) * p.Hq + h] = del;
+    }
     f32x16 dQ[4];
 #pragma unroll
     for (int n = 0; n < 4; ++n)
@@ -371,6 +409,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_dq_mfma(AttnMfmaParams p) {
         }
     }
 
+    if (p.rope_log2_base > 0.f) rope_backward_rows(dQ, p, seq_start, i0, len, lane);
     __bf16* dQb = p.dQ + (long long)seq_start * p.ldo + h * kD;
 #pragma unroll
     for (int nb = 0; nb < 4; ++nb)
@@ -516,21 +555,22 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd_mfma(AttnFwdParams p) {
 
 bool attn_mfma_supported(const AttnArgs& a) {
     return a.dtype == ALCH_BF16 && a.D == kD && a.T > 0 && a.ld_dqkv % 8 == 0 && aligned16(a.Q) && aligned16(a.K) &&
-           aligned16(a.V) && aligned16(a.dO);
+           aligned16(a.V) && aligned16(a.dO) && aligned16(a.O);
 }
 
 int launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t stream) {
     AttnMfmaParams p;
     p.Q = (const __bf16*)a.Q; p.K = (const __bf16*)a.K; p.V = (const __bf16*)a.V; p.dO = (const __bf16*)a.dO;
-    p.LSE = a.LSE; p.delta = a.delta;
+    p.O = (const __bf16*)a.O; p.LSE = a.LSE; p.delta = a.delta;
+    p.positions = a.positions; p.rope_log2_base = a.rope_base > 0.f ? log2f(a.rope_base) : 0.f;
     p.dQ = (__bf16*)a.dQ; p.dK = (__bf16*)a.dK; p.dV = (__bf16*)a.dV;
     p.cu = a.cu_seqlens; p.Hq = a.Hq; p.Hkv = a.Hkv;
     p.ldq = (long long)a.Hq * a.D; p.ldk = (long long)a.Hkv * a.D; p.ldo = a.ld_dqkv;
     p.scale = 1.0f / sqrtf((float)a.D);
     const int nb = ceil_div(a.max_seqlen, 128);
     if (nb <= 0 || a.n_seqs <= 0) return ALCH_OK;
+    k_attn_bwd_dq_mfma<<<dim3(nb, a.Hq, a.n_seqs), 256, 0, stream>>>(p);   // also writes delta
     k_attn_bwd_dkv_mfma<<<dim3(nb, a.Hkv, a.n_seqs), 256, 0, stream>>>(p);
-    k_attn_bwd_dq_mfma<<<dim3(nb, a.Hq, a.n_seqs), 256, 0, stream>>>(p);
     ALCH_HIP_TRY(hipGetLastError());
     return ALCH_OK;
 }

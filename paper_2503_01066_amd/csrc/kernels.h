@@ -6,7 +6,7 @@ namespace alch {
 
 // ---- capture/pack ----------------------------------------------------------------------
 static constexpr int kMaxStreamsPerLaunch = 16;
-static constexpr int kGatherGrid = 256 * 8;  // persistent work-groups: 8 per compute unit
+static constexpr int kGatherGridMax = 1 << 20;  // one work-group per candidate row, capped
 size_t pack_workspace_bytes(int total_tokens);
 int launch_pack(const uint8_t* mask, int T, const int* cu_seqlens, int n_seqs, int n_streams,
                 const alch_stream* streams, long long capacity, int* kept_index, int* cu_kept,
@@ -90,9 +90,12 @@ struct AttnArgs {
     const int* cu_seqlens_host;  // host
     const void *Q, *K, *V, *O, *dO;  // dense [T, heads*D]
     const float* LSE;                // [T, Hq]
-    const float* delta;              // [T, Hq]
-    void *dQ, *dK, *dV;              // row stride ld_dqkv elements
+    float* delta;                    // scratch [T, Hq]: row sums of dO*O, produced inside launch_attn_bwd
+    void *dQ, *dK, *dV;              // row stride ld_dqkv elements; dQ, dK, dV adjacent: [dQ | dK | dV] rows
     long long ld_dqkv;
+    // rope_base > 0: dQ and dK come out already rotated by minus the RoPE angle (RoPE backward)
+    const int* positions = nullptr;  // device [T] or null (index inside the sequence)
+    float rope_base = 0.f;
 };
 int launch_attn_bwd(const AttnArgs& a, hipStream_t stream);
 int launch_attn_bwd_generic(const AttnArgs& a, hipStream_t stream);

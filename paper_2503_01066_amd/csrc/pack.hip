@@ -2,8 +2,8 @@
 // prefill that are to be trained on are recorded; Section 5: one record per layer).
 //
 // The scan is three small kernels over the byte mask (per-block popcount, scan of the
-// block counts, index fill); the gather is a persistent grid of work-groups, one kept
-// row at a time, moving 16 bytes per lane per access.  Everything is bit-exact and
+// block counts, index fill); the gather runs one work-group per kept row,
+// moving 16 bytes per lane per access.  Everything is bit-exact and
 // deterministic: the output order is the ascending token order.
 #include "common.h"
 #include "kernels.h"
@@ -132,6 +132,9 @@ struct GatherArgs {
     int n;
 };
 
+// One work-group per kept row (the grid is sized for the most rows the call can produce; work-groups
+// beyond n_kept leave at once).  Letting the hardware dispatcher hand out rows measured faster than a
+// persistent grid: the rows of the wide streams are long enough to keep every lane busy.
 template <typename V>
 __global__ __launch_bounds__(256) void k_pack_gather(GatherArgs a, const int* __restrict__ kept_index,
                                                      const int* __restrict__ n_kept_and_status,
@@ -146,16 +149,12 @@ __global__ __launch_bounds__(256) void k_pack_gather(GatherArgs a, const int* __
             const char* __restrict__ s = a.src[k] + (unsigned long long)t * a.src_stride[k];
             char* __restrict__ d = a.dst[k] + (unsigned long long)r * rb;
             unsigned long long off = (unsigned long long)threadIdx.x * sizeof(V);
-            // four independent accesses in flight per lane
-            for (; off + 3 * kStep < rb; off += 4 * kStep) {
+            // two independent accesses in flight per lane; non-temporal both ways (nothing is reused)
+            for (; off + kStep < rb; off += 2 * kStep) {
                 V v0 = __builtin_nontemporal_load(reinterpret_cast<const V*>(s + off));
                 V v1 = __builtin_nontemporal_load(reinterpret_cast<const V*>(s + off + kStep));
-                V v2 = __builtin_nontemporal_load(reinterpret_cast<const V*>(s + off + 2 * kStep));
-                V v3 = __builtin_nontemporal_load(reinterpret_cast<const V*>(s + off + 3 * kStep));
                 __builtin_nontemporal_store(v0, reinterpret_cast<V*>(d + off));
                 __builtin_nontemporal_store(v1, reinterpret_cast<V*>(d + off + kStep));
-                __builtin_nontemporal_store(v2, reinterpret_cast<V*>(d + off + 2 * kStep));
-                __builtin_nontemporal_store(v3, reinterpret_cast<V*>(d + off + 3 * kStep));
             }
             for (; off < rb; off += kStep) {
                 V v = __builtin_nontemporal_load(reinterpret_cast<const V*>(s + off));
@@ -194,7 +193,7 @@ int launch_pack(const uint8_t* mask, int T, const int* cu_seqlens, int n_seqs, i
     TraceScope ts(kTracePackGather, 0.0, row_bytes_rw, stream);
 
     long long max_rows = (long long)T < capacity ? (long long)T : capacity;
-    int grid = (int)(max_rows < (long long)kGatherGrid ? max_rows : (long long)kGatherGrid);
+    int grid = (int)(max_rows < (long long)kGatherGridMax ? max_rows : (long long)kGatherGridMax);
     for (int base = 0; base < n_streams; base += kMaxStreamsPerLaunch) {
         GatherArgs a;
         a.n = n_streams - base < kMaxStreamsPerLaunch ? n_streams - base : kMaxStreamsPerLaunch;
