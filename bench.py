@@ -68,7 +68,7 @@ def cpu_baseline_layer(workload, seed=0):
                       % (S, shape_name, dt)}
 
 
-def cpu_baseline_config3(seed=0, layers=16):
+def cpu_baseline_config3(seed=0, layers=3):
     """The gather oracle, as it stands, on the config-3 batch for a bounded number of layers."""
     import synth_inputs as synth
     from oracle import gather_pack
