@@ -41,9 +41,63 @@ __global__ __launch_bounds__(256) void k_rmsnorm_fwd(const T* __restrict__ X, co
     for (int c = threadIdx.x; c < width; c += 256) stf(H + row * width + c, ldf(x + c) * r * ldf(g + c));
 }
 
+// bf16 fast path: one wavefront per row, 16-byte accesses (lane l owns the 8-column chunks k*64 + l)
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_f;
+template <int NC>
+__global__ __launch_bounds__(256) void k_rmsnorm_fwd_bf16(const __bf16* __restrict__ X, const __bf16* __restrict__ g,
+                                                          __bf16* __restrict__ H, int Trows, int width, float eps) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    bf16x8_f gv[NC];
+#pragma unroll
+    for (int k = 0; k < NC; ++k) {
+        const int col = (k * 64 + lane) * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) gv[k][e] = (__bf16)0.f;
+        if (col < width) gv[k] = *reinterpret_cast<const bf16x8_f*>(g + col);
+    }
+    const float inv_w = 1.f / (float)width;
+    for (long long row = (long long)blockIdx.x * 4 + wave; row < Trows; row += (long long)gridDim.x * 4) {
+        bf16x8_f xv[NC];
+        float ss = 0.f;
+#pragma unroll
+        for (int k = 0; k < NC; ++k) {
+            const int col = (k * 64 + lane) * 8;
+            if (col < width) {
+                xv[k] = *reinterpret_cast<const bf16x8_f*>(X + row * width + col);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ss += (float)xv[k][e] * (float)xv[k][e];
+            }
+        }
+        ss = wave_sum(ss);
+        const float r = rsqrtf(ss * inv_w + eps);
+#pragma unroll
+        for (int k = 0; k < NC; ++k) {
+            const int col = (k * 64 + lane) * 8;
+            if (col < width) {
+                bf16x8_f o;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = (__bf16)((float)xv[k][e] * r * (float)gv[k][e]);
+                *reinterpret_cast<bf16x8_f*>(H + row * width + col) = o;
+            }
+        }
+    }
+}
+
 int launch_rmsnorm_fwd(alch_dtype dt, const void* X, const void* g, void* H, int T, int width, float eps,
                        hipStream_t stream) {
     if (T <= 0) return ALCH_OK;
+    if (dt == ALCH_BF16 && width % 8 == 0 && width <= 8192 && aligned16(X) && aligned16(g) && aligned16(H)) {
+        const int nblk = ceil_div(T, 4) < 2048 ? ceil_div(T, 4) : 2048;
+#define ALCH_NORM_FWD(NC) \
+    k_rmsnorm_fwd_bf16<NC><<<nblk, 256, 0, stream>>>((const __bf16*)X, (const __bf16*)g, (__bf16*)H, T, width, eps)
+        if (width <= 1024) ALCH_NORM_FWD(2);
+        else if (width <= 2048) ALCH_NORM_FWD(4);
+        else if (width <= 4096) ALCH_NORM_FWD(8);
+        else ALCH_NORM_FWD(16);
+#undef ALCH_NORM_FWD
+        ALCH_HIP_TRY(hipGetLastError());
+        return ALCH_OK;
+    }
     if (dt == ALCH_BF16)
         k_rmsnorm_fwd<__bf16><<<T, 256, 0, stream>>>((const __bf16*)X, (const __bf16*)g, (__bf16*)H, width, eps);
     else
