@@ -162,9 +162,13 @@ __device__ __forceinline__ bf16x8 global_frag_d(const __bf16* base, long long ld
 __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
     __shared__ __attribute__((aligned(1024))) char smem[2 * kStageBytes];
     const uint32_t lds0 = (uint32_t)(uintptr_t)ALCH_LDS(smem);
-    const int seq = blockIdx.z, kv = blockIdx.y, kb = blockIdx.x;
+    // Work-groups are handed out in order of blockIdx.z first, so z counts the work down: a key block
+    // with `rem` blocks of queries at or after it costs rem units, and the heaviest of all sequences
+    // and heads start first (longest-processing-time-first keeps the last compute units busy).
+    const int seq = blockIdx.y, kv = blockIdx.x;
     const int seq_start = p.cu[seq], len = p.cu[seq + 1] - seq_start;
-    if (kb * 128 >= len) return;
+    const int rem = (int)gridDim.z - (int)blockIdx.z, kb = (len + 127) / 128 - rem;
+    if (kb < 0) return;
     const int lane = threadIdx.x & 63, half = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int G = p.Hq / p.Hkv;
@@ -309,12 +313,11 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
 __global__ __launch_bounds__(256, 2) void k_attn_bwd_dq_mfma(AttnMfmaParams p) {
     __shared__ __attribute__((aligned(1024))) char smem[2 * kStageBytes];
     const uint32_t lds0 = (uint32_t)(uintptr_t)ALCH_LDS(smem);
-    const int seq = blockIdx.z, h = blockIdx.y;
+    const int seq = blockIdx.y, h = blockIdx.x;
     const int seq_start = p.cu[seq], len = p.cu[seq + 1] - seq_start;
-    // heaviest (last) query blocks first
-    const int nqb = (len + 127) / 128;
-    if ((int)blockIdx.x >= nqb) return;
-    const int qb = nqb - 1 - blockIdx.x;
+    // heaviest (last) query blocks of every sequence and head first: blockIdx.z is the slowest index
+    const int qb = (int)gridDim.z - 1 - (int)blockIdx.z;
+    if (qb * 128 >= len) return;
     const int lane = threadIdx.x & 63, half = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int kv = h / (p.Hq / p.Hkv);
@@ -440,11 +443,11 @@ struct AttnFwdParams {
 __global__ __launch_bounds__(256, 2) void k_attn_fwd_mfma(AttnFwdParams p) {
     __shared__ __attribute__((aligned(1024))) char smem[2 * kStageBytes];
     const uint32_t lds0 = (uint32_t)(uintptr_t)ALCH_LDS(smem);
-    const int seq = blockIdx.z, h = blockIdx.y;
+    const int seq = blockIdx.y, h = blockIdx.x;
     const int seq_start = p.cu[seq], len = p.cu[seq + 1] - seq_start;
-    const int nqb = (len + 127) / 128;
-    if ((int)blockIdx.x >= nqb) return;
-    const int qb = nqb - 1 - blockIdx.x;  // heaviest (last) query blocks first
+    // heaviest (last) query blocks of every sequence and head first: blockIdx.z is the slowest index
+    const int qb = (int)gridDim.z - 1 - (int)blockIdx.z;
+    if (qb * 128 >= len) return;
     const int lane = threadIdx.x & 63, half = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int kv = h / (p.Hq / p.Hkv);
@@ -569,8 +572,9 @@ int launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t stream) {
     p.scale = 1.0f / sqrtf((float)a.D);
     const int nb = ceil_div(a.max_seqlen, 128);
     if (nb <= 0 || a.n_seqs <= 0) return ALCH_OK;
-    k_attn_bwd_dq_mfma<<<dim3(nb, a.Hq, a.n_seqs), 256, 0, stream>>>(p);   // also writes delta
-    k_attn_bwd_dkv_mfma<<<dim3(nb, a.Hkv, a.n_seqs), 256, 0, stream>>>(p);
+    if (nb > 65535 || a.n_seqs > 65535) return fail(ALCH_ERR_UNSUPPORTED, "attention: more than 65535 sequences or 128-token blocks");
+    k_attn_bwd_dq_mfma<<<dim3(a.Hq, a.n_seqs, nb), 256, 0, stream>>>(p);   // also writes delta
+    k_attn_bwd_dkv_mfma<<<dim3(a.Hkv, a.n_seqs, nb), 256, 0, stream>>>(p);
     ALCH_HIP_TRY(hipGetLastError());
     return ALCH_OK;
 }
@@ -591,7 +595,8 @@ int launch_attn_fwd(alch_dtype dt, const void* Q, const void* K, const void* V, 
         p.scale = 1.0f / sqrtf((float)D);
         const int nb = ceil_div(max_seqlen, 128);
         if (nb <= 0 || n_seqs <= 0) return ALCH_OK;
-        k_attn_fwd_mfma<<<dim3(nb, Hq, n_seqs), 256, 0, stream>>>(p);
+        if (nb > 65535 || n_seqs > 65535) return fail(ALCH_ERR_UNSUPPORTED, "attention: more than 65535 sequences or 128-token blocks");
+        k_attn_fwd_mfma<<<dim3(Hq, n_seqs, nb), 256, 0, stream>>>(p);
         ALCH_HIP_TRY(hipGetLastError());
         return ALCH_OK;
     }
