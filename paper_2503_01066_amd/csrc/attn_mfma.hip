@@ -160,7 +160,7 @@ __device__ __forceinline__ bf16x8 global_frag_d(const __bf16* base, long long ld
 // ---------------------------------------------------------------------------------------------
 // dK / dV
 __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
-    __shared__ __attribute__((aligned(1024))) char smem[2 * kStageBytes];
+    __shared__ __attribute__((aligned(1024))) char smem[3 * kStageBytes];
     const uint32_t lds0 = (uint32_t)(uintptr_t)ALCH_LDS(smem);
     // Work-groups are handed out in order of blockIdx.z first, so z counts the work down: a key block
     // with `rem` blocks of queries at or after it costs rem units, and the heaviest of all sequences
@@ -197,99 +197,192 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
     const int n_it = G * nqt;
     const float sl2 = p.scale * kLog2e;
 
+    // Tile `it` of the stream (query head it / nqt of the group, 64-query tile qt0 + it % nqt) goes to
+    // stage it % 3.  Beyond the end of the stream the loads are issued with zero extent: they move
+    // nothing and keep every wave's count of outstanding loads the same.
     auto issue = [&](int it) {
         const int h = kv * G + it / nqt, qt = qt0 + it % nqt;
-        const int row_first = qt * kTileRows, rows_valid = len - row_first;
-        const uint32_t st = lds0 + (uint32_t)(it & 1) * kStageBytes;
+        const int row_first = qt * kTileRows, rows_valid = it < n_it ? len - row_first : 0;
+        const uint32_t st = lds0 + (uint32_t)(it % 3) * kStageBytes;
         issue_rows_tile(p.Q + (long long)(seq_start + row_first) * p.ldq + h * kD, p.ldq, rows_valid, st, wave, voff);
         issue_rows_tile(p.dO + (long long)(seq_start + row_first) * p.ldq + h * kD, p.ldq, rows_valid, st + kTileBytes, wave, voff);
         if (wave == 0) issue_row_scalars(p.LSE + (long long)(seq_start + row_first) * p.Hq + h, p.Hq, rows_valid, st + 2 * kTileBytes, lane);
         if (wave == 1) issue_row_scalars(p.delta + (long long)(seq_start + row_first) * p.Hq + h, p.Hq, rows_valid, st + 2 * kTileBytes + 256, lane);
     };
 
-    // One iteration = one 64-query tile = two 32-query blocks.  The two blocks are interleaved by hand
-    // so that independent work sits next to each other in program order (the wave issues in order):
-    //   LDS reads + S/dP MFMAs(0) | LDS reads + S/dP MFMAs(1) | softmax(0)
-    //   | dV/dK MFMAs(0) | softmax(1) under them | dV/dK MFMAs(1); the next tile's loads go out in between.
+    // Software pipeline over the tile stream, three LDS stages.  At the top of iteration `it` the
+    // scores S = Q K^T and dP = dO V^T of tile `it` are already in registers.  The iteration
+    //   1. turns them into P and dS (exp, mask, pack to bf16) -- vector ALU only;
+    //   2. waits for tile it+1, meets the other waves, and sends the loads of tile it+2 into the stage
+    //      that tile it-1 occupied (every wave is past its reads of it);
+    //   3. runs 64 matrix instructions back to back: dV += P^T dO and dK += dS^T Q of tile `it`
+    //      interleaved with S and dP of tile it+1, so the transposing LDS reads of one and the row reads
+    //      of the other are both covered by independent matrix work.
+    f32x16 S[2], dP[2];
     issue(0);
+    issue(1);
+    if (wave < 2)
+        asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
+    else
+        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    __syncthreads();
+#pragma unroll
+    for (int ib = 0; ib < 2; ++ib) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) S[ib][e] = dP[ib][e] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            S[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_d(smem + ib * 32 * 256, lane_d, kk), kf[kk], S[ib], 0, 0, 0);
+            dP[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_d(smem + kTileBytes + ib * 32 * 256, lane_d, kk), vf[kk], dP[ib], 0, 0, 0);
+        }
+    }
+
+#ifdef ALCH_ATTN_TIMING
+    const bool stamp = blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0;
+    long long acc_t[4] = {0, 0, 0, 0};
+    const long long k_t0 = __builtin_readcyclecounter(), k_r0 = __builtin_amdgcn_s_memrealtime();
+#define ALCH_STAMP(i) { const long long t_now = __builtin_readcyclecounter(); acc_t[i] += t_now - t_prev; t_prev = t_now; }
+#else
+#define ALCH_STAMP(i)
+#endif
+    // stream state, advanced by one tile per iteration (no divisions in the loop):
+    // LDS byte offsets of the stages of tiles it, it+1, it+2 and (head, tile) of tile it and it+2
+    uint32_t s_cur = 0, s_nxt = kStageBytes, s_ld = 2 * kStageBytes;
+    int qt_cur = qt0;
+    int h_ld = kv * G + 2 / nqt, qt_ld = qt0 + 2 % nqt;
+    const int jl = j0 + (lane & 31);  // this lane's key
+    const unsigned live = (unsigned)max(len - jl, 0);
     for (int it = 0; it < n_it; ++it) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        const int qt = qt0 + it % nqt;
-        const char* tq = smem + (it & 1) * kStageBytes;
+#ifdef ALCH_ATTN_TIMING
+        long long t_prev = __builtin_readcyclecounter();
+#endif
+        const char* tq = smem + s_cur;
         const char* tdo = tq + kTileBytes;
         const float* lse_s = reinterpret_cast<const float*>(tq + 2 * kTileBytes);
         const float* del_s = lse_s + 64;
-        const int i00 = qt * kTileRows;
+        const int i00 = qt_cur * kTileRows;
 
-        f32x16 S[2], dP[2];
+        // P, dS of accumulator elements e0 .. e0+n-1 of block ib, in place in S, dP.
+        // element e: query row i = i00 + 32*ib + 8*(e>>2) + 4*half + (e&3), key column jl.  Pairs above
+        // the diagonal (jl > i) and rows or keys past the end of the sequence get exponent -inf, i.e.
+        // p = 0 exactly: with rel = i - jl that is one unsigned test, rel >= max(len - jl, 0).
+        const int rel0 = i00 + 4 * half - jl;
+        auto softmax_part = [&](int ib, const f32x4 (&l4)[4], const f32x4 (&d4)[4], int e0, int n) {
 #pragma unroll
-        for (int ib = 0; ib < 2; ++ib) {
-            bf16x8 fq[8], fdo[8];
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk) {
-                fq[kk] = lds_frag_d(tq + ib * 32 * 256, lane_d, kk);
-                fdo[kk] = lds_frag_d(tdo + ib * 32 * 256, lane_d, kk);
+            for (int e = e0; e < e0 + n; ++e) {
+                const unsigned rel = (unsigned)(rel0 + ib * 32 + 8 * (e >> 2) + (e & 3));
+                float arg = __builtin_fmaf(S[ib][e], sl2, -l4[e >> 2][e & 3] * kLog2e);
+                arg = rel >= live ? -INFINITY : arg;
+                const float pr = __builtin_amdgcn_exp2f(arg);
+                S[ib][e] = pr;
+                dP[ib][e] = pr * (dP[ib][e] - d4[e >> 2][e & 3]);
             }
+        };
+        f32x4 l4[2][4], d4[2][4];
 #pragma unroll
-            for (int e = 0; e < 16; ++e) S[ib][e] = dP[ib][e] = 0.f;
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk) {
-                S[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[kk], kf[kk], S[ib], 0, 0, 0);
-                dP[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fdo[kk], vf[kk], dP[ib], 0, 0, 0);
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        if (it + 1 < n_it) issue(it + 1);  // the other stage is free since the barrier
-        __builtin_amdgcn_sched_barrier(0);
-
-        auto softmax = [&](int ib) {
-            // accumulator element e: query row i0 + 8*(e>>2) + 4*half + (e&3), key column j0 + (lane&31)
-            const int i0 = i00 + ib * 32;
+        for (int ib = 0; ib < 2; ++ib)
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
-                const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_s + ib * 32 + 8 * b + 4 * half);
-                const f32x4 d4 = *reinterpret_cast<const f32x4*>(del_s + ib * 32 + 8 * b + 4 * half);
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int e = 4 * b + r;
-                    const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(S[ib][e], sl2, -l4[r] * kLog2e));
-                    S[ib][e] = pr;
-                    dP[ib][e] = pr * (dP[ib][e] - d4[r]);
-                }
+                l4[ib][b] = *reinterpret_cast<const f32x4*>(lse_s + ib * 32 + 8 * b + 4 * half);
+                d4[ib][b] = *reinterpret_cast<const f32x4*>(del_s + ib * 32 + 8 * b + 4 * half);
             }
-            // blocks wholly above the diagonal are computed too and masked to zero (a branch around a
-            // block would make the compiler shuffle the 128 accumulator registers at the join)
-            if ((i0 < j0 + 31) || (i0 + 32 > len)) {
-                const int j = j0 + (lane & 31);
+        bf16x8 pf[2][2], dsf[2][2];
+        softmax_part(0, l4[0], d4[0], 0, 16);
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int i = i0 + 8 * (e >> 2) + 4 * half + (e & 3);
-                    if (j > i || i >= len) S[ib][e] = dP[ib][e] = 0.f;
-                }
-            }
+        for (int ks = 0; ks < 2; ++ks) {
+            pf[0][ks] = pack8(S[0], ks);
+            dsf[0][ks] = pack8(dP[0], ks);
+        }
+
+        __builtin_amdgcn_sched_barrier(0);
+        ALCH_STAMP(0)
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // tile it+1 (the only loads in flight)
+        __syncthreads();
+        ALCH_STAMP(1)
+        // Loads of tile it+2: descriptors now, the nine load instructions one per group below (a
+        // burst of them would hold the wave at the issue stage for over a thousand cycles).
+        const int rows2 = it + 2 < n_it ? len - qt_ld * kTileRows : 0;
+        const uint32_t st2 = lds0 + s_ld;
+        const long long ext2 = rows2 > 0 ? ((long long)(rows2 - 1) * p.ldq + kD) * 2 : 0;
+        const long long row2 = (long long)(seq_start + qt_ld * kTileRows);
+        const i32x4 rs_q = rsrc_of(p.Q + row2 * p.ldq + h_ld * kD, ext2);
+        const i32x4 rs_do = rsrc_of(p.dO + row2 * p.ldq + h_ld * kD, ext2);
+        const i32x4 rs_sc = rsrc_of((wave == 0 ? p.LSE : p.delta) + row2 * p.Hq + h_ld,
+                                    rows2 > 0 ? ((long long)(rows2 - 1) * p.Hq + 1) * 4 : 0);
+        __builtin_amdgcn_sched_barrier(0);
+        ALCH_STAMP(2)
+
+        const char* nq = smem + s_nxt;
+        const char* ndo = nq + kTileBytes;
+        // 16 groups of four matrix instructions: dV += P^T dO, dK += dS^T Q of this tile and S, dP of
+        // the next.  The six LDS reads of a group are issued two groups ahead of their use.  Groups 0-7
+        // work on block 0 and carry the exp/mask/pack of block 1 (two elements of S and dP each) in
+        // the shadow of their matrix instructions; groups 8-15 then consume block 1.
+        struct Frags { bf16x8 rdo, rq, dq, ddo; };
+        auto load_group = [&](int g) {
+            const int ib = g >> 3, ks = (g >> 2) & 1, nb = g & 3, kk = ks * 4 + nb;
+            Frags f;
+            f.rdo = lds_frag_rows(tdo + ib * 32 * 256, lane_r0, lane_r1, ks, nb);
+            f.rq = lds_frag_rows(tq + ib * 32 * 256, lane_r0, lane_r1, ks, nb);
+            f.dq = lds_frag_d(nq + ib * 32 * 256, lane_d, kk);
+            f.ddo = lds_frag_d(ndo + ib * 32 * 256, lane_d, kk);
+            return f;
         };
-        auto accumulate = [&](int ib) {
-            const char* bq = tq + ib * 32 * 256;
-            const char* bdo = tdo + ib * 32 * 256;
+        Frags fr[3];
+        fr[0] = load_group(0);
+        fr[1] = load_group(1);
+        f32x16 Sn, dPn;  // S, dP of block 0 of the next tile (block 1 goes straight into S[1], dP[1])
 #pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                const bf16x8 pf = pack8(S[ib], ks), dsf = pack8(dP[ib], ks);
-#pragma unroll
-                for (int nb = 0; nb < 4; ++nb) {
-                    dV[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf, lds_frag_rows(bdo, lane_r0, lane_r1, ks, nb), dV[nb], 0, 0, 0);
-                    dK[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf, lds_frag_rows(bq, lane_r0, lane_r1, ks, nb), dK[nb], 0, 0, 0);
-                }
+        for (int g = 0; g < 16; ++g) {
+            const int ib = g >> 3, ks = (g >> 2) & 1, nb = g & 3, kk = ks * 4 + nb;
+            if (g < 4) dma16(rs_q, st2 + (uint32_t)(wave * 4 + g) * 1024u, voff[g & 3]);
+            else if (g < 8) dma16(rs_do, st2 + kTileBytes + (uint32_t)(wave * 4 + g - 4) * 1024u, voff[g & 3]);
+            else if (g == 8 && wave < 2) dma4(rs_sc, st2 + 2 * kTileBytes + (uint32_t)wave * 256u, (uint32_t)(lane * p.Hq * 4));
+            if (g + 2 < 16) fr[(g + 2) % 3] = load_group(g + 2);
+            if (g < 8) {
+                softmax_part(1, l4[1], d4[1], 2 * g, 2);
+                if (g == 3) { pf[1][0] = pack8(S[1], 0); dsf[1][0] = pack8(dP[1], 0); }
+                if (g == 7) { pf[1][1] = pack8(S[1], 1); dsf[1][1] = pack8(dP[1], 1); }
             }
-        };
-        softmax(0);
-        __builtin_amdgcn_sched_barrier(0);
-        accumulate(0);
-        __builtin_amdgcn_sched_barrier(0);
-        softmax(1);
-        __builtin_amdgcn_sched_barrier(0);
-        accumulate(1);
+            __builtin_amdgcn_sched_barrier(0);
+            const Frags& f = fr[g % 3];
+            dV[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[ib][ks], f.rdo, dV[nb], 0, 0, 0);
+            dK[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf[ib][ks], f.rq, dK[nb], 0, 0, 0);
+            if (ib == 0) {
+                if (g == 0) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) Sn[e] = dPn[e] = 0.f;
+                }
+                Sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.dq, kf[kk], Sn, 0, 0, 0);
+                dPn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ddo, vf[kk], dPn, 0, 0, 0);
+            } else {
+                if (g == 8) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) S[1][e] = dP[1][e] = 0.f;
+                }
+                S[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.dq, kf[kk], S[1], 0, 0, 0);
+                dP[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ddo, vf[kk], dP[1], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        S[0] = Sn;
+        dP[0] = dPn;
+        ALCH_STAMP(3)
+        // advance the stream
+        const uint32_t s_free = s_cur;
+        s_cur = s_nxt; s_nxt = s_ld; s_ld = s_free;
+        if (++qt_cur == qt0 + nqt) qt_cur = qt0;
+        if (++qt_ld == qt0 + nqt) { qt_ld = qt0; ++h_ld; }
     }
+#ifdef ALCH_ATTN_TIMING
+    if (stamp) {
+        for (int i = 0; i < 4; ++i) g_attn_stamps[i] = acc_t[i];
+        g_attn_stamps[5] = n_it;
+        g_attn_stamps[6] = __builtin_readcyclecounter() - k_t0;
+        g_attn_stamps[7] = __builtin_amdgcn_s_memrealtime() - k_r0;
+    }
+#endif
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // accumulator element e of block nb: key row j0 + 8*(e>>2) + 4*half + (e&3), column nb*32 + (lane&31)
     if (p.rope_log2_base > 0.f) rope_backward_rows(dK, p, seq_start, j0, len, lane);

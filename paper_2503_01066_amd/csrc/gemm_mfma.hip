@@ -340,7 +340,7 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
     if (!p.accumulate) {
         // Stage the wave's 128x128 bf16 result through the (now idle) pipeline LDS so that it leaves
         // as whole 256-byte row segments: 8-byte LDS writes, 16-byte LDS reads, 16-byte global stores.
-        constexpr int kRowStride = 272;  // 256 + 16: rows stay 16-byte aligned, reads conflict-free
+        constexpr int kRowStride = 256;  // chunks XOR-ed with the row: 8-byte writes 2-way, 16-byte reads conflict-free
         char* stage = smem + wave * (128 * kRowStride);
         __syncthreads();  // every wave's loads have landed and every wave is done reading the pipeline
         static_for4([&](auto ic) {
@@ -353,33 +353,47 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
                     bf16x4 o;
 #pragma unroll
                     for (int r = 0; r < 4; ++r) o[r] = (__bf16)acc[i][j][4 * b + r];
-                    *reinterpret_cast<bf16x4*>(row + (j * 32 + 8 * b + 4 * half) * 2) = o;
+                    *reinterpret_cast<bf16x4*>(row + ((((4 * j + b) ^ (lane & 15)) << 4) | (half << 3))) = o;
                 }
         });
         // (a wave reads back only what it wrote itself: no barrier needed in between)
         const int n = n0 + wn * 128 + (lane & 15) * 8;
         if (p.epilogue == kEpiSwigluBwd) {
-#pragma unroll 4
-            for (int qq = 0; qq < 32; ++qq) {
-                const int rl = 4 * qq + (lane >> 4);
-                const int m = m0 + wm * 128 + rl;
-                const bf16x8 d8 = *reinterpret_cast<const bf16x8*>(stage + rl * kRowStride + (lane & 15) * 16);
-                if (m < p.M && n < p.N) {
-                    const bf16x8 g8 = *reinterpret_cast<const bf16x8*>(p.G + (long long)m * p.ldgu + n);
-                    const bf16x8 u8 = *reinterpret_cast<const bf16x8*>(p.U + (long long)m * p.ldgu + n);
-                    bf16x8 dg8, du8, a8;
+            // G and U rows are fetched eight row-steps at a time before any store is issued: the
+            // compiler may not move a load above a store it cannot prove disjoint, and one round trip
+            // to memory per row-step would leave the epilogue bound by latency.
+            constexpr int kBatch = 8;
+#pragma unroll 1
+            for (int q0 = 0; q0 < 32; q0 += kBatch) {
+                bf16x8 g8[kBatch], u8[kBatch];
 #pragma unroll
-                    for (int r = 0; r < 8; ++r) {
-                        const float g = bf2f(g8[r]), u = bf2f(u8[r]), d = bf2f(d8[r]);
-                        const float sg = 1.f / (1.f + __expf(-g));
-                        const float silu = g * sg;
-                        dg8[r] = (__bf16)(d * u * sg * (1.f + g * (1.f - sg)));
-                        du8[r] = (__bf16)(d * silu);
-                        a8[r] = (__bf16)(silu * u);
+                for (int k = 0; k < kBatch; ++k) {
+                    const int m = m0 + wm * 128 + 4 * (q0 + k) + (lane >> 4);
+                    if (m < p.M && n < p.N) {
+                        g8[k] = *reinterpret_cast<const bf16x8*>(p.G + (long long)m * p.ldgu + n);
+                        u8[k] = *reinterpret_cast<const bf16x8*>(p.U + (long long)m * p.ldgu + n);
                     }
-                    *reinterpret_cast<bf16x8*>(C + (long long)m * ldc + n) = dg8;
-                    *reinterpret_cast<bf16x8*>(C + (long long)m * ldc + p.N + n) = du8;
-                    if (p.act_out) *reinterpret_cast<bf16x8*>(p.act_out + (long long)m * p.N + n) = a8;
+                }
+#pragma unroll
+                for (int k = 0; k < kBatch; ++k) {
+                    const int rl = 4 * (q0 + k) + (lane >> 4);
+                    const int m = m0 + wm * 128 + rl;
+                    const bf16x8 d8 = *reinterpret_cast<const bf16x8*>(stage + rl * kRowStride + (((lane & 15) ^ (rl & 15)) << 4));
+                    if (m < p.M && n < p.N) {
+                        bf16x8 dg8, du8, a8;
+#pragma unroll
+                        for (int r = 0; r < 8; ++r) {
+                            const float g = bf2f(g8[k][r]), u = bf2f(u8[k][r]), d = bf2f(d8[r]);
+                            const float sg = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g));
+                            const float silu = g * sg;
+                            dg8[r] = (__bf16)(d * u * sg * (1.f + g * (1.f - sg)));
+                            du8[r] = (__bf16)(d * silu);
+                            a8[r] = (__bf16)(silu * u);
+                        }
+                        *reinterpret_cast<bf16x8*>(C + (long long)m * ldc + n) = dg8;
+                        *reinterpret_cast<bf16x8*>(C + (long long)m * ldc + p.N + n) = du8;
+                        if (p.act_out) *reinterpret_cast<bf16x8*>(p.act_out + (long long)m * p.N + n) = a8;
+                    }
                 }
             }
         } else {
@@ -387,31 +401,38 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
             for (int qq = 0; qq < 32; ++qq) {
                 const int rl = 4 * qq + (lane >> 4);
                 const int ml = wm * 128 + rl;
-                const bf16x8 d8 = *reinterpret_cast<const bf16x8*>(stage + rl * kRowStride + (lane & 15) * 16);
+                const bf16x8 d8 = *reinterpret_cast<const bf16x8*>(stage + rl * kRowStride + (((lane & 15) ^ (rl & 15)) << 4));
                 if (m0 + ml < m_end && n < p.N) *reinterpret_cast<bf16x8*>(C + (long long)(mrel0 + ml) * ldc + n) = d8;
             }
         }
     } else {
-        // accumulate: C = round(acc + C) with the sum in fp32, straight from the accumulators
+        // accumulate: C = round(acc + C) with the sum in fp32, straight from the accumulators.  The old
+        // values of a 32-row block are all fetched before its first store (see the note on loads above).
         static_for4([&](auto ic) {
             constexpr int i = decltype(ic)::value;
             const int ml = wm * 128 + i * 32 + (lane & 31);
-            if (m0 + ml < m_end) {
-                __bf16* row = C + (long long)(mrel0 + ml) * ldc;
+            __bf16* row = C + (long long)(mrel0 + ml) * ldc;
+            const bool row_ok = m0 + ml < m_end;
+            bf16x4 old[4][4];
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
-                    for (int b = 0; b < 4; ++b) {
-                        const int nn = n0 + wn * 128 + j * 32 + 8 * b + 4 * half;
-                        if (nn < p.N) {
-                            const bf16x4 old = *reinterpret_cast<const bf16x4*>(row + nn);
-                            bf16x4 o;
+                for (int b = 0; b < 4; ++b) {
+                    const int nn = n0 + wn * 128 + j * 32 + 8 * b + 4 * half;
+                    if (row_ok && nn < p.N) old[j][b] = *reinterpret_cast<const bf16x4*>(row + nn);
+                }
 #pragma unroll
-                            for (int r = 0; r < 4; ++r) o[r] = (__bf16)(acc[i][j][4 * b + r] + bf2f(old[r]));
-                            *reinterpret_cast<bf16x4*>(row + nn) = o;
-                        }
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const int nn = n0 + wn * 128 + j * 32 + 8 * b + 4 * half;
+                    if (row_ok && nn < p.N) {
+                        bf16x4 o;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) o[r] = (__bf16)(acc[i][j][4 * b + r] + bf2f(old[j][b][r]));
+                        *reinterpret_cast<bf16x4*>(row + nn) = o;
                     }
-            }
+                }
         });
     }
 #ifdef ALCH_GEMM_TIMING
