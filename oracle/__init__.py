@@ -22,6 +22,7 @@ Modules:
   layer   -- decoder-layer forward, and backward from a saved record (reuse) or
              from a recomputed forward (recompute)
   stack   -- L-layer stack with final norm, LM head and cross-entropy loss
+  lora    -- the layer with low-rank adapters on its projections (Section 3 A1, Section 6: rank 8)
 Every function is pinned by tests/test_oracle_*.py (finite differences, the
 reuse == recompute invariant, brute-force gather, closed forms, special cases).
 """
