@@ -176,6 +176,49 @@ int alch_layer_backward(const alch_layer_shape* shape, const alch_batch* batch,
 size_t alch_layer_backward_workspace_bytes(const alch_layer_shape* shape, int32_t total_tokens,
                                            int32_t max_seqlen);
 
+/* ------------------------------------------------------------------------------------
+ * Low-rank adapters on the projections (Section 3, assumption A1: the system trains with
+ * parameter-efficient fine-tuning such as LoRA on a frozen base; Section 6, "Training": the
+ * evaluated models carry an adapter of rank 8).
+ *
+ * Projection p (order q, k, v, o, g, u, d) computes y = x W_p^T + scale * (x A_p^T) B_p^T with
+ * A_p [rank, in_p] and B_p [out_p, rank], row-major, dtype of the shape.  A NULL pair means the
+ * projection carries no adapter.  The saved record is the one the serving forward produced with
+ * the adapters attached (Q, K, V, O, G, U contain the low-rank terms).
+ * rank: multiple of 8, 8..64; every projection width must be a multiple of 8. */
+enum { ALCH_PROJ_Q = 0, ALCH_PROJ_K, ALCH_PROJ_V, ALCH_PROJ_O, ALCH_PROJ_G, ALCH_PROJ_U, ALCH_PROJ_D, ALCH_N_PROJ };
+typedef struct {
+    int32_t rank;
+    float scale;               /* alpha / rank of the LoRA formulation */
+    const void* A[ALCH_N_PROJ];
+    const void* B[ALCH_N_PROJ];
+} alch_lora;
+
+/* Adapter gradients, same shapes as A and B; a NULL member is skipped; accumulate as in alch_wgrads. */
+typedef struct {
+    void* dA[ALCH_N_PROJ];
+    void* dB[ALCH_N_PROJ];
+    int32_t accumulate;
+} alch_lora_grads;
+
+/*
+ * alch_layer_backward_lora: alch_layer_backward for a layer with adapters.
+ *   dX includes the low-rank paths (dx = dy W + scale (dy B) A for every adapted projection);
+ *   wgrads may be NULL or hold NULL members: the frozen base of Section 3 A1 (then only the
+ *   data-gradient products run: 2 flops per parameter and token instead of 4);
+ *   lora_grads->dA[p] = scale * (dy_p B_p)^T x_p, dB[p] = scale * dy_p^T (x_p A_p^T).
+ * The rank-r intermediates x A^T and dy B are rounded to the storage dtype once.
+ * Same parity bar as alch_layer_backward.  Workspace: alch_layer_backward_lora_workspace_bytes.
+ */
+int alch_layer_backward_lora(const alch_layer_shape* shape, const alch_batch* batch,
+                             const alch_saved* saved, const alch_weights* weights, const alch_lora* lora,
+                             const void* dY, const uint8_t* loss_mask, void* dX, const alch_wgrads* wgrads,
+                             const alch_lora_grads* lora_grads, void* workspace, size_t workspace_bytes,
+                             void* hip_stream);
+
+size_t alch_layer_backward_lora_workspace_bytes(const alch_layer_shape* shape, int32_t total_tokens,
+                                                int32_t max_seqlen, int32_t rank);
+
 /* Host callbacks of the stack walk (Section 4.2: a hook at the start of each layer's
  * backward lets serving pre-empt training; Section 4.3.2: a layer's activations may
  * still be on their way back to the GPU).  layer_ready(user, l) is called before layer
@@ -238,7 +281,7 @@ size_t alch_layer_forward_workspace_bytes(const alch_layer_shape* shape, int32_t
  *   a_kmajor != 0: A_i(m,k) = A_i[m*lda + k], else A_i(m,k) = A_i[k*lda + m]
  *   b_kmajor != 0: B_i(k,n) = B_i[n*ldb + k], else B_i(k,n) = B_i[k*ldb + n]
  * (data gradient: a_kmajor=1, b_kmajor=0; weight gradient: both 0; forward projection: both 1).
- * terms is a HOST array of 1..3 operand pairs.  bf16 problems with 16-byte aligned operands and
+ * terms is a HOST array of 1..4 operand pairs.  bf16 problems with 16-byte aligned operands and
  * leading dimensions that are multiples of 8 run on the matrix cores; anything else takes a plain
  * fp32 kernel.
  */

@@ -52,6 +52,17 @@ class CWgrads(C.Structure):
     _fields_ = [("d" + k, C.c_void_p) for k in WEIGHT_KEYS] + [("accumulate", C.c_int32)]
 
 
+PROJECTIONS = ("q", "k", "v", "o", "g", "u", "d")  # order of the adapter arrays
+
+
+class CLora(C.Structure):
+    _fields_ = [("rank", C.c_int32), ("scale", C.c_float), ("A", C.c_void_p * 7), ("B", C.c_void_p * 7)]
+
+
+class CLoraGrads(C.Structure):
+    _fields_ = [("dA", C.c_void_p * 7), ("dB", C.c_void_p * 7), ("accumulate", C.c_int32)]
+
+
 class CRecordOut(C.Structure):
     _fields_ = [(k, C.c_void_p) for k in RECORD_KEYS] + [("LSE", C.c_void_p)]
 
@@ -107,6 +118,12 @@ def lib():
     L.alch_layer_backward.argtypes = [C.POINTER(LayerShape), C.POINTER(CBatch), C.POINTER(CSaved),
                                       C.POINTER(CWeights), C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.POINTER(CWgrads), C.c_void_p, C.c_size_t, C.c_void_p]
+    L.alch_layer_backward_lora_workspace_bytes.restype = C.c_size_t
+    L.alch_layer_backward_lora_workspace_bytes.argtypes = [C.POINTER(LayerShape), C.c_int32, C.c_int32, C.c_int32]
+    L.alch_layer_backward_lora.restype = C.c_int
+    L.alch_layer_backward_lora.argtypes = [C.POINTER(LayerShape), C.POINTER(CBatch), C.POINTER(CSaved),
+                                           C.POINTER(CWeights), C.POINTER(CLora), C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.POINTER(CWgrads), C.POINTER(CLoraGrads), C.c_void_p, C.c_size_t, C.c_void_p]
     L.alch_stack_backward.restype = C.c_int
     L.alch_stack_backward.argtypes = [C.POINTER(LayerShape), C.c_int32, C.c_int32, C.POINTER(CBatch),
                                       C.POINTER(CSaved), C.POINTER(CWeights), C.c_void_p, C.c_void_p, C.c_void_p,
@@ -229,6 +246,43 @@ def alch_layer_backward(shape, batch, saved, weights, dY, loss_mask=None, want=W
     _check(L.alch_layer_backward(C.byref(shape), C.byref(batch.c), C.byref(sv), C.byref(w), _ptr(dY), _ptr(loss_mask),
                                  _ptr(dX), C.byref(g), _ptr(ws), ws.numel(), _stream_handle(stream)))
     out = dict(grads)
+    out["dX"] = dX
+    return out
+
+
+def alch_layer_backward_lora(shape, batch, saved, weights, lora, rank, scale, dY, loss_mask=None, want=(), grads=None,
+                             lora_grads=None, accumulate=False, dX=None, workspace=None, stream=None):
+    """Layer backward with low-rank adapters.  lora: dict projection -> (A [rank, in], B [out, rank]) for the
+    adapted projections among PROJECTIONS.  want: base weight gradients to produce (default none: frozen base).
+    lora_grads: dict 'dAq', 'dBq', ... -> tensor (default: all adapters).  Returns dict with dX, the base
+    gradients asked for and the adapter gradients."""
+    L = lib()
+    dev = dY.device
+    if grads is None:
+        grads = {"d" + k: torch.empty_like(weights[k]) for k in want}
+    if lora_grads is None:
+        lora_grads = {}
+        for p_, (A_, B_) in lora.items():
+            lora_grads["dA" + p_] = torch.empty_like(A_)
+            lora_grads["dB" + p_] = torch.empty_like(B_)
+    if dX is None:
+        dX = torch.empty_like(dY)
+    cl = CLora(rank=rank, scale=scale)
+    cg = CLoraGrads(accumulate=1 if accumulate else 0)
+    for i, p_ in enumerate(PROJECTIONS):
+        if p_ in lora:
+            cl.A[i], cl.B[i] = lora[p_][0].data_ptr(), lora[p_][1].data_ptr()
+        for arr, key in ((cg.dA, "dA" + p_), (cg.dB, "dB" + p_)):
+            if lora_grads.get(key) is not None:
+                arr[i] = lora_grads[key].data_ptr()
+    need = L.alch_layer_backward_lora_workspace_bytes(C.byref(shape), batch.total_tokens, batch.max_seqlen, rank)
+    ws = workspace if workspace is not None else _workspace(need, dev)
+    sv, w, g = _saved_struct(saved, 0), _weights_struct(weights, 0), _wgrads_struct(grads, accumulate)
+    _check(L.alch_layer_backward_lora(C.byref(shape), C.byref(batch.c), C.byref(sv), C.byref(w), C.byref(cl), _ptr(dY),
+                                      _ptr(loss_mask), _ptr(dX), C.byref(g), C.byref(cg), _ptr(ws), ws.numel(),
+                                      _stream_handle(stream)))
+    out = dict(grads)
+    out.update(lora_grads)
     out["dX"] = dX
     return out
 

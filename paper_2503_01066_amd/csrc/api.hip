@@ -5,6 +5,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
 #include <mutex>
 #include <vector>
 
@@ -95,10 +96,14 @@ static int check_batch(const alch_batch* b) {
 struct LayerBwdPlan {
     void *dYm, *dGU, *Act, *Hn, *dHn, *dX2, *dO, *dQKV;
     float *delta, *partial;
+    // adapters (rank > 0): t1 = s x A^T [T, 64]; t2 = s dy B, three zero-padded 64-column slots [T, 192];
+    // the adapters' A matrices stacked and zero-padded [192, max width]; partial sums of the adapter gradients
+    void *T1 = nullptr, *T2 = nullptr, *Ap = nullptr;
+    float* up_scratch = nullptr;
     size_t bytes;
 };
 
-static LayerBwdPlan plan_layer_bwd(const alch_layer_shape& s, int T, void* ws, size_t ws_bytes) {
+static LayerBwdPlan plan_layer_bwd(const alch_layer_shape& s, int T, void* ws, size_t ws_bytes, int lora_rank = 0) {
     Arena a(ws, ws_bytes);
     const size_t E = dtype_size(s.dtype);
     const size_t t = (size_t)(T > 0 ? T : 1);
@@ -114,6 +119,13 @@ static LayerBwdPlan plan_layer_bwd(const alch_layer_shape& s, int T, void* ws, s
     p.dQKV = a.take(t * (QD + 2 * KD) * E);
     p.delta = static_cast<float*>(a.take(t * s.n_q_heads * sizeof(float)));
     p.partial = static_cast<float*>(a.take((size_t)rmsnorm_bwd_blocks(T) * H * sizeof(float)));
+    if (lora_rank > 0) {
+        const size_t wmax = std::max(std::max(H, QD), F);
+        p.T1 = a.take(t * kLoraSlot * E);
+        p.T2 = a.take(t * 3 * kLoraSlot * E);
+        p.Ap = a.take(3 * kLoraSlot * wmax * E);
+        p.up_scratch = static_cast<float*>(a.take(lora_up_scratch_bytes(lora_rank, (int)wmax)));
+    }
     p.bytes = round_up(a.used, 256);
     return p;
 }
@@ -207,7 +219,8 @@ static int check_wgrads(const alch_wgrads* g) {
 // Enqueues steps of one layer's backward pass; arguments already validated.
 static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b, const alch_saved& sv,
                                   const alch_weights& w, const void* dY, const uint8_t* loss_mask, void* dX,
-                                  const alch_wgrads* wg, const LayerBwdPlan& p, hipStream_t st) {
+                                  const alch_wgrads* wg, const LayerBwdPlan& p, hipStream_t st,
+                                  const alch_lora* lo = nullptr, const alch_lora_grads* lg = nullptr) {
     const alch_dtype dt = s.dtype;
     const size_t E = dtype_size(dt);
     const int T = b.total_tokens, H = s.hidden, F = s.ffn, D = s.head_dim;
@@ -215,6 +228,39 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
     const int acc = wg ? (wg->accumulate != 0) : 0;
     static const alch_wgrads none = {};
     const alch_wgrads& g = wg ? *wg : none;
+
+    // ---- adapters.  For an adapted projection y = x W^T + s (x A^T) B^T with incoming gradient dy:
+    //   t2 = s dy B  [T, r]      -> data gradient  dx += t2 A   (an extra operand pair of the projection's
+    //                               data-gradient product: t2 zero-padded to 64 columns, A to 64 rows)
+    //                            -> dA = t2^T x
+    //   t1 = s x A^T [T, r]      -> dB = dy^T t1
+    const int r = lo ? lo->rank : 0;
+    const int lacc = lg ? (lg->accumulate != 0) : 0;
+    const long long ldt2 = 3 * kLoraSlot;
+    auto has = [&](int pj) { return lo && lo->A[pj] && lo->B[pj]; };
+    auto wants = [&](int pj) { return has(pj) && lg && (lg->dA[pj] || lg->dB[pj]); };
+    // t2 of projection pj into slot `slot` (zeros when the projection has no adapter)
+    auto down_t2 = [&](int pj, int slot, const void* dy, long long lddy, int out_p) {
+        return launch_lora_down(dt, dy, lddy, T, out_p, has(pj) ? lo->B[pj] : nullptr, r, false, has(pj) ? r : 0,
+                                lo->scale, const_cast<char*>(at(p.T2, (size_t)slot * kLoraSlot, E)), ldt2, kLoraSlot, st);
+    };
+    // A of projection pj, zero-padded to 64 rows, at rows slot*64 of the stacked buffer of width in_p
+    auto pad_A = [&](int pj, int slot, int in_p) {
+        return launch_lora_pad_rows(dt, has(pj) ? lo->A[pj] : nullptr, r, in_p,
+                                    const_cast<char*>(at(p.Ap, (size_t)slot * kLoraSlot * in_p, E)), kLoraSlot, st);
+    };
+    auto adapter_grads = [&](int pj, int slot, const void* x, long long ldx, int in_p, const void* dy, long long lddy,
+                             int out_p) -> int {
+        if (!wants(pj)) return ALCH_OK;
+        if (lg->dB[pj]) {
+            ALCH_TRY(launch_lora_down(dt, x, ldx, T, in_p, lo->A[pj], in_p, true, r, lo->scale, p.T1, kLoraSlot, kLoraSlot, st));
+            ALCH_TRY(launch_lora_up(dt, p.T1, kLoraSlot, dy, lddy, T, out_p, r, 1.f, lg->dB[pj], r, true, lacc, p.up_scratch, st));
+        }
+        if (lg->dA[pj])
+            ALCH_TRY(launch_lora_up(dt, at(p.T2, (size_t)slot * kLoraSlot, E), ldt2, x, ldx, T, in_p, r, 1.f, lg->dA[pj], in_p,
+                                    false, lacc, p.up_scratch, st));
+        return ALCH_OK;
+    };
 
     // the loss mask zeroes rows of dY once, up front
     const void* dYp = dY;
@@ -224,13 +270,18 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
     }
 
     // MLP down projection: dAct = dY Wd, fused with the SwiGLU gradient -> [dG | dU] and Act
+    if (has(ALCH_PROJ_D)) {
+        ALCH_TRY(down_t2(ALCH_PROJ_D, 0, dYp, H, H));
+        ALCH_TRY(pad_A(ALCH_PROJ_D, 0, F));
+    }
     {
         GemmDesc d = gemm(dt, T, F, true, false);
         add_seg(d, dYp, H, w.Wd, F, H);
+        if (has(ALCH_PROJ_D)) add_seg(d, p.T2, ldt2, p.Ap, F, kLoraSlot);
         add_out(d, p.dGU, 0, 2 * (long long)F);
         d.epilogue = kEpiSwigluBwd;
         d.G = sv.G; d.U = sv.U; d.ldgu = F;
-        d.act_out = g.dWd ? p.Act : nullptr;
+        d.act_out = (g.dWd || wants(ALCH_PROJ_D)) ? p.Act : nullptr;
         ALCH_TRY(launch_gemm(d, st));
     }
     if (g.dWd) {  // dWd = dY^T Act
@@ -240,15 +291,27 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
         d.accumulate = acc;
         ALCH_TRY(launch_gemm(d, st));
     }
+    ALCH_TRY(adapter_grads(ALCH_PROJ_D, 0, p.Act, F, F, dYp, H, H));
+    const bool lora_gu = has(ALCH_PROJ_G) || has(ALCH_PROJ_U);
+    if (lora_gu) {
+        ALCH_TRY(down_t2(ALCH_PROJ_G, 0, p.dGU, 2 * (long long)F, F));
+        ALCH_TRY(down_t2(ALCH_PROJ_U, 1, at(p.dGU, F, E), 2 * (long long)F, F));
+        ALCH_TRY(pad_A(ALCH_PROJ_G, 0, H));
+        ALCH_TRY(pad_A(ALCH_PROJ_U, 1, H));
+    }
     {  // dH2 = dG Wg + dU Wu
         GemmDesc d = gemm(dt, T, H, true, false);
         add_seg(d, p.dGU, 2 * (long long)F, w.Wg, H, F);
         add_seg(d, at(p.dGU, F, E), 2 * (long long)F, w.Wu, H, F);
+        if (lora_gu) add_seg(d, p.T2, ldt2, p.Ap, H, 2 * kLoraSlot);
         add_out(d, p.dHn, 0, H);
         ALCH_TRY(launch_gemm(d, st));
     }
-    if (g.dWg || g.dWu) {  // [dWg; dWu] = [dG | dU]^T H2
+    if (g.dWg || g.dWu || wants(ALCH_PROJ_G) || wants(ALCH_PROJ_U))
         ALCH_TRY(launch_rmsnorm_fwd(dt, sv.X2, w.g2, p.Hn, T, H, s.rms_eps, st));
+    ALCH_TRY(adapter_grads(ALCH_PROJ_G, 0, p.Hn, H, H, p.dGU, 2 * (long long)F, F));
+    ALCH_TRY(adapter_grads(ALCH_PROJ_U, 1, p.Hn, H, H, at(p.dGU, F, E), 2 * (long long)F, F));
+    if (g.dWg || g.dWu) {  // [dWg; dWu] = [dG | dU]^T H2
         if (g.dWg && g.dWu) {
             GemmDesc d = gemm(dt, 2 * F, H, false, false);
             add_seg(d, p.dGU, 2 * (long long)F, p.Hn, H, T);
@@ -274,12 +337,18 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
     // dX2 = dY + RMSNorm-2 backward(dH2); dg2
     ALCH_TRY(launch_rmsnorm_bwd(dt, p.dHn, sv.X2, w.g2, dYp, nullptr, p.dX2, g.dg2, acc, p.partial, T, H, s.rms_eps, st));
 
+    if (has(ALCH_PROJ_O)) {
+        ALCH_TRY(down_t2(ALCH_PROJ_O, 0, p.dX2, H, H));
+        ALCH_TRY(pad_A(ALCH_PROJ_O, 0, QD));
+    }
     {  // dO = dX2 Wo
         GemmDesc d = gemm(dt, T, QD, true, false);
         add_seg(d, p.dX2, H, w.Wo, QD, H);
+        if (has(ALCH_PROJ_O)) add_seg(d, p.T2, ldt2, p.Ap, QD, kLoraSlot);
         add_out(d, p.dO, 0, QD);
         ALCH_TRY(launch_gemm(d, st));
     }
+    ALCH_TRY(adapter_grads(ALCH_PROJ_O, 0, sv.O, QD, QD, p.dX2, H, H));
     if (g.dWo) {  // dWo = dX2^T O
         GemmDesc d = gemm(dt, H, QD, false, false);
         add_seg(d, p.dX2, H, sv.O, QD, T);
@@ -300,16 +369,28 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
         ALCH_TRY(launch_attn_bwd(a, st));
     }
 
+    const bool lora_qkv = has(ALCH_PROJ_Q) || has(ALCH_PROJ_K) || has(ALCH_PROJ_V);
+    if (lora_qkv) {
+        ALCH_TRY(down_t2(ALCH_PROJ_Q, 0, p.dQKV, QKV, QD));
+        ALCH_TRY(down_t2(ALCH_PROJ_K, 1, at(p.dQKV, QD, E), QKV, KD));
+        ALCH_TRY(down_t2(ALCH_PROJ_V, 2, at(p.dQKV, QD + KD, E), QKV, KD));
+        for (int i = 0; i < 3; ++i) ALCH_TRY(pad_A(ALCH_PROJ_Q + i, i, H));
+    }
     {  // dH1 = dQ Wq + dK Wk + dV Wv
         GemmDesc d = gemm(dt, T, H, true, false);
         add_seg(d, p.dQKV, QKV, w.Wq, H, QD);
         add_seg(d, at(p.dQKV, QD, E), QKV, w.Wk, H, KD);
         add_seg(d, at(p.dQKV, QD + KD, E), QKV, w.Wv, H, KD);
+        if (lora_qkv) add_seg(d, p.T2, ldt2, p.Ap, H, 3 * kLoraSlot);
         add_out(d, p.dHn, 0, H);
         ALCH_TRY(launch_gemm(d, st));
     }
-    if (g.dWq || g.dWk || g.dWv) {  // dW{q,k,v} = d{Q,K,V}^T H1
+    if (g.dWq || g.dWk || g.dWv || wants(ALCH_PROJ_Q) || wants(ALCH_PROJ_K) || wants(ALCH_PROJ_V))
         ALCH_TRY(launch_rmsnorm_fwd(dt, sv.X, w.g1, p.Hn, T, H, s.rms_eps, st));
+    ALCH_TRY(adapter_grads(ALCH_PROJ_Q, 0, p.Hn, H, H, p.dQKV, QKV, QD));
+    ALCH_TRY(adapter_grads(ALCH_PROJ_K, 1, p.Hn, H, H, at(p.dQKV, QD, E), QKV, KD));
+    ALCH_TRY(adapter_grads(ALCH_PROJ_V, 2, p.Hn, H, H, at(p.dQKV, QD + KD, E), QKV, KD));
+    if (g.dWq || g.dWk || g.dWv) {  // dW{q,k,v} = d{Q,K,V}^T H1
         if (g.dWq && g.dWk && g.dWv && QD % 256 == 0 && KD % 256 == 0) {
             GemmDesc d = gemm(dt, QKV, H, false, false);
             add_seg(d, p.dQKV, QKV, p.Hn, H, T);
@@ -393,7 +474,7 @@ int alch_gemm(alch_dtype dtype, int32_t M, int32_t N, int32_t a_kmajor, int32_t 
     clear_error();
     if (dtype != ALCH_F32 && dtype != ALCH_BF16) return fail(ALCH_ERR_INVALID_ARG, "bad dtype %d", (int)dtype);
     if (M < 0 || N < 0) return fail(ALCH_ERR_SHAPE, "negative M or N");
-    if (n_terms < 1 || n_terms > 3 || !terms) return fail(ALCH_ERR_INVALID_ARG, "n_terms must be 1..3 and terms non-NULL");
+    if (n_terms < 1 || n_terms > kMaxGemmSegs || !terms) return fail(ALCH_ERR_INVALID_ARG, "n_terms must be 1..%d and terms non-NULL", kMaxGemmSegs);
     if (!C || ldc < N) return fail(ALCH_ERR_INVALID_ARG, "C is NULL or ldc < N");
     GemmDesc d = gemm(dtype, M, N, a_kmajor != 0, b_kmajor != 0);
     for (int i = 0; i < n_terms; ++i) {
@@ -461,6 +542,56 @@ int alch_layer_backward(const alch_layer_shape* shape, const alch_batch* batch, 
     const LayerBwdPlan p = plan_layer_bwd(*shape, batch->total_tokens, workspace, workspace_bytes);
     return layer_backward_enqueue(*shape, *batch, *saved, *weights, dY, loss_mask, dX, wgrads, p,
                                   static_cast<hipStream_t>(hip_stream));
+}
+
+static int check_lora(const alch_layer_shape* s, const alch_lora* lora, const alch_lora_grads* lg) {
+    if (!lora) return fail(ALCH_ERR_INVALID_ARG, "lora is NULL");
+    if (lora->rank < 8 || lora->rank > kLoraSlot || lora->rank % 8)
+        return fail(ALCH_ERR_SHAPE, "adapter rank %d: must be a multiple of 8 in 8..%d", lora->rank, kLoraSlot);
+    const int QD = s->n_q_heads * s->head_dim, KD = s->n_kv_heads * s->head_dim;
+    if (s->hidden % 8 || s->ffn % 8 || QD % 8 || KD % 8)
+        return fail(ALCH_ERR_UNSUPPORTED, "adapters need every projection width to be a multiple of 8");
+    for (int p = 0; p < ALCH_N_PROJ; ++p) {
+        if ((lora->A[p] == nullptr) != (lora->B[p] == nullptr))
+            return fail(ALCH_ERR_INVALID_ARG, "adapter %d: A and B must both be given or both be NULL", p);
+        if (!aligned16(lora->A[p]) || !aligned16(lora->B[p]))
+            return fail(ALCH_ERR_INVALID_ARG, "adapter %d: A or B is not 16-byte aligned", p);
+        if (lg) {
+            if ((lg->dA[p] || lg->dB[p]) && !lora->A[p])
+                return fail(ALCH_ERR_INVALID_ARG, "adapter %d: gradient requested for a projection without adapter", p);
+            if (!aligned16(lg->dA[p]) || !aligned16(lg->dB[p]))
+                return fail(ALCH_ERR_INVALID_ARG, "adapter %d: dA or dB is not 16-byte aligned", p);
+        }
+    }
+    return ALCH_OK;
+}
+
+size_t alch_layer_backward_lora_workspace_bytes(const alch_layer_shape* shape, int32_t total_tokens, int32_t max_seqlen,
+                                                int32_t rank) {
+    (void)max_seqlen;
+    if (!shape || check_shape(shape) != ALCH_OK || total_tokens < 0 || rank < 8 || rank > kLoraSlot || rank % 8) return 0;
+    return plan_layer_bwd(*shape, total_tokens, nullptr, 0, rank).bytes;
+}
+
+int alch_layer_backward_lora(const alch_layer_shape* shape, const alch_batch* batch, const alch_saved* saved,
+                             const alch_weights* weights, const alch_lora* lora, const void* dY,
+                             const uint8_t* loss_mask, void* dX, const alch_wgrads* wgrads,
+                             const alch_lora_grads* lora_grads, void* workspace, size_t workspace_bytes,
+                             void* hip_stream) {
+    clear_error();
+    ALCH_TRY(check_shape(shape));
+    ALCH_TRY(check_batch(batch));
+    ALCH_TRY(check_saved_weights(saved, weights, batch->total_tokens));
+    ALCH_TRY(check_wgrads(wgrads));
+    ALCH_TRY(check_lora(shape, lora, lora_grads));
+    REQUIRE_ACT(dY, "dY", batch->total_tokens);
+    REQUIRE_ACT(dX, "dX", batch->total_tokens);
+    const size_t need = plan_layer_bwd(*shape, batch->total_tokens, nullptr, 0, lora->rank).bytes;
+    if (!workspace || workspace_bytes < need) return fail(ALCH_ERR_WORKSPACE, "workspace %zu bytes < %zu needed", workspace_bytes, need);
+    if (!aligned16(workspace)) return fail(ALCH_ERR_INVALID_ARG, "workspace is not 16-byte aligned");
+    const LayerBwdPlan p = plan_layer_bwd(*shape, batch->total_tokens, workspace, workspace_bytes, lora->rank);
+    return layer_backward_enqueue(*shape, *batch, *saved, *weights, dY, loss_mask, dX, wgrads, p,
+                                  static_cast<hipStream_t>(hip_stream), lora, lora_grads);
 }
 
 size_t alch_stack_backward_workspace_bytes(const alch_layer_shape* shape, int32_t n_layers, int32_t vocab,

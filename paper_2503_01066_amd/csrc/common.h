@@ -27,6 +27,7 @@ void clear_error();
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
 inline size_t dtype_size(alch_dtype d) { return d == ALCH_BF16 ? 2 : 4; }
 
 // Bump allocator over the caller's workspace (256-byte aligned slices).

@@ -8,10 +8,10 @@ namespace alch {
 
 struct GenericGemmParams {
     int M, N, n_seg, n_out, accumulate, a_kmajor, b_kmajor;
-    const void* A[3];
-    const void* B[3];
-    int K[3];
-    long long lda[3], ldb[3];
+    const void* A[kMaxGemmSegs];
+    const void* B[kMaxGemmSegs];
+    int K[kMaxGemmSegs];
+    long long lda[kMaxGemmSegs], ldb[kMaxGemmSegs];
     void* C[3];
     int m_begin[3];
     long long ldc[3];
@@ -109,13 +109,15 @@ int launch_gemm_generic(const GemmDesc& d, hipStream_t stream) {
     GenericGemmParams p;
     p.M = d.M; p.N = d.N; p.n_seg = d.n_seg; p.n_out = d.n_out; p.accumulate = d.accumulate;
     p.a_kmajor = d.a_kmajor; p.b_kmajor = d.b_kmajor;
-    for (int s = 0; s < 3; ++s) {
+    for (int s = 0; s < kMaxGemmSegs; ++s) {
         const bool on = s < d.n_seg;
         p.A[s] = on ? d.seg[s].A : nullptr;
         p.B[s] = on ? d.seg[s].B : nullptr;
         p.K[s] = on ? d.seg[s].K : 0;
         p.lda[s] = on ? d.seg[s].lda : 0;
         p.ldb[s] = on ? d.seg[s].ldb : 0;
+    }
+    for (int s = 0; s < kMaxGemmOuts; ++s) {
         const bool oo = s < d.n_out;
         p.C[s] = oo ? d.out[s].C : nullptr;
         p.m_begin[s] = oo ? d.out[s].m_begin : 0x7fffffff;

@@ -43,10 +43,10 @@ static constexpr int kGroupM = ALCH_GROUP_M;             // tile rows per raster
 
 struct MfmaGemmParams {
     int M, N, n_seg, n_out, accumulate, tiles_m, tiles_n;
-    const __bf16* A[3];
-    const __bf16* B[3];
-    int K[3];
-    long long lda[3], ldb[3];
+    const __bf16* A[kMaxGemmSegs];
+    const __bf16* B[kMaxGemmSegs];
+    int K[kMaxGemmSegs];
+    long long lda[kMaxGemmSegs], ldb[kMaxGemmSegs];
     __bf16* C[3];
     int m_begin[3];
     long long ldc[3];
@@ -445,7 +445,7 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
 }
 
 bool gemm_mfma_supported(const GemmDesc& d) {
-    if (d.dtype != ALCH_BF16 || d.M <= 0 || d.N <= 0 || d.n_seg < 1 || d.n_seg > 3 || d.n_out < 1 || d.n_out > 3)
+    if (d.dtype != ALCH_BF16 || d.M <= 0 || d.N <= 0 || d.n_seg < 1 || d.n_seg > kMaxGemmSegs || d.n_out < 1 || d.n_out > 3)
         return false;
     if (d.row_mask) return false;
     for (int s = 0; s < d.n_seg; ++s) {
@@ -479,13 +479,15 @@ int launch_gemm_mfma(const GemmDesc& d, hipStream_t stream) {
     p.accumulate = d.accumulate;
     p.tiles_m = ceil_div(d.M, BM);
     p.tiles_n = ceil_div(d.N, BN);
-    for (int s = 0; s < 3; ++s) {
+    for (int s = 0; s < kMaxGemmSegs; ++s) {
         const bool on = s < d.n_seg;
         p.A[s] = on ? static_cast<const __bf16*>(d.seg[s].A) : nullptr;
         p.B[s] = on ? static_cast<const __bf16*>(d.seg[s].B) : nullptr;
         p.K[s] = on ? d.seg[s].K : 0;
         p.lda[s] = on ? d.seg[s].lda : 0;
         p.ldb[s] = on ? d.seg[s].ldb : 0;
+    }
+    for (int s = 0; s < kMaxGemmOuts; ++s) {
         const bool oo = s < d.n_out;
         p.C[s] = oo ? static_cast<__bf16*>(d.out[s].C) : nullptr;
         p.m_begin[s] = oo ? d.out[s].m_begin : 0x7fffffff;

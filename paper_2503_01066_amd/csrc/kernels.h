@@ -19,6 +19,8 @@ int launch_pack(const uint8_t* mask, int T, const int* cu_seqlens, int n_seqs, i
 // The output may be split along M into up to three row ranges with their own base
 // pointers (rows [m_begin_i, m_begin_{i+1}) go to out[i].C, row index relative to
 // m_begin_i, leading dimension ldc).
+static constexpr int kMaxGemmSegs = 4;  // operand pairs summed into one product
+static constexpr int kMaxGemmOuts = 3;  // row ranges of C with their own base pointers
 struct GemmSeg {
     const void* A;
     const void* B;
@@ -35,9 +37,9 @@ struct GemmDesc {
     int M = 0, N = 0;
     bool a_kmajor = true, b_kmajor = true;
     int n_seg = 0;
-    GemmSeg seg[3];
+    GemmSeg seg[kMaxGemmSegs];
     int n_out = 0;
-    GemmOut out[3];
+    GemmOut out[kMaxGemmOuts];
     int accumulate = 0;
     alch_dtype dtype = ALCH_BF16;
     // kEpiSwigluBwd: the product is dAct [M, N]; with G, U [M, N] (ld = ldgu) the kernel writes
@@ -81,6 +83,22 @@ int launch_masked_copy(alch_dtype dt, const void* a, const uint8_t* mask, void* 
                        hipStream_t stream);
 // y = a + b
 int launch_add(alch_dtype dt, const void* a, const void* b, void* y, long long n, hipStream_t stream);
+
+// ---- low-rank adapters ---------------------------------------------------------------------
+static constexpr int kLoraSlot = 64;       // columns of one zero-padded rank slot (rank <= 64)
+static constexpr int kLoraMaxSplits = 64;  // token splits of the adapter-gradient reduction
+// Y[t, 0:r] = alpha * sum_k X[t, k] * S(k, j); S(k, j) = S[j*lds + k] if s_kmajor else S[k*lds + j];
+// columns r .. slot_cols-1 of Y are written as zeros.  r = 0 (S may be null) zero-fills the slot.
+int launch_lora_down(alch_dtype dt, const void* X, long long ldx, int Trows, int K, const void* S, long long lds,
+                     bool s_kmajor, int r, float alpha, void* Y, long long ldy, int slot_cols, hipStream_t stream);
+// C(j, n) (+)= alpha * sum_t S[t*lds + j] * X[t*ldx + n], j < r, n < N; stored C[j*ldc + n], or C[n*ldc + j]
+// when transposed.  scratch: lora_up_scratch_bytes(r, N) bytes of fp32 partial sums.
+size_t lora_up_scratch_bytes(int rank, int n_max);
+int launch_lora_up(alch_dtype dt, const void* S, long long lds, const void* X, long long ldx, int Trows, int N, int r,
+                   float alpha, void* C, long long ldc, bool transposed, int accumulate, float* scratch,
+                   hipStream_t stream);
+// dst[i, :] = i < r ? A[i, :] : 0 for i < rows_out (A null: all zeros)
+int launch_lora_pad_rows(alch_dtype dt, const void* A, int r, int width, void* dst, int rows_out, hipStream_t stream);
 
 // ---- attention ---------------------------------------------------------------------------
 struct AttnArgs {

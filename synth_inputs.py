@@ -97,3 +97,21 @@ def drawn_record(shape, T, seed, dtype, std=1.0):
 
 def activations(T, width, seed, dtype, std=1.0):
     return normal(np.random.default_rng(seed), (T, width), std, dtype)
+
+
+PROJECTIONS = ("q", "k", "v", "o", "g", "u", "d")
+
+
+def lora_adapters(shape, rank, seed, dtype, projections=PROJECTIONS, std=0.05):
+    """Adapter pairs (A [rank, in], B [out, rank]) ~ N(0, std) for the named projections.
+    (The usual initialisation B = 0 makes half of the gradients trivially zero, so both are drawn.)"""
+    rng = np.random.default_rng(seed)
+    H, Hq, Hkv, D, F = (shape[k] for k in ("hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn"))
+    dims = dict(q=(Hq * D, H), k=(Hkv * D, H), v=(Hkv * D, H), o=(H, Hq * D), g=(F, H), u=(F, H), d=(H, F))
+    out = {}
+    for p in PROJECTIONS:  # fixed draw order whatever subset is asked for
+        o, i = dims[p]
+        A, B = normal(rng, (rank, i), std, dtype), normal(rng, (o, rank), std, dtype)
+        if p in projections:
+            out[p] = (A, B)
+    return out
