@@ -36,6 +36,10 @@ def parse():
     ap.add_argument("--workload", default="config2", choices=["config2", "config3", "config4", "config5", "copy"])
     ap.add_argument("--layers", type=int, default=32, help="config4: number of layers")
     ap.add_argument("--loss-mask", action="store_true", help="config5: zero dY rows with a Bernoulli(0.25) loss mask")
+    ap.add_argument("--lora-rank", type=int, default=0,
+                    help="config2/config5: rank-r adapters on all seven projections (alch_layer_backward_lora)")
+    ap.add_argument("--frozen-base", action="store_true",
+                    help="config2/config5: no base weight gradients (the frozen base of parameter-efficient fine-tuning)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
                     help="measured HBM bytes per launch (from the rocprofv3 --pmc summaries)")
@@ -148,16 +152,36 @@ def run_layer(args, torch, A):
     dst = {k: torch.empty((T, src[k].shape[1]), dtype=src[k].dtype, device=dev) for k in keys}
     src_batch = A.Batch(synth.uniform_cu(n_src, S))
     kept_batch = A.Batch(synth.uniform_cu(n_keep, S))
-    grads = {"d" + k: torch.empty_like(v) for k, v in W.items()}
+    grads = {} if args.frozen_base else {"d" + k: torch.empty_like(v) for k, v in W.items()}
     dX = torch.empty_like(dY)
     ws_pack = torch.empty(A.lib().alch_capture_pack_workspace_bytes(T_src), dtype=torch.uint8, device=dev)
-    ws_bwd = torch.empty(A.layer_backward_workspace_bytes(shape, T, S), dtype=torch.uint8, device=dev)
     streams = [src[k] for k in keys]
     dsts = [dst[k] for k in keys]
+    r = args.lora_rank
+    wflops = 2.0 if args.frozen_base else 4.0   # GEMM flops per parameter and token
+    if args.frozen_base:
+        descr += ", frozen base (data-gradient products only)"
+    if r:
+        import ctypes
+        dims = dict(q=(QD, H), k=(KD, H), v=(KD, H), o=(H, QD), g=(F, H), u=(F, H), d=(H, F))
+        lora = {p: (rnd((r, i), 0.05), rnd((o, r), 0.05)) for p, (o, i) in dims.items()}
+        lgrads = {}
+        for p, (a, b) in lora.items():
+            lgrads["dA" + p], lgrads["dB" + p] = torch.empty_like(a), torch.empty_like(b)
+        need = A.lib().alch_layer_backward_lora_workspace_bytes(ctypes.byref(shape), T, S, r)
+        ws_bwd = torch.empty(need, dtype=torch.uint8, device=dev)
+        descr += ", rank-%d adapters on all seven projections" % r
 
-    def step():
-        A.alch_capture_pack(src_batch, mask, streams, capacity=T, dsts=dsts, workspace=ws_pack)
-        A.alch_layer_backward(shape, kept_batch, dst, W, dY, loss_mask=loss_mask, grads=grads, dX=dX, workspace=ws_bwd)
+        def step():
+            A.alch_capture_pack(src_batch, mask, streams, capacity=T, dsts=dsts, workspace=ws_pack)
+            A.alch_layer_backward_lora(shape, kept_batch, dst, W, lora, r, 2.0, dY, loss_mask=loss_mask, grads=grads,
+                                       lora_grads=lgrads, dX=dX, workspace=ws_bwd)
+    else:
+        ws_bwd = torch.empty(A.layer_backward_workspace_bytes(shape, T, S), dtype=torch.uint8, device=dev)
+
+        def step():
+            A.alch_capture_pack(src_batch, mask, streams, capacity=T, dsts=dsts, workspace=ws_pack)
+            A.alch_layer_backward(shape, kept_batch, dst, W, dY, loss_mask=loss_mask, grads=grads, dX=dX, workspace=ws_bwd)
 
     for _ in range(args.warmup):
         step()
@@ -189,8 +213,8 @@ def run_layer(args, torch, A):
         "config": {"workload": descr,
                    "hidden": H, "q_heads": shp["n_q_heads"], "kv_heads": shp["n_kv_heads"],
                    "head_dim": shp["head_dim"], "ffn": F, "tokens": T, "seq_len": S},
-        "step_tflops": (4.0 * P * T + attn_flops) / 1e12,
-        "step_mfma_frac": (4.0 * P * T + attn_flops) / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "step_tflops": (wflops * P * T + attn_flops) / 1e12,
+        "step_mfma_frac": (wflops * P * T + attn_flops) / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "capture_gbps": pack_gbps,
         "roofline": {"kernel": "k_gemm_mfma (all contractions of the layer backward)", "bound": "mfma",
                      "achieved": achieved_tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
@@ -203,6 +227,12 @@ def run_layer(args, torch, A):
                           "avg_launch_ms": pk[2] / max(pk[3], 1)},
         "kernel_ms_per_step": {k: v[2] / args.steps for k, v in by.items()},
     }
+    if "lora" in by:
+        lo = by["lora"]
+        out["roofline_lora"] = {"kernel": "k_lora_down / k_lora_up_* (rank-r adapter products)", "bound": "hbm",
+                                "achieved": lo[1] / (lo[2] * 1e-3) / 1e9, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                                "frac": lo[1] / (lo[2] * 1e-3) / 1e9 / PEAK_HBM_GBPS, "traffic": None,
+                                "launches_per_step": lo[3] / args.steps}
     return out
 
 

@@ -314,7 +314,7 @@ int alch_attention_forward(const alch_layer_shape* shape, const alch_batch* batc
 typedef enum {
     ALCH_TRACE_GEMM_MFMA = 0, ALCH_TRACE_GEMM_GENERIC = 1, ALCH_TRACE_PACK_SCAN = 2,
     ALCH_TRACE_PACK_GATHER = 3, ALCH_TRACE_ATTN_BWD = 4, ALCH_TRACE_ATTN_FWD = 5,
-    ALCH_TRACE_ROW_OPS = 6, ALCH_TRACE_CROSS_ENTROPY = 7
+    ALCH_TRACE_ROW_OPS = 6, ALCH_TRACE_CROSS_ENTROPY = 7, ALCH_TRACE_LORA = 8
 } alch_trace_kind;
 typedef struct {
     int32_t kind; /* alch_trace_kind */

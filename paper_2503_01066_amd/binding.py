@@ -76,7 +76,7 @@ class CTraceRecord(C.Structure):
 
 
 TRACE_KINDS = ("gemm_mfma", "gemm_generic", "pack_scan", "pack_gather", "attn_bwd", "attn_fwd", "row_ops",
-               "cross_entropy")
+               "cross_entropy", "lora")
 
 HOOK_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.c_int)
 

@@ -97,8 +97,11 @@ struct LayerBwdPlan {
     void *dYm, *dGU, *Act, *Hn, *dHn, *dX2, *dO, *dQKV;
     float *delta, *partial;
     // adapters (rank > 0): t1 = s x A^T [T, 64]; t2 = s dy B, three zero-padded 64-column slots [T, 192];
-    // the adapters' A matrices stacked and zero-padded [192, max width]; partial sums of the adapter gradients
-    void *T1 = nullptr, *T2 = nullptr, *Ap = nullptr;
+    // the adapters' A matrices zero-padded to 64 rows and stacked per product; B transposed; partial sums of
+    // the adapter gradients
+    void *T1 = nullptr, *T2 = nullptr;
+    void *Ap_d = nullptr, *Ap_gu = nullptr, *Ap_o = nullptr, *Ap_qkv = nullptr;  // [64,F] [128,H] [64,QD] [192,H]
+    void* Bt[ALCH_N_PROJ] = {};                                                  // B_p transposed: [rank, out_p]
     float* up_scratch = nullptr;
     size_t bytes;
 };
@@ -123,7 +126,12 @@ static LayerBwdPlan plan_layer_bwd(const alch_layer_shape& s, int T, void* ws, s
         const size_t wmax = std::max(std::max(H, QD), F);
         p.T1 = a.take(t * kLoraSlot * E);
         p.T2 = a.take(t * 3 * kLoraSlot * E);
-        p.Ap = a.take(3 * kLoraSlot * wmax * E);
+        p.Ap_d = a.take(kLoraSlot * F * E);
+        p.Ap_gu = a.take(2 * kLoraSlot * H * E);
+        p.Ap_o = a.take(kLoraSlot * QD * E);
+        p.Ap_qkv = a.take(3 * kLoraSlot * H * E);
+        const size_t outs[ALCH_N_PROJ] = {QD, KD, KD, H, F, F, H};
+        for (int i = 0; i < ALCH_N_PROJ; ++i) p.Bt[i] = a.take((size_t)lora_rank * outs[i] * E);
         p.up_scratch = static_cast<float*>(a.take(lora_up_scratch_bytes(lora_rank, (int)wmax)));
     }
     p.bytes = round_up(a.used, 256);
@@ -239,21 +247,39 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
     const long long ldt2 = 3 * kLoraSlot;
     auto has = [&](int pj) { return lo && lo->A[pj] && lo->B[pj]; };
     auto wants = [&](int pj) { return has(pj) && lg && (lg->dA[pj] || lg->dB[pj]); };
-    // t2 of projection pj into slot `slot` (zeros when the projection has no adapter)
-    auto down_t2 = [&](int pj, int slot, const void* dy, long long lddy, int out_p) {
-        return launch_lora_down(dt, dy, lddy, T, out_p, has(pj) ? lo->B[pj] : nullptr, r, false, has(pj) ? r : 0,
-                                lo->scale, const_cast<char*>(at(p.T2, (size_t)slot * kLoraSlot, E)), ldt2, kLoraSlot, st);
+    // t2 of up to three projections (first one pj0) into slots 0, 1, ... (zeros where there is no adapter)
+    auto down_t2 = [&](int pj0, int n, const void* const* dy, long long lddy, const int* out_p) {
+        LoraDown jobs[3];
+        for (int i = 0; i < n; ++i) {
+            const bool on = has(pj0 + i);
+            jobs[i] = LoraDown{dy[i], lddy, out_p[i], on ? p.Bt[pj0 + i] : nullptr, out_p[i], on ? r : 0,
+                               const_cast<char*>(at(p.T2, (size_t)i * kLoraSlot, E))};
+        }
+        return launch_lora_down(dt, jobs, n, T, lo->scale, ldt2, kLoraSlot, st);
     };
-    // A of projection pj, zero-padded to 64 rows, at rows slot*64 of the stacked buffer of width in_p
-    auto pad_A = [&](int pj, int slot, int in_p) {
-        return launch_lora_pad_rows(dt, has(pj) ? lo->A[pj] : nullptr, r, in_p,
-                                    const_cast<char*>(at(p.Ap, (size_t)slot * kLoraSlot * in_p, E)), kLoraSlot, st);
-    };
+    if (lo) {  // operand preparation for the whole layer, one launch
+        LoraPrepParams pp;
+        int nj = 0;
+        auto pad = [&](int pj, void* base, int slot, int in_p) {
+            pp.job[nj++] = LoraPrepJob{has(pj) ? lo->A[pj] : nullptr, const_cast<char*>(at(base, (size_t)slot * kLoraSlot * in_p, E)),
+                                       r, in_p, kLoraSlot, 0};
+        };
+        pad(ALCH_PROJ_D, p.Ap_d, 0, F);
+        pad(ALCH_PROJ_G, p.Ap_gu, 0, H);
+        pad(ALCH_PROJ_U, p.Ap_gu, 1, H);
+        pad(ALCH_PROJ_O, p.Ap_o, 0, QD);
+        for (int i = 0; i < 3; ++i) pad(ALCH_PROJ_Q + i, p.Ap_qkv, i, H);
+        const int outs[ALCH_N_PROJ] = {QD, KD, KD, H, F, F, H};
+        for (int pj = 0; pj < ALCH_N_PROJ; ++pj)
+            if (has(pj)) pp.job[nj++] = LoraPrepJob{lo->B[pj], p.Bt[pj], r, outs[pj], r, 1};
+        ALCH_TRY(launch_lora_prep(dt, pp, nj, st));
+    }
     auto adapter_grads = [&](int pj, int slot, const void* x, long long ldx, int in_p, const void* dy, long long lddy,
                              int out_p) -> int {
         if (!wants(pj)) return ALCH_OK;
         if (lg->dB[pj]) {
-            ALCH_TRY(launch_lora_down(dt, x, ldx, T, in_p, lo->A[pj], in_p, true, r, lo->scale, p.T1, kLoraSlot, kLoraSlot, st));
+            const LoraDown job{x, ldx, in_p, lo->A[pj], in_p, r, p.T1};
+            ALCH_TRY(launch_lora_down(dt, &job, 1, T, lo->scale, kLoraSlot, kLoraSlot, st));
             ALCH_TRY(launch_lora_up(dt, p.T1, kLoraSlot, dy, lddy, T, out_p, r, 1.f, lg->dB[pj], r, true, lacc, p.up_scratch, st));
         }
         if (lg->dA[pj])
@@ -271,13 +297,14 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
 
     // MLP down projection: dAct = dY Wd, fused with the SwiGLU gradient -> [dG | dU] and Act
     if (has(ALCH_PROJ_D)) {
-        ALCH_TRY(down_t2(ALCH_PROJ_D, 0, dYp, H, H));
-        ALCH_TRY(pad_A(ALCH_PROJ_D, 0, F));
+        const void* dys[1] = {dYp};
+        const int outs1[1] = {H};
+        ALCH_TRY(down_t2(ALCH_PROJ_D, 1, dys, H, outs1));
     }
     {
         GemmDesc d = gemm(dt, T, F, true, false);
         add_seg(d, dYp, H, w.Wd, F, H);
-        if (has(ALCH_PROJ_D)) add_seg(d, p.T2, ldt2, p.Ap, F, kLoraSlot);
+        if (has(ALCH_PROJ_D)) add_seg(d, p.T2, ldt2, p.Ap_d, F, kLoraSlot);
         add_out(d, p.dGU, 0, 2 * (long long)F);
         d.epilogue = kEpiSwigluBwd;
         d.G = sv.G; d.U = sv.U; d.ldgu = F;
@@ -294,16 +321,15 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
     ALCH_TRY(adapter_grads(ALCH_PROJ_D, 0, p.Act, F, F, dYp, H, H));
     const bool lora_gu = has(ALCH_PROJ_G) || has(ALCH_PROJ_U);
     if (lora_gu) {
-        ALCH_TRY(down_t2(ALCH_PROJ_G, 0, p.dGU, 2 * (long long)F, F));
-        ALCH_TRY(down_t2(ALCH_PROJ_U, 1, at(p.dGU, F, E), 2 * (long long)F, F));
-        ALCH_TRY(pad_A(ALCH_PROJ_G, 0, H));
-        ALCH_TRY(pad_A(ALCH_PROJ_U, 1, H));
+        const void* dys[2] = {p.dGU, at(p.dGU, F, E)};
+        const int outs2[2] = {F, F};
+        ALCH_TRY(down_t2(ALCH_PROJ_G, 2, dys, 2 * (long long)F, outs2));
     }
     {  // dH2 = dG Wg + dU Wu
         GemmDesc d = gemm(dt, T, H, true, false);
         add_seg(d, p.dGU, 2 * (long long)F, w.Wg, H, F);
         add_seg(d, at(p.dGU, F, E), 2 * (long long)F, w.Wu, H, F);
-        if (lora_gu) add_seg(d, p.T2, ldt2, p.Ap, H, 2 * kLoraSlot);
+        if (lora_gu) add_seg(d, p.T2, ldt2, p.Ap_gu, H, 2 * kLoraSlot);
         add_out(d, p.dHn, 0, H);
         ALCH_TRY(launch_gemm(d, st));
     }
@@ -338,13 +364,14 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
     ALCH_TRY(launch_rmsnorm_bwd(dt, p.dHn, sv.X2, w.g2, dYp, nullptr, p.dX2, g.dg2, acc, p.partial, T, H, s.rms_eps, st));
 
     if (has(ALCH_PROJ_O)) {
-        ALCH_TRY(down_t2(ALCH_PROJ_O, 0, p.dX2, H, H));
-        ALCH_TRY(pad_A(ALCH_PROJ_O, 0, QD));
+        const void* dys[1] = {p.dX2};
+        const int outs1[1] = {H};
+        ALCH_TRY(down_t2(ALCH_PROJ_O, 1, dys, H, outs1));
     }
     {  // dO = dX2 Wo
         GemmDesc d = gemm(dt, T, QD, true, false);
         add_seg(d, p.dX2, H, w.Wo, QD, H);
-        if (has(ALCH_PROJ_O)) add_seg(d, p.T2, ldt2, p.Ap, QD, kLoraSlot);
+        if (has(ALCH_PROJ_O)) add_seg(d, p.T2, ldt2, p.Ap_o, QD, kLoraSlot);
         add_out(d, p.dO, 0, QD);
         ALCH_TRY(launch_gemm(d, st));
     }
@@ -371,17 +398,16 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
 
     const bool lora_qkv = has(ALCH_PROJ_Q) || has(ALCH_PROJ_K) || has(ALCH_PROJ_V);
     if (lora_qkv) {
-        ALCH_TRY(down_t2(ALCH_PROJ_Q, 0, p.dQKV, QKV, QD));
-        ALCH_TRY(down_t2(ALCH_PROJ_K, 1, at(p.dQKV, QD, E), QKV, KD));
-        ALCH_TRY(down_t2(ALCH_PROJ_V, 2, at(p.dQKV, QD + KD, E), QKV, KD));
-        for (int i = 0; i < 3; ++i) ALCH_TRY(pad_A(ALCH_PROJ_Q + i, i, H));
+        const void* dys[3] = {p.dQKV, at(p.dQKV, QD, E), at(p.dQKV, QD + KD, E)};
+        const int outs3[3] = {QD, KD, KD};
+        ALCH_TRY(down_t2(ALCH_PROJ_Q, 3, dys, QKV, outs3));
     }
     {  // dH1 = dQ Wq + dK Wk + dV Wv
         GemmDesc d = gemm(dt, T, H, true, false);
         add_seg(d, p.dQKV, QKV, w.Wq, H, QD);
         add_seg(d, at(p.dQKV, QD, E), QKV, w.Wk, H, KD);
         add_seg(d, at(p.dQKV, QD + KD, E), QKV, w.Wv, H, KD);
-        if (lora_qkv) add_seg(d, p.T2, ldt2, p.Ap, H, 3 * kLoraSlot);
+        if (lora_qkv) add_seg(d, p.T2, ldt2, p.Ap_qkv, H, 3 * kLoraSlot);
         add_out(d, p.dHn, 0, H);
         ALCH_TRY(launch_gemm(d, st));
     }

@@ -46,7 +46,7 @@ struct Arena {
 // Optional per-launch timing (alch_trace_enable): when on, a TraceScope brackets the kernels
 // launched inside it with two HIP events on their stream.
 enum TraceKind { kTraceGemmMfma = 0, kTraceGemmGeneric = 1, kTracePackScan = 2, kTracePackGather = 3,
-                 kTraceAttnBwd = 4, kTraceAttnFwd = 5, kTraceRowOps = 6, kTraceCrossEntropy = 7 };
+                 kTraceAttnBwd = 4, kTraceAttnFwd = 5, kTraceRowOps = 6, kTraceCrossEntropy = 7, kTraceLora = 8 };
 struct TraceScope {
     void* rec;
     hipStream_t stream;

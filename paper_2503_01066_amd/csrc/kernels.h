@@ -87,18 +87,30 @@ int launch_add(alch_dtype dt, const void* a, const void* b, void* y, long long n
 // ---- low-rank adapters ---------------------------------------------------------------------
 static constexpr int kLoraSlot = 64;       // columns of one zero-padded rank slot (rank <= 64)
 static constexpr int kLoraMaxSplits = 64;  // token splits of the adapter-gradient reduction
-// Y[t, 0:r] = alpha * sum_k X[t, k] * S(k, j); S(k, j) = S[j*lds + k] if s_kmajor else S[k*lds + j];
-// columns r .. slot_cols-1 of Y are written as zeros.  r = 0 (S may be null) zero-fills the slot.
-int launch_lora_down(alch_dtype dt, const void* X, long long ldx, int Trows, int K, const void* S, long long lds,
-                     bool s_kmajor, int r, float alpha, void* Y, long long ldy, int slot_cols, hipStream_t stream);
+// Y[t, 0:r] = alpha * sum_k X[t, k] * S[j*lds + k] (S is an [r, K] matrix); columns r .. slot_cols-1 of Y
+// are written as zeros; r = 0 (S may be null) zero-fills the slot.  Up to three problems per launch, all
+// with Trows rows, the same alpha, and outputs of row stride ldy.
+struct LoraDown {
+    const void* X; long long ldx; int K;
+    const void* S; long long lds; int r;
+    void* Y;
+};
+int launch_lora_down(alch_dtype dt, const LoraDown* jobs, int n_jobs, int Trows, float alpha, long long ldy,
+                     int slot_cols, hipStream_t stream);
 // C(j, n) (+)= alpha * sum_t S[t*lds + j] * X[t*ldx + n], j < r, n < N; stored C[j*ldc + n], or C[n*ldc + j]
 // when transposed.  scratch: lora_up_scratch_bytes(r, N) bytes of fp32 partial sums.
 size_t lora_up_scratch_bytes(int rank, int n_max);
 int launch_lora_up(alch_dtype dt, const void* S, long long lds, const void* X, long long ldx, int Trows, int N, int r,
                    float alpha, void* C, long long ldc, bool transposed, int accumulate, float* scratch,
                    hipStream_t stream);
-// dst[i, :] = i < r ? A[i, :] : 0 for i < rows_out (A null: all zeros)
-int launch_lora_pad_rows(alch_dtype dt, const void* A, int r, int width, void* dst, int rows_out, hipStream_t stream);
+// Operand preparation: job i writes dst [rows_out, cols] = src [r, cols] (or, transpose, src [cols, r]
+// transposed) followed by zero rows; src null: all zeros.
+struct LoraPrepJob {
+    const void* src; void* dst;
+    int r, cols, rows_out, transpose;
+};
+struct LoraPrepParams { LoraPrepJob job[16]; };
+int launch_lora_prep(alch_dtype dt, const LoraPrepParams& p, int n_jobs, hipStream_t stream);
 
 // ---- attention ---------------------------------------------------------------------------
 struct AttnArgs {

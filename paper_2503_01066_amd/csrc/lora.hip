@@ -6,6 +6,8 @@
 //   down:  Y[T, r]  = alpha * X[T, K] * S         (S = A^T or B; "t1 = x A^T", "t2 = dy B")
 //   up:    C[r, N]  = alpha * S[T, r]^T * X[T, N] (adapter gradients dA = t2^T x, dB^T = t1^T dy)
 // Storage type T is float or bf16, arithmetic fp32, sums over tokens in a fixed order (deterministic).
+#include <algorithm>
+
 #include "kernels.h"
 
 namespace alch {
@@ -24,11 +26,11 @@ __device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
     for (int e = 0; e < 4; ++e) { v[e] = a[e]; v[4 + e] = b[e]; }
 }
 
-// ---- down: 16 rows per work-group (4 per wavefront), 8 output columns per blockIdx.y ----------------
-// S_KMAJOR: S(k, j) = S[j*lds + k] (the [r, K] matrix A), else S(k, j) = S[k*lds + j] (the [K, r] matrix B).
-// Columns j >= r of the slot_cols-wide output slot are written as zeros (the slot is later read as a
-// zero-padded operand of a matrix-core product).
-template <typename T, bool S_KMAJOR>
+// ---- down, vector-ALU version (any dtype): 16 rows per work-group (4 per wavefront), 8 output columns
+// per blockIdx.y.  S(k, j) = S[j*lds + k] (an [r, K] matrix: A, or B transposed).  Columns j >= r of the
+// slot_cols-wide output slot are written as zeros (the slot is later read as a zero-padded operand of a
+// matrix-core product).
+template <typename T>
 __global__ __launch_bounds__(256) void k_lora_down(const T* __restrict__ X, long long ldx, int Trows, int K,
                                                    const T* __restrict__ S, long long lds, int r, float alpha,
                                                    T* __restrict__ Y, long long ldy) {
@@ -59,19 +61,11 @@ __global__ __launch_bounds__(256) void k_lora_down(const T* __restrict__ X, long
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             float s[8];
-            if (S_KMAJOR) {  // q = output column: s = S(k0..k0+7, j0+q)
-                load8(S + (long long)(j0 + q) * lds + k0, s);
+            load8(S + (long long)(j0 + q) * lds + k0, s);
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < 4; ++i)
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[i][q] = __builtin_fmaf(x[i][e], s[e], acc[i][q]);
-            } else {  // q = k index inside the chunk: s = S(k0+q, j0..j0+7)
-                load8(S + (long long)(k0 + q) * lds + j0, s);
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) acc[i][j] = __builtin_fmaf(x[i][q], s[j], acc[i][j]);
-            }
+                for (int e = 0; e < 8; ++e) acc[i][q] = __builtin_fmaf(x[i][e], s[e], acc[i][q]);
         }
     }
 #pragma unroll
@@ -84,6 +78,88 @@ __global__ __launch_bounds__(256) void k_lora_down(const T* __restrict__ X, long
         for (int l = 0; l < 64; ++l) s += red[wave][l][lane];
         const long long t = t0 + (lane >> 3);
         if (t < Trows) Y[t * ldy + j0 + (lane & 7)] = (T)(alpha * s);
+    }
+}
+
+// ---- down on the matrix cores (bf16, K a multiple of 64): eight multiply-adds per streamed element are
+// too many for the vector ALU to keep up with HBM, so the [32 rows x 16 k] x [16 k x 32 columns] MFMA does
+// them (columns >= r are zero operands).  A work-group owns 32 rows; its four wavefronts split K and fold
+// their sums through LDS in a fixed order.  Up to three (X, S, Y) problems per launch (blockIdx.z).
+typedef __attribute__((ext_vector_type(16))) float f32x16_l;
+struct LoraDownJob {
+    const __bf16* X; long long ldx; int K;
+    const __bf16* S; long long lds; int r;   // r = 0: zero-fill the slot
+    __bf16* Y;
+};
+struct LoraDownParams {
+    LoraDownJob job[3];
+    int Trows; long long ldy; float alpha; int slot_cols;
+};
+__global__ __launch_bounds__(256) void k_lora_down_mfma(LoraDownParams p) {
+    __shared__ float red[3][64][17];
+    const LoraDownJob jb = p.job[blockIdx.z];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 31, kh = lane >> 5;
+    const long long t0 = (long long)blockIdx.x * 32;
+    const int j0 = blockIdx.y * 32;  // first output column of this pass
+    f32x16_l acc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+    if (j0 < jb.r) {
+        const int kq = jb.K / 4;  // this wave's share of K (a multiple of 16)
+        // rows past the end and columns past r read a valid row instead: their results are never stored
+        const long long tr = t0 + c < p.Trows ? t0 + c : p.Trows - 1;
+        const int jc = j0 + c < jb.r ? j0 + c : 0;
+        const __bf16* xp = jb.X + tr * jb.ldx + wave * kq + 8 * kh;
+        const __bf16* sp = jb.S + (long long)jc * jb.lds + wave * kq + 8 * kh;
+        // batches of 128 k (eight 16-byte loads of X and of S per lane), double buffered: the loads of
+        // the next batch are in flight while the matrix instructions consume the current one
+        auto load_batch = [&](bf16x8_l (&a)[8], bf16x8_l (&b)[8], int kb) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                a[u] = *reinterpret_cast<const bf16x8_l*>(xp + kb + 16 * u);
+                b[u] = *reinterpret_cast<const bf16x8_l*>(sp + kb + 16 * u);
+            }
+        };
+        auto mma_batch = [&](const bf16x8_l (&a)[8], const bf16x8_l (&b)[8]) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u], b[u], acc, 0, 0, 0);
+        };
+        const int nb = kq / 128;
+        bf16x8_l a0[8], b0[8], a1[8], b1[8];
+        if (nb > 0) load_batch(a0, b0, 0);
+        int i = 0;
+        for (; i + 2 <= nb; i += 2) {
+            load_batch(a1, b1, (i + 1) * 128);
+            __builtin_amdgcn_sched_barrier(0);
+            mma_batch(a0, b0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (i + 2 < nb) load_batch(a0, b0, (i + 2) * 128);
+            __builtin_amdgcn_sched_barrier(0);
+            mma_batch(a1, b1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (i < nb) mma_batch(a0, b0);
+        int k = nb * 128;
+        for (; k < kq; k += 16) {
+            const bf16x8_l a = *reinterpret_cast<const bf16x8_l*>(xp + k);
+            const bf16x8_l b = *reinterpret_cast<const bf16x8_l*>(sp + k);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+        }
+    }
+    if (wave > 0) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) red[wave - 1][lane][e] = acc[e];
+    }
+    __syncthreads();
+    if (wave == 0) {
+        // accumulator element e: row 8*(e>>2) + 4*kh + (e&3), column c
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const float v = ((acc[e] + red[0][lane][e]) + red[1][lane][e]) + red[2][lane][e];
+            const long long t = t0 + 8 * (e >> 2) + 4 * kh + (e & 3);
+            if (t < p.Trows && j0 + c < p.slot_cols) jb.Y[t * p.ldy + j0 + c] = (__bf16)(j0 + c < jb.r ? p.alpha * v : 0.f);
+        }
     }
 }
 
@@ -140,33 +216,48 @@ __global__ __launch_bounds__(256) void k_lora_up_partial(const T* __restrict__ S
     }
 }
 
-// ---- up, pass 2: C(j, n) (+)= alpha * sum over splits, written as C[j*ldc + n] or transposed C[n*ldc + j] ----
+// ---- up, pass 2: C(j, n) (+)= alpha * sum over splits, written as C[j*ldc + n] or transposed C[n*ldc + j].
+// Eight lanes share one output: lane q adds splits q, q+8, ... and the eight sums are folded in a fixed order.
 template <typename T>
 __global__ __launch_bounds__(256) void k_lora_up_finish(const float* __restrict__ partial, int nsplit, int N, int r,
                                                         float alpha, T* __restrict__ C, long long ldc, int transposed,
                                                         int accumulate) {
-    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (long long)N * r) return;
-    // consecutive threads walk the contiguous index of the output
-    const int jj = transposed ? (int)(idx % r) : (int)(idx / N);
-    const int n = transposed ? (int)(idx / r) : (int)(idx % N);
+    const long long idx = ((long long)blockIdx.x * 256 + threadIdx.x) >> 3;
+    const int q = threadIdx.x & 7;
+    const bool live = idx < (long long)N * r;
+    // consecutive outputs walk n: the partial sums are read in order (C itself is small)
+    const int jj = !live ? 0 : (int)(idx / N);
+    const int n = !live ? 0 : (int)(idx % N);
     const float* p = partial + ((long long)(jj >> 3) * nsplit * 8 + (jj & 7)) * N + n;
     float s = 0.f;
-    for (int k = 0; k < nsplit; ++k) s += p[(long long)k * 8 * N];
-    T* dst = transposed ? C + (long long)n * ldc + jj : C + (long long)jj * ldc + n;
-    s *= alpha;
-    if (accumulate) s += (float)*dst;
-    *dst = (T)s;
+    if (live)
+        for (int k = q; k < nsplit; k += 8) s += p[(long long)k * 8 * N];
+    s += __shfl_xor(s, 1, 64);
+    s += __shfl_xor(s, 2, 64);
+    s += __shfl_xor(s, 4, 64);
+    if (live && q == 0) {
+        T* dst = transposed ? C + (long long)n * ldc + jj : C + (long long)jj * ldc + n;
+        s *= alpha;
+        if (accumulate) s += (float)*dst;
+        *dst = (T)s;
+    }
 }
 
-// ---- zero-padded stacked copy: dst[i, :] = i < r ? A[i, :] : 0 for i < rows_out (A may be null: all zeros) ----
+// ---- operand preparation, all adapters of a layer in one launch: job z writes dst [rows_out, cols] with
+// dst[i, c] = i < r ? (transpose ? src[c*r + i] : src[i*cols + c]) : 0   (src null: all zeros).
+// Used for the zero-padded stacks of the A matrices (extra operand of the data-gradient products) and for
+// B^T (so that both rank-r "down" products read an [r, K] matrix).
 template <typename T>
-__global__ __launch_bounds__(256) void k_lora_pad_rows(const T* __restrict__ A, int r, int width, T* __restrict__ dst,
-                                                       int rows_out) {
-    const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (long long)rows_out * width) return;
-    const int i = (int)(idx / width);
-    dst[idx] = (A && i < r) ? A[idx] : (T)0.f;
+__global__ __launch_bounds__(256) void k_lora_prep(LoraPrepParams p) {
+    const LoraPrepJob jb = p.job[blockIdx.y];
+    const long long n = (long long)jb.rows_out * jb.cols;
+    for (long long idx = (long long)blockIdx.x * 256 + threadIdx.x; idx < n; idx += (long long)gridDim.x * 256) {
+        const int i = (int)(idx / jb.cols), c = (int)(idx % jb.cols);
+        const T* src = static_cast<const T*>(jb.src);
+        T v = (T)0.f;
+        if (src && i < jb.r) v = jb.transpose ? src[(long long)c * jb.r + i] : src[idx];
+        static_cast<T*>(jb.dst)[idx] = v;
+    }
 }
 
 static int up_splits(int Trows, int N) {
@@ -183,24 +274,44 @@ size_t lora_up_scratch_bytes(int rank, int n_max) {
 }
 
 template <typename T>
-static int lora_down_t(const void* X, long long ldx, int Trows, int K, const void* S, long long lds, bool s_kmajor, int r,
-                       float alpha, void* Y, long long ldy, int slot_cols, hipStream_t stream) {
-    if (Trows <= 0) return ALCH_OK;
+static int lora_down_valu(const LoraDown& j, int Trows, float alpha, long long ldy, int slot_cols, hipStream_t stream) {
     const dim3 grid(ceil_div(Trows, 16), slot_cols / 8);
-    if (s_kmajor)
-        k_lora_down<T, true><<<grid, 256, 0, stream>>>((const T*)X, ldx, Trows, K, (const T*)S, lds, r, alpha, (T*)Y, ldy);
-    else
-        k_lora_down<T, false><<<grid, 256, 0, stream>>>((const T*)X, ldx, Trows, K, (const T*)S, lds, r, alpha, (T*)Y, ldy);
-    ALCH_HIP_TRY(hipGetLastError());
+    k_lora_down<T><<<grid, 256, 0, stream>>>((const T*)j.X, j.ldx, Trows, j.K, (const T*)j.S, j.lds, j.r, alpha, (T*)j.Y, ldy);
     return ALCH_OK;
 }
 
-int launch_lora_down(alch_dtype dt, const void* X, long long ldx, int Trows, int K, const void* S, long long lds,
-                     bool s_kmajor, int r, float alpha, void* Y, long long ldy, int slot_cols, hipStream_t stream) {
-    if (K % 8 || ldx % 8 || r % 8 || slot_cols % 8 || (S && lds % 8) || ldy % 8)
-        return fail(ALCH_ERR_UNSUPPORTED, "adapter product: widths, strides and rank must be multiples of 8");
-    return dt == ALCH_BF16 ? lora_down_t<__bf16>(X, ldx, Trows, K, S, lds, s_kmajor, r, alpha, Y, ldy, slot_cols, stream)
-                           : lora_down_t<float>(X, ldx, Trows, K, S, lds, s_kmajor, r, alpha, Y, ldy, slot_cols, stream);
+int launch_lora_down(alch_dtype dt, const LoraDown* jobs, int n_jobs, int Trows, float alpha, long long ldy,
+                     int slot_cols, hipStream_t stream) {
+    if (n_jobs < 1 || n_jobs > 3) return fail(ALCH_ERR_INVALID_ARG, "adapter product: 1..3 problems per launch");
+    double flops = 0, bytes = 0;
+    bool fast = dt == ALCH_BF16;
+    for (int i = 0; i < n_jobs; ++i) {
+        const LoraDown& j = jobs[i];
+        if (j.K % 8 || j.ldx % 8 || j.r % 8 || (j.r > 0 && j.lds % 8))
+            return fail(ALCH_ERR_UNSUPPORTED, "adapter product: widths, strides and rank must be multiples of 8");
+        if (j.r > 0) { flops += 2.0 * Trows * j.K * j.r; bytes += (double)Trows * j.K * dtype_size(dt); }
+        fast = fast && j.K % 64 == 0 && aligned16(j.X) && (j.r == 0 || aligned16(j.S));
+    }
+    if (slot_cols % 8 || ldy % 8) return fail(ALCH_ERR_UNSUPPORTED, "adapter product: slot width must be a multiple of 8");
+    if (Trows <= 0) return ALCH_OK;
+    // algorithmic bytes: each streamed activation once (nothing for slots that are only zero-filled)
+    TraceScope ts(kTraceLora, flops, bytes, stream);
+    if (fast) {
+        LoraDownParams p;
+        for (int i = 0; i < 3; ++i) {
+            const LoraDown& j = jobs[i < n_jobs ? i : 0];
+            p.job[i] = LoraDownJob{(const __bf16*)j.X, j.ldx, j.K, (const __bf16*)j.S, j.lds, j.r, (__bf16*)j.Y};
+        }
+        p.Trows = Trows; p.ldy = ldy; p.alpha = alpha; p.slot_cols = slot_cols;
+        k_lora_down_mfma<<<dim3(ceil_div(Trows, 32), ceil_div(slot_cols, 32), n_jobs), 256, 0, stream>>>(p);
+    } else {
+        for (int i = 0; i < n_jobs; ++i) {
+            if (dt == ALCH_BF16) lora_down_valu<__bf16>(jobs[i], Trows, alpha, ldy, slot_cols, stream);
+            else lora_down_valu<float>(jobs[i], Trows, alpha, ldy, slot_cols, stream);
+        }
+    }
+    ALCH_HIP_TRY(hipGetLastError());
+    return ALCH_OK;
 }
 
 template <typename T>
@@ -212,7 +323,7 @@ static int lora_up_t(const void* S, long long lds, const void* X, long long ldx,
         k_lora_up_partial<T><<<dim3(ceil_div(N, 512), nsplit, r / 8), 256, 0, stream>>>((const T*)S, lds, (const T*)X, ldx,
                                                                                        Trows, N, rps, scratch);
     }
-    k_lora_up_finish<T><<<ceil_div((long long)N * r, 256LL), 256, 0, stream>>>(scratch, nsplit, N, r, alpha, (T*)C, ldc,
+    k_lora_up_finish<T><<<ceil_div((long long)N * r * 8, 256LL), 256, 0, stream>>>(scratch, nsplit, N, r, alpha, (T*)C, ldc,
                                                                               transposed ? 1 : 0, accumulate);
     ALCH_HIP_TRY(hipGetLastError());
     return ALCH_OK;
@@ -223,17 +334,20 @@ int launch_lora_up(alch_dtype dt, const void* S, long long lds, const void* X, l
                    hipStream_t stream) {
     if (N % 8 || ldx % 8 || lds % 8 || r % 8 || r <= 0)
         return fail(ALCH_ERR_UNSUPPORTED, "adapter gradient: widths, strides and rank must be multiples of 8");
+    TraceScope ts(kTraceLora, 2.0 * Trows * N * r, (double)Trows * N * dtype_size(dt), stream);
     return dt == ALCH_BF16 ? lora_up_t<__bf16>(S, lds, X, ldx, Trows, N, r, alpha, C, ldc, transposed, accumulate, scratch, stream)
                            : lora_up_t<float>(S, lds, X, ldx, Trows, N, r, alpha, C, ldc, transposed, accumulate, scratch, stream);
 }
 
-int launch_lora_pad_rows(alch_dtype dt, const void* A, int r, int width, void* dst, int rows_out, hipStream_t stream) {
-    const long long n = (long long)rows_out * width;
-    if (n <= 0) return ALCH_OK;
-    if (dt == ALCH_BF16)
-        k_lora_pad_rows<__bf16><<<ceil_div(n, 256LL), 256, 0, stream>>>((const __bf16*)A, r, width, (__bf16*)dst, rows_out);
-    else
-        k_lora_pad_rows<float><<<ceil_div(n, 256LL), 256, 0, stream>>>((const float*)A, r, width, (float*)dst, rows_out);
+int launch_lora_prep(alch_dtype dt, const LoraPrepParams& p, int n_jobs, hipStream_t stream) {
+    if (n_jobs <= 0) return ALCH_OK;
+    long long most = 0;
+    for (int i = 0; i < n_jobs; ++i) most = std::max(most, (long long)p.job[i].rows_out * p.job[i].cols);
+    int gx = ceil_div(most, 256LL);
+    if (gx > 512) gx = 512;
+    if (gx < 1) gx = 1;
+    if (dt == ALCH_BF16) k_lora_prep<__bf16><<<dim3(gx, n_jobs), 256, 0, stream>>>(p);
+    else k_lora_prep<float><<<dim3(gx, n_jobs), 256, 0, stream>>>(p);
     ALCH_HIP_TRY(hipGetLastError());
     return ALCH_OK;
 }
