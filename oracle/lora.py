@@ -100,3 +100,30 @@ def layer_backward_reuse_lora(shape, cu_seqlens, positions, rec, W, lora, scale,
         g["dA" + p] = scale * np.asarray(B, dtype=np.float64).T @ dWm
         g["dB" + p] = scale * dWm @ np.asarray(A, dtype=np.float64).T
     return g
+
+
+def stack_forward_lora(shape, cu_seqlens, positions, X0, layers_W, layers_lora, scale):
+    """The adapted layers in order.  Returns (X_final, [record_l])."""
+    X = np.asarray(X0, dtype=np.float64)
+    recs = []
+    for W, lora in zip(layers_W, layers_lora):
+        X, rec = layer_forward_lora(shape, cu_seqlens, positions, X, W, lora, scale)
+        recs.append(rec)
+    return X, recs
+
+
+def stack_backward_reuse_lora(shape, cu_seqlens, positions, recs, layers_W, layers_lora, scale, X_final,
+                              g_final, W_lm, labels, loss_mask=None):
+    """Cross-entropy head (Section 5) on the saved stack output, then the adapted layers from the output
+    layer to the input layer (Section 4.2), each from its own saved record.  The head carries no adapter.
+    Returns the dict of stack_backward_reuse; the per-layer dicts also hold dA_p, dB_p."""
+    from .stack import _head_loss_and_grads
+    X_final = np.asarray(X_final, dtype=np.float64)
+    loss, dX, dg_final, dW_lm = _head_loss_and_grads(shape, X_final, np.asarray(g_final, dtype=np.float64),
+                                                     np.asarray(W_lm, dtype=np.float64), labels, loss_mask)
+    per_layer = [None] * len(layers_W)
+    for l in range(len(layers_W) - 1, -1, -1):
+        g = layer_backward_reuse_lora(shape, cu_seqlens, positions, recs[l], layers_W[l], layers_lora[l], scale, dX)
+        dX = g["dX"]
+        per_layer[l] = g
+    return dict(loss=loss, dX_embed=dX, dg_final=dg_final, dW_lm=dW_lm, layers=per_layer)

@@ -125,3 +125,43 @@ def test_loss_mask_equals_zeroed_rows():
     b = layer_backward_reuse_lora(shape, cu, None, rec, W, lora, 1.0, Rz)
     for k in a:
         assert np.array_equal(a[k], b[k]), k
+
+
+def test_stack_adapter_gradients_by_finite_differences_of_the_loss():
+    # two adapted layers + head: d loss / d A, d B of BOTH layers against central differences of the
+    # scalar loss computed by the unmerged forward (the gradient of layer 0 passes through layer 1)
+    from oracle.lora import stack_forward_lora, stack_backward_reuse_lora
+    from oracle.stack import _head_loss_and_grads
+    shape, cu, T, W0, l0, X, _ = make(11, adapted=("q", "o", "d"), r=2)
+    _, _, _, W1, l1, _, _ = make(12, adapted=("k", "g"), r=2)
+    rng = np.random.default_rng(5)
+    V = 13
+    gf = 1 + 0.1 * rng.normal(size=shape.hidden)
+    Wlm = rng.normal(0, 0.3, (V, shape.hidden))
+    labels = rng.integers(0, V, T)
+    labels[cu[1:] - 1] = -1
+    scale = 0.8
+    Ws, Ls = [W0, W1], [l0, l1]
+
+    def loss():
+        Xf, _ = stack_forward_lora(shape, cu, None, X, Ws, Ls, scale)
+        return _head_loss_and_grads(shape, Xf, gf, Wlm, labels, None)[0]
+
+    Xf, recs = stack_forward_lora(shape, cu, None, X, Ws, Ls, scale)
+    g = stack_backward_reuse_lora(shape, cu, None, recs, Ws, Ls, scale, Xf, gf, Wlm, labels)
+    assert abs(g["loss"] - loss()) < 1e-12
+    h = 1e-5
+    for l, lora in enumerate(Ls):
+        for p, (A, B) in lora.items():
+            for name, P in (("dA" + p, A), ("dB" + p, B)):
+                an = g["layers"][l][name]
+                ref = max(np.abs(an).max(), 1e-30)
+                idx = list(np.ndindex(*P.shape))
+                for i in [idx[k] for k in rng.choice(len(idx), min(12, len(idx)), replace=False)]:
+                    old = P[i]
+                    P[i] = old + h
+                    fp = loss()
+                    P[i] = old - h
+                    fm = loss()
+                    P[i] = old
+                    assert abs((fp - fm) / (2 * h) - an[i]) <= 5e-6 * ref, (l, name, i)
