@@ -219,6 +219,7 @@ int alch_layer_backward_lora(const alch_layer_shape* shape, const alch_batch* ba
 size_t alch_layer_backward_lora_workspace_bytes(const alch_layer_shape* shape, int32_t total_tokens,
                                                 int32_t max_seqlen, int32_t rank);
 
+
 /* Host callbacks of the stack walk (Section 4.2: a hook at the start of each layer's
  * backward lets serving pre-empt training; Section 4.3.2: a layer's activations may
  * still be on their way back to the GPU).  layer_ready(user, l) is called before layer
@@ -255,6 +256,24 @@ int alch_stack_backward(const alch_layer_shape* shape, int32_t n_layers, int32_t
 
 size_t alch_stack_backward_workspace_bytes(const alch_layer_shape* shape, int32_t n_layers,
                                            int32_t vocab, int32_t total_tokens, int32_t max_seqlen);
+
+/*
+ * alch_stack_backward_lora: alch_stack_backward for a stack whose layers carry low-rank adapters
+ * (Section 3 assumption A1, Section 6).  lora, lora_grads: HOST arrays of n_layers entries, the same
+ * rank in every layer; lora_grads may be NULL.  The head carries no adapter.  With wgrads == NULL,
+ * dg_final == NULL and dW_lm == NULL this is the paper's training setting: frozen base, adapter
+ * gradients only.
+ */
+int alch_stack_backward_lora(const alch_layer_shape* shape, int32_t n_layers, int32_t vocab,
+                             const alch_batch* batch, const alch_saved* saved, const alch_weights* weights,
+                             const alch_lora* lora, const void* X_final, const void* g_final, const void* W_lm,
+                             const int32_t* labels, const uint8_t* loss_mask, const alch_wgrads* wgrads,
+                             const alch_lora_grads* lora_grads, void* dg_final, void* dW_lm, void* dX_embed,
+                             float* loss_out, const alch_hooks* hooks, void* workspace, size_t workspace_bytes,
+                             void* hip_stream);
+
+size_t alch_stack_backward_lora_workspace_bytes(const alch_layer_shape* shape, int32_t n_layers, int32_t vocab,
+                                                int32_t total_tokens, int32_t max_seqlen, int32_t rank);
 
 /*
  * alch_layer_forward: the forward pass of one layer, writing Y and the full record.

@@ -129,6 +129,15 @@ def lib():
                                       C.POINTER(CSaved), C.POINTER(CWeights), C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.POINTER(CWgrads), C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.POINTER(CHooks), C.c_void_p, C.c_size_t, C.c_void_p]
+    L.alch_stack_backward_lora_workspace_bytes.restype = C.c_size_t
+    L.alch_stack_backward_lora_workspace_bytes.argtypes = [C.POINTER(LayerShape), C.c_int32, C.c_int32, C.c_int32,
+                                                           C.c_int32, C.c_int32]
+    L.alch_stack_backward_lora.restype = C.c_int
+    L.alch_stack_backward_lora.argtypes = [C.POINTER(LayerShape), C.c_int32, C.c_int32, C.POINTER(CBatch),
+                                           C.POINTER(CSaved), C.POINTER(CWeights), C.POINTER(CLora), C.c_void_p,
+                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(CWgrads),
+                                           C.POINTER(CLoraGrads), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.POINTER(CHooks), C.c_void_p, C.c_size_t, C.c_void_p]
     L.alch_layer_forward.restype = C.c_int
     L.alch_layer_forward.argtypes = [C.POINTER(LayerShape), C.POINTER(CBatch), C.c_void_p, C.POINTER(CWeights),
                                      C.c_void_p, C.POINTER(CRecordOut), C.c_void_p, C.c_size_t, C.c_void_p]
@@ -267,14 +276,7 @@ def alch_layer_backward_lora(shape, batch, saved, weights, lora, rank, scale, dY
             lora_grads["dB" + p_] = torch.empty_like(B_)
     if dX is None:
         dX = torch.empty_like(dY)
-    cl = CLora(rank=rank, scale=scale)
-    cg = CLoraGrads(accumulate=1 if accumulate else 0)
-    for i, p_ in enumerate(PROJECTIONS):
-        if p_ in lora:
-            cl.A[i], cl.B[i] = lora[p_][0].data_ptr(), lora[p_][1].data_ptr()
-        for arr, key in ((cg.dA, "dA" + p_), (cg.dB, "dB" + p_)):
-            if lora_grads.get(key) is not None:
-                arr[i] = lora_grads[key].data_ptr()
+    cl, cg = _lora_structs(lora, lora_grads, rank, scale, accumulate)
     need = L.alch_layer_backward_lora_workspace_bytes(C.byref(shape), batch.total_tokens, batch.max_seqlen, rank)
     ws = workspace if workspace is not None else _workspace(need, dev)
     sv, w, g = _saved_struct(saved, 0), _weights_struct(weights, 0), _wgrads_struct(grads, accumulate)
@@ -334,6 +336,62 @@ def alch_stack_backward(shape, batch, saved_layers, weights_layers, X_final, g_f
                                  _ptr(dW_lm), _ptr(dX_embed), _ptr(loss), C.byref(hk) if hk else None, _ptr(ws),
                                  ws.numel(), _stream_handle(stream)))
     return dict(loss=loss, dX_embed=dX_embed, dg_final=dg_final, dW_lm=dW_lm, layers=grads_layers)
+
+
+def _lora_structs(lora, lora_grads, rank, scale, accumulate):
+    cl = CLora(rank=rank, scale=scale)
+    cg = CLoraGrads(accumulate=1 if accumulate else 0)
+    for i, p_ in enumerate(PROJECTIONS):
+        if p_ in lora:
+            cl.A[i], cl.B[i] = lora[p_][0].data_ptr(), lora[p_][1].data_ptr()
+        for arr, key in ((cg.dA, "dA" + p_), (cg.dB, "dB" + p_)):
+            if lora_grads.get(key) is not None:
+                arr[i] = lora_grads[key].data_ptr()
+    return cl, cg
+
+
+def alch_stack_backward_lora(shape, batch, saved_layers, weights_layers, lora_layers, rank, scale, X_final, g_final,
+                             W_lm, labels, loss_mask=None, want=(), want_head=False, lora_grads_layers=None,
+                             accumulate=False, workspace=None, stream=None):
+    """Stack backward with adapters.  lora_layers: list of dicts projection -> (A, B).  Defaults: frozen base and
+    frozen head (want=(), want_head=False), gradients of every adapter.  Returns the dict of alch_stack_backward;
+    the per-layer dicts hold the adapter gradients ('dAq', 'dBq', ...) and any base gradients asked for."""
+    L = lib()
+    dev = X_final.device
+    n_layers = len(saved_layers)
+    vocab = W_lm.shape[0]
+    grads_layers = [{"d" + k: torch.empty_like(w[k]) for k in want} for w in weights_layers]
+    if lora_grads_layers is None:
+        lora_grads_layers = []
+        for lo in lora_layers:
+            g = {}
+            for p_, (A_, B_) in lo.items():
+                g["dA" + p_], g["dB" + p_] = torch.empty_like(A_), torch.empty_like(B_)
+            lora_grads_layers.append(g)
+    n = max(n_layers, 1)
+    SA = (CSaved * n)(*[_saved_struct(s, 0) for s in saved_layers])
+    WA = (CWeights * n)(*[_weights_struct(w, 0) for w in weights_layers])
+    GA = (CWgrads * n)(*[_wgrads_struct(g, accumulate) for g in grads_layers])
+    pairs = [_lora_structs(lo, lg, rank, scale, accumulate) for lo, lg in zip(lora_layers, lora_grads_layers)]
+    LA = (CLora * n)(*[p_[0] for p_ in pairs])
+    LG = (CLoraGrads * n)(*[p_[1] for p_ in pairs])
+    dg_final = torch.empty_like(g_final) if want_head else None
+    dW_lm = torch.empty_like(W_lm) if want_head else None
+    dX_embed = torch.empty_like(X_final)
+    loss = torch.empty(1, dtype=torch.float32, device=dev)
+    need = L.alch_stack_backward_lora_workspace_bytes(C.byref(shape), n_layers, vocab, batch.total_tokens,
+                                                      batch.max_seqlen, rank)
+    ws = workspace if workspace is not None else _workspace(need, dev)
+    _check(L.alch_stack_backward_lora(C.byref(shape), n_layers, vocab, C.byref(batch.c), SA, WA, LA, _ptr(X_final),
+                                      _ptr(g_final), _ptr(W_lm), _ptr(labels), _ptr(loss_mask), GA, LG, _ptr(dg_final),
+                                      _ptr(dW_lm), _ptr(dX_embed), _ptr(loss), None, _ptr(ws), ws.numel(),
+                                      _stream_handle(stream)))
+    layers = []
+    for g, lg in zip(grads_layers, lora_grads_layers):
+        d = dict(g)
+        d.update(lg)
+        layers.append(d)
+    return dict(loss=loss, dX_embed=dX_embed, dg_final=dg_final, dW_lm=dW_lm, layers=layers)
 
 
 def alch_gemm(M, N, terms, a_kmajor, b_kmajor, out=None, accumulate=False, stream=None):

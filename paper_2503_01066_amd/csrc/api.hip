@@ -161,7 +161,7 @@ struct StackPlan {
     float* partial;
     size_t layer_ws_bytes, bytes;
 };
-static StackPlan plan_stack(const alch_layer_shape& s, int vocab, int T, void* ws, size_t ws_bytes) {
+static StackPlan plan_stack(const alch_layer_shape& s, int vocab, int T, void* ws, size_t ws_bytes, int lora_rank = 0) {
     Arena a(ws, ws_bytes);
     const size_t E = dtype_size(s.dtype), t = (size_t)(T > 0 ? T : 1), H = s.hidden;
     const size_t chunk = t < (size_t)kHeadChunkRows ? t : (size_t)kHeadChunkRows;
@@ -174,7 +174,7 @@ static StackPlan plan_stack(const alch_layer_shape& s, int vocab, int T, void* w
     p.row_loss = static_cast<float*>(a.take(t * sizeof(float)));
     p.n_counted = static_cast<int*>(a.take(256));
     p.partial = static_cast<float*>(a.take((size_t)rmsnorm_bwd_blocks(T) * H * sizeof(float)));
-    p.layer_ws_bytes = plan_layer_bwd(s, T, nullptr, 0).bytes;
+    p.layer_ws_bytes = plan_layer_bwd(s, T, nullptr, 0, lora_rank).bytes;
     p.layer_ws = a.take(p.layer_ws_bytes);
     p.bytes = round_up(a.used, 256);
     return p;
@@ -627,11 +627,12 @@ size_t alch_stack_backward_workspace_bytes(const alch_layer_shape* shape, int32_
     return plan_stack(*shape, vocab, total_tokens, nullptr, 0).bytes;
 }
 
-int alch_stack_backward(const alch_layer_shape* shape, int32_t n_layers, int32_t vocab, const alch_batch* batch,
-                        const alch_saved* saved, const alch_weights* weights, const void* X_final,
-                        const void* g_final, const void* W_lm, const int32_t* labels, const uint8_t* loss_mask,
-                        const alch_wgrads* wgrads, void* dg_final, void* dW_lm, void* dX_embed, float* loss_out,
-                        const alch_hooks* hooks, void* workspace, size_t workspace_bytes, void* hip_stream) {
+static int stack_backward_impl(const alch_layer_shape* shape, int32_t n_layers, int32_t vocab, const alch_batch* batch,
+                               const alch_saved* saved, const alch_weights* weights, const alch_lora* lora,
+                               const void* X_final, const void* g_final, const void* W_lm, const int32_t* labels,
+                               const uint8_t* loss_mask, const alch_wgrads* wgrads, const alch_lora_grads* lora_grads,
+                               void* dg_final, void* dW_lm, void* dX_embed, float* loss_out, const alch_hooks* hooks,
+                               void* workspace, size_t workspace_bytes, void* hip_stream) {
     clear_error();
     ALCH_TRY(check_shape(shape));
     ALCH_TRY(check_batch(batch));
@@ -641,17 +642,22 @@ int alch_stack_backward(const alch_layer_shape* shape, int32_t n_layers, int32_t
     for (int l = 0; l < n_layers; ++l) {
         ALCH_TRY(check_saved_weights(&saved[l], &weights[l], batch->total_tokens));
         if (wgrads) ALCH_TRY(check_wgrads(&wgrads[l]));
+        if (lora) {
+            ALCH_TRY(check_lora(shape, &lora[l], lora_grads ? &lora_grads[l] : nullptr));
+            if (lora[l].rank != lora[0].rank) return fail(ALCH_ERR_SHAPE, "layer %d: adapter rank differs from layer 0", l);
+        }
     }
+    const int rank = (lora && n_layers > 0) ? lora[0].rank : 0;
     REQUIRE_ACT(X_final, "X_final", batch->total_tokens); REQUIRE_PTR(g_final, "g_final"); REQUIRE_PTR(W_lm, "W_lm");
     REQUIRE_ACT(dX_embed, "dX_embed", batch->total_tokens);
     if ((batch->total_tokens > 0 && !labels) || !loss_out) return fail(ALCH_ERR_INVALID_ARG, "labels / loss_out is NULL");
     OPTIONAL_PTR(dg_final, "dg_final"); OPTIONAL_PTR(dW_lm, "dW_lm");
-    const size_t need = plan_stack(*shape, vocab, batch->total_tokens, nullptr, 0).bytes;
+    const size_t need = plan_stack(*shape, vocab, batch->total_tokens, nullptr, 0, rank).bytes;
     if (!workspace || workspace_bytes < need) return fail(ALCH_ERR_WORKSPACE, "workspace %zu bytes < %zu needed", workspace_bytes, need);
     if (!aligned16(workspace)) return fail(ALCH_ERR_INVALID_ARG, "workspace is not 16-byte aligned");
 
     const alch_layer_shape& s = *shape;
-    const StackPlan p = plan_stack(s, vocab, batch->total_tokens, workspace, workspace_bytes);
+    const StackPlan p = plan_stack(s, vocab, batch->total_tokens, workspace, workspace_bytes, rank);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const alch_dtype dt = s.dtype;
     const size_t E = dtype_size(dt);
@@ -701,7 +707,7 @@ int alch_stack_backward(const alch_layer_shape* shape, int32_t n_layers, int32_t
     ALCH_TRY(launch_rmsnorm_bwd(dt, p.dHf, X_final, g_final, nullptr, nullptr, cur, dg_final, acc, p.partial, T, H,
                                 s.rms_eps, st));
 
-    const LayerBwdPlan lp = plan_layer_bwd(s, T, p.layer_ws, p.layer_ws_bytes);
+    const LayerBwdPlan lp = plan_layer_bwd(s, T, p.layer_ws, p.layer_ws_bytes, rank);
     for (int l = n_layers - 1; l >= 0; --l) {
         if (hooks && hooks->preempt && hooks->preempt(hooks->user, l) != 0)
             return fail(ALCH_ERR_ABORTED, "preempt hook stopped the walk before layer %d", l);
@@ -709,10 +715,44 @@ int alch_stack_backward(const alch_layer_shape* shape, int32_t n_layers, int32_t
             return fail(ALCH_ERR_ABORTED, "layer_ready hook failed for layer %d", l);
         void* out = l == 0 ? dX_embed : (cur == p.ping ? p.pong : p.ping);
         ALCH_TRY(layer_backward_enqueue(s, *batch, saved[l], weights[l], cur, nullptr, out,
-                                        wgrads ? &wgrads[l] : nullptr, lp, st));
+                                        wgrads ? &wgrads[l] : nullptr, lp, st, lora ? &lora[l] : nullptr,
+                                        lora_grads ? &lora_grads[l] : nullptr));
         cur = out;
     }
     return ALCH_OK;
+}
+
+int alch_stack_backward(const alch_layer_shape* shape, int32_t n_layers, int32_t vocab, const alch_batch* batch,
+                        const alch_saved* saved, const alch_weights* weights, const void* X_final,
+                        const void* g_final, const void* W_lm, const int32_t* labels, const uint8_t* loss_mask,
+                        const alch_wgrads* wgrads, void* dg_final, void* dW_lm, void* dX_embed, float* loss_out,
+                        const alch_hooks* hooks, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return stack_backward_impl(shape, n_layers, vocab, batch, saved, weights, nullptr, X_final, g_final, W_lm, labels,
+                               loss_mask, wgrads, nullptr, dg_final, dW_lm, dX_embed, loss_out, hooks, workspace,
+                               workspace_bytes, hip_stream);
+}
+
+size_t alch_stack_backward_lora_workspace_bytes(const alch_layer_shape* shape, int32_t n_layers, int32_t vocab,
+                                                int32_t total_tokens, int32_t max_seqlen, int32_t rank) {
+    (void)max_seqlen; (void)n_layers;
+    if (!shape || check_shape(shape) != ALCH_OK || total_tokens < 0 || vocab <= 0 || rank < 8 || rank > kLoraSlot || rank % 8)
+        return 0;
+    return plan_stack(*shape, vocab, total_tokens, nullptr, 0, rank).bytes;
+}
+
+int alch_stack_backward_lora(const alch_layer_shape* shape, int32_t n_layers, int32_t vocab, const alch_batch* batch,
+                             const alch_saved* saved, const alch_weights* weights, const alch_lora* lora,
+                             const void* X_final, const void* g_final, const void* W_lm, const int32_t* labels,
+                             const uint8_t* loss_mask, const alch_wgrads* wgrads, const alch_lora_grads* lora_grads,
+                             void* dg_final, void* dW_lm, void* dX_embed, float* loss_out, const alch_hooks* hooks,
+                             void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (n_layers > 0 && !lora) {
+        clear_error();
+        return fail(ALCH_ERR_INVALID_ARG, "lora array is NULL");
+    }
+    return stack_backward_impl(shape, n_layers, vocab, batch, saved, weights, lora, X_final, g_final, W_lm, labels,
+                               loss_mask, wgrads, lora_grads, dg_final, dW_lm, dX_embed, loss_out, hooks, workspace,
+                               workspace_bytes, hip_stream);
 }
 
 int alch_attention_forward(const alch_layer_shape* shape, const alch_batch* batch, const void* Q, const void* K,

@@ -132,3 +132,61 @@ def test_llama8b_width_frozen_base_short_batch():
     ref = layer_backward_reuse_lora(osh, cu, None, f64(rec), f64(W), lora64, scale, dY)
     gpu = run_gpu(shp, "bf16", cu, W, lora, 8, scale, rec, dY)
     compare(gpu, ref, "bf16")
+
+
+@pytest.mark.parametrize("dtype,shape_name,lens,L,V,wstd", [("f32", "tiny", [5, 1, 9], 3, 37, 0.3),
+                                                           ("bf16", "medium64", [130, 61, 200], 2, 1000, 0.05)])
+def test_stack_frozen_base_adapter_gradients(dtype, shape_name, lens, L, V, wstd):
+    # the paper's training setting end to end: head + L adapted layers, frozen base and head, adapters on q and v
+    # (layer 0) or on every projection (other layers); records from the adapted oracle forward
+    import paper_2503_01066_amd as A
+    from oracle.lora import stack_forward_lora, stack_backward_reuse_lora
+    cu = synth.ragged_cu(lens)
+    shp = synth.shape_dict(shape_name)
+    osh = oracle_shape(shp)
+    T = int(cu[-1])
+    scale, rank = 2.0, 8
+    Ws = [synth.layer_weights(shp, 40 + 10 * l, dtype, std=wstd, gain_std=0.1) for l in range(L)]
+    loras = [synth.lora_adapters(shp, rank, 90 + l, dtype, ("q", "v") if l == 0 else synth.PROJECTIONS, std=0.1) for l in range(L)]
+    loras64 = [{p: (a.astype(np.float64), b.astype(np.float64)) for p, (a, b) in lo.items()} for lo in loras]
+    rng = np.random.default_rng(77)
+    X0 = synth.normal(rng, (T, shp["hidden"]), 1.0, dtype)
+    gf = synth.quantize(1.0 + 0.1 * rng.standard_normal(shp["hidden"]).astype(np.float32), dtype)
+    Wlm = synth.normal(rng, (V, shp["hidden"]), wstd, dtype)
+    ids = rng.integers(0, V, T)
+    labels = np.full(T, -1, dtype=np.int32)
+    for s in range(len(cu) - 1):
+        a, b = int(cu[s]), int(cu[s + 1])
+        if b - a > 1:
+            labels[a:b - 1] = ids[a + 1:b]
+    Xf64, recs64 = stack_forward_lora(osh, cu, None, X0.astype(np.float64), [f64(W) for W in Ws], loras64, scale)
+    recs = []
+    for r in recs64:
+        q = {k: synth.quantize(r[k].astype(np.float32), dtype) for k in REC}
+        q["LSE"] = r["LSE"].astype(np.float32)
+        recs.append(q)
+    Xf = synth.quantize(Xf64.astype(np.float32), dtype)
+    ref = stack_backward_reuse_lora(osh, cu, None, [f64(r) for r in recs], [f64(W) for W in Ws], loras64, scale,
+                                    Xf.astype(np.float64), gf.astype(np.float64), Wlm.astype(np.float64), labels)
+
+    drecs = []
+    for r in recs:
+        d = {k: to_dev(r[k], dtype) for k in REC}
+        d["LSE"] = torch.from_numpy(r["LSE"]).cuda()
+        drecs.append(d)
+    out = A.alch_stack_backward_lora(alch_shape(shp, dtype), A.Batch(cu), drecs,
+                                     [{k: to_dev(v, dtype) for k, v in W.items()} for W in Ws],
+                                     [{p: (to_dev(a, dtype), to_dev(b, dtype)) for p, (a, b) in lo.items()} for lo in loras],
+                                     rank, scale, to_dev(Xf, dtype), to_dev(gf, dtype), to_dev(Wlm, dtype),
+                                     torch.from_numpy(labels).cuda())
+    torch.cuda.synchronize()
+    tol = TOL[dtype]
+    assert abs(out["loss"].item() - ref["loss"]) <= tol * max(1.0, abs(ref["loss"]))
+    assert rel_err(to_np(out["dX_embed"]), ref["dX_embed"]) <= tol
+    assert out["dW_lm"] is None and out["dg_final"] is None
+    for l in range(L):
+        keys = sorted(out["layers"][l])
+        assert keys == sorted("d" + m + p for p in loras[l] for m in "AB"), keys
+        for k in keys:
+            e = rel_err(to_np(out["layers"][l][k]), ref["layers"][l][k])
+            assert e <= tol, (l, k, e)
