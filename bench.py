@@ -271,11 +271,37 @@ def run_config4(args, torch, A):
         return X, recs
 
     X_final, recs = forward()          # the records a serving prefill would have left behind
-    grads = [{"d" + k: torch.empty_like(v) for k, v in W.items()} for W in Ws]
-    ws = torch.empty(A.stack_backward_workspace_bytes(shape, L, V, T, S), dtype=torch.uint8, device=dev)
+    r = args.lora_rank
+    wflops = 2.0 if args.frozen_base else 4.0   # GEMM flops per parameter and token
+    mode = "full backward"
+    if r:
+        # the paper's training setting (Section 6): rank-r adapters, here on all seven projections of every
+        # layer; B = 0, the usual initialisation, so the records of the plain forward above are the adapted
+        # model's records.  Base and head are frozen with --frozen-base, trained too without it.
+        import ctypes
+        dims = dict(q=(QD, H), k=(KD, H), v=(KD, H), o=(H, QD), g=(F, H), u=(F, H), d=(H, F))
+        loras = [{p: (rnd((r, i), 0.05), torch.zeros((o, r), device=dev, dtype=bf)) for p, (o, i) in dims.items()}
+                 for _ in range(L)]
+        lgrads = [{"d" + m + p: torch.empty_like(ab[0] if m == "A" else ab[1]) for p, ab in lo.items() for m in "AB"}
+                  for lo in loras]
+        need = A.lib().alch_stack_backward_lora_workspace_bytes(ctypes.byref(shape), L, V, T, S, r)
+        ws = torch.empty(need, dtype=torch.uint8, device=dev)
+        bgrads = [({} if args.frozen_base else {"d" + k: torch.empty_like(v) for k, v in W.items()}) for W in Ws]
+        mode = "rank-%d adapter gradients on a %s base" % (r, "frozen" if args.frozen_base else "trained")
 
-    def backward(xf, rs):
-        return A.alch_stack_backward(shape, batch, rs, Ws, xf, g_final, W_lm, labels, grads_layers=grads, workspace=ws)
+        def backward(xf, rs):
+            return A.alch_stack_backward_lora(shape, batch, rs, Ws, loras, r, 2.0, xf, g_final, W_lm, labels,
+                                              grads_layers=bgrads, want_head=not args.frozen_base,
+                                              lora_grads_layers=lgrads, workspace=ws)
+    else:
+        grads = [({} if args.frozen_base else {"d" + k: torch.empty_like(v) for k, v in W.items()}) for W in Ws]
+        ws = torch.empty(A.stack_backward_workspace_bytes(shape, L, V, T, S), dtype=torch.uint8, device=dev)
+        if args.frozen_base:
+            mode = "data gradients only (frozen base and head)"
+
+        def backward(xf, rs):
+            return A.alch_stack_backward(shape, batch, rs, Ws, xf, g_final, W_lm, labels, grads_layers=grads,
+                                         want_head=not args.frozen_base, workspace=ws)
 
     def timed(fn, steps, warmup):
         for _ in range(warmup):
@@ -303,7 +329,8 @@ def run_config4(args, torch, A):
     gm_ms = sum(r[3] for r in gm)
     achieved_tf = sum(r[1] for r in gm) / (gm_ms * 1e-3) / 1e12
     P = 2 * H * QD + 2 * H * KD + 3 * H * F
-    flops = T * (L * 4.0 * P + 6.0 * V * H) + L * 10.0 * shp["head_dim"] * shp["n_q_heads"] * B * S * (S + 1) / 2
+    head_flops = (4.0 if args.frozen_base else 6.0) * V * H   # logits + dHf (+ dW_lm)
+    flops = T * (L * wflops * P + head_flops) + L * 10.0 * shp["head_dim"] * shp["n_q_heads"] * B * S * (S + 1) / 2
     by = {}
     for kind, fl, nb, ms in trace:
         by[kind] = by.get(kind, 0.0) + ms
@@ -313,7 +340,7 @@ def run_config4(args, torch, A):
         "warmup": args.warmup, "ms_per_step": t_reuse * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "config4: %d-layer Llama-3-8B-shaped stack, bf16, 8 x 4096 tokens, vocab 128256, "
-                               "cross-entropy + full backward from reused records" % L,
+                               "cross-entropy + %s from reused records" % (L, mode),
                    "layers": L, "tokens": T, "seq_len": S, "vocab": V},
         "loss": loss, "loss_expected_random_init": float(np.log(V) + 0.5 * 0.02 ** 2 * H),
         "step_tflops": flops / 1e12, "step_mfma_frac": flops / t_reuse / 1e12 / PEAK_BF16_TFLOPS,

@@ -352,7 +352,7 @@ def _lora_structs(lora, lora_grads, rank, scale, accumulate):
 
 def alch_stack_backward_lora(shape, batch, saved_layers, weights_layers, lora_layers, rank, scale, X_final, g_final,
                              W_lm, labels, loss_mask=None, want=(), want_head=False, lora_grads_layers=None,
-                             accumulate=False, workspace=None, stream=None):
+                             grads_layers=None, accumulate=False, workspace=None, stream=None):
     """Stack backward with adapters.  lora_layers: list of dicts projection -> (A, B).  Defaults: frozen base and
     frozen head (want=(), want_head=False), gradients of every adapter.  Returns the dict of alch_stack_backward;
     the per-layer dicts hold the adapter gradients ('dAq', 'dBq', ...) and any base gradients asked for."""
@@ -360,7 +360,8 @@ def alch_stack_backward_lora(shape, batch, saved_layers, weights_layers, lora_la
     dev = X_final.device
     n_layers = len(saved_layers)
     vocab = W_lm.shape[0]
-    grads_layers = [{"d" + k: torch.empty_like(w[k]) for k in want} for w in weights_layers]
+    if grads_layers is None:
+        grads_layers = [{"d" + k: torch.empty_like(w[k]) for k in want} for w in weights_layers]
     if lora_grads_layers is None:
         lora_grads_layers = []
         for lo in lora_layers:
