@@ -28,5 +28,5 @@ reuse == recompute invariant, brute-force gather, closed forms, special cases).
 """
 from .gather import gather_pack
 from .layer import (LayerShape, layer_forward, layer_backward_reuse,
-                    layer_backward_recompute, attention_lse, RECORD_KEYS, WEIGHT_KEYS)
+                    layer_backward_recompute, complete_record, attention_lse, RECORD_KEYS, WEIGHT_KEYS)
 from .stack import stack_forward, stack_backward_reuse, stack_backward_recompute

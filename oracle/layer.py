@@ -227,6 +227,36 @@ def layer_backward_reuse(shape, cu_seqlens, positions, rec, W, dY, loss_mask=Non
                 dg1=dg1, dg2=dg2)
 
 
+def complete_record(shape, cu_seqlens, rec, W):
+    """The six-tensor record {X, Q, K, V, G, U} (the tensors the capture step is asked to pack in
+    the paper's setting, Section 4.1 / Section 5: layer input, KV cache, query, MLP pre-activations)
+    completed to the full record: O and LSE by running causal grouped-query attention on the saved
+    post-RoPE Q, K, V, then X2 = X + O Wo^T.  Tensors already present in `rec` are kept as given.
+    (The decision between loading a saved tensor and recomputing it is the hedging of Section 4.3.2.)"""
+    out = {k: np.asarray(v, dtype=np.float64) for k, v in rec.items() if v is not None}
+    T = out["X"].shape[0]
+    Hq, Hkv, D = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
+    G = Hq // Hkv
+    if "O" not in out or "LSE" not in out:
+        Q, K, V = out["Q"].reshape(T, Hq, D), out["K"].reshape(T, Hkv, D), out["V"].reshape(T, Hkv, D)
+        LSE = attention_lse(shape, cu_seqlens, out["Q"], out["K"])
+        O = np.zeros((T, Hq, D), dtype=np.float64)
+        for s in range(len(cu_seqlens) - 1):
+            a, b = int(cu_seqlens[s]), int(cu_seqlens[s + 1])
+            n = b - a
+            if n == 0:
+                continue
+            allowed = np.tril(np.ones((n, n), dtype=bool))
+            for h in range(Hq):
+                sc = Q[a:b, h] @ K[a:b, h // G].T / np.sqrt(D)
+                P = np.where(allowed, np.exp(sc - LSE[a:b, h][:, None]), 0.0)
+                O[a:b, h] = P @ V[a:b, h // G]
+        out["O"], out["LSE"] = O.reshape(T, Hq * D), LSE
+    if "X2" not in out:
+        out["X2"] = out["X"] + out["O"] @ np.asarray(W["Wo"], dtype=np.float64).T
+    return out
+
+
 def layer_backward_recompute(shape, cu_seqlens, positions, X, W, dY, loss_mask=None):
     """The comparison path (Section 6, the separate-cluster baseline): re-run the
     forward from X and the weights, then back-propagate through what it produced."""

@@ -251,3 +251,21 @@ def test_tail_rows_shortcut_equals_full_backward(m):
         seq = {k: rec[k][a:b] for k in RECORD_KEYS}
         tail = layer_backward_reuse_tail_rows(shape, None, seq, W, R[b - mm:b])
         assert np.max(np.abs(tail - full[b - mm:b])) <= 1e-12 * np.abs(full).max()
+
+
+def test_complete_record_restores_the_dropped_tensors():
+    # a forward's record with X2, O, LSE dropped is completed to the same record (Section 4.3.2: a saved
+    # tensor may be recomputed instead of loaded); tensors that are present are passed through untouched
+    from oracle import complete_record
+    shape, cu, T, W, X, R = make(21, Hq=6, Hkv=2, D=4, F=20, lens=(3, 1, 0, 6))
+    _, rec = layer_forward(shape, cu, None, X, W)
+    six = {k: rec[k] for k in ("X", "Q", "K", "V", "G", "U")}
+    full = complete_record(shape, cu, six, W)
+    for k in RECORD_KEYS:
+        np.testing.assert_allclose(full[k], rec[k], rtol=1e-12, atol=1e-12, err_msg=k)
+    marked = dict(six, X2=rec["X2"] + 1.0)
+    assert np.array_equal(complete_record(shape, cu, marked, W)["X2"], rec["X2"] + 1.0)
+    g_full = layer_backward_reuse(shape, cu, None, rec, W, R)
+    g_six = layer_backward_reuse(shape, cu, None, full, W, R)
+    for k in g_full:
+        np.testing.assert_allclose(g_six[k], g_full[k], rtol=1e-10, atol=1e-12, err_msg=k)
