@@ -133,7 +133,10 @@ size_t alch_capture_pack_workspace_bytes(int32_t total_tokens);
 /* The saved record of one layer (all [total_tokens, width], dtype of the shape):
  * X, X2 [T,hidden]; Q, O [T,n_q_heads*head_dim]; K, V [T,n_kv_heads*head_dim];
  * G, U [T,ffn]; LSE fp32 [T,n_q_heads].  weights_version tags the weights the record
- * was produced under: gradients from a record are only valid at those weights. */
+ * was produced under: gradients from a record are only valid at those weights.
+ * X2, O and LSE may be NULL (a record of the six streams X, Q, K, V, G, U): the backward calls then
+ * recompute O and LSE by an attention forward on the saved Q, K, V and X2 = X + O Wo^T, the
+ * recompute-instead-of-load choice of Section 4.3.2. */
 typedef struct {
     const void *X, *X2, *Q, *K, *V, *O, *G, *U;
     const float* LSE;

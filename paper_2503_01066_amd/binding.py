@@ -220,7 +220,9 @@ def alch_capture_pack(batch, keep_mask, streams, capacity=None, dsts=None, strea
 
 
 def _saved_struct(saved, version):
-    return CSaved(*[saved[k].data_ptr() for k in RECORD_KEYS], saved["LSE"].data_ptr(), version)
+    # X2, O and LSE may be absent (six-stream record): the library recomputes them
+    ptr = lambda k: saved[k].data_ptr() if saved.get(k) is not None else None
+    return CSaved(*[ptr(k) for k in RECORD_KEYS], ptr("LSE"), version)
 
 
 def _weights_struct(weights, version):

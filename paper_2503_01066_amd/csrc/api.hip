@@ -96,6 +96,9 @@ static int check_batch(const alch_batch* b) {
 struct LayerBwdPlan {
     void *dYm, *dGU, *Act, *Hn, *dHn, *dX2, *dO, *dQKV;
     float *delta, *partial;
+    // stand-ins for record tensors the caller did not save (O, LSE, X2)
+    void *O_re = nullptr, *X2_re = nullptr;
+    float* LSE_re = nullptr;
     // adapters (rank > 0): t1 = s x A^T [T, 64]; t2 = s dy B, three zero-padded 64-column slots [T, 192];
     // the adapters' A matrices zero-padded to 64 rows and stacked per product; B transposed; partial sums of
     // the adapter gradients
@@ -122,6 +125,9 @@ static LayerBwdPlan plan_layer_bwd(const alch_layer_shape& s, int T, void* ws, s
     p.dQKV = a.take(t * (QD + 2 * KD) * E);
     p.delta = static_cast<float*>(a.take(t * s.n_q_heads * sizeof(float)));
     p.partial = static_cast<float*>(a.take((size_t)rmsnorm_bwd_blocks(T) * H * sizeof(float)));
+    p.O_re = a.take(t * QD * E);
+    p.X2_re = a.take(t * H * E);
+    p.LSE_re = static_cast<float*>(a.take(t * s.n_q_heads * sizeof(float)));
     if (lora_rank > 0) {
         const size_t wmax = std::max(std::max(H, QD), F);
         p.T1 = a.take(t * kLoraSlot * E);
@@ -204,9 +210,11 @@ static inline char* at(void* p, size_t elems, size_t E) { return static_cast<cha
 
 static int check_saved_weights(const alch_saved* sv, const alch_weights* w, int T) {
     if (!sv || !w) return fail(ALCH_ERR_INVALID_ARG, "saved / weights is NULL");
-    REQUIRE_ACT(sv->X, "saved.X", T); REQUIRE_ACT(sv->X2, "saved.X2", T); REQUIRE_ACT(sv->Q, "saved.Q", T);
-    REQUIRE_ACT(sv->K, "saved.K", T); REQUIRE_ACT(sv->V, "saved.V", T); REQUIRE_ACT(sv->O, "saved.O", T);
-    REQUIRE_ACT(sv->G, "saved.G", T); REQUIRE_ACT(sv->U, "saved.U", T); REQUIRE_ACT(sv->LSE, "saved.LSE", T);
+    REQUIRE_ACT(sv->X, "saved.X", T); REQUIRE_ACT(sv->Q, "saved.Q", T);
+    REQUIRE_ACT(sv->K, "saved.K", T); REQUIRE_ACT(sv->V, "saved.V", T);
+    REQUIRE_ACT(sv->G, "saved.G", T); REQUIRE_ACT(sv->U, "saved.U", T);
+    // X2, O and LSE may be NULL: they are then recomputed from the rest of the record
+    OPTIONAL_PTR(sv->X2, "saved.X2"); OPTIONAL_PTR(sv->O, "saved.O"); OPTIONAL_PTR(sv->LSE, "saved.LSE");
     REQUIRE_PTR(w->Wq, "weights.Wq"); REQUIRE_PTR(w->Wk, "weights.Wk"); REQUIRE_PTR(w->Wv, "weights.Wv");
     REQUIRE_PTR(w->Wo, "weights.Wo"); REQUIRE_PTR(w->Wg, "weights.Wg"); REQUIRE_PTR(w->Wu, "weights.Wu");
     REQUIRE_PTR(w->Wd, "weights.Wd"); REQUIRE_PTR(w->g1, "weights.g1"); REQUIRE_PTR(w->g2, "weights.g2");
@@ -225,7 +233,7 @@ static int check_wgrads(const alch_wgrads* g) {
 }
 
 // Enqueues steps of one layer's backward pass; arguments already validated.
-static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b, const alch_saved& sv,
+static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b, const alch_saved& sv_in,
                                   const alch_weights& w, const void* dY, const uint8_t* loss_mask, void* dX,
                                   const alch_wgrads* wg, const LayerBwdPlan& p, hipStream_t st,
                                   const alch_lora* lo = nullptr, const alch_lora_grads* lg = nullptr) {
@@ -233,6 +241,28 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
     const size_t E = dtype_size(dt);
     const int T = b.total_tokens, H = s.hidden, F = s.ffn, D = s.head_dim;
     const int QD = s.n_q_heads * D, KD = s.n_kv_heads * D, QKV = QD + 2 * KD;
+
+    // A record without O / LSE / X2 (Section 4.3.2: recompute instead of load): attention forward on the saved
+    // post-RoPE Q, K, V gives O and LSE; X2 = X + O Wo^T (sum in fp32, one rounding, as the forward does).
+    alch_saved sv = sv_in;
+    if (T > 0 && (!sv.O || !sv.LSE)) {
+        ALCH_TRY(launch_attn_fwd(dt, sv.Q, sv.K, sv.V, p.O_re, p.LSE_re, T, b.n_seqs, b.max_seqlen, b.cu_seqlens,
+                                 b.cu_seqlens_host, s.n_q_heads, s.n_kv_heads, D, st));
+        sv.O = p.O_re;
+        sv.LSE = p.LSE_re;
+    }
+    if (T > 0 && !sv.X2) {
+        if (lo && lo->A[ALCH_PROJ_O])
+            return fail(ALCH_ERR_UNSUPPORTED, "saved.X2 must be given when the output projection carries an adapter");
+        ALCH_TRY(launch_masked_copy(dt, sv.X, nullptr, p.X2_re, T, H, st));
+        GemmDesc d;
+        d.M = T; d.N = H; d.a_kmajor = true; d.b_kmajor = true; d.dtype = dt;
+        d.seg[d.n_seg++] = GemmSeg{sv.O, w.Wo, QD, QD, QD};
+        d.out[d.n_out++] = GemmOut{p.X2_re, 0, H};
+        d.accumulate = 1;
+        ALCH_TRY(launch_gemm(d, st));
+        sv.X2 = p.X2_re;
+    }
     const int acc = wg ? (wg->accumulate != 0) : 0;
     static const alch_wgrads none = {};
     const alch_wgrads& g = wg ? *wg : none;

@@ -119,3 +119,30 @@ def test_empty_batch_and_stale_record():
     with pytest.raises(A.AlchError) as e:
         run_gpu(shp, "f32", cu, W, rec, dY, saved_version=3, weights_version=4)
     assert e.value.code == -4
+
+
+@pytest.mark.parametrize("dtype,shape_name,lens", [("f32", "tiny", [1, 5, 0, 8, 3]), ("bf16", "medium", [300, 1, 257, 64]),
+                                                   ("bf16", "medium64", [130, 200, 77])])
+def test_six_stream_record_is_completed_on_the_device(dtype, shape_name, lens):
+    # the record of the capture workload (X, Q, K, V, G, U only): O, LSE and X2 are recomputed by the library;
+    # the oracle completes the same rounded six tensors in fp64
+    from oracle import complete_record
+    cu = synth.ragged_cu(lens)
+    shp, osh, W, rec, dY = make_case(shape_name, dtype, cu, 17, "forward", wstd=0.3 if shape_name == "tiny" else 0.02,
+                                     dy_std=1.0 if dtype == "f32" else 0.01)
+    six = {k: rec[k] for k in ("X", "Q", "K", "V", "G", "U")}
+    ref = layer_backward_reuse(osh, cu, None, complete_record(osh, cu, f64(six), f64(W)), f64(W), dY)
+    import paper_2503_01066_amd as A
+    out = A.alch_layer_backward(alch_shape(shp, dtype), A.Batch(cu), {k: to_dev(v, dtype) for k, v in six.items()},
+                                {k: to_dev(v, dtype) for k, v in W.items()}, to_dev(dY, dtype))
+    torch.cuda.synchronize()
+    compare({k: to_np(v) for k, v in out.items()}, ref, dtype)
+    # only X2 missing: O and LSE are taken as saved
+    part = {k: rec[k] for k in rec if k != "X2"}
+    ref2 = layer_backward_reuse(osh, cu, None, complete_record(osh, cu, {k: np.asarray(v, dtype=np.float64) for k, v in part.items()}, f64(W)), f64(W), dY)
+    d = {k: to_dev(v, dtype) for k, v in part.items() if k != "LSE"}
+    d["LSE"] = torch.from_numpy(rec["LSE"]).cuda()
+    out2 = A.alch_layer_backward(alch_shape(shp, dtype), A.Batch(cu), d, {k: to_dev(v, dtype) for k, v in W.items()},
+                                 to_dev(dY, dtype))
+    torch.cuda.synchronize()
+    compare({k: to_np(v) for k, v in out2.items()}, ref2, dtype)
