@@ -145,8 +145,11 @@ def run_layer(args, torch, A):
     dY = rnd((T, H), 0.01)
     loss_mask = None
     if args.loss_mask:
-        loss_mask = torch.from_numpy(synth.keep_mask(T, 0.25, 7)).to(dev)
-        descr += ", dY rows zeroed by a Bernoulli(0.25) loss mask (dense kernels)"
+        lm_np = synth.keep_mask(T, 0.25, 7)
+        n_loss = int(lm_np.sum())
+        loss_mask = torch.from_numpy(lm_np).to(dev)
+        descr += (", dY rows zeroed by a Bernoulli(0.25) loss mask (%d of %d rows kept): the row-local products run on "
+                  "the kept rows, attention and the QKV products stay dense" % (n_loss, T))
 
     keys = list(widths) + ["LSE"]
     dst = {k: torch.empty((T, src[k].shape[1]), dtype=src[k].dtype, device=dev) for k in keys}
@@ -201,10 +204,16 @@ def run_layer(args, torch, A):
         e = by.setdefault(kind, [0.0, 0.0, 0.0, 0])
         e[0] += flops; e[1] += nbytes; e[2] += ms; e[3] += 1
     gm = by.get("gemm_mfma", [0, 0, 1e-9, 1])
+    P = 2 * H * QD + 2 * H * KD + 3 * H * F
+    gemm_flops_step = wflops * P * T
+    if args.loss_mask and not r:
+        # products whose row count lives on the device are traced without flops: count what the method must touch
+        p_rows = 3 * H * F + H * QD                    # Wd, Wg, Wu, Wo: row-local, run on the kept rows
+        gemm_flops_step = wflops * (p_rows * n_loss + (P - p_rows) * T)
+        gm[0] = gemm_flops_step * args.steps
     achieved_tf = gm[0] / (gm[2] * 1e-3) / 1e12
     pk = by.get("pack_gather", [0, 0, 1e-9, 1])
     pack_gbps = pk[1] * T / (pk[2] * 1e-3) / 1e9       # traced bytes are per kept row
-    P = 2 * H * QD + 2 * H * KD + 3 * H * F
     attn_flops = 10.0 * shp["head_dim"] * shp["n_q_heads"] * n_keep * S * (S + 1) / 2
     out = {
         "metric": METRIC, "value": T * args.steps / dt, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -213,8 +222,8 @@ def run_layer(args, torch, A):
         "config": {"workload": descr,
                    "hidden": H, "q_heads": shp["n_q_heads"], "kv_heads": shp["n_kv_heads"],
                    "head_dim": shp["head_dim"], "ffn": F, "tokens": T, "seq_len": S},
-        "step_tflops": (wflops * P * T + attn_flops) / 1e12,
-        "step_mfma_frac": (wflops * P * T + attn_flops) / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "step_tflops": (gemm_flops_step + attn_flops) / 1e12,
+        "step_mfma_frac": (gemm_flops_step + attn_flops) / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "capture_gbps": pack_gbps,
         "roofline": {"kernel": "k_gemm_mfma (all contractions of the layer backward)", "bound": "mfma",
                      "achieved": achieved_tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",

@@ -99,6 +99,10 @@ struct LayerBwdPlan {
     // stand-ins for record tensors the caller did not save (O, LSE, X2)
     void *O_re = nullptr, *X2_re = nullptr;
     float* LSE_re = nullptr;
+    // loss-mask compaction: kept rows of dY, X2, O, G, U; compact dX2, dO; kept-row index, its inverse,
+    // per-sequence counts, {n_kept, overflow}; scratch of the mask scan
+    void *c_dY, *c_X2, *c_O, *c_G, *c_U, *c_dX2, *c_dO, *c_packws;
+    int *c_index, *c_inv, *c_cu, *c_n;
     // adapters (rank > 0): t1 = s x A^T [T, 64]; t2 = s dy B, three zero-padded 64-column slots [T, 192];
     // the adapters' A matrices zero-padded to 64 rows and stacked per product; B transposed; partial sums of
     // the adapter gradients
@@ -128,6 +132,14 @@ static LayerBwdPlan plan_layer_bwd(const alch_layer_shape& s, int T, void* ws, s
     p.O_re = a.take(t * QD * E);
     p.X2_re = a.take(t * H * E);
     p.LSE_re = static_cast<float*>(a.take(t * s.n_q_heads * sizeof(float)));
+    p.c_dY = a.take(t * H * E); p.c_X2 = a.take(t * H * E); p.c_O = a.take(t * QD * E);
+    p.c_G = a.take(t * F * E); p.c_U = a.take(t * F * E);
+    p.c_dX2 = a.take(t * H * E); p.c_dO = a.take(t * QD * E);
+    p.c_packws = a.take(pack_workspace_bytes(T > 0 ? T : 1));
+    p.c_index = static_cast<int*>(a.take(t * sizeof(int)));
+    p.c_inv = static_cast<int*>(a.take(t * sizeof(int)));
+    p.c_cu = static_cast<int*>(a.take(256));
+    p.c_n = static_cast<int*>(a.take(256));
     if (lora_rank > 0) {
         const size_t wmax = std::max(std::max(H, QD), F);
         p.T1 = a.take(t * kLoraSlot * E);
@@ -318,37 +330,59 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
         return ALCH_OK;
     };
 
-    // the loss mask zeroes rows of dY once, up front
-    const void* dYp = dY;
-    if (loss_mask) {
+    // Loss mask.  Rows of dY whose mask byte is 0 count as zero.  Everything from the MLP down to the
+    // attention output projection is row-local, so those rows contribute nothing there and receive nothing:
+    //   compact mode (bf16, matrix-core shapes, no adapters): the kept rows of dY, X2, O, G, U are gathered
+    //     into dense [n, width] tensors, the row-local part runs on n rows (n stays on the device: the
+    //     products take their row or contraction count from device memory), and dX2, dO are scattered back
+    //     into zero-filled [T, width] tensors for the attention backward, which is dense in the keys;
+    //   otherwise dY is copied once with the masked rows zeroed and every step runs on all T rows.
+    const bool compact = loss_mask && T > 0 && !lo && dt == ALCH_BF16 && H % 64 == 0 && F % 64 == 0 && QD % 64 == 0 &&
+                         aligned16(dY);
+    const void *mY = dY, *mX2 = sv.X2, *mO = sv.O, *mG = sv.G, *mU = sv.U;  // inputs of the row-local part
+    void *mdX2 = p.dX2, *mdO = p.dO;                                      // its outputs
+    const int* ndev = nullptr;                                              // device-resident row count
+    if (compact) {
+        const alch_stream rows5[5] = {{dY, p.c_dY, (size_t)H * E, (size_t)H * E}, {sv.X2, p.c_X2, (size_t)H * E, (size_t)H * E},
+                                      {sv.O, p.c_O, (size_t)QD * E, (size_t)QD * E}, {sv.G, p.c_G, (size_t)F * E, (size_t)F * E},
+                                      {sv.U, p.c_U, (size_t)F * E, (size_t)F * E}};
+        // (per-sequence counts are not needed: zero sequences asked for, one boundary written)
+        ALCH_TRY(launch_pack(loss_mask, T, b.cu_seqlens, 0, 5, rows5, T, p.c_index, p.c_cu, p.c_n, p.c_packws, st, false));
+        ALCH_TRY(launch_rank_of_kept(p.c_index, p.c_n, p.c_inv, T, st));
+        mY = p.c_dY; mX2 = p.c_X2; mO = p.c_O; mG = p.c_G; mU = p.c_U;
+        mdX2 = p.c_dX2; mdO = p.c_dO;
+        ndev = p.c_n;
+    } else if (loss_mask) {
         ALCH_TRY(launch_masked_copy(dt, dY, loss_mask, p.dYm, T, H, st));
-        dYp = p.dYm;
+        mY = p.dYm;
     }
 
     // MLP down projection: dAct = dY Wd, fused with the SwiGLU gradient -> [dG | dU] and Act
     if (has(ALCH_PROJ_D)) {
-        const void* dys[1] = {dYp};
+        const void* dys[1] = {mY};
         const int outs1[1] = {H};
         ALCH_TRY(down_t2(ALCH_PROJ_D, 1, dys, H, outs1));
     }
     {
         GemmDesc d = gemm(dt, T, F, true, false);
-        add_seg(d, dYp, H, w.Wd, F, H);
+        d.m_dev = ndev;
+        add_seg(d, mY, H, w.Wd, F, H);
         if (has(ALCH_PROJ_D)) add_seg(d, p.T2, ldt2, p.Ap_d, F, kLoraSlot);
         add_out(d, p.dGU, 0, 2 * (long long)F);
         d.epilogue = kEpiSwigluBwd;
-        d.G = sv.G; d.U = sv.U; d.ldgu = F;
+        d.G = mG; d.U = mU; d.ldgu = F;
         d.act_out = (g.dWd || wants(ALCH_PROJ_D)) ? p.Act : nullptr;
         ALCH_TRY(launch_gemm(d, st));
     }
     if (g.dWd) {  // dWd = dY^T Act
         GemmDesc d = gemm(dt, H, F, false, false);
-        add_seg(d, dYp, H, p.Act, F, T);
+        d.k_dev = ndev;
+        add_seg(d, mY, H, p.Act, F, T);
         add_out(d, g.dWd, 0, F);
         d.accumulate = acc;
         ALCH_TRY(launch_gemm(d, st));
     }
-    ALCH_TRY(adapter_grads(ALCH_PROJ_D, 0, p.Act, F, F, dYp, H, H));
+    ALCH_TRY(adapter_grads(ALCH_PROJ_D, 0, p.Act, F, F, mY, H, H));
     const bool lora_gu = has(ALCH_PROJ_G) || has(ALCH_PROJ_U);
     if (lora_gu) {
         const void* dys[2] = {p.dGU, at(p.dGU, F, E)};
@@ -357,6 +391,7 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
     }
     {  // dH2 = dG Wg + dU Wu
         GemmDesc d = gemm(dt, T, H, true, false);
+        d.m_dev = ndev;
         add_seg(d, p.dGU, 2 * (long long)F, w.Wg, H, F);
         add_seg(d, at(p.dGU, F, E), 2 * (long long)F, w.Wu, H, F);
         if (lora_gu) add_seg(d, p.T2, ldt2, p.Ap_gu, H, 2 * kLoraSlot);
@@ -364,12 +399,13 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
         ALCH_TRY(launch_gemm(d, st));
     }
     if (g.dWg || g.dWu || wants(ALCH_PROJ_G) || wants(ALCH_PROJ_U))
-        ALCH_TRY(launch_rmsnorm_fwd(dt, sv.X2, w.g2, p.Hn, T, H, s.rms_eps, st));
+        ALCH_TRY(launch_rmsnorm_fwd(dt, mX2, w.g2, p.Hn, T, H, s.rms_eps, st, ndev));
     ALCH_TRY(adapter_grads(ALCH_PROJ_G, 0, p.Hn, H, H, p.dGU, 2 * (long long)F, F));
     ALCH_TRY(adapter_grads(ALCH_PROJ_U, 1, p.Hn, H, H, at(p.dGU, F, E), 2 * (long long)F, F));
     if (g.dWg || g.dWu) {  // [dWg; dWu] = [dG | dU]^T H2
         if (g.dWg && g.dWu) {
             GemmDesc d = gemm(dt, 2 * F, H, false, false);
+        d.k_dev = ndev;
             add_seg(d, p.dGU, 2 * (long long)F, p.Hn, H, T);
             add_out(d, g.dWg, 0, H);
             add_out(d, g.dWu, F, H);
@@ -384,6 +420,7 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
             }
         } else {
             GemmDesc d = gemm(dt, F, H, false, false);
+        d.k_dev = ndev;
             add_seg(d, g.dWg ? p.dGU : at(p.dGU, F, E), 2 * (long long)F, p.Hn, H, T);
             add_out(d, g.dWg ? g.dWg : g.dWu, 0, H);
             d.accumulate = acc;
@@ -391,27 +428,34 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
         }
     }
     // dX2 = dY + RMSNorm-2 backward(dH2); dg2
-    ALCH_TRY(launch_rmsnorm_bwd(dt, p.dHn, sv.X2, w.g2, dYp, nullptr, p.dX2, g.dg2, acc, p.partial, T, H, s.rms_eps, st));
+    ALCH_TRY(launch_rmsnorm_bwd(dt, p.dHn, mX2, w.g2, mY, nullptr, mdX2, g.dg2, acc, p.partial, T, H, s.rms_eps, st, ndev));
 
     if (has(ALCH_PROJ_O)) {
-        const void* dys[1] = {p.dX2};
+        const void* dys[1] = {mdX2};
         const int outs1[1] = {H};
         ALCH_TRY(down_t2(ALCH_PROJ_O, 1, dys, H, outs1));
     }
     {  // dO = dX2 Wo
         GemmDesc d = gemm(dt, T, QD, true, false);
-        add_seg(d, p.dX2, H, w.Wo, QD, H);
+        d.m_dev = ndev;
+        add_seg(d, mdX2, H, w.Wo, QD, H);
         if (has(ALCH_PROJ_O)) add_seg(d, p.T2, ldt2, p.Ap_o, QD, kLoraSlot);
-        add_out(d, p.dO, 0, QD);
+        add_out(d, mdO, 0, QD);
         ALCH_TRY(launch_gemm(d, st));
     }
-    ALCH_TRY(adapter_grads(ALCH_PROJ_O, 0, sv.O, QD, QD, p.dX2, H, H));
+    ALCH_TRY(adapter_grads(ALCH_PROJ_O, 0, mO, QD, QD, mdX2, H, H));
     if (g.dWo) {  // dWo = dX2^T O
         GemmDesc d = gemm(dt, H, QD, false, false);
-        add_seg(d, p.dX2, H, sv.O, QD, T);
+        d.k_dev = ndev;
+        add_seg(d, mdX2, H, mO, QD, T);
         add_out(d, g.dWo, 0, QD);
         d.accumulate = acc;
         ALCH_TRY(launch_gemm(d, st));
+    }
+
+    if (compact) {  // back to [T, width]: zeros in the masked rows
+        ALCH_TRY(launch_scatter_rows(p.c_dO, p.c_inv, p.dO, T, (size_t)QD * E, st));
+        ALCH_TRY(launch_scatter_rows(p.c_dX2, p.c_inv, p.dX2, T, (size_t)H * E, st));
     }
 
     // attention backward from saved Q, K, V, O, LSE -> [dQ | dK | dV] with RoPE backward applied to dQ, dK

@@ -138,9 +138,14 @@ int launch_gemm(const GemmDesc& d, hipStream_t stream) {
     if (d.M <= 0 || d.N <= 0) return ALCH_OK;
     double k_total = 0;
     for (int s = 0; s < d.n_seg; ++s) k_total += d.seg[s].K;
-    const double flops = 2.0 * d.M * d.N * k_total;
+    // a size that lives on the device is not known here: such launches are traced with zero work and the
+    // caller accounts for them from the row count it knows
+    const bool dev_sized = d.m_dev || d.k_dev;
+    const double flops = dev_sized ? 0.0 : 2.0 * d.M * d.N * k_total;
     const size_t E = dtype_size(d.dtype);
-    const double bytes = ((double)d.M * k_total + (double)d.N * k_total + (double)d.M * d.N) * E;
+    const double bytes = dev_sized ? 0.0 : ((double)d.M * k_total + (double)d.N * k_total + (double)d.M * d.N) * E;
+    if (dev_sized && !gemm_mfma_supported(d))
+        return fail(ALCH_ERR_UNSUPPORTED, "device-resident sizes need the matrix-core kernel (bf16, aligned, K %% 64 == 0)");
     if (gemm_mfma_supported(d)) {
         TraceScope ts(kTraceGemmMfma, flops, bytes, stream);
         return launch_gemm_mfma(d, stream);

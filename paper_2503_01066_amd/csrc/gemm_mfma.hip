@@ -43,6 +43,10 @@ static constexpr int kGroupM = ALCH_GROUP_M;             // tile rows per raster
 
 struct MfmaGemmParams {
     int M, N, n_seg, n_out, accumulate, tiles_m, tiles_n;
+    // optional device-resident sizes (row compaction decided on the device): the effective M, or the
+    // effective K of every operand pair, is min(*ptr, host value)
+    const int* m_dev;
+    const int* k_dev;
     const __bf16* A[kMaxGemmSegs];
     const __bf16* B[kMaxGemmSegs];
     int K[kMaxGemmSegs];
@@ -166,7 +170,9 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
     // ---- work-group -> output tile: XCD-contiguous chunks, banded raster inside a chunk
     // The grid is persistent (one work-group per compute unit): each work-group walks its share of
     // the tiles, so the stores of one tile drain while the next tile's loads are already in flight.
-    const int nt = p.tiles_m * p.tiles_n;
+    const int Mv = p.m_dev ? min(__builtin_amdgcn_readfirstlane(*p.m_dev), p.M) : p.M;
+    const int tiles_m = p.m_dev ? (Mv + BM - 1) / BM : p.tiles_m;
+    const int nt = tiles_m * p.tiles_n;
     const int per_xcd = (nt + 7) / 8;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -176,7 +182,7 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
     if (t >= nt) break;
     const int band_tiles = kGroupM * p.tiles_n;
     const int band = t / band_tiles, in_band = t % band_tiles;
-    const int band_rows = min(kGroupM, p.tiles_m - band * kGroupM);
+    const int band_rows = min(kGroupM, tiles_m - band * kGroupM);
     const int tm = band * kGroupM + in_band % band_rows;
     const int tn = in_band / band_rows;
     const int m0 = tm * BM, n0 = tn * BN;
@@ -194,17 +200,17 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
 
     for (int seg = 0; seg < p.n_seg; ++seg) {
         const long long lda = p.lda[seg], ldb = p.ldb[seg];
-        const int K = p.K[seg];
+        const int K = p.k_dev ? min(__builtin_amdgcn_readfirstlane(*p.k_dev), p.K[seg]) : p.K[seg];
         const int nk = (K + BK - 1) / BK;
         const char *pa, *pb, *enda, *endb;
         long long stepa, stepb;
         if (AK) {
             pa = (const char*)(p.A[seg] + (long long)m0 * lda);
-            enda = (const char*)(p.A[seg] + (long long)(p.M - 1) * lda + K);
+            enda = (const char*)(p.A[seg] + (long long)(Mv - 1) * lda + K);
             stepa = BK * 2;
         } else {
             pa = (const char*)(p.A[seg] + m0);
-            enda = (const char*)(p.A[seg] + (long long)(K - 1) * lda + p.M);
+            enda = (const char*)(p.A[seg] + (long long)(K - 1) * lda + Mv);
             stepa = (long long)BK * lda * 2;
         }
         if (BKM) {
@@ -217,7 +223,7 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
             stepb = (long long)BK * ldb * 2;
         }
         uint32_t va[4], vb[4];
-        tile_offsets<AK>(va, wave, lane, lda, p.M - m0);
+        tile_offsets<AK>(va, wave, lane, lda, Mv - m0);
         tile_offsets<BKM>(vb, wave, lane, ldb, p.N - n0);
 
         // Loads of the next k-tile go out one instruction at a time between MFMAs (a burst of
@@ -334,7 +340,7 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
     __bf16* __restrict__ C = p.C[oseg];
     const long long ldc = p.ldc[oseg];
     const int mrel0 = m0 - p.m_begin[oseg];
-    const int m_end = (oseg + 1 < p.n_out ? p.m_begin[oseg + 1] : p.M);
+    const int m_end = (oseg + 1 < p.n_out ? min(p.m_begin[oseg + 1], Mv) : Mv);
     const int half = lane >> 5;
 
     if (!p.accumulate) {
@@ -369,7 +375,7 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
 #pragma unroll
                 for (int k = 0; k < kBatch; ++k) {
                     const int m = m0 + wm * 128 + 4 * (q0 + k) + (lane >> 4);
-                    if (m < p.M && n < p.N) {
+                    if (m < Mv && n < p.N) {
                         g8[k] = *reinterpret_cast<const bf16x8*>(p.G + (long long)m * p.ldgu + n);
                         u8[k] = *reinterpret_cast<const bf16x8*>(p.U + (long long)m * p.ldgu + n);
                     }
@@ -379,7 +385,7 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
                     const int rl = 4 * (q0 + k) + (lane >> 4);
                     const int m = m0 + wm * 128 + rl;
                     const bf16x8 d8 = *reinterpret_cast<const bf16x8*>(stage + rl * kRowStride + (((lane & 15) ^ (rl & 15)) << 4));
-                    if (m < p.M && n < p.N) {
+                    if (m < Mv && n < p.N) {
                         bf16x8 dg8, du8, a8;
 #pragma unroll
                         for (int r = 0; r < 8; ++r) {
@@ -477,6 +483,8 @@ int launch_gemm_mfma(const GemmDesc& d, hipStream_t stream) {
     p.n_seg = d.n_seg;
     p.n_out = d.n_out;
     p.accumulate = d.accumulate;
+    p.m_dev = d.m_dev;
+    p.k_dev = d.k_dev;
     p.tiles_m = ceil_div(d.M, BM);
     p.tiles_n = ceil_div(d.N, BN);
     for (int s = 0; s < kMaxGemmSegs; ++s) {

@@ -10,7 +10,7 @@ static constexpr int kGatherGridMax = 1 << 20;  // one work-group per candidate 
 size_t pack_workspace_bytes(int total_tokens);
 int launch_pack(const uint8_t* mask, int T, const int* cu_seqlens, int n_seqs, int n_streams,
                 const alch_stream* streams, long long capacity, int* kept_index, int* cu_kept,
-                int* n_kept_and_status, void* workspace, hipStream_t stream);
+                int* n_kept_and_status, void* workspace, hipStream_t stream, bool traced = true);
 
 // ---- GEMM ------------------------------------------------------------------------------
 // C[M,N] (+)= sum over segments of A_s(M,K_s) * B_s(K_s,N), fp32 accumulation.
@@ -50,6 +50,10 @@ struct GemmDesc {
     long long ldgu = 0;
     void* act_out = nullptr;
     const uint8_t* row_mask = nullptr;  // optional: rows of A whose mask byte is 0 count as zero (A k-major only)
+    // optional device-resident sizes (matrix-core kernel only): effective M = min(*m_dev, M); effective K of
+    // every operand pair = min(*k_dev, K).  Rows / contraction steps beyond them are neither read nor written.
+    const int* m_dev = nullptr;
+    const int* k_dev = nullptr;
 };
 int launch_gemm(const GemmDesc& d, hipStream_t stream);
 // used by launch_gemm
@@ -59,14 +63,19 @@ int launch_gemm_generic(const GemmDesc& d, hipStream_t stream);
 
 // ---- row-wise kernels --------------------------------------------------------------------
 // H = X * rsqrt(mean(X^2)+eps) * g   (rows of width `width`)
+// rows_dev (optional, bf16 row kernel only): the row count is min(*rows_dev, T), read on the device.
 int launch_rmsnorm_fwd(alch_dtype dt, const void* X, const void* g, void* H, int T, int width, float eps,
-                       hipStream_t stream);
+                       hipStream_t stream, const int* rows_dev = nullptr);
 // dX = resid + rmsnorm_bwd(dH; X, g)   (resid may be NULL; resid_mask zeroes resid rows where mask==0);
 // dg (+)= sum_t dH*X*r  (dg may be NULL).  partial: fp32 scratch [rmsnorm_bwd_blocks(T), width].
 int rmsnorm_bwd_blocks(int T);
 int launch_rmsnorm_bwd(alch_dtype dt, const void* dH, const void* X, const void* g, const void* resid,
                        const uint8_t* resid_mask, void* dX, void* dg, int accumulate, float* partial, int T,
-                       int width, float eps, hipStream_t stream);
+                       int width, float eps, hipStream_t stream, const int* rows_dev = nullptr);
+// inv[t] = rank of token t among the first *n_rows entries of index (the kept tokens), -1 if absent
+int launch_rank_of_kept(const int* index, const int* n_rows, int* inv, int T, hipStream_t stream);
+// out [T, row_bytes] = src[inv[t], :] where inv[t] >= 0, zeros elsewhere
+int launch_scatter_rows(const void* src, const int* inv, void* out, int T, size_t row_bytes, hipStream_t stream);
 // Act = silu(G) * U
 int launch_swiglu_act(alch_dtype dt, const void* G, const void* U, void* Act, long long n, hipStream_t stream);
 // dGU[:, 0:F] = dAct*U*silu'(G), dGU[:, F:2F] = dAct*silu(G); optionally Act = silu(G)*U

@@ -173,11 +173,11 @@ size_t pack_workspace_bytes(int total_tokens) {
 
 int launch_pack(const uint8_t* mask, int T, const int* cu_seqlens, int n_seqs, int n_streams,
                 const alch_stream* streams, long long capacity, int* kept_index, int* cu_kept,
-                int* n_kept_and_status, void* workspace, hipStream_t stream) {
+                int* n_kept_and_status, void* workspace, hipStream_t stream, bool traced) {
     int* block_offsets = static_cast<int*>(workspace);
     const int nblocks = T > 0 ? ceil_div(T, kTokPerBlock) : 0;
     {
-    TraceScope ts(kTracePackScan, 0.0, (double)T + 4.0 * (n_seqs + 1), stream);
+    TraceScope ts(traced ? kTracePackScan : kTraceRowOps, 0.0, (double)T + 4.0 * (n_seqs + 1), stream);
     if (nblocks > 0) k_pack_count<<<nblocks, kScanThreads, 0, stream>>>(mask, T, block_offsets);
     k_pack_scan_blocks<<<1, kScanThreads, 0, stream>>>(block_offsets, nblocks, n_kept_and_status, capacity);
     if (nblocks > 0) k_pack_fill<<<nblocks, kScanThreads, 0, stream>>>(mask, T, block_offsets, kept_index, capacity);
@@ -190,7 +190,7 @@ int launch_pack(const uint8_t* mask, int T, const int* cu_seqlens, int n_seqs, i
     // traced bytes of the gather: per kept row (read once + written once); the row count is on the device
     double row_bytes_rw = 0;
     for (int k = 0; k < n_streams; ++k) row_bytes_rw += 2.0 * (double)streams[k].row_bytes;
-    TraceScope ts(kTracePackGather, 0.0, row_bytes_rw, stream);
+    TraceScope ts(traced ? kTracePackGather : kTraceRowOps, 0.0, row_bytes_rw, stream);
 
     long long max_rows = (long long)T < capacity ? (long long)T : capacity;
     int grid = (int)(max_rows < (long long)kGatherGridMax ? max_rows : (long long)kGatherGridMax);

@@ -45,7 +45,9 @@ __global__ __launch_bounds__(256) void k_rmsnorm_fwd(const T* __restrict__ X, co
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_f;
 template <int NC>
 __global__ __launch_bounds__(256) void k_rmsnorm_fwd_bf16(const __bf16* __restrict__ X, const __bf16* __restrict__ g,
-                                                          __bf16* __restrict__ H, int Trows, int width, float eps) {
+                                                          __bf16* __restrict__ H, int Trows, int width, float eps,
+                                                          const int* __restrict__ rows_dev) {
+    if (rows_dev) Trows = min(Trows, *rows_dev);  // row count decided on the device (compacted rows)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     bf16x8_f gv[NC];
 #pragma unroll
@@ -84,12 +86,14 @@ __global__ __launch_bounds__(256) void k_rmsnorm_fwd_bf16(const __bf16* __restri
 }
 
 int launch_rmsnorm_fwd(alch_dtype dt, const void* X, const void* g, void* H, int T, int width, float eps,
-                       hipStream_t stream) {
+                       hipStream_t stream, const int* rows_dev) {
     if (T <= 0) return ALCH_OK;
+    if (rows_dev && !(dt == ALCH_BF16 && width % 8 == 0 && width <= 8192 && aligned16(X) && aligned16(g) && aligned16(H)))
+        return fail(ALCH_ERR_UNSUPPORTED, "device-side row count needs the bf16 row kernel");
     if (dt == ALCH_BF16 && width % 8 == 0 && width <= 8192 && aligned16(X) && aligned16(g) && aligned16(H)) {
         const int nblk = ceil_div(T, 4) < 2048 ? ceil_div(T, 4) : 2048;
 #define ALCH_NORM_FWD(NC) \
-    k_rmsnorm_fwd_bf16<NC><<<nblk, 256, 0, stream>>>((const __bf16*)X, (const __bf16*)g, (__bf16*)H, T, width, eps)
+    k_rmsnorm_fwd_bf16<NC><<<nblk, 256, 0, stream>>>((const __bf16*)X, (const __bf16*)g, (__bf16*)H, T, width, eps, rows_dev)
         if (width <= 1024) ALCH_NORM_FWD(2);
         else if (width <= 2048) ALCH_NORM_FWD(4);
         else if (width <= 4096) ALCH_NORM_FWD(8);
@@ -172,8 +176,10 @@ template <int NC>
 __global__ __launch_bounds__(256) void k_rmsnorm_bwd_bf16(const __bf16* __restrict__ dH, const __bf16* __restrict__ X,
                                                           const __bf16* __restrict__ g, const __bf16* __restrict__ resid,
                                                           const uint8_t* __restrict__ resid_mask, __bf16* __restrict__ dX,
-                                                          float* __restrict__ partial, int Trows, int width, float eps) {
+                                                          float* __restrict__ partial, int Trows, int width, float eps,
+                                                          const int* __restrict__ rows_dev) {
     __shared__ float sred[NC * 512];
+    if (rows_dev) Trows = min(Trows, *rows_dev);  // row count decided on the device (compacted rows)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     bf16x8_t gv[NC];
     float dgp[NC][8];
@@ -295,12 +301,12 @@ static int rmsnorm_bwd_t(const void* dH, const void* X, const void* g, const voi
 
 static int rmsnorm_bwd_bf16_fast(const void* dH, const void* X, const void* g, const void* resid,
                                  const uint8_t* resid_mask, void* dX, void* dg, int accumulate, float* partial, int T_,
-                                 int width, float eps, hipStream_t stream) {
+                                 int width, float eps, hipStream_t stream, const int* rows_dev) {
     const int nblk = ceil_div(T_, 4) < kNormFastBlocks ? ceil_div(T_, 4) : kNormFastBlocks;
     float* part = dg ? partial : nullptr;
 #define ALCH_NORM_BWD(NC)                                                                                          \
     k_rmsnorm_bwd_bf16<NC><<<nblk, 256, 0, stream>>>((const __bf16*)dH, (const __bf16*)X, (const __bf16*)g,         \
-                                                     (const __bf16*)resid, resid_mask, (__bf16*)dX, part, T_, width, eps)
+                                                     (const __bf16*)resid, resid_mask, (__bf16*)dX, part, T_, width, eps, rows_dev)
     if (width <= 1024) ALCH_NORM_BWD(2);
     else if (width <= 2048) ALCH_NORM_BWD(4);
     else if (width <= 4096) ALCH_NORM_BWD(8);
@@ -313,7 +319,7 @@ static int rmsnorm_bwd_bf16_fast(const void* dH, const void* X, const void* g, c
 
 int launch_rmsnorm_bwd(alch_dtype dt, const void* dH, const void* X, const void* g, const void* resid,
                        const uint8_t* resid_mask, void* dX, void* dg, int accumulate, float* partial, int T,
-                       int width, float eps, hipStream_t stream) {
+                       int width, float eps, hipStream_t stream, const int* rows_dev) {
     if (width > 256 * kNormMaxCols) return fail(ALCH_ERR_UNSUPPORTED, "hidden %d > %d", width, 256 * kNormMaxCols);
     if (T <= 0) {
         // no rows: the gain gradient is zero (or unchanged when accumulating)
@@ -328,7 +334,8 @@ int launch_rmsnorm_bwd(alch_dtype dt, const void* dH, const void* X, const void*
     }
     if (dt == ALCH_BF16 && width % 8 == 0 && aligned16(dH) && aligned16(X) && aligned16(g) && aligned16(dX) &&
         (!resid || aligned16(resid)))
-        return rmsnorm_bwd_bf16_fast(dH, X, g, resid, resid_mask, dX, dg, accumulate, partial, T, width, eps, stream);
+        return rmsnorm_bwd_bf16_fast(dH, X, g, resid, resid_mask, dX, dg, accumulate, partial, T, width, eps, stream, rows_dev);
+    if (rows_dev) return fail(ALCH_ERR_UNSUPPORTED, "device-side row count needs the bf16 row kernel");
     return dt == ALCH_BF16
                ? rmsnorm_bwd_t<__bf16>(dH, X, g, resid, resid_mask, dX, dg, accumulate, partial, T, width, eps, stream)
                : rmsnorm_bwd_t<float>(dH, X, g, resid, resid_mask, dX, dg, accumulate, partial, T, width, eps, stream);
@@ -499,6 +506,47 @@ int launch_add(alch_dtype dt, const void* a, const void* b, void* y, long long n
         k_add<__bf16><<<grid, 256, 0, stream>>>((const __bf16*)a, (const __bf16*)b, (__bf16*)y, n);
     else
         k_add<float><<<grid, 256, 0, stream>>>((const float*)a, (const float*)b, (float*)y, n);
+    ALCH_HIP_TRY(hipGetLastError());
+    return ALCH_OK;
+}
+
+// ---- row scatter: out [T, width] = src[rank of t among the kept rows, :] for kept t, zeros elsewhere.
+// inv[t] = that rank or -1 is built first (two launches: clear, then fill from the kept-row index), so the
+// scatter writes every row of `out` exactly once, 16 bytes per lane.
+__global__ __launch_bounds__(256) void k_rank_clear(int* __restrict__ inv, int T_) {
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < T_; i += gridDim.x * 256) inv[i] = -1;
+}
+__global__ __launch_bounds__(256) void k_rank_fill(const int* __restrict__ index, const int* __restrict__ n_rows,
+                                                   int* __restrict__ inv, int T_) {
+    const int n = min(*n_rows, T_);
+    for (int r = blockIdx.x * 256 + threadIdx.x; r < n; r += gridDim.x * 256) inv[index[r]] = r;
+}
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
+__global__ __launch_bounds__(256) void k_scatter_rows(const u32x4_t* __restrict__ src, const int* __restrict__ inv,
+                                                      u32x4_t* __restrict__ out, int T_, int pieces) {
+    for (int t = blockIdx.x; t < T_; t += gridDim.x) {
+        const int r = inv[t];
+        for (int c = threadIdx.x; c < pieces; c += 256) {
+            u32x4_t v = {0u, 0u, 0u, 0u};
+            if (r >= 0) v = src[(long long)r * pieces + c];
+            out[(long long)t * pieces + c] = v;
+        }
+    }
+}
+
+int launch_rank_of_kept(const int* index, const int* n_rows, int* inv, int T_, hipStream_t stream) {
+    if (T_ <= 0) return ALCH_OK;
+    const int nb = ceil_div(T_, 256) < 1024 ? ceil_div(T_, 256) : 1024;
+    k_rank_clear<<<nb, 256, 0, stream>>>(inv, T_);
+    k_rank_fill<<<nb, 256, 0, stream>>>(index, n_rows, inv, T_);
+    ALCH_HIP_TRY(hipGetLastError());
+    return ALCH_OK;
+}
+
+int launch_scatter_rows(const void* src, const int* inv, void* out, int T_, size_t row_bytes, hipStream_t stream) {
+    if (T_ <= 0) return ALCH_OK;
+    if (row_bytes % 16 || !aligned16(src) || !aligned16(out)) return fail(ALCH_ERR_UNSUPPORTED, "scatter: rows must be 16-byte multiples");
+    k_scatter_rows<<<T_ < 65536 ? T_ : 65536, 256, 0, stream>>>((const u32x4_t*)src, inv, (u32x4_t*)out, T_, (int)(row_bytes / 16));
     ALCH_HIP_TRY(hipGetLastError());
     return ALCH_OK;
 }

@@ -146,3 +146,22 @@ def test_six_stream_record_is_completed_on_the_device(dtype, shape_name, lens):
                                  to_dev(dY, dtype))
     torch.cuda.synchronize()
     compare({k: to_np(v) for k, v in out2.items()}, ref2, dtype)
+
+
+@pytest.mark.parametrize("keep", [0.0, 0.3, 1.0])
+def test_loss_mask_row_compaction_bf16(keep):
+    # bf16 with a loss mask runs the row-local part on the kept rows only (row count on the device);
+    # the result must still be the dense backward with the masked dY rows zeroed (the oracle's definition),
+    # including the degenerate masks "nothing kept" and "everything kept" and a ragged, multi-tile T
+    cu = synth.ragged_cu([300, 1, 257, 64, 409])
+    T = int(cu[-1])
+    shp, osh, W, rec, dY = make_case("medium", "bf16", cu, 23, "drawn", dy_std=0.01)
+    mask = synth.keep_mask(T, keep, 5)
+    ref = layer_backward_reuse(osh, cu, None, f64(rec), f64(W), dY, mask)
+    gpu = run_gpu(shp, "bf16", cu, W, rec, dY, loss_mask=mask)
+    for k in gpu:
+        assert np.isfinite(gpu[k]).all(), k
+        if np.abs(ref[k]).max() == 0:
+            assert np.abs(gpu[k]).max() == 0, k
+        else:
+            assert rel_err(gpu[k], ref[k]) <= TOL["bf16"], (k, rel_err(gpu[k], ref[k]))
