@@ -7,7 +7,7 @@
 // Two kernels, no atomics, deterministic:
 //   dK/dV kernel: a work-group owns 128 keys of one (sequence, kv head) -- 32 per wavefront,
 //     their K and V fragments held in registers -- and streams 64-query tiles of Q and dO of
-//     every query head of the group through LDS (direct-to-LDS loads, double buffered).
+//     every query head of the group through LDS (direct-to-LDS loads, three stages, software pipelined).
 //       S = Q K^T, dP = dO V^T            (tile rows from LDS with ds_read_b128)
 //       P, dS in the accumulator layout feed straight back as the left operand of
 //       dV += P^T dO, dK += dS^T Q        (dO, Q rows read with the transposing LDS read)
@@ -212,12 +212,14 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
 
     // Software pipeline over the tile stream, three LDS stages.  At the top of iteration `it` the
     // scores S = Q K^T and dP = dO V^T of tile `it` are already in registers.  The iteration
-    //   1. turns them into P and dS (exp, mask, pack to bf16) -- vector ALU only;
-    //   2. waits for tile it+1, meets the other waves, and sends the loads of tile it+2 into the stage
-    //      that tile it-1 occupied (every wave is past its reads of it);
+    //   1. turns block 0 of them into P and dS (exp, mask, pack to bf16) -- vector ALU only;
+    //   2. waits for tile it+1 and meets the other waves: every wave is now past its reads of tile it-1,
+    //      whose stage receives tile it+2;
     //   3. runs 64 matrix instructions back to back: dV += P^T dO and dK += dS^T Q of tile `it`
     //      interleaved with S and dP of tile it+1, so the transposing LDS reads of one and the row reads
-    //      of the other are both covered by independent matrix work.
+    //      of the other are both covered by independent matrix work.  The same instruction stream carries
+    //      the loads of tile it+2 (one per group of four matrix instructions) and the exp/mask/pack of
+    //      block 1, which its consumers (the second half of the groups) find ready.
     f32x16 S[2], dP[2];
     issue(0);
     issue(1);
@@ -237,14 +239,6 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
         }
     }
 
-#ifdef ALCH_ATTN_TIMING
-    const bool stamp = blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0;
-    long long acc_t[4] = {0, 0, 0, 0};
-    const long long k_t0 = __builtin_readcyclecounter(), k_r0 = __builtin_amdgcn_s_memrealtime();
-#define ALCH_STAMP(i) { const long long t_now = __builtin_readcyclecounter(); acc_t[i] += t_now - t_prev; t_prev = t_now; }
-#else
-#define ALCH_STAMP(i)
-#endif
     // stream state, advanced by one tile per iteration (no divisions in the loop):
     // LDS byte offsets of the stages of tiles it, it+1, it+2 and (head, tile) of tile it and it+2
     uint32_t s_cur = 0, s_nxt = kStageBytes, s_ld = 2 * kStageBytes;
@@ -253,9 +247,6 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
     const int jl = j0 + (lane & 31);  // this lane's key
     const unsigned live = (unsigned)max(len - jl, 0);
     for (int it = 0; it < n_it; ++it) {
-#ifdef ALCH_ATTN_TIMING
-        long long t_prev = __builtin_readcyclecounter();
-#endif
         const char* tq = smem + s_cur;
         const char* tdo = tq + kTileBytes;
         const float* lse_s = reinterpret_cast<const float*>(tq + 2 * kTileBytes);
@@ -295,10 +286,8 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
         }
 
         __builtin_amdgcn_sched_barrier(0);
-        ALCH_STAMP(0)
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // tile it+1 (the only loads in flight)
         __syncthreads();
-        ALCH_STAMP(1)
         // Loads of tile it+2: descriptors now, the nine load instructions one per group below (a
         // burst of them would hold the wave at the issue stage for over a thousand cycles).
         const int rows2 = it + 2 < n_it ? len - qt_ld * kTileRows : 0;
@@ -310,7 +299,6 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
         const i32x4 rs_sc = rsrc_of((wave == 0 ? p.LSE : p.delta) + row2 * p.Hq + h_ld,
                                     rows2 > 0 ? ((long long)(rows2 - 1) * p.Hq + 1) * 4 : 0);
         __builtin_amdgcn_sched_barrier(0);
-        ALCH_STAMP(2)
 
         const char* nq = smem + s_nxt;
         const char* ndo = nq + kTileBytes;
@@ -367,21 +355,12 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
         }
         S[0] = Sn;
         dP[0] = dPn;
-        ALCH_STAMP(3)
         // advance the stream
         const uint32_t s_free = s_cur;
         s_cur = s_nxt; s_nxt = s_ld; s_ld = s_free;
         if (++qt_cur == qt0 + nqt) qt_cur = qt0;
         if (++qt_ld == qt0 + nqt) { qt_ld = qt0; ++h_ld; }
     }
-#ifdef ALCH_ATTN_TIMING
-    if (stamp) {
-        for (int i = 0; i < 4; ++i) g_attn_stamps[i] = acc_t[i];
-        g_attn_stamps[5] = n_it;
-        g_attn_stamps[6] = __builtin_readcyclecounter() - k_t0;
-        g_attn_stamps[7] = __builtin_amdgcn_s_memrealtime() - k_r0;
-    }
-#endif
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // accumulator element e of block nb: key row j0 + 8*(e>>2) + 4*half + (e&3), column nb*32 + (lane&31)

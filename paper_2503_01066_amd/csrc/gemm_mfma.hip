@@ -36,10 +36,7 @@ static constexpr int kOperandStageBytes = 256 * BK * 2;  // 16 KB per operand pe
 static constexpr int kLoadsPerTile = 8;                  // direct-to-LDS instructions per wave per k-tile (A + B)
 static constexpr uint32_t kOobOffset = 0x80000000u;      // >= any num_records we set
 static constexpr uint32_t kMaxRecords = 0x80000000u;
-#ifndef ALCH_GROUP_M
-#define ALCH_GROUP_M 4
-#endif
-static constexpr int kGroupM = ALCH_GROUP_M;             // tile rows per raster band
+static constexpr int kGroupM = 4;                        // tile rows per raster band
 
 struct MfmaGemmParams {
     int M, N, n_seg, n_out, accumulate, tiles_m, tiles_n;
@@ -194,9 +191,6 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-#ifdef ALCH_GEMM_TIMING
-    if (blockIdx.x == 8 && threadIdx.x == 0 && q == blockIdx.x / 8) g_stamps[0] = __builtin_readcyclecounter();
-#endif
 
     for (int seg = 0; seg < p.n_seg; ++seg) {
         const long long lda = p.lda[seg], ldb = p.ldb[seg];
@@ -283,9 +277,6 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
         __syncthreads();
         Frags f0, f1;
         read_frags<AK, BKM>(f0, smem, smem + kOperandStageBytes, wm, wn, 0, lane);
-#ifdef ALCH_GEMM_TIMING
-        if (blockIdx.x == 8 && threadIdx.x == 0 && q == blockIdx.x / 8) g_stamps[1] = __builtin_readcyclecounter();
-#endif
         for (int kt = 0; kt < nk; kt += kStages) {
 #pragma unroll
             for (int s = 0; s < kStages; ++s) {
@@ -326,9 +317,6 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
 #undef ALCH_RA
 #undef ALCH_RB
     }
-#ifdef ALCH_GEMM_TIMING
-    if (blockIdx.x == 8 && threadIdx.x == 0 && q == blockIdx.x / 8) g_stamps[2] = __builtin_readcyclecounter();
-#endif
 
     // ---- epilogue.  The MFMAs were issued with the operand roles swapped, so block (i, j) holds
     // the transposed 32x32 result: this lane owns output row m = .. + i*32 + (lane&31) and, in
@@ -441,13 +429,7 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
                 }
         });
     }
-#ifdef ALCH_GEMM_TIMING
-    if (blockIdx.x == 8 && threadIdx.x == 0 && q == blockIdx.x / 8) g_stamps[3] = __builtin_readcyclecounter();
-#endif
     }  // tiles of this work-group
-#ifdef ALCH_GEMM_TIMING
-    if (blockIdx.x == 8 && threadIdx.x == 0) g_stamps[4] = __builtin_readcyclecounter();
-#endif
 }
 
 bool gemm_mfma_supported(const GemmDesc& d) {
