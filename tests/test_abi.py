@@ -44,8 +44,8 @@ def test_workspace_queries():
     L = A.lib()
     s = A.make_shape(4096, 32, 8, 128, 14336, 1e-5, 5e5, "bf16")
     n = L.alch_layer_backward_workspace_bytes(C.byref(s), 8192, 2048)
-    # dominated by [T, 2F] + [T, F] bf16
-    assert 8192 * 3 * 14336 * 2 < n < 2 * 8192 * 3 * 14336 * 2
+    # dominated by [T, 2F] + [T, F] bf16, plus the compacted copies of G, U (loss-mask mode) and the [T, H]-sized rest
+    assert 8192 * 3 * 14336 * 2 < n < 3 * 8192 * 3 * 14336 * 2
     assert L.alch_layer_backward_workspace_bytes(C.byref(s), 0, 0) > 0
     bad = A.make_shape(4096, 32, 7, 128, 14336, 1e-5, 5e5, "bf16")
     assert L.alch_layer_backward_workspace_bytes(C.byref(bad), 8192, 2048) == 0
@@ -119,3 +119,65 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(B, "library_path", lambda: "/nonexistent/libalch.so")
     with pytest.raises(RuntimeError, match="no fallback"):
         B.lib()
+
+
+def test_lora_entry_points_reject_bad_arguments():
+    L = A.lib()
+    P = 0x10000
+    s = A.make_shape(256, 4, 4, 64, 1024, 1e-6, 1e4, "f32")
+    b = _batch([0, 128, 256])
+    sv, w, g = B.CSaved(*([P] * 9), 0), B.CWeights(*([P] * 9), 0), B.CWgrads(*([None] * 9), 0)
+
+    def lora(rank=8, A_q=P, B_q=P):
+        lo = B.CLora(rank=rank, scale=1.0)
+        lo.A[0], lo.B[0] = A_q, B_q
+        return lo
+
+    def grads(dA_q=None, dA_k=None):
+        lg = B.CLoraGrads(accumulate=0)
+        lg.dA[0], lg.dA[1] = dA_q, dA_k
+        return lg
+
+    call = lambda lo, lg=None, wsb=1 << 40, sv_=sv: L.alch_layer_backward_lora(
+        C.byref(s), C.byref(b), C.byref(sv_), C.byref(w), C.byref(lo) if lo is not None else None, P, None, P,
+        C.byref(g), C.byref(lg) if lg is not None else None, P, wsb, None)
+    assert call(None) == -1 and "lora" in _err()
+    assert call(lora(rank=4)) == -2 and "rank" in _err()
+    assert call(lora(rank=12)) == -2
+    assert call(lora(rank=128)) == -2
+    assert call(lora(B_q=None)) == -1 and "both" in _err()
+    assert call(lora(A_q=P + 2)) == -1 and "aligned" in _err()
+    assert call(lora(), grads(dA_k=P)) == -1 and "without adapter" in _err()   # projection k carries no adapter
+    assert call(lora(), grads(dA_q=P), wsb=4096) == -3
+    # a record without X2 is fine in general, but not when the output projection is adapted (validated at enqueue
+    # time, after the workspace check, so it needs no GPU either: T > 0 and the first launch is never reached)
+    q = L.alch_layer_backward_lora_workspace_bytes
+    assert q(C.byref(s), 256, 128, 8) > L.alch_layer_backward_workspace_bytes(C.byref(s), 256, 128)
+    assert q(C.byref(s), 256, 128, 7) == 0
+    assert L.alch_stack_backward_lora_workspace_bytes(C.byref(s), 2, 1000, 256, 128, 8) > q(C.byref(s), 256, 128, 8)
+
+    # stack: the rank must be the same in every layer; the adapter array is required
+    sva = (B.CSaved * 2)(sv, sv)
+    wa = (B.CWeights * 2)(w, w)
+    la = (B.CLora * 2)(lora(rank=8), lora(rank=16))
+    sargs = lambda lo: (C.byref(s), 2, 1000, C.byref(b), sva, wa, lo, P, P, P, P, None, None, None, None, None, P, P,
+                        None, P, 1 << 40, None)
+    assert L.alch_stack_backward_lora(*sargs(la)) == -2 and "rank differs" in _err()
+    assert L.alch_stack_backward_lora(*sargs(None)) == -1
+
+
+def test_six_stream_record_passes_validation_but_missing_required_tensors_do_not():
+    L = A.lib()
+    P = 0x10000
+    s = A.make_shape(256, 4, 4, 64, 1024, 1e-6, 1e4, "f32")
+    b = _batch([0, 128, 256])
+    w, g = B.CWeights(*([P] * 9), 0), B.CWgrads(*([None] * 9), 0)
+    # field order X, X2, Q, K, V, O, G, U, LSE: X2, O, LSE may be NULL -> validation passes, the call then stops at
+    # the workspace check (-3) before anything is launched
+    six = B.CSaved(P, None, P, P, P, None, P, P, None, 0)
+    assert L.alch_layer_backward(C.byref(s), C.byref(b), C.byref(six), C.byref(w), P, None, P, C.byref(g), P, 1024, None) == -3
+    for missing in (0, 2, 3, 4, 6, 7):  # X, Q, K, V, G, U are required
+        ptrs = [P] * 9
+        ptrs[missing] = None
+        sv = B.CSaved(*ptrs, 0)
+        assert L.alch_layer_backward(C.byref(s), C.byref(b), C.byref(sv), C.byref(w), P, None, P, C.byref(g), P, 1 << 40, None) == -1
