@@ -40,6 +40,8 @@ def parse():
                     help="config2/config5: rank-r adapters on all seven projections (alch_layer_backward_lora)")
     ap.add_argument("--frozen-base", action="store_true",
                     help="config2/config5: no base weight gradients (the frozen base of parameter-efficient fine-tuning)")
+    ap.add_argument("--six-stream", action="store_true",
+                    help="config2/config5: pack only X, Q, K, V, G, U; the backward recomputes O, LSE and X2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
                     help="measured HBM bytes per launch (from the rocprofv3 --pmc summaries)")
@@ -152,6 +154,9 @@ def run_layer(args, torch, A):
                   "the kept rows, attention and the QKV products stay dense" % (n_loss, T))
 
     keys = list(widths) + ["LSE"]
+    if args.six_stream:
+        keys = ["X", "Q", "K", "V", "G", "U"]
+        descr += ", six-stream record (O, LSE, X2 recomputed by the backward)"
     dst = {k: torch.empty((T, src[k].shape[1]), dtype=src[k].dtype, device=dev) for k in keys}
     src_batch = A.Batch(synth.uniform_cu(n_src, S))
     kept_batch = A.Batch(synth.uniform_cu(n_keep, S))
