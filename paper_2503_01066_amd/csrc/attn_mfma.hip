@@ -210,17 +210,47 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
         if (wave == 1) issue_row_scalars(p.delta + (long long)(seq_start + row_first) * p.Hq + h, p.Hq, rows_valid, st + 2 * kTileBytes + 256, lane);
     };
 
-    // Software pipeline over the tile stream, three LDS stages.  At the top of iteration `it` the
-    // scores S = Q K^T and dP = dO V^T of tile `it` are already in registers.  The iteration
-    //   1. turns block 0 of them into P and dS (exp, mask, pack to bf16) -- vector ALU only;
-    //   2. waits for tile it+1 and meets the other waves: every wave is now past its reads of tile it-1,
-    //      whose stage receives tile it+2;
-    //   3. runs 64 matrix instructions back to back: dV += P^T dO and dK += dS^T Q of tile `it`
-    //      interleaved with S and dP of tile it+1, so the transposing LDS reads of one and the row reads
-    //      of the other are both covered by independent matrix work.  The same instruction stream carries
-    //      the loads of tile it+2 (one per group of four matrix instructions) and the exp/mask/pack of
-    //      block 1, which its consumers (the second half of the groups) find ready.
-    f32x16 S[2], dP[2];
+    // Software pipeline over the tile stream, three LDS stages.  Entering iteration `it`, of tile `it`
+    // (two blocks of 32 queries) the wave holds P, dS of block 0 packed to bf16 and the raw scores
+    // S = Q K^T, dP = dO V^T of block 1.  The iteration waits for tile it+1 and meets the other waves
+    // (every wave is then past its reads of tile it-1, whose stage receives tile it+2), then runs 64
+    // matrix instructions back to back, in 16 groups of four:
+    //   groups 0-7:  dV += P^T dO, dK += dS^T Q of block 0   |  S, dP of block 0 of tile it+1
+    //   groups 8-15: the same for block 1                     |  S, dP of block 1 of tile it+1
+    // so the transposing LDS reads of one product and the row reads of the other are covered by
+    // independent matrix work (six LDS reads per group, issued two groups ahead of their use).  The same
+    // instruction stream carries, in the shadow of the matrix instructions, the nine direct-to-LDS loads
+    // of tile it+2 (one per group) and all of the exp/mask/pack work: block 1 of tile `it` during groups
+    // 0-7 (its consumers, groups 8-15, find it ready) and block 0 of tile it+1 during groups 8-15.
+    f32x16 S1, dP1;         // raw scores of block 1 of the current tile
+    bf16x8 pf0[2], dsf0[2]; // P, dS of block 0 of the current tile
+    const int jl = j0 + (lane & 31);  // this lane's key
+    const unsigned live = (unsigned)max(len - jl, 0);
+    // P, dS of accumulator elements e0 .. e0+n-1 of one block, in place.  Element e is query row
+    // i = i0 + 8*(e>>2) + 4*half + (e&3) against key column jl.  Pairs above the diagonal (jl > i) and rows
+    // or keys past the end of the sequence get exponent -inf, i.e. p = 0 exactly: with rel = i - jl that
+    // is one unsigned test, rel >= max(len - jl, 0).  l, d: LSE and delta of the block's 16 rows of this lane.
+    auto softmax_part = [&](f32x16& s, f32x16& dp, const f32x4 (&l)[4], const f32x4 (&d)[4], int i0, int e0, int n) {
+        const int rel0 = i0 + 4 * half - jl;
+#pragma unroll
+        for (int e = e0; e < e0 + n; ++e) {
+            const unsigned rel = (unsigned)(rel0 + 8 * (e >> 2) + (e & 3));
+            float arg = __builtin_fmaf(s[e], sl2, -l[e >> 2][e & 3] * kLog2e);
+            arg = rel >= live ? -INFINITY : arg;
+            const float pr = __builtin_amdgcn_exp2f(arg);
+            s[e] = pr;
+            dp[e] = pr * (dp[e] - d[e >> 2][e & 3]);
+        }
+    };
+    auto load_row_scalars = [&](const char* stage, int ib, f32x4 (&l)[4], f32x4 (&d)[4]) {
+        const float* lse_s = reinterpret_cast<const float*>(stage + 2 * kTileBytes);
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            l[b] = *reinterpret_cast<const f32x4*>(lse_s + ib * 32 + 8 * b + 4 * half);
+            d[b] = *reinterpret_cast<const f32x4*>(lse_s + 64 + ib * 32 + 8 * b + 4 * half);
+        }
+    };
+
     issue(0);
     issue(1);
     if (wave < 2)
@@ -228,14 +258,24 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
     else
         asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
     __syncthreads();
+    {   // tile 0: scores of both blocks, P and dS of block 0
+        f32x16 S0, dP0;
 #pragma unroll
-    for (int ib = 0; ib < 2; ++ib) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) S[ib][e] = dP[ib][e] = 0.f;
+        for (int e = 0; e < 16; ++e) S0[e] = dP0[e] = S1[e] = dP1[e] = 0.f;
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
-            S[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_d(smem + ib * 32 * 256, lane_d, kk), kf[kk], S[ib], 0, 0, 0);
-            dP[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_d(smem + kTileBytes + ib * 32 * 256, lane_d, kk), vf[kk], dP[ib], 0, 0, 0);
+            S0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_d(smem, lane_d, kk), kf[kk], S0, 0, 0, 0);
+            dP0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_d(smem + kTileBytes, lane_d, kk), vf[kk], dP0, 0, 0, 0);
+            S1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_d(smem + 32 * 256, lane_d, kk), kf[kk], S1, 0, 0, 0);
+            dP1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_d(smem + kTileBytes + 32 * 256, lane_d, kk), vf[kk], dP1, 0, 0, 0);
+        }
+        f32x4 l[4], d[4];
+        load_row_scalars(smem, 0, l, d);
+        softmax_part(S0, dP0, l, d, qt0 * kTileRows, 0, 16);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            pf0[ks] = pack8(S0, ks);
+            dsf0[ks] = pack8(dP0, ks);
         }
     }
 
@@ -244,46 +284,13 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
     uint32_t s_cur = 0, s_nxt = kStageBytes, s_ld = 2 * kStageBytes;
     int qt_cur = qt0;
     int h_ld = kv * G + 2 / nqt, qt_ld = qt0 + 2 % nqt;
-    const int jl = j0 + (lane & 31);  // this lane's key
-    const unsigned live = (unsigned)max(len - jl, 0);
     for (int it = 0; it < n_it; ++it) {
         const char* tq = smem + s_cur;
         const char* tdo = tq + kTileBytes;
-        const float* lse_s = reinterpret_cast<const float*>(tq + 2 * kTileBytes);
-        const float* del_s = lse_s + 64;
         const int i00 = qt_cur * kTileRows;
-
-        // P, dS of accumulator elements e0 .. e0+n-1 of block ib, in place in S, dP.
-        // element e: query row i = i00 + 32*ib + 8*(e>>2) + 4*half + (e&3), key column jl.  Pairs above
-        // the diagonal (jl > i) and rows or keys past the end of the sequence get exponent -inf, i.e.
-        // p = 0 exactly: with rel = i - jl that is one unsigned test, rel >= max(len - jl, 0).
-        const int rel0 = i00 + 4 * half - jl;
-        auto softmax_part = [&](int ib, const f32x4 (&l4)[4], const f32x4 (&d4)[4], int e0, int n) {
-#pragma unroll
-            for (int e = e0; e < e0 + n; ++e) {
-                const unsigned rel = (unsigned)(rel0 + ib * 32 + 8 * (e >> 2) + (e & 3));
-                float arg = __builtin_fmaf(S[ib][e], sl2, -l4[e >> 2][e & 3] * kLog2e);
-                arg = rel >= live ? -INFINITY : arg;
-                const float pr = __builtin_amdgcn_exp2f(arg);
-                S[ib][e] = pr;
-                dP[ib][e] = pr * (dP[ib][e] - d4[e >> 2][e & 3]);
-            }
-        };
-        f32x4 l4[2][4], d4[2][4];
-#pragma unroll
-        for (int ib = 0; ib < 2; ++ib)
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                l4[ib][b] = *reinterpret_cast<const f32x4*>(lse_s + ib * 32 + 8 * b + 4 * half);
-                d4[ib][b] = *reinterpret_cast<const f32x4*>(del_s + ib * 32 + 8 * b + 4 * half);
-            }
-        bf16x8 pf[2][2], dsf[2][2];
-        softmax_part(0, l4[0], d4[0], 0, 16);
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            pf[0][ks] = pack8(S[0], ks);
-            dsf[0][ks] = pack8(dP[0], ks);
-        }
+        const int qt_nxt = qt_cur + 1 == qt0 + nqt ? qt0 : qt_cur + 1;
+        f32x4 l1[4], d1[4];  // LSE, delta of block 1 of this tile
+        load_row_scalars(tq, 1, l1, d1);
 
         __builtin_amdgcn_sched_barrier(0);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // tile it+1 (the only loads in flight)
@@ -298,14 +305,12 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
         const i32x4 rs_do = rsrc_of(p.dO + row2 * p.ldq + h_ld * kD, ext2);
         const i32x4 rs_sc = rsrc_of((wave == 0 ? p.LSE : p.delta) + row2 * p.Hq + h_ld,
                                     rows2 > 0 ? ((long long)(rows2 - 1) * p.Hq + 1) * 4 : 0);
-        __builtin_amdgcn_sched_barrier(0);
-
         const char* nq = smem + s_nxt;
         const char* ndo = nq + kTileBytes;
-        // 16 groups of four matrix instructions: dV += P^T dO, dK += dS^T Q of this tile and S, dP of
-        // the next.  The six LDS reads of a group are issued two groups ahead of their use.  Groups 0-7
-        // work on block 0 and carry the exp/mask/pack of block 1 (two elements of S and dP each) in
-        // the shadow of their matrix instructions; groups 8-15 then consume block 1.
+        f32x4 ln[4], dn[4];  // LSE, delta of block 0 of the next tile (its stage is complete since the barrier)
+        load_row_scalars(nq, 0, ln, dn);
+        __builtin_amdgcn_sched_barrier(0);
+
         struct Frags { bf16x8 rdo, rq, dq, ddo; };
         auto load_group = [&](int g) {
             const int ib = g >> 3, ks = (g >> 2) & 1, nb = g & 3, kk = ks * 4 + nb;
@@ -319,7 +324,8 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
         Frags fr[3];
         fr[0] = load_group(0);
         fr[1] = load_group(1);
-        f32x16 Sn, dPn;  // S, dP of block 0 of the next tile (block 1 goes straight into S[1], dP[1])
+        f32x16 Sn0, dPn0, Sn1, dPn1;  // scores of the next tile
+        bf16x8 pf1[2], dsf1[2], pfn[2], dsfn[2];
 #pragma unroll
         for (int g = 0; g < 16; ++g) {
             const int ib = g >> 3, ks = (g >> 2) & 1, nb = g & 3, kk = ks * 4 + nb;
@@ -328,37 +334,44 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
             else if (g == 8 && wave < 2) dma4(rs_sc, st2 + 2 * kTileBytes + (uint32_t)wave * 256u, (uint32_t)(lane * p.Hq * 4));
             if (g + 2 < 16) fr[(g + 2) % 3] = load_group(g + 2);
             if (g < 8) {
-                softmax_part(1, l4[1], d4[1], 2 * g, 2);
-                if (g == 3) { pf[1][0] = pack8(S[1], 0); dsf[1][0] = pack8(dP[1], 0); }
-                if (g == 7) { pf[1][1] = pack8(S[1], 1); dsf[1][1] = pack8(dP[1], 1); }
+                softmax_part(S1, dP1, l1, d1, i00 + 32, 2 * g, 2);
+                if (g == 3) { pf1[0] = pack8(S1, 0); dsf1[0] = pack8(dP1, 0); }
+                if (g == 7) { pf1[1] = pack8(S1, 1); dsf1[1] = pack8(dP1, 1); }
+            } else {
+                softmax_part(Sn0, dPn0, ln, dn, qt_nxt * kTileRows, 2 * (g - 8), 2);
+                if (g == 11) { pfn[0] = pack8(Sn0, 0); dsfn[0] = pack8(dPn0, 0); }
+                if (g == 15) { pfn[1] = pack8(Sn0, 1); dsfn[1] = pack8(dPn0, 1); }
             }
             __builtin_amdgcn_sched_barrier(0);
             const Frags& f = fr[g % 3];
-            dV[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[ib][ks], f.rdo, dV[nb], 0, 0, 0);
-            dK[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf[ib][ks], f.rq, dK[nb], 0, 0, 0);
             if (ib == 0) {
                 if (g == 0) {
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) Sn[e] = dPn[e] = 0.f;
+                    for (int e = 0; e < 16; ++e) Sn0[e] = dPn0[e] = 0.f;
                 }
-                Sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.dq, kf[kk], Sn, 0, 0, 0);
-                dPn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ddo, vf[kk], dPn, 0, 0, 0);
+                dV[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf0[ks], f.rdo, dV[nb], 0, 0, 0);
+                dK[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf0[ks], f.rq, dK[nb], 0, 0, 0);
+                Sn0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.dq, kf[kk], Sn0, 0, 0, 0);
+                dPn0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ddo, vf[kk], dPn0, 0, 0, 0);
             } else {
                 if (g == 8) {
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) S[1][e] = dP[1][e] = 0.f;
+                    for (int e = 0; e < 16; ++e) Sn1[e] = dPn1[e] = 0.f;
                 }
-                S[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.dq, kf[kk], S[1], 0, 0, 0);
-                dP[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ddo, vf[kk], dP[1], 0, 0, 0);
+                dV[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf1[ks], f.rdo, dV[nb], 0, 0, 0);
+                dK[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf1[ks], f.rq, dK[nb], 0, 0, 0);
+                Sn1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.dq, kf[kk], Sn1, 0, 0, 0);
+                dPn1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ddo, vf[kk], dPn1, 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        S[0] = Sn;
-        dP[0] = dPn;
-        // advance the stream
+        // hand over to the next iteration
+        S1 = Sn1; dP1 = dPn1;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) { pf0[ks] = pfn[ks]; dsf0[ks] = dsfn[ks]; }
         const uint32_t s_free = s_cur;
         s_cur = s_nxt; s_nxt = s_ld; s_ld = s_free;
-        if (++qt_cur == qt0 + nqt) qt_cur = qt0;
+        qt_cur = qt_nxt;
         if (++qt_ld == qt0 + nqt) { qt_ld = qt0; ++h_ld; }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
