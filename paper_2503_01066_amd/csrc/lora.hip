@@ -166,6 +166,46 @@ __global__ __launch_bounds__(256) void k_lora_down_mfma(LoraDownParams p) {
 // ---- up, pass 1: partial[jc][split][j][n] = sum over the rows of the split of S[t, 8*jc + j] * X[t, n] ----
 // work-group = 512 columns (8 per lane) x one row split; its four wavefronts interleave the rows and
 // fold their sums through LDS in a fixed order.
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_l;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_l;
+
+// One token (float storage) or one pair of tokens (bf16 storage) of the rank-8 outer-product sum
+// acc[j][c] += S[t, j] * X[t, c].  For bf16 the two tokens of a pair are interleaved into (t, t+1)
+// halfword pairs (one byte-permute per pair) and each 2-term sum is one packed dot-product instruction
+// accumulating in fp32: half the vector instructions of convert + multiply-add per element.
+__device__ __forceinline__ void up_step(const float* xr, const float* sr, long long, long long, bool, float (&acc)[8][8]) {
+    float x[8], s[8];
+    load8(xr, x);
+    load8(sr, s);
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[j][c] = __builtin_fmaf(s[j], x[c], acc[j][c]);
+}
+__device__ __forceinline__ void up_step(const __bf16* xr, const __bf16* sr, long long ldx, long long lds, bool second,
+                                        float (&acc)[8][8]) {
+    const u32x4_l zero = {0u, 0u, 0u, 0u};
+    const u32x4_l x0 = *reinterpret_cast<const u32x4_l*>(xr), s0 = *reinterpret_cast<const u32x4_l*>(sr);
+    const u32x4_l x1 = second ? *reinterpret_cast<const u32x4_l*>(xr + ldx) : zero;
+    const u32x4_l s1 = second ? *reinterpret_cast<const u32x4_l*>(sr + lds) : zero;
+    unsigned xp[8], sp[8];
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        xp[2 * m] = __builtin_amdgcn_perm(x1[m], x0[m], 0x05040100u);      // (x[t][2m],   x[t+1][2m])
+        xp[2 * m + 1] = __builtin_amdgcn_perm(x1[m], x0[m], 0x07060302u);  // (x[t][2m+1], x[t+1][2m+1])
+        sp[2 * m] = __builtin_amdgcn_perm(s1[m], s0[m], 0x05040100u);
+        sp[2 * m + 1] = __builtin_amdgcn_perm(s1[m], s0[m], 0x07060302u);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+            acc[j][c] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_l, sp[j]), __builtin_bit_cast(bf16x2_l, xp[c]),
+                                                        acc[j][c], false);
+}
+template <typename T> struct UpStep { static constexpr int kTokens = 1; };
+template <> struct UpStep<__bf16> { static constexpr int kTokens = 2; };
+
 template <typename T>
 __global__ __launch_bounds__(256) void k_lora_up_partial(const T* __restrict__ S, long long lds, const T* __restrict__ X,
                                                          long long ldx, int Trows, int N, int rows_per_split,
@@ -176,6 +216,7 @@ __global__ __launch_bounds__(256) void k_lora_up_partial(const T* __restrict__ S
     const int split = blockIdx.y, nsplit = gridDim.y, jc = blockIdx.z;
     const long long r0 = (long long)split * rows_per_split;
     const long long r1 = r0 + rows_per_split < Trows ? r0 + rows_per_split : Trows;
+    constexpr int kTok = UpStep<T>::kTokens;
     float acc[8][8];
 #pragma unroll
     for (int j = 0; j < 8; ++j)
@@ -183,15 +224,8 @@ __global__ __launch_bounds__(256) void k_lora_up_partial(const T* __restrict__ S
         for (int c = 0; c < 8; ++c) acc[j][c] = 0.f;
     if (n0 < N) {
 #pragma unroll 2
-        for (long long t = r0 + wave; t < r1; t += 4) {
-            float x[8], s[8];
-            load8(X + t * ldx + n0, x);
-            load8(S + t * lds + jc * 8, s);
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-#pragma unroll
-                for (int c = 0; c < 8; ++c) acc[j][c] = __builtin_fmaf(s[j], x[c], acc[j][c]);
-        }
+        for (long long t = r0 + wave * kTok; t < r1; t += 4 * kTok)
+            up_step(X + t * ldx + n0, S + t * lds + jc * 8, ldx, lds, t + 1 < r1, acc);
     }
     if (wave > 0) {
 #pragma unroll
