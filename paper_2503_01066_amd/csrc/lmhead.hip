@@ -74,6 +74,90 @@ __global__ __launch_bounds__(256) void k_ce_chunk(T* __restrict__ logits, long l
     if (threadIdx.x == 0) row_loss[r] = logz - x_label;
 }
 
+// bf16 fast path: one 1024-thread work-group per row keeps the whole row in registers (up to 16 chunks of
+// 8 logits per thread, i.e. vocab <= 131072), so the logits are read once and the gradient written once:
+// the three passes (max, sum of exponentials, gradient) run on registers.
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_c;
+static constexpr int kCeThreads = 1024, kCeChunks = 16;
+__global__ __launch_bounds__(kCeThreads) void k_ce_chunk_bf16_row(__bf16* __restrict__ logits, long long ld, int vocab,
+                                                                   const int* __restrict__ labels,
+                                                                   const uint8_t* __restrict__ mask,
+                                                                   const int* __restrict__ n_counted,
+                                                                   float* __restrict__ row_loss) {
+    __shared__ float red[kCeThreads / 64];
+    const int r = blockIdx.x;
+    __bf16* row = logits + (long long)r * ld;
+    const int label = labels[r];
+    const bool counted = label >= 0 && label < vocab && (!mask || mask[r] != 0);
+    const int nchunks = vocab >> 3;
+    if (!counted) {
+        bf16x8_c z;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) z[e] = (__bf16)0.f;
+        for (int c = threadIdx.x; c < nchunks; c += kCeThreads) *reinterpret_cast<bf16x8_c*>(row + c * 8) = z;
+        return;
+    }
+    bf16x8_c x[kCeChunks];
+    float m = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < kCeChunks; ++k) {
+        const int c = threadIdx.x + k * kCeThreads;
+        if (c < nchunks) {
+            x[k] = *reinterpret_cast<const bf16x8_c*>(row + c * 8);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) m = fmaxf(m, (float)x[k][e]);
+        }
+    }
+    m = wmax(m);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    m = red[0];
+#pragma unroll
+    for (int w = 1; w < kCeThreads / 64; ++w) m = fmaxf(m, red[w]);
+    __syncthreads();
+    const float kL2e = 1.4426950408889634f;
+    float s = 0.f;
+    // (the empty asm keeps the row packed in registers between passes: without it the compiler carries the
+    // converted fp32 copies across and runs out of registers)
+#pragma unroll
+    for (int k = 0; k < kCeChunks; ++k) asm volatile("" : "+v"(x[k]));
+#pragma unroll
+    for (int k = 0; k < kCeChunks; ++k) {
+        const int c = threadIdx.x + k * kCeThreads;
+        if (c < nchunks) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s += __builtin_amdgcn_exp2f(((float)x[k][e] - m) * kL2e);
+        }
+    }
+    s = wsum2(s);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    s = 0.f;
+#pragma unroll
+    for (int w = 0; w < kCeThreads / 64; ++w) s += red[w];
+    const float logz = m + __logf(s);
+    const float inv_n = 1.f / (float)n_counted[0];
+#pragma unroll
+    for (int k = 0; k < kCeChunks; ++k) asm volatile("" : "+v"(x[k]));
+#pragma unroll
+    for (int k = 0; k < kCeChunks; ++k) {
+        const int c = threadIdx.x + k * kCeThreads;
+        if (c < nchunks) {
+            bf16x8_c o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float pr = __builtin_amdgcn_exp2f(((float)x[k][e] - logz) * kL2e);
+                if (c * 8 + e == label) {
+                    pr -= 1.f;
+                    row_loss[r] = logz - (float)x[k][e];
+                }
+                o[e] = (__bf16)(pr * inv_n);
+            }
+            *reinterpret_cast<bf16x8_c*>(row + c * 8) = o;
+        }
+    }
+}
+
 __global__ __launch_bounds__(256) void k_finish_loss(const float* __restrict__ row_loss, const int* __restrict__ n_counted,
                                                      float* __restrict__ loss_out, int T) {
     __shared__ float red[4];
@@ -98,7 +182,9 @@ int launch_count_labels(const int* labels, const uint8_t* loss_mask, int T, int*
 int launch_ce_chunk(alch_dtype dt, void* logits, long long ld, int rows, int vocab, const int* labels,
                     const uint8_t* loss_mask, const int* n_counted, float* row_loss, hipStream_t stream) {
     if (rows <= 0) return ALCH_OK;
-    if (dt == ALCH_BF16)
+    if (dt == ALCH_BF16 && vocab % 8 == 0 && ld % 8 == 0 && vocab <= kCeThreads * kCeChunks * 8 && aligned16(logits))
+        k_ce_chunk_bf16_row<<<rows, kCeThreads, 0, stream>>>((__bf16*)logits, ld, vocab, labels, loss_mask, n_counted, row_loss);
+    else if (dt == ALCH_BF16)
         k_ce_chunk<__bf16><<<rows, 256, 0, stream>>>((__bf16*)logits, ld, vocab, labels, loss_mask, n_counted, row_loss);
     else
         k_ce_chunk<float><<<rows, 256, 0, stream>>>((float*)logits, ld, vocab, labels, loss_mask, n_counted, row_loss);
