@@ -91,3 +91,57 @@ def test_graph_replays_match_eager():
     again = snapshot(outs)
     for k in again:
         assert torch.equal(got[k], again[k]), k
+
+
+def test_graph_with_loss_mask_compaction_and_adapters():
+    # the row count of the loss-mask mode lives on the device: a captured graph must follow a mask whose
+    # contents change between replays (same address); the adapter mode is captured in the same graph
+    import paper_2503_01066_amd as A
+    shp = synth.shape_dict("medium")
+    cu = synth.ragged_cu([200, 96, 130])
+    T = int(cu[-1])
+    shape = alch_shape(shp, "bf16")
+    batch = A.Batch(cu)
+    W = {k: to_dev(v, "bf16") for k, v in synth.layer_weights(shp, 0, "bf16").items()}
+    rec = {k: to_dev(v, "bf16") for k, v in synth.drawn_record(shp, T, 1, "bf16").items()}
+    rec["LSE"] = torch.from_numpy(np.random.default_rng(2).normal(6.0, 0.3, (T, shp["n_q_heads"])).astype(np.float32)).cuda()
+    dY = to_dev(synth.activations(T, shp["hidden"], 3, "bf16", std=0.01), "bf16")
+    mask = torch.from_numpy(synth.keep_mask(T, 0.3, 1)).cuda()
+    lora = {p: (to_dev(a, "bf16"), to_dev(b, "bf16")) for p, (a, b) in synth.lora_adapters(shp, 8, 4, "bf16").items()}
+    grads = {"d" + k: torch.empty_like(v) for k, v in W.items()}
+    lgrads = {}
+    for p, (a, b) in lora.items():
+        lgrads["dA" + p], lgrads["dB" + p] = torch.empty_like(a), torch.empty_like(b)
+    dX1, dX2 = torch.empty_like(dY), torch.empty_like(dY)
+    import ctypes
+    ws1 = torch.empty(A.layer_backward_workspace_bytes(shape, T, 200), dtype=torch.uint8, device="cuda")
+    ws2 = torch.empty(A.lib().alch_layer_backward_lora_workspace_bytes(ctypes.byref(shape), T, 200, 8), dtype=torch.uint8,
+                      device="cuda")
+
+    def step():
+        A.alch_layer_backward(shape, batch, rec, W, dY, loss_mask=mask, grads=grads, dX=dX1, workspace=ws1)
+        A.alch_layer_backward_lora(shape, batch, rec, W, lora, 8, 2.0, dY, lora_grads=lgrads, dX=dX2, workspace=ws2)
+
+    outs = dict(grads, dX1=dX1, dX2=dX2, **lgrads)
+    step()
+    eager = snapshot(outs)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for rep in range(2):
+        for v in outs.values():
+            v.fill_(float(rep))
+        torch.cuda.synchronize()
+        g.replay()
+        got = snapshot(outs)
+        for k in eager:
+            assert torch.equal(got[k], eager[k]), (rep, k)
+    mask.copy_(torch.from_numpy(synth.keep_mask(T, 0.7, 9)).cuda())   # other rows, another count
+    torch.cuda.synchronize()
+    g.replay()
+    got = snapshot(outs)
+    step()
+    again = snapshot(outs)
+    assert not torch.equal(again["dWd"], eager["dWd"])
+    for k in again:
+        assert torch.equal(got[k], again[k]), k
