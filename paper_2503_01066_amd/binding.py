@@ -354,7 +354,7 @@ def _lora_structs(lora, lora_grads, rank, scale, accumulate):
 
 def alch_stack_backward_lora(shape, batch, saved_layers, weights_layers, lora_layers, rank, scale, X_final, g_final,
                              W_lm, labels, loss_mask=None, want=(), want_head=False, lora_grads_layers=None,
-                             grads_layers=None, accumulate=False, workspace=None, stream=None):
+                             grads_layers=None, accumulate=False, hooks=None, workspace=None, stream=None):
     """Stack backward with adapters.  lora_layers: list of dicts projection -> (A, B).  Defaults: frozen base and
     frozen head (want=(), want_head=False), gradients of every adapter.  Returns the dict of alch_stack_backward;
     the per-layer dicts hold the adapter gradients ('dAq', 'dBq', ...) and any base gradients asked for."""
@@ -385,10 +385,14 @@ def alch_stack_backward_lora(shape, batch, saved_layers, weights_layers, lora_la
     need = L.alch_stack_backward_lora_workspace_bytes(C.byref(shape), n_layers, vocab, batch.total_tokens,
                                                       batch.max_seqlen, rank)
     ws = workspace if workspace is not None else _workspace(need, dev)
+    hk = None
+    if hooks is not None:
+        ready, preempt = hooks
+        hk = CHooks(HOOK_FN(ready) if ready else HOOK_FN(), HOOK_FN(preempt) if preempt else HOOK_FN(), None)
     _check(L.alch_stack_backward_lora(C.byref(shape), n_layers, vocab, C.byref(batch.c), SA, WA, LA, _ptr(X_final),
                                       _ptr(g_final), _ptr(W_lm), _ptr(labels), _ptr(loss_mask), GA, LG, _ptr(dg_final),
-                                      _ptr(dW_lm), _ptr(dX_embed), _ptr(loss), None, _ptr(ws), ws.numel(),
-                                      _stream_handle(stream)))
+                                      _ptr(dW_lm), _ptr(dX_embed), _ptr(loss), C.byref(hk) if hk else None, _ptr(ws),
+                                      ws.numel(), _stream_handle(stream)))
     layers = []
     for g, lg in zip(grads_layers, lora_grads_layers):
         d = dict(g)

@@ -1,0 +1,71 @@
+"""Offloaded records (Section 4.3 of the paper): device -> pinned host on a side stream, then prefetched back
+layer by layer through the layer_ready hook while alch_stack_backward walks the stack.  The result must be
+bit-identical to the backward that finds every record resident."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as synth
+from helpers import to_dev, f64, oracle_shape, alch_shape
+from oracle import stack_forward
+
+pytestmark = pytest.mark.gpu
+REC = ("X", "X2", "Q", "K", "V", "O", "G", "U")
+
+
+@pytest.mark.parametrize("L", [1, 2, 5])
+def test_prefetched_backward_is_bit_identical(L):
+    import paper_2503_01066_amd as A
+    shp = synth.shape_dict("medium64")
+    osh = oracle_shape(shp)
+    cu = synth.ragged_cu([130, 61, 200])
+    T, V, dtype = int(cu[-1]), 1000, "bf16"
+    Ws = [synth.layer_weights(shp, 40 + 10 * l, dtype, std=0.05, gain_std=0.1) for l in range(L)]
+    rng = np.random.default_rng(7)
+    X0 = synth.normal(rng, (T, shp["hidden"]), 1.0, dtype)
+    gf = synth.quantize(1.0 + 0.1 * rng.standard_normal(shp["hidden"]).astype(np.float32), dtype)
+    Wlm = synth.normal(rng, (V, shp["hidden"]), 0.05, dtype)
+    labels = rng.integers(0, V, T).astype(np.int32)
+    labels[np.asarray(cu[1:]) - 1] = -1
+    Xf64, recs64 = stack_forward(osh, cu, None, X0.astype(np.float64), [f64(W) for W in Ws])
+    drecs = []
+    for r in recs64:
+        d = {k: to_dev(synth.quantize(r[k].astype(np.float32), dtype), dtype) for k in REC}
+        d["LSE"] = torch.from_numpy(r["LSE"].astype(np.float32)).cuda()
+        drecs.append(d)
+    shape, batch = alch_shape(shp, dtype), A.Batch(cu)
+    dWs = [{k: to_dev(v, dtype) for k, v in W.items()} for W in Ws]
+    Xf = to_dev(synth.quantize(Xf64.astype(np.float32), dtype), dtype)
+    args = (Xf, to_dev(gf, dtype), to_dev(Wlm, dtype), torch.from_numpy(labels).cuda())
+
+    direct = A.alch_stack_backward(shape, batch, drecs, dWs, *args)
+    torch.cuda.synchronize()
+
+    store = A.RecordStore(L, drecs[0])
+    for l in range(L):
+        store.offload(l, drecs[l])
+    torch.cuda.synchronize()
+    for l in range(L):
+        for k in store.keys:
+            assert torch.equal(store.host[l][k], drecs[l][k].cpu()), (l, k)
+    calls = []
+
+    def backward(saved, hooks):
+        ready, _ = hooks
+
+        def counting(user, l):
+            calls.append(l)
+            return ready(user, l)
+        return A.alch_stack_backward(shape, batch, saved, dWs, *args, hooks=(counting, None))
+
+    for rep in range(2):   # the second walk reuses the staging slots
+        calls.clear()
+        out = store.prefetching_backward(backward)
+        torch.cuda.synchronize()
+        assert calls == list(range(L - 1, -1, -1))
+        assert torch.equal(out["loss"], direct["loss"])
+        for k in ("dX_embed", "dg_final", "dW_lm"):
+            assert torch.equal(out[k], direct[k]), k
+        for l in range(L):
+            for k in direct["layers"][l]:
+                assert torch.equal(out["layers"][l][k], direct["layers"][l][k]), (l, k)
