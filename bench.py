@@ -290,6 +290,9 @@ def run_config4(args, torch, A):
     r = args.lora_rank
     wflops = 2.0 if args.frozen_base else 4.0   # GEMM flops per parameter and token
     mode = "full backward"
+    loss_mask = None
+    if args.loss_mask:
+        loss_mask = torch.from_numpy(synth.keep_mask(T, 0.25, 7)).to(dev)
     if r:
         # the paper's training setting (Section 6): rank-r adapters, here on all seven projections of every
         # layer; B = 0, the usual initialisation, so the records of the plain forward above are the adapted
@@ -307,7 +310,7 @@ def run_config4(args, torch, A):
 
         def backward(xf, rs, hooks=None):
             return A.alch_stack_backward_lora(shape, batch, rs, Ws, loras, r, 2.0, xf, g_final, W_lm, labels,
-                                              grads_layers=bgrads, want_head=not args.frozen_base,
+                                              loss_mask=loss_mask, grads_layers=bgrads, want_head=not args.frozen_base,
                                               lora_grads_layers=lgrads, hooks=hooks, workspace=ws)
     else:
         grads = [({} if args.frozen_base else {"d" + k: torch.empty_like(v) for k, v in W.items()}) for W in Ws]
@@ -316,8 +319,8 @@ def run_config4(args, torch, A):
             mode = "data gradients only (frozen base and head)"
 
         def backward(xf, rs, hooks=None):
-            return A.alch_stack_backward(shape, batch, rs, Ws, xf, g_final, W_lm, labels, grads_layers=grads,
-                                         want_head=not args.frozen_base, hooks=hooks, workspace=ws)
+            return A.alch_stack_backward(shape, batch, rs, Ws, xf, g_final, W_lm, labels, loss_mask=loss_mask,
+                                         grads_layers=grads, want_head=not args.frozen_base, hooks=hooks, workspace=ws)
 
     def timed(fn, steps, warmup):
         for _ in range(warmup):
@@ -330,6 +333,8 @@ def run_config4(args, torch, A):
         return (time.perf_counter() - t0) / steps, out
 
     offload = None
+    if args.loss_mask:
+        mode += ", loss on a Bernoulli(0.25) subset of the tokens (head and top layer run on the counted rows)"
     if args.offload:
         # Section 4.3: the records wait in pinned host memory; the walk prefetches them one layer ahead
         store = A.RecordStore(L, recs[0])
@@ -365,7 +370,15 @@ def run_config4(args, torch, A):
     achieved_tf = sum(r[1] for r in gm) / (gm_ms * 1e-3) / 1e12
     P = 2 * H * QD + 2 * H * KD + 3 * H * F
     head_flops = (4.0 if args.frozen_base else 6.0) * V * H   # logits + dHf (+ dW_lm)
-    flops = T * (L * wflops * P + head_flops) + L * 10.0 * shp["head_dim"] * shp["n_q_heads"] * B * S * (S + 1) / 2
+    gemm_flops = T * (L * wflops * P + head_flops)
+    if args.loss_mask:
+        # the head and the row-local products of the top layer run on the counted rows only (their launches are
+        # traced without flops because the row count lives on the device): count what the method must touch
+        n_cnt = int(((labels >= 0) & (loss_mask != 0)).sum().item())
+        p_rows = 3 * H * F + H * QD
+        gemm_flops = T * wflops * ((L - 1) * P + (P - p_rows)) + n_cnt * (wflops * p_rows + head_flops)
+        achieved_tf = gemm_flops / (gm_ms / n_traced_steps * 1e-3) / 1e12
+    flops = gemm_flops + L * 10.0 * shp["head_dim"] * shp["n_q_heads"] * B * S * (S + 1) / 2
     by = {}
     for kind, fl, nb, ms in trace:
         by[kind] = by.get(kind, 0.0) + ms

@@ -177,6 +177,11 @@ struct StackPlan {
     float* row_loss;
     int* n_counted;
     float* partial;
+    // loss-mask compaction of the head: counted-token mask, compacted Hf / labels / dHf, kept-row index and
+    // its inverse, {n, overflow}, rows per chunk, scratch of the mask scan
+    uint8_t* h_counted;
+    void *h_Hf, *h_dHf, *h_packws;
+    int *h_labels, *h_index, *h_inv, *h_cu, *h_n, *h_chunk_rows;
     size_t layer_ws_bytes, bytes;
 };
 static StackPlan plan_stack(const alch_layer_shape& s, int vocab, int T, void* ws, size_t ws_bytes, int lora_rank = 0) {
@@ -192,6 +197,16 @@ static StackPlan plan_stack(const alch_layer_shape& s, int vocab, int T, void* w
     p.row_loss = static_cast<float*>(a.take(t * sizeof(float)));
     p.n_counted = static_cast<int*>(a.take(256));
     p.partial = static_cast<float*>(a.take((size_t)rmsnorm_bwd_blocks(T) * H * sizeof(float)));
+    p.h_counted = static_cast<uint8_t*>(a.take(t));
+    p.h_Hf = a.take(t * H * E);
+    p.h_dHf = a.take(t * H * E);
+    p.h_packws = a.take(pack_workspace_bytes(T > 0 ? T : 1));
+    p.h_labels = static_cast<int*>(a.take(t * sizeof(int)));
+    p.h_index = static_cast<int*>(a.take(t * sizeof(int)));
+    p.h_inv = static_cast<int*>(a.take(t * sizeof(int)));
+    p.h_cu = static_cast<int*>(a.take(256));
+    p.h_n = static_cast<int*>(a.take(256));
+    p.h_chunk_rows = static_cast<int*>(a.take(((t + kHeadChunkRows - 1) / kHeadChunkRows) * sizeof(int)));
     p.layer_ws_bytes = plan_layer_bwd(s, T, nullptr, 0, lora_rank).bytes;
     p.layer_ws = a.take(p.layer_ws_bytes);
     p.bytes = round_up(a.used, 256);
@@ -738,25 +753,45 @@ static int stack_backward_impl(const alch_layer_shape* shape, int32_t n_layers, 
     const int T = batch->total_tokens, H = s.hidden;
     const int acc = wgrads ? (wgrads[0].accumulate != 0) : 0;
 
-    // LM head + cross-entropy in row chunks: logits -> dlogits in place, never stored whole
+    // LM head + cross-entropy in row chunks: logits -> dlogits in place, never stored whole.
+    // With a loss mask (bf16, matrix-core shapes) only the counted tokens -- label >= 0 and mask byte nonzero --
+    // go through the head: their Hf rows and labels are gathered, the three products and the cross-entropy
+    // take their row counts from device memory, and dHf is scattered back into a zero-filled [T, H].
+    const bool compact_head = loss_mask && T > 0 && dt == ALCH_BF16 && H % 64 == 0 && vocab % 64 == 0;
     ALCH_TRY(launch_count_labels(labels, loss_mask, T, p.n_counted, p.row_loss, st));
     ALCH_TRY(launch_rmsnorm_fwd(dt, X_final, g_final, p.Hf, T, H, s.rms_eps, st));
+    const void* head_in = p.Hf;
+    void* head_out = p.dHf;
+    const int* head_labels = labels;
+    const uint8_t* head_mask = loss_mask;
+    if (compact_head) {
+        ALCH_TRY(launch_counted_mask(labels, loss_mask, T, p.h_counted, st));
+        const alch_stream rows1[1] = {{p.Hf, p.h_Hf, (size_t)H * E, (size_t)H * E}};
+        ALCH_TRY(launch_pack(p.h_counted, T, batch->cu_seqlens, 0, 1, rows1, T, p.h_index, p.h_cu, p.h_n, p.h_packws, st, false));
+        ALCH_TRY(launch_gather_int(labels, p.h_index, p.h_n, p.h_labels, T, st));
+        ALCH_TRY(launch_rank_of_kept(p.h_index, p.h_n, p.h_inv, T, st));
+        ALCH_TRY(launch_chunk_rows(p.h_n, ceil_div(T, kHeadChunkRows), kHeadChunkRows, p.h_chunk_rows, st));
+        head_in = p.h_Hf; head_out = p.h_dHf; head_labels = p.h_labels; head_mask = nullptr;
+    }
     bool first = true;
     for (int r0 = 0; r0 < T; r0 += kHeadChunkRows) {
         const int rows = T - r0 < kHeadChunkRows ? T - r0 : kHeadChunkRows;
-        const void* hf = at(p.Hf, (size_t)r0 * H, E);
+        const int* rows_dev = compact_head ? p.h_chunk_rows + r0 / kHeadChunkRows : nullptr;
+        const void* hf = at(head_in, (size_t)r0 * H, E);
         {  // logits = Hf W_lm^T
             GemmDesc d = gemm(dt, rows, vocab, true, true);
             add_seg(d, hf, H, W_lm, H, H);
             add_out(d, p.logits, 0, vocab);
+            d.m_dev = rows_dev;
             ALCH_TRY(launch_gemm(d, st));
         }
-        ALCH_TRY(launch_ce_chunk(dt, p.logits, vocab, rows, vocab, labels + r0, loss_mask ? loss_mask + r0 : nullptr,
-                                 p.n_counted, p.row_loss + r0, st));
+        ALCH_TRY(launch_ce_chunk(dt, p.logits, vocab, rows, vocab, head_labels + r0, head_mask ? head_mask + r0 : nullptr,
+                                 p.n_counted, p.row_loss + r0, st, rows_dev));
         {  // dHf = dlogits W_lm
             GemmDesc d = gemm(dt, rows, H, true, false);
             add_seg(d, p.logits, vocab, W_lm, H, vocab);
-            add_out(d, at(p.dHf, (size_t)r0 * H, E), 0, H);
+            add_out(d, const_cast<char*>(at(head_out, (size_t)r0 * H, E)), 0, H);
+            d.m_dev = rows_dev;
             ALCH_TRY(launch_gemm(d, st));
         }
         if (dW_lm) {  // dW_lm (+)= dlogits^T Hf
@@ -764,10 +799,12 @@ static int stack_backward_impl(const alch_layer_shape* shape, int32_t n_layers, 
             add_seg(d, p.logits, vocab, hf, H, rows);
             add_out(d, dW_lm, 0, H);
             d.accumulate = first ? acc : 1;
+            d.k_dev = rows_dev;
             ALCH_TRY(launch_gemm(d, st));
         }
         first = false;
     }
+    if (compact_head) ALCH_TRY(launch_scatter_rows(p.h_dHf, p.h_inv, p.dHf, T, (size_t)H * E, st));
     if (T == 0 && dW_lm && !acc) {
         GemmDesc d = gemm(dt, vocab, H, false, false);  // zero rows contracted: writes zeros
         add_seg(d, p.logits, vocab, p.Hf, H, 0);
@@ -788,7 +825,10 @@ static int stack_backward_impl(const alch_layer_shape* shape, int32_t n_layers, 
         if (hooks && hooks->layer_ready && hooks->layer_ready(hooks->user, l) != 0)
             return fail(ALCH_ERR_ABORTED, "layer_ready hook failed for layer %d", l);
         void* out = l == 0 ? dX_embed : (cur == p.ping ? p.pong : p.ping);
-        ALCH_TRY(layer_backward_enqueue(s, *batch, saved[l], weights[l], cur, nullptr, out,
+        // the gradient entering the top layer is exactly zero in the rows the head did not count: that layer may
+        // compact its row-local part (lower layers see dense gradients: attention spreads them over earlier tokens)
+        const uint8_t* top_mask = (compact_head && l == n_layers - 1) ? p.h_counted : nullptr;
+        ALCH_TRY(layer_backward_enqueue(s, *batch, saved[l], weights[l], cur, top_mask, out,
                                         wgrads ? &wgrads[l] : nullptr, lp, st, lora ? &lora[l] : nullptr,
                                         lora_grads ? &lora_grads[l] : nullptr));
         cur = out;

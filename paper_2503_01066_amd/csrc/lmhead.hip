@@ -39,9 +39,11 @@ __global__ __launch_bounds__(256) void k_count_labels(const int* __restrict__ la
 template <typename T>
 __global__ __launch_bounds__(256) void k_ce_chunk(T* __restrict__ logits, long long ld, int vocab,
                                                   const int* __restrict__ labels, const uint8_t* __restrict__ mask,
-                                                  const int* __restrict__ n_counted, float* __restrict__ row_loss) {
+                                                  const int* __restrict__ n_counted, float* __restrict__ row_loss,
+                                                  const int* __restrict__ rows_dev) {
     __shared__ float red[4];
     const int r = blockIdx.x;
+    if (rows_dev && r >= *rows_dev) return;  // row count decided on the device (compacted rows)
     T* row = logits + (long long)r * ld;
     const int label = labels[r];
     const bool counted = label >= 0 && label < vocab && (!mask || mask[r] != 0);
@@ -83,9 +85,11 @@ __global__ __launch_bounds__(kCeThreads) void k_ce_chunk_bf16_row(__bf16* __rest
                                                                    const int* __restrict__ labels,
                                                                    const uint8_t* __restrict__ mask,
                                                                    const int* __restrict__ n_counted,
-                                                                   float* __restrict__ row_loss) {
+                                                                   float* __restrict__ row_loss,
+                                                                   const int* __restrict__ rows_dev) {
     __shared__ float red[kCeThreads / 64];
     const int r = blockIdx.x;
+    if (rows_dev && r >= *rows_dev) return;  // row count decided on the device (compacted rows)
     __bf16* row = logits + (long long)r * ld;
     const int label = labels[r];
     const bool counted = label >= 0 && label < vocab && (!mask || mask[r] != 0);
@@ -172,6 +176,45 @@ __global__ __launch_bounds__(256) void k_finish_loss(const float* __restrict__ r
     }
 }
 
+// counted[t] = 1 where the token contributes to the loss (label >= 0 and loss-mask byte nonzero)
+__global__ __launch_bounds__(256) void k_counted_mask(const int* __restrict__ labels, const uint8_t* __restrict__ mask,
+                                                      int T, uint8_t* __restrict__ counted) {
+    for (int t = blockIdx.x * 256 + threadIdx.x; t < T; t += gridDim.x * 256)
+        counted[t] = (labels[t] >= 0 && (!mask || mask[t] != 0)) ? 1 : 0;
+}
+// chunk_rows[c] = number of the n compacted rows that fall into row chunk c
+__global__ void k_chunk_rows(const int* __restrict__ n_rows, int n_chunks, int chunk, int* __restrict__ chunk_rows) {
+    const int n = n_rows[0];
+    for (int c = threadIdx.x; c < n_chunks; c += blockDim.x) {
+        const int left = n - c * chunk;
+        chunk_rows[c] = left < 0 ? 0 : (left > chunk ? chunk : left);
+    }
+}
+// dst[r] = src[index[r]] for r < *n_rows
+__global__ __launch_bounds__(256) void k_gather_int(const int* __restrict__ src, const int* __restrict__ index,
+                                                    const int* __restrict__ n_rows, int* __restrict__ dst, int T) {
+    const int n = min(n_rows[0], T);
+    for (int r = blockIdx.x * 256 + threadIdx.x; r < n; r += gridDim.x * 256) dst[r] = src[index[r]];
+}
+int launch_gather_int(const int* src, const int* index, const int* n_rows, int* dst, int T, hipStream_t stream) {
+    if (T <= 0) return ALCH_OK;
+    k_gather_int<<<ceil_div(T, 256) < 1024 ? ceil_div(T, 256) : 1024, 256, 0, stream>>>(src, index, n_rows, dst, T);
+    ALCH_HIP_TRY(hipGetLastError());
+    return ALCH_OK;
+}
+int launch_counted_mask(const int* labels, const uint8_t* loss_mask, int T, uint8_t* counted, hipStream_t stream) {
+    if (T <= 0) return ALCH_OK;
+    k_counted_mask<<<ceil_div(T, 256) < 1024 ? ceil_div(T, 256) : 1024, 256, 0, stream>>>(labels, loss_mask, T, counted);
+    ALCH_HIP_TRY(hipGetLastError());
+    return ALCH_OK;
+}
+int launch_chunk_rows(const int* n_rows, int n_chunks, int chunk, int* chunk_rows, hipStream_t stream) {
+    if (n_chunks <= 0) return ALCH_OK;
+    k_chunk_rows<<<1, 64, 0, stream>>>(n_rows, n_chunks, chunk, chunk_rows);
+    ALCH_HIP_TRY(hipGetLastError());
+    return ALCH_OK;
+}
+
 int launch_count_labels(const int* labels, const uint8_t* loss_mask, int T, int* n_counted, float* row_loss,
                         hipStream_t stream) {
     k_count_labels<<<1, 256, 0, stream>>>(labels, loss_mask, T, n_counted, row_loss);
@@ -180,14 +223,15 @@ int launch_count_labels(const int* labels, const uint8_t* loss_mask, int T, int*
 }
 
 int launch_ce_chunk(alch_dtype dt, void* logits, long long ld, int rows, int vocab, const int* labels,
-                    const uint8_t* loss_mask, const int* n_counted, float* row_loss, hipStream_t stream) {
+                    const uint8_t* loss_mask, const int* n_counted, float* row_loss, hipStream_t stream,
+                    const int* rows_dev) {
     if (rows <= 0) return ALCH_OK;
     if (dt == ALCH_BF16 && vocab % 8 == 0 && ld % 8 == 0 && vocab <= kCeThreads * kCeChunks * 8 && aligned16(logits))
-        k_ce_chunk_bf16_row<<<rows, kCeThreads, 0, stream>>>((__bf16*)logits, ld, vocab, labels, loss_mask, n_counted, row_loss);
+        k_ce_chunk_bf16_row<<<rows, kCeThreads, 0, stream>>>((__bf16*)logits, ld, vocab, labels, loss_mask, n_counted, row_loss, rows_dev);
     else if (dt == ALCH_BF16)
-        k_ce_chunk<__bf16><<<rows, 256, 0, stream>>>((__bf16*)logits, ld, vocab, labels, loss_mask, n_counted, row_loss);
+        k_ce_chunk<__bf16><<<rows, 256, 0, stream>>>((__bf16*)logits, ld, vocab, labels, loss_mask, n_counted, row_loss, rows_dev);
     else
-        k_ce_chunk<float><<<rows, 256, 0, stream>>>((float*)logits, ld, vocab, labels, loss_mask, n_counted, row_loss);
+        k_ce_chunk<float><<<rows, 256, 0, stream>>>((float*)logits, ld, vocab, labels, loss_mask, n_counted, row_loss, rows_dev);
     ALCH_HIP_TRY(hipGetLastError());
     return ALCH_OK;
 }

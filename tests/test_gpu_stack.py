@@ -126,3 +126,23 @@ def test_layer_forward_and_reuse_equals_recompute(dtype, shape_name, lens, wstd)
     torch.cuda.synchronize()
     for k, v in out.items():
         assert rel_err(to_np(v), ref[k]) <= (tol if dtype == "f32" else 3e-2), k
+
+
+@pytest.mark.parametrize("keep", [0.0, 0.3])
+def test_stack_loss_mask_compacts_head_and_top_layer(keep):
+    # bf16 with a loss mask: only counted tokens go through the LM head (two row chunks here: T > 8192) and the top
+    # layer runs its row-local part on them; the result must equal the oracle's dense definition
+    cu = synth.ragged_cu([3000, 2500, 3500])
+    L, V = 1, 1024
+    shp, osh, Ws, recs, Xf, gf, Wlm, labels = make_stack("medium", "bf16", cu, L, V, 11, 0.05)
+    T = int(cu[-1])
+    mask = synth.keep_mask(T, keep, 2)
+    ref = stack_backward_reuse(osh, cu, None, [f64(r) for r in recs], [f64(W) for W in Ws], Xf.astype(np.float64),
+                               gf.astype(np.float64), Wlm.astype(np.float64), labels, mask)
+    out = run_stack(shp, "bf16", cu, Ws, recs, Xf, gf, Wlm, labels, mask)
+    if keep == 0.0:
+        assert out["loss"].item() == 0.0
+        for k in ("dX_embed", "dg_final", "dW_lm"):
+            assert float(out[k].abs().max()) == 0.0, k
+    else:
+        check_stack(out, ref, "bf16", L)
