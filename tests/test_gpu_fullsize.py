@@ -150,3 +150,67 @@ def test_llama70b_width_short_batch_elementwise_with_loss_mask():
     for k, v in out.items():
         e = rel_err(to_np(v), ref[k])
         assert e <= 2e-2, (k, e)
+
+
+def test_config2_full_size_adapter_mode_sampled_outputs():
+    # the paper's training setting at the size bench.py times (frozen 8B-shaped base, rank-8 adapters on all seven
+    # projections, 4 x 2048 tokens): dX rows by causality at the merged weights, sampled adapter-gradient entries
+    # from their definitions
+    import paper_2503_01066_amd as A
+    from oracle.lora import merged_weights
+    shp = synth.shape_dict("llama8b")
+    osh = oracle_shape(shp)
+    S, B, r, scale = 2048, 4, 8, 2.0
+    cu = synth.uniform_cu(B, S)
+    T = B * S
+    H, F = shp["hidden"], shp["ffn"]
+    W = synth.layer_weights(shp, 0, "bf16")
+    lora = synth.lora_adapters(shp, r, 5, "bf16", std=0.05)
+    rec = synth.drawn_record(shp, T, 1, "bf16")
+    print("lse ...", flush=True)
+    rec["LSE"] = attention_lse(osh, cu, rec["Q"].astype(np.float64), rec["K"].astype(np.float64)).astype(np.float32)
+    dY = synth.activations(T, H, 2, "bf16", std=0.01)
+    print("gpu ...", flush=True)
+    drec = {k: to_dev(rec[k], "bf16") for k in REC}
+    drec["LSE"] = torch.from_numpy(rec["LSE"]).cuda()
+    out = A.alch_layer_backward_lora(alch_shape(shp, "bf16"), A.Batch(cu), drec, {k: to_dev(v, "bf16") for k, v in W.items()},
+                                     {p: (to_dev(a, "bf16"), to_dev(b, "bf16")) for p, (a, b) in lora.items()}, r, scale,
+                                     to_dev(dY, "bf16"))
+    torch.cuda.synchronize()
+    lora64 = {p: (a.astype(np.float64), b.astype(np.float64)) for p, (a, b) in lora.items()}
+    Wm = merged_weights(f64(W), lora64, scale)
+    rng = np.random.default_rng(4)
+
+    # (a) dX rows of the last tokens of a sequence (exact by causality), merged weights
+    m = 16
+    dX = to_np(out["dX"])
+    a, b = 2 * S, 3 * S
+    seq = {k: rec[k][a:b].astype(np.float64) for k in REC + ("LSE",)}
+    tail = layer_backward_reuse_tail_rows(osh, None, seq, Wm, dY[b - m:b].astype(np.float64))
+    e = np.abs(dX[b - m:b] - tail).max() / np.abs(tail).max()
+    assert e <= 2e-2, ("dX tail", e)
+
+    # (b) down-projection adapter: dB_d = s dY^T (Act A_d^T), dA_d = s (dY B_d)^T Act, all entries of the small matrices
+    G64, U64, dY64 = rec["G"].astype(np.float64), rec["U"].astype(np.float64), dY.astype(np.float64)
+    Act = G64 * _sigmoid(G64) * U64
+    Ad, Bd = lora64["d"]
+    want_dB = scale * dY64.T @ (Act @ Ad.T)
+    want_dA = scale * (dY64 @ Bd).T @ Act
+    assert rel_err(to_np(out["dBd"]), want_dB) <= 2e-2
+    assert rel_err(to_np(out["dAd"]), want_dA) <= 2e-2
+
+    # (c) gate adapter, sampled columns f: dG[:, f] from dAct[:, f] = dY Wd'[:, f]; dB_g[f, :] = s dG[:, f]^T (H2 A_g^T)
+    H2, _ = _rms_norm(rec["X2"].astype(np.float64), Wm["g2"], osh.rms_eps)
+    Ag, Bg = lora64["g"]
+    t1 = scale * (H2 @ Ag.T)
+    dBg = to_np(out["dBg"])
+    ff = rng.integers(0, F, 10)
+    want = []
+    for f in ff:
+        dAct = dY64 @ Wm["Wd"][:, f]
+        sg = _sigmoid(G64[:, f])
+        want.append((dAct * U64[:, f] * sg * (1 + G64[:, f] * (1 - sg))) @ t1)
+    want = np.array(want)
+    assert np.abs(dBg[ff] - want).max() <= 2e-2 * max(np.abs(want).max(), np.abs(dBg).max())
+    for k, v in out.items():
+        assert torch.isfinite(v.float()).all(), k
