@@ -299,6 +299,109 @@ static int rmsnorm_bwd_t(const void* dH, const void* X, const void* g, const voi
     return ALCH_OK;
 }
 
+// Wide rows (width > 2048): WPR wavefronts share a row, each owning a quarter or half of its columns (4 chunks of
+// 8 per lane), so the per-lane state stays small enough for several wavefronts per SIMD; the two row sums meet
+// through LDS in wavefront order.  Every wavefront runs the same number of iterations (barriers inside).
+template <int WPR>
+__global__ __launch_bounds__(256) void k_rmsnorm_bwd_bf16_split(const __bf16* __restrict__ dH, const __bf16* __restrict__ X,
+                                                                const __bf16* __restrict__ g, const __bf16* __restrict__ resid,
+                                                                const uint8_t* __restrict__ resid_mask,
+                                                                __bf16* __restrict__ dX, float* __restrict__ partial,
+                                                                int Trows, int width, float eps,
+                                                                const int* __restrict__ rows_dev) {
+    constexpr int RPB = 4 / WPR;  // rows per work-group per iteration
+    __shared__ float rsum[2][4][2];
+    __shared__ float sred[2 * 4 * 8 * 64];  // [part][chunk][element][lane], used when two rows share a work-group
+    if (rows_dev) Trows = min(Trows, *rows_dev);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int part = wave % WPR, rsel = wave / WPR;
+    bf16x8_t gv[4];
+    float dgp[4][8];
+    int col[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        col[k] = ((k * WPR + part) * 64 + lane) * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { gv[k][e] = (__bf16)0.f; dgp[k][e] = 0.f; }
+        if (col[k] < width) gv[k] = *reinterpret_cast<const bf16x8_t*>(g + col[k]);
+    }
+    const float inv_w = 1.f / (float)width;
+    const long long stride = (long long)gridDim.x * RPB;
+    const int iters = (int)((Trows + stride - 1) / stride);
+    for (int it = 0; it < iters; ++it) {
+        const long long row = (long long)it * stride + (long long)blockIdx.x * RPB + rsel;
+        const bool live = row < Trows;
+        const bool keep = live && resid && !(resid_mask && resid_mask[row] == 0);
+        bf16x8_t xv[4], dv[4], rv[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { xv[k][e] = (__bf16)0.f; dv[k][e] = (__bf16)0.f; rv[k][e] = (__bf16)0.f; }
+            if (live && col[k] < width) {
+                xv[k] = *reinterpret_cast<const bf16x8_t*>(X + row * width + col[k]);
+                dv[k] = *reinterpret_cast<const bf16x8_t*>(dH + row * width + col[k]);
+                if (keep) rv[k] = *reinterpret_cast<const bf16x8_t*>(resid + row * width + col[k]);
+            }
+        }
+        float ss = 0.f, dot = 0.f;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float x = (float)xv[k][e];
+                ss += x * x;
+                dot += (float)gv[k][e] * (float)dv[k][e] * x;
+            }
+        ss = wave_sum(ss);
+        dot = wave_sum(dot);
+        if (WPR > 1) {
+            if (lane == 0) { rsum[it & 1][wave][0] = ss; rsum[it & 1][wave][1] = dot; }
+            __syncthreads();
+            ss = 0.f; dot = 0.f;
+#pragma unroll
+            for (int w = 0; w < WPR; ++w) { ss += rsum[it & 1][rsel * WPR + w][0]; dot += rsum[it & 1][rsel * WPR + w][1]; }
+        }
+        const float r = rsqrtf(ss * inv_w + eps);
+        const float coef = r * r * r * inv_w * dot;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (live && col[k] < width) {
+                bf16x8_t ov;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float x = (float)xv[k][e], d = (float)dv[k][e];
+                    const float v = r * (float)gv[k][e] * d - x * coef + (float)rv[k][e];
+                    ov[e] = (__bf16)v;
+                    dgp[k][e] += d * x * r;
+                }
+                *reinterpret_cast<bf16x8_t*>(dX + row * width + col[k]) = ov;
+            }
+        }
+    }
+    if (!partial) return;
+    // column sums: the RPB wavefronts that own the same columns fold theirs in a fixed order
+    for (int rs = 1; rs < RPB; ++rs) {
+        __syncthreads();
+        if (rsel == rs)
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) sred[((part * 4 + k) * 8 + e) * 64 + lane] = dgp[k][e];
+        __syncthreads();
+        if (rsel == 0)
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dgp[k][e] += sred[((part * 4 + k) * 8 + e) * 64 + lane];
+    }
+    if (rsel == 0)
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (col[k] < width)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) partial[(long long)blockIdx.x * width + col[k] + e] = dgp[k][e];
+}
+
 static int rmsnorm_bwd_bf16_fast(const void* dH, const void* X, const void* g, const void* resid,
                                  const uint8_t* resid_mask, void* dX, void* dg, int accumulate, float* partial, int T_,
                                  int width, float eps, hipStream_t stream, const int* rows_dev) {
@@ -307,11 +410,15 @@ static int rmsnorm_bwd_bf16_fast(const void* dH, const void* X, const void* g, c
 #define ALCH_NORM_BWD(NC)                                                                                          \
     k_rmsnorm_bwd_bf16<NC><<<nblk, 256, 0, stream>>>((const __bf16*)dH, (const __bf16*)X, (const __bf16*)g,         \
                                                      (const __bf16*)resid, resid_mask, (__bf16*)dX, part, T_, width, eps, rows_dev)
+#define ALCH_NORM_BWD_SPLIT(WPR)                                                                                    \
+    k_rmsnorm_bwd_bf16_split<WPR><<<nblk, 256, 0, stream>>>((const __bf16*)dH, (const __bf16*)X, (const __bf16*)g,  \
+                                                            (const __bf16*)resid, resid_mask, (__bf16*)dX, part, T_, width, eps, rows_dev)
     if (width <= 1024) ALCH_NORM_BWD(2);
     else if (width <= 2048) ALCH_NORM_BWD(4);
-    else if (width <= 4096) ALCH_NORM_BWD(8);
-    else ALCH_NORM_BWD(16);
+    else if (width <= 4096) ALCH_NORM_BWD_SPLIT(2);
+    else ALCH_NORM_BWD_SPLIT(4);
 #undef ALCH_NORM_BWD
+#undef ALCH_NORM_BWD_SPLIT
     if (dg) k_colsum_finish_wide<__bf16><<<ceil_div(width, 64), 1024, 0, stream>>>(partial, nblk, width, (__bf16*)dg, accumulate);
     ALCH_HIP_TRY(hipGetLastError());
     return ALCH_OK;
