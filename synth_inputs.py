@@ -16,6 +16,7 @@ SHAPES = {
     "medium64": (384, 6, 3, 64, 1024, 1e-5, 10000.0),
     "llama8b":  (4096, 32, 8, 128, 14336, 1e-5, 500000.0),
     "llama70b": (8192, 64, 8, 128, 28672, 1e-5, 500000.0),
+    "phi4":     (5120, 40, 10, 128, 17920, 1e-5, 250000.0),   # the third model of the paper's evaluation (Section 6)
 }
 SHAPE_FIELDS = ("hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn", "rms_eps", "rope_base")
 

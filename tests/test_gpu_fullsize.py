@@ -24,9 +24,11 @@ def gpu_layer(shp, cu, W, rec, dY):
     return out
 
 
-def test_llama8b_width_short_batch_elementwise():
-    # every GEMM dimension at its real width (hidden 4096, ffn 14336, 32/8 heads x 128), ragged short batch
-    shp = synth.shape_dict("llama8b")
+@pytest.mark.parametrize("shape_name", ["llama8b", "phi4"])
+def test_real_layer_width_short_batch_elementwise(shape_name):
+    # every GEMM dimension at its real width (Llama-3-8B / Mistral-7B: hidden 4096, ffn 14336, 32/8 heads x 128;
+    # Phi-4: hidden 5120, ffn 17920, 40/10 heads x 128 -- tile counts that are not powers of two), ragged short batch
+    shp = synth.shape_dict(shape_name)
     osh = oracle_shape(shp)
     cu = synth.ragged_cu([150, 41, 129])
     T = int(cu[-1])
