@@ -231,8 +231,11 @@ def complete_record(shape, cu_seqlens, rec, W):
     """The six-tensor record {X, Q, K, V, G, U} (the tensors the capture step is asked to pack in
     the paper's setting, Section 4.1 / Section 5: layer input, KV cache, query, MLP pre-activations)
     completed to the full record: O and LSE by running causal grouped-query attention on the saved
-    post-RoPE Q, K, V, then X2 = X + O Wo^T.  Tensors already present in `rec` are kept as given.
-    (The decision between loading a saved tensor and recomputing it is the hedging of Section 4.3.2.)"""
+    post-RoPE Q, K, V, then X2 = X + O Wo^T.  The four-tensor record {X, Q, K, V} (layer input, query and
+    KV cache alone) is completed further: G = H2 Wg^T, U = H2 Wu^T with H2 the RMS-normalised X2 under gain
+    g2, the forward's own definition of the MLP pre-activations.  Tensors already present in `rec` are kept
+    as given.  (The decision between loading a saved tensor and recomputing it is the hedging of
+    Section 4.3.2.)"""
     out = {k: np.asarray(v, dtype=np.float64) for k, v in rec.items() if v is not None}
     T = out["X"].shape[0]
     Hq, Hkv, D = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
@@ -254,6 +257,12 @@ def complete_record(shape, cu_seqlens, rec, W):
         out["O"], out["LSE"] = O.reshape(T, Hq * D), LSE
     if "X2" not in out:
         out["X2"] = out["X"] + out["O"] @ np.asarray(W["Wo"], dtype=np.float64).T
+    if "G" not in out or "U" not in out:
+        H2, _ = _rms_norm(out["X2"], np.asarray(W["g2"], dtype=np.float64), shape.rms_eps)
+        if "G" not in out:
+            out["G"] = H2 @ np.asarray(W["Wg"], dtype=np.float64).T
+        if "U" not in out:
+            out["U"] = H2 @ np.asarray(W["Wu"], dtype=np.float64).T
     return out
 
 

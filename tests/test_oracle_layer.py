@@ -263,6 +263,13 @@ def test_complete_record_restores_the_dropped_tensors():
     full = complete_record(shape, cu, six, W)
     for k in RECORD_KEYS:
         np.testing.assert_allclose(full[k], rec[k], rtol=1e-12, atol=1e-12, err_msg=k)
+    # layer input, query and KV cache alone: the MLP pre-activations come back too
+    four = complete_record(shape, cu, {k: rec[k] for k in ("X", "Q", "K", "V")}, W)
+    for k in RECORD_KEYS:
+        np.testing.assert_allclose(four[k], rec[k], rtol=1e-12, atol=1e-12, err_msg=k)
+    # a wrong gain or a swapped gate/up weight is visible: the completed tensors differ from the forward's
+    swapped = complete_record(shape, cu, {k: rec[k] for k in ("X", "Q", "K", "V")}, dict(W, Wg=W["Wu"], Wu=W["Wg"]))
+    assert np.max(np.abs(swapped["G"] - rec["G"])) > 1e-3
     marked = dict(six, X2=rec["X2"] + 1.0)
     assert np.array_equal(complete_record(shape, cu, marked, W)["X2"], rec["X2"] + 1.0)
     g_full = layer_backward_reuse(shape, cu, None, rec, W, R)
