@@ -43,7 +43,9 @@ def parse():
     ap.add_argument("--offload", action="store_true",
                     help="config4: records live in pinned host memory and are prefetched layer by layer during the walk")
     ap.add_argument("--six-stream", action="store_true",
-                    help="config2/config5: pack only X, Q, K, V, G, U; the backward recomputes O, LSE and X2")
+                    help="pack / keep only X, Q, K, V, G, U; the backward recomputes O, LSE and X2")
+    ap.add_argument("--four-stream", action="store_true",
+                    help="pack / keep only X, Q, K, V; the backward recomputes O, LSE, X2, G and U")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
                     help="measured HBM bytes per launch (from the rocprofv3 --pmc summaries)")
@@ -161,6 +163,9 @@ def run_layer(args, torch, A):
     if args.six_stream:
         keys = ["X", "Q", "K", "V", "G", "U"]
         descr += ", six-stream record (O, LSE, X2 recomputed by the backward)"
+    if args.four_stream:
+        keys = ["X", "Q", "K", "V"]
+        descr += ", four-stream record (O, LSE, X2, G, U recomputed by the backward)"
     dst = {k: torch.empty((T, src[k].shape[1]), dtype=src[k].dtype, device=dev) for k in keys}
     src_batch = A.Batch(synth.uniform_cu(n_src, S))
     kept_batch = A.Batch(synth.uniform_cu(n_keep, S))
@@ -335,6 +340,12 @@ def run_config4(args, torch, A):
         return (time.perf_counter() - t0) / steps, out
 
     offload = None
+    if args.six_stream or args.four_stream:
+        # Section 4.3.2, per tensor: what is cheap to recompute is not kept (and, with --offload, not transferred)
+        keep = ("X", "Q", "K", "V", "G", "U") if args.six_stream else ("X", "Q", "K", "V")
+        recs = [{k: rec[k] for k in keep} for rec in recs]
+        torch.cuda.empty_cache()
+        mode += ", records hold %s only (the rest is recomputed by the backward)" % ", ".join(keep)
     if args.loss_mask:
         mode += ", loss on a Bernoulli(0.25) subset of the tokens (head and top layer run on the counted rows)"
     if args.offload:

@@ -136,7 +136,10 @@ size_t alch_capture_pack_workspace_bytes(int32_t total_tokens);
  * was produced under: gradients from a record are only valid at those weights.
  * X2, O and LSE may be NULL (a record of the six streams X, Q, K, V, G, U): the backward calls then
  * recompute O and LSE by an attention forward on the saved Q, K, V and X2 = X + O Wo^T, the
- * recompute-instead-of-load choice of Section 4.3.2. */
+ * recompute-instead-of-load choice of Section 4.3.2.  G and U may be NULL as well (a record of the
+ * layer input, the query and the KV cache alone): they are recomputed as H2 Wg^T and H2 Wu^T from
+ * the normalised X2, on the kept rows only under a loss mask.  Not supported for a projection that
+ * carries an adapter (ALCH_ERR_UNSUPPORTED). */
 typedef struct {
     const void *X, *X2, *Q, *K, *V, *O, *G, *U;
     const float* LSE;

@@ -239,8 +239,8 @@ static int check_saved_weights(const alch_saved* sv, const alch_weights* w, int 
     if (!sv || !w) return fail(ALCH_ERR_INVALID_ARG, "saved / weights is NULL");
     REQUIRE_ACT(sv->X, "saved.X", T); REQUIRE_ACT(sv->Q, "saved.Q", T);
     REQUIRE_ACT(sv->K, "saved.K", T); REQUIRE_ACT(sv->V, "saved.V", T);
-    REQUIRE_ACT(sv->G, "saved.G", T); REQUIRE_ACT(sv->U, "saved.U", T);
-    // X2, O and LSE may be NULL: they are then recomputed from the rest of the record
+    // X2, O, LSE, G and U may be NULL: they are then recomputed from the rest of the record
+    OPTIONAL_PTR(sv->G, "saved.G"); OPTIONAL_PTR(sv->U, "saved.U");
     OPTIONAL_PTR(sv->X2, "saved.X2"); OPTIONAL_PTR(sv->O, "saved.O"); OPTIONAL_PTR(sv->LSE, "saved.LSE");
     REQUIRE_PTR(w->Wq, "weights.Wq"); REQUIRE_PTR(w->Wk, "weights.Wk"); REQUIRE_PTR(w->Wv, "weights.Wv");
     REQUIRE_PTR(w->Wo, "weights.Wo"); REQUIRE_PTR(w->Wg, "weights.Wg"); REQUIRE_PTR(w->Wu, "weights.Wu");
@@ -290,6 +290,29 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
         ALCH_TRY(launch_gemm(d, st));
         sv.X2 = p.X2_re;
     }
+    // A record without G / U: the MLP pre-activations are H2 Wg^T, H2 Wu^T with H2 the normalised X2, computed
+    // below on the rows the MLP backward will read (all T, or the kept rows under a loss mask).
+    const bool re_gu = T > 0 && (!sv.G || !sv.U);
+    if (re_gu && lo && (lo->A[ALCH_PROJ_G] || lo->A[ALCH_PROJ_U]))
+        return fail(ALCH_ERR_UNSUPPORTED, "saved.G and saved.U must be given when the gate or up projection carries an adapter");
+    bool hn_ready = false;  // p.Hn already holds the normalised X2 rows
+    auto recompute_gu = [&](const void* x2, const int* rows_dev) -> int {
+        ALCH_TRY(launch_rmsnorm_fwd(dt, x2, w.g2, p.Hn, T, H, s.rms_eps, st, rows_dev));
+        hn_ready = true;
+        const void* Wm[2] = {w.Wg, w.Wu};
+        void* om[2] = {p.c_G, p.c_U};
+        const void* have[2] = {sv.G, sv.U};
+        for (int i = 0; i < 2; ++i) {
+            if (have[i]) continue;
+            GemmDesc d;
+            d.M = T; d.N = F; d.a_kmajor = true; d.b_kmajor = true; d.dtype = dt;
+            d.m_dev = rows_dev;
+            d.seg[d.n_seg++] = GemmSeg{p.Hn, Wm[i], H, H, H};
+            d.out[d.n_out++] = GemmOut{om[i], 0, F};
+            ALCH_TRY(launch_gemm(d, st));
+        }
+        return ALCH_OK;
+    };
     const int acc = wg ? (wg->accumulate != 0) : 0;
     static const alch_wgrads none = {};
     const alch_wgrads& g = wg ? *wg : none;
@@ -358,18 +381,28 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
     void *mdX2 = p.dX2, *mdO = p.dO;                                      // its outputs
     const int* ndev = nullptr;                                              // device-resident row count
     if (compact) {
-        const alch_stream rows5[5] = {{dY, p.c_dY, (size_t)H * E, (size_t)H * E}, {sv.X2, p.c_X2, (size_t)H * E, (size_t)H * E},
-                                      {sv.O, p.c_O, (size_t)QD * E, (size_t)QD * E}, {sv.G, p.c_G, (size_t)F * E, (size_t)F * E},
-                                      {sv.U, p.c_U, (size_t)F * E, (size_t)F * E}};
+        alch_stream rows[5] = {{dY, p.c_dY, (size_t)H * E, (size_t)H * E}, {sv.X2, p.c_X2, (size_t)H * E, (size_t)H * E},
+                               {sv.O, p.c_O, (size_t)QD * E, (size_t)QD * E}};
+        int n_rows = 3;
+        if (sv.G) rows[n_rows++] = alch_stream{sv.G, p.c_G, (size_t)F * E, (size_t)F * E};
+        if (sv.U) rows[n_rows++] = alch_stream{sv.U, p.c_U, (size_t)F * E, (size_t)F * E};
         // (per-sequence counts are not needed: zero sequences asked for, one boundary written)
-        ALCH_TRY(launch_pack(loss_mask, T, b.cu_seqlens, 0, 5, rows5, T, p.c_index, p.c_cu, p.c_n, p.c_packws, st, false));
+        ALCH_TRY(launch_pack(loss_mask, T, b.cu_seqlens, 0, n_rows, rows, T, p.c_index, p.c_cu, p.c_n, p.c_packws, st, false));
         ALCH_TRY(launch_rank_of_kept(p.c_index, p.c_n, p.c_inv, T, st));
         mY = p.c_dY; mX2 = p.c_X2; mO = p.c_O; mG = p.c_G; mU = p.c_U;
         mdX2 = p.c_dX2; mdO = p.c_dO;
         ndev = p.c_n;
-    } else if (loss_mask) {
-        ALCH_TRY(launch_masked_copy(dt, dY, loss_mask, p.dYm, T, H, st));
-        mY = p.dYm;
+        if (re_gu) ALCH_TRY(recompute_gu(mX2, ndev));
+    } else {
+        if (loss_mask) {
+            ALCH_TRY(launch_masked_copy(dt, dY, loss_mask, p.dYm, T, H, st));
+            mY = p.dYm;
+        }
+        if (re_gu) {
+            ALCH_TRY(recompute_gu(sv.X2, nullptr));
+            if (!sv.G) mG = p.c_G;
+            if (!sv.U) mU = p.c_U;
+        }
     }
 
     // MLP down projection: dAct = dY Wd, fused with the SwiGLU gradient -> [dG | dU] and Act
@@ -413,7 +446,7 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
         add_out(d, p.dHn, 0, H);
         ALCH_TRY(launch_gemm(d, st));
     }
-    if (g.dWg || g.dWu || wants(ALCH_PROJ_G) || wants(ALCH_PROJ_U))
+    if (!hn_ready && (g.dWg || g.dWu || wants(ALCH_PROJ_G) || wants(ALCH_PROJ_U)))
         ALCH_TRY(launch_rmsnorm_fwd(dt, mX2, w.g2, p.Hn, T, H, s.rms_eps, st, ndev));
     ALCH_TRY(adapter_grads(ALCH_PROJ_G, 0, p.Hn, H, H, p.dGU, 2 * (long long)F, F));
     ALCH_TRY(adapter_grads(ALCH_PROJ_U, 1, p.Hn, H, H, at(p.dGU, F, E), 2 * (long long)F, F));

@@ -176,7 +176,10 @@ def test_six_stream_record_passes_validation_but_missing_required_tensors_do_not
     # the workspace check (-3) before anything is launched
     six = B.CSaved(P, None, P, P, P, None, P, P, None, 0)
     assert L.alch_layer_backward(C.byref(s), C.byref(b), C.byref(six), C.byref(w), P, None, P, C.byref(g), P, 1024, None) == -3
-    for missing in (0, 2, 3, 4, 6, 7):  # X, Q, K, V, G, U are required
+    # layer input, query and KV cache alone: G and U may be NULL too
+    four = B.CSaved(P, None, P, P, P, None, None, None, None, 0)
+    assert L.alch_layer_backward(C.byref(s), C.byref(b), C.byref(four), C.byref(w), P, None, P, C.byref(g), P, 1024, None) == -3
+    for missing in (0, 2, 3, 4):  # X, Q, K, V are required
         ptrs = [P] * 9
         ptrs[missing] = None
         sv = B.CSaved(*ptrs, 0)

@@ -148,6 +148,32 @@ def test_six_stream_record_is_completed_on_the_device(dtype, shape_name, lens):
     compare({k: to_np(v) for k, v in out2.items()}, ref2, dtype)
 
 
+@pytest.mark.parametrize("dtype,shape_name,lens,keep", [("f32", "tiny", [1, 5, 0, 8, 3], None), ("bf16", "medium", [300, 1, 257, 64], None),
+                                                        ("bf16", "medium", [300, 1, 257, 64], 0.3), ("f32", "tiny", [4, 9], 0.5),
+                                                        ("bf16", "medium64", [130, 200, 77], None)])
+def test_four_stream_record_is_completed_on_the_device(dtype, shape_name, lens, keep):
+    # layer input, query and KV cache alone (X, Q, K, V): O, LSE, X2 and the MLP pre-activations G, U are
+    # recomputed by the library -- on the kept rows only when a loss mask compacts the row-local part;
+    # the oracle completes the same rounded four tensors in fp64
+    from oracle import complete_record
+    import paper_2503_01066_amd as A
+    cu = synth.ragged_cu(lens)
+    shp, osh, W, rec, dY = make_case(shape_name, dtype, cu, 23, "forward", wstd=0.3 if shape_name == "tiny" else 0.02,
+                                     dy_std=1.0 if dtype == "f32" else 0.01)
+    T = int(cu[-1])
+    mask = None if keep is None else synth.keep_mask(T, keep, 5)
+    Wd_ = {k: to_dev(v, dtype) for k, v in W.items()}
+    for keys in (("X", "Q", "K", "V"), ("X", "Q", "K", "V", "U"), ("X", "X2", "Q", "K", "V", "O", "LSE", "G")):
+        part = {k: rec[k] for k in keys}
+        full = complete_record(osh, cu, {k: np.asarray(v, dtype=np.float64) for k, v in part.items()}, f64(W))
+        ref = layer_backward_reuse(osh, cu, None, full, f64(W), dY, mask)
+        d = {k: (torch.from_numpy(v).cuda() if k == "LSE" else to_dev(v, dtype)) for k, v in part.items()}
+        out = A.alch_layer_backward(alch_shape(shp, dtype), A.Batch(cu), d, Wd_, to_dev(dY, dtype),
+                                    loss_mask=None if mask is None else torch.from_numpy(mask).cuda())
+        torch.cuda.synchronize()
+        compare({k: to_np(v) for k, v in out.items()}, ref, dtype)
+
+
 @pytest.mark.parametrize("keep", [0.0, 0.3, 1.0])
 def test_loss_mask_row_compaction_bf16(keep):
     # bf16 with a loss mask runs the row-local part on the kept rows only (row count on the device);

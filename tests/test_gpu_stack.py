@@ -44,8 +44,9 @@ def run_stack(shp, dtype, cu, Ws, recs, Xf, gf, Wlm, labels, mask=None, hooks=No
     dWs = [{k: to_dev(v, dtype) for k, v in W.items()} for W in Ws]
     drecs = []
     for r in recs:
-        d = {k: to_dev(r[k], dtype) for k in REC}
-        d["LSE"] = torch.from_numpy(r["LSE"]).cuda()
+        d = {k: to_dev(r[k], dtype) for k in REC if k in r}
+        if "LSE" in r:
+            d["LSE"] = torch.from_numpy(r["LSE"]).cuda()
         drecs.append(d)
     out = A.alch_stack_backward(alch_shape(shp, dtype), batch, drecs, dWs, to_dev(Xf, dtype), to_dev(gf, dtype),
                                 to_dev(Wlm, dtype), torch.from_numpy(labels).cuda(),
@@ -126,6 +127,23 @@ def test_layer_forward_and_reuse_equals_recompute(dtype, shape_name, lens, wstd)
     torch.cuda.synchronize()
     for k, v in out.items():
         assert rel_err(to_np(v), ref[k]) <= (tol if dtype == "f32" else 3e-2), k
+
+
+def test_stack_from_four_stream_records():
+    # every layer's record holds X, Q, K, V only (Section 4.3.2: the rest is recomputed rather than kept);
+    # the oracle completes the same rounded tensors in fp64 and walks the stack on them
+    from oracle import complete_record
+    cu = synth.ragged_cu([200, 150, 31])
+    L, dtype = 3, "bf16"
+    shp, osh, Ws, recs, Xf, gf, Wlm, labels = make_stack("medium", dtype, cu, L, 1024, 9, 0.05)
+    T = int(cu[-1])
+    four = [{k: r[k] for k in ("X", "Q", "K", "V")} for r in recs]
+    full = [complete_record(osh, cu, f64(r), f64(W)) for r, W in zip(four, Ws)]
+    for m in (None, synth.keep_mask(T, 0.4, 3)):
+        ref = stack_backward_reuse(osh, cu, None, full, [f64(W) for W in Ws], Xf.astype(np.float64),
+                                   gf.astype(np.float64), Wlm.astype(np.float64), labels, m)
+        out = run_stack(shp, dtype, cu, Ws, four, Xf, gf, Wlm, labels, m)
+        check_stack(out, ref, dtype, L)
 
 
 @pytest.mark.parametrize("keep", [0.0, 0.3])
