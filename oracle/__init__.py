@@ -23,6 +23,8 @@ Modules:
              from a recomputed forward (recompute)
   stack   -- L-layer stack with final norm, LM head and cross-entropy loss
   lora    -- the layer with low-rank adapters on its projections (Section 3 A1, Section 6: rank 8)
+  prefix  -- sequences that share a prefix (responses on the saved KV cache of their prompt, Section 4.1)
+             and the DPO loss on them (Section 6)
 Every function is pinned by tests/test_oracle_*.py (finite differences, the
 reuse == recompute invariant, brute-force gather, closed forms, special cases).
 """

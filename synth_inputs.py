@@ -116,3 +116,40 @@ def lora_adapters(shape, rank, seed, dtype, projections=PROJECTIONS, std=0.05):
         if p in projections:
             out[p] = (A, B)
     return out
+
+
+def preference_batch(prompt_lens, response_lens, vocab, seed):
+    """Layout of a preference-alignment batch (Section 4.1, Section 6 of the paper: prompts answered by a
+    chosen and a rejected response): all prompts first, then for prompt g its responses in order.
+    response_lens[g] = lengths of the responses of prompt g (two for a pair: chosen, rejected).
+    Returns dict: cu [n_seqs+1], prefix [n_seqs] (-1 for prompts, the prompt's index for responses),
+    positions [T] (index in the sequence plus the prefix length), tokens [T] (random ids), and the scored
+    items sorted by row: item_row, item_label, item_slot (slot = running index of the response).  Token 0 of
+    a response is scored from the last row of its prompt, token i+1 from row i of the response."""
+    rng = np.random.default_rng(seed)
+    n_p = len(prompt_lens)
+    lens = [int(n) for n in prompt_lens] + [int(n) for rl in response_lens for n in rl]
+    cu = ragged_cu(lens)
+    T = int(cu[-1])
+    prefix = np.full(len(lens), -1, dtype=np.int32)
+    positions = np.zeros(T, dtype=np.int32)
+    for s in range(n_p):
+        positions[cu[s]:cu[s + 1]] = np.arange(lens[s])
+    tokens = rng.integers(0, vocab, T).astype(np.int32)
+    items = []
+    s = n_p
+    for g, rl in enumerate(response_lens):
+        for n in rl:
+            prefix[s] = g
+            a = int(cu[s])
+            positions[a:a + int(n)] = lens[g] + np.arange(int(n))
+            slot = s - n_p
+            if n > 0 and lens[g] > 0:
+                items.append((int(cu[g + 1]) - 1, int(tokens[a]), slot))
+            for i in range(int(n) - 1):
+                items.append((a + i, int(tokens[a + i + 1]), slot))
+            s += 1
+    items.sort(key=lambda it: (it[0], it[2]))
+    arr = np.asarray(items, dtype=np.int32).reshape(-1, 3)
+    return dict(cu=cu, prefix=prefix, positions=positions, tokens=tokens, n_prompts=n_p,
+                item_row=arr[:, 0].copy(), item_label=arr[:, 1].copy(), item_slot=arr[:, 2].copy())
