@@ -78,13 +78,23 @@ typedef struct {
     alch_dtype dtype;
 } alch_layer_shape;
 
-/* A ragged batch of prompts laid end to end (Section 4.1: the prefill batch). */
+/* A ragged batch of prompts laid end to end (Section 4.1: the prefill batch).
+ *
+ * Shared prefixes (Section 4.1, preference alignment: the responses attend to the saved KV cache of their
+ * prompt, and the chosen and the rejected response share it).  With seq_prefix given, sequence s with
+ * p = seq_prefix[s] >= 0 attends to every token of sequence p and causally to its own tokens; sequence p
+ * must come earlier in the batch and have no prefix itself (seq_prefix[p] = -1).  Everything else of a
+ * layer is row-local and unchanged.  The keys and values of p then receive gradient from the sequences
+ * that attend to them.  positions must be given with seq_prefix (a response token i sits at position
+ * len(p) + i); at most 4096 sequences.  seq_prefix == NULL: every sequence stands alone. */
 typedef struct {
     int32_t n_seqs, total_tokens, max_seqlen;
     const int32_t* cu_seqlens; /* device [n_seqs+1]: cu[0]=0, non-decreasing, cu[n_seqs]=total_tokens */
     const int32_t* positions;  /* device [total_tokens] RoPE positions, or NULL => index inside the sequence */
     const int32_t* cu_seqlens_host; /* host copy of cu_seqlens (same values); used for validation and
                                        launch planning so that no call has to read device memory */
+    const int32_t* seq_prefix;      /* device [n_seqs] or NULL */
+    const int32_t* seq_prefix_host; /* host copy of seq_prefix (NULL exactly when seq_prefix is NULL) */
 } alch_batch;
 
 /* ------------------------------------------------------------------------------------
@@ -298,6 +308,21 @@ int alch_layer_forward(const alch_layer_shape* shape, const alch_batch* batch, c
 
 size_t alch_layer_forward_workspace_bytes(const alch_layer_shape* shape, int32_t total_tokens,
                                           int32_t max_seqlen);
+
+/*
+ * alch_layer_forward_from: alch_layer_forward for the sequences seq_begin .. n_seqs-1 only, i.e. rows
+ * cu_seqlens[seq_begin] .. total_tokens-1 of X, Y and every record_out member (all of them
+ * [total_tokens, width]; earlier rows are neither read nor written, except that the attention reads
+ * record_out->K and record_out->V of the prefix sequences named by batch->seq_prefix).  This is the
+ * forward over the response tokens alone on the saved KV cache of their prompts (Section 4.1,
+ * preference alignment): the prompts' rows of the record come from serving, the responses' rows from
+ * this call.  batch->positions must be given when seq_begin > 0.  The workspace is that of
+ * alch_layer_forward for the rows computed (the bound for total_tokens always suffices).
+ */
+int alch_layer_forward_from(const alch_layer_shape* shape, const alch_batch* batch, int32_t seq_begin,
+                            const void* X, const alch_weights* weights, void* Y,
+                            const alch_record_out* record_out, void* workspace, size_t workspace_bytes,
+                            void* hip_stream);
 
 /*
  * alch_gemm: the dense contraction every projection gradient of the per-layer backward

@@ -32,7 +32,8 @@ class LayerShape(C.Structure):
 
 class CBatch(C.Structure):
     _fields_ = [("n_seqs", C.c_int32), ("total_tokens", C.c_int32), ("max_seqlen", C.c_int32),
-                ("cu_seqlens", C.c_void_p), ("positions", C.c_void_p), ("cu_seqlens_host", C.c_void_p)]
+                ("cu_seqlens", C.c_void_p), ("positions", C.c_void_p), ("cu_seqlens_host", C.c_void_p),
+                ("seq_prefix", C.c_void_p), ("seq_prefix_host", C.c_void_p)]
 
 
 class CStream(C.Structure):
@@ -141,6 +142,10 @@ def lib():
     L.alch_layer_forward.restype = C.c_int
     L.alch_layer_forward.argtypes = [C.POINTER(LayerShape), C.POINTER(CBatch), C.c_void_p, C.POINTER(CWeights),
                                      C.c_void_p, C.POINTER(CRecordOut), C.c_void_p, C.c_size_t, C.c_void_p]
+    L.alch_layer_forward_from.restype = C.c_int
+    L.alch_layer_forward_from.argtypes = [C.POINTER(LayerShape), C.POINTER(CBatch), C.c_int32, C.c_void_p,
+                                          C.POINTER(CWeights), C.c_void_p, C.POINTER(CRecordOut), C.c_void_p,
+                                          C.c_size_t, C.c_void_p]
     L.alch_gemm.restype = C.c_int
     L.alch_gemm.argtypes = [C.c_int, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(CGemmTerm),
                             C.c_void_p, C.c_int64, C.c_int32, C.c_void_p]
@@ -177,9 +182,10 @@ def _torch_dtype(shape):
 
 
 class Batch:
-    """A ragged batch: host cu_seqlens (int32 numpy) mirrored on the device."""
+    """A ragged batch: host cu_seqlens (int32 numpy) mirrored on the device.  prefix: per sequence -1 or the
+    index of the earlier sequence whose tokens it also attends to (positions must then be given)."""
 
-    def __init__(self, cu_seqlens, device="cuda", positions=None):
+    def __init__(self, cu_seqlens, device="cuda", positions=None, prefix=None):
         self.cu_host = np.ascontiguousarray(cu_seqlens, dtype=np.int32)
         self.n_seqs = int(self.cu_host.shape[0] - 1)
         self.total_tokens = int(self.cu_host[-1])
@@ -187,8 +193,12 @@ class Batch:
         self.max_seqlen = int(lens.max()) if self.n_seqs > 0 else 0
         self.cu_dev = torch.from_numpy(self.cu_host.copy()).to(device)
         self.positions = None if positions is None else torch.as_tensor(positions, dtype=torch.int32).to(device)
+        self.prefix_host = None if prefix is None else np.ascontiguousarray(prefix, dtype=np.int32)
+        self.prefix_dev = None if prefix is None else torch.from_numpy(self.prefix_host.copy()).to(device)
         self.c = CBatch(self.n_seqs, self.total_tokens, self.max_seqlen, self.cu_dev.data_ptr(),
-                        0 if self.positions is None else self.positions.data_ptr(), self.cu_host.ctypes.data)
+                        0 if self.positions is None else self.positions.data_ptr(), self.cu_host.ctypes.data,
+                        None if prefix is None else self.prefix_dev.data_ptr(),
+                        None if prefix is None else self.prefix_host.ctypes.data)
 
 
 def _workspace(nbytes, device):
@@ -291,22 +301,29 @@ def alch_layer_backward_lora(shape, batch, saved, weights, lora, rank, scale, dY
     return out
 
 
-def alch_layer_forward(shape, batch, X, weights, workspace=None, stream=None):
-    """Runs the layer forward; returns (Y, record dict incl. LSE)."""
+def alch_layer_forward(shape, batch, X, weights, workspace=None, stream=None, seq_begin=0, rec=None, Y=None):
+    """Runs the layer forward; returns (Y, record dict incl. LSE).  seq_begin > 0: only the sequences from
+    seq_begin on are computed (alch_layer_forward_from); rec and Y then hold the earlier rows already."""
     L = lib()
     dev, dt = X.device, X.dtype
     T = batch.total_tokens
     QD, KD = shape.n_q_heads * shape.head_dim, shape.n_kv_heads * shape.head_dim
     widths = dict(X=shape.hidden, X2=shape.hidden, Q=QD, K=KD, V=KD, O=QD, G=shape.ffn, U=shape.ffn)
-    rec = {k: torch.empty((T, w), dtype=dt, device=dev) for k, w in widths.items()}
-    rec["LSE"] = torch.empty((T, shape.n_q_heads), dtype=torch.float32, device=dev)
-    Y = torch.empty_like(X)
+    if rec is None:
+        rec = {k: torch.empty((T, w), dtype=dt, device=dev) for k, w in widths.items()}
+        rec["LSE"] = torch.empty((T, shape.n_q_heads), dtype=torch.float32, device=dev)
+    if Y is None:
+        Y = torch.empty_like(X)
     need = L.alch_layer_forward_workspace_bytes(C.byref(shape), T, batch.max_seqlen)
     ws = workspace if workspace is not None else _workspace(need, dev)
     ro = CRecordOut(*[rec[k].data_ptr() for k in RECORD_KEYS], rec["LSE"].data_ptr())
     w = _weights_struct(weights, 0)
-    _check(L.alch_layer_forward(C.byref(shape), C.byref(batch.c), _ptr(X), C.byref(w), _ptr(Y), C.byref(ro),
-                                _ptr(ws), ws.numel(), _stream_handle(stream)))
+    if seq_begin:
+        _check(L.alch_layer_forward_from(C.byref(shape), C.byref(batch.c), seq_begin, _ptr(X), C.byref(w), _ptr(Y),
+                                         C.byref(ro), _ptr(ws), ws.numel(), _stream_handle(stream)))
+    else:
+        _check(L.alch_layer_forward(C.byref(shape), C.byref(batch.c), _ptr(X), C.byref(w), _ptr(Y), C.byref(ro),
+                                    _ptr(ws), ws.numel(), _stream_handle(stream)))
     return Y, rec
 
 

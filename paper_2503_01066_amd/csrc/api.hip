@@ -78,6 +78,17 @@ static int check_batch(const alch_batch* b) {
     }
     if (cu[b->n_seqs] != b->total_tokens)
         return fail(ALCH_ERR_SHAPE, "cu_seqlens[n_seqs] = %d but total_tokens = %d", cu[b->n_seqs], b->total_tokens);
+    if ((b->seq_prefix == nullptr) != (b->seq_prefix_host == nullptr))
+        return fail(ALCH_ERR_INVALID_ARG, "seq_prefix and seq_prefix_host must be given together");
+    if (b->seq_prefix_host) {
+        if (b->n_seqs > kMaxPrefixSeqs) return fail(ALCH_ERR_UNSUPPORTED, "shared prefixes: more than %d sequences", kMaxPrefixSeqs);
+        if (b->total_tokens > 0 && !b->positions) return fail(ALCH_ERR_INVALID_ARG, "positions must be given with seq_prefix");
+        for (int s = 0; s < b->n_seqs; ++s) {
+            const int p = b->seq_prefix_host[s];
+            if (p < -1 || p >= s) return fail(ALCH_ERR_SHAPE, "seq_prefix[%d] = %d is not -1 or an earlier sequence", s, p);
+            if (p >= 0 && b->seq_prefix_host[p] != -1) return fail(ALCH_ERR_SHAPE, "seq_prefix[%d] = %d has a prefix itself", s, p);
+        }
+    }
     return ALCH_OK;
 }
 
@@ -274,7 +285,7 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
     alch_saved sv = sv_in;
     if (T > 0 && (!sv.O || !sv.LSE)) {
         ALCH_TRY(launch_attn_fwd(dt, sv.Q, sv.K, sv.V, p.O_re, p.LSE_re, T, b.n_seqs, b.max_seqlen, b.cu_seqlens,
-                                 b.cu_seqlens_host, s.n_q_heads, s.n_kv_heads, D, st));
+                                 b.cu_seqlens_host, b.seq_prefix, b.seq_prefix_host, 0, s.n_q_heads, s.n_kv_heads, D, st));
         sv.O = p.O_re;
         sv.LSE = p.LSE_re;
     }
@@ -512,6 +523,7 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
         a.dtype = dt; a.T = T; a.n_seqs = b.n_seqs; a.max_seqlen = b.max_seqlen;
         a.Hq = s.n_q_heads; a.Hkv = s.n_kv_heads; a.D = D;
         a.cu_seqlens = b.cu_seqlens; a.cu_seqlens_host = b.cu_seqlens_host;
+        a.prefix = b.seq_prefix; a.prefix_host = b.seq_prefix_host;
         a.Q = sv.Q; a.K = sv.K; a.V = sv.V; a.O = sv.O; a.dO = p.dO; a.LSE = sv.LSE; a.delta = p.delta;
         a.dQ = p.dQKV; a.dK = at(p.dQKV, QD, E); a.dV = at(p.dQKV, QD + KD, E); a.ld_dqkv = QKV;
         a.positions = b.positions; a.rope_base = s.rope_base;
@@ -565,13 +577,19 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
     return ALCH_OK;
 }
 
-int launch_attn_bwd(const AttnArgs& a, hipStream_t stream) {
-    double pairs = 0;  // causal (query, key) pairs per query head
-    for (int s = 0; s < a.n_seqs; ++s) {
-        const double n = a.cu_seqlens_host[s + 1] - a.cu_seqlens_host[s];
+// (query, key) pairs per query head: causal inside a sequence, all keys of its prefix
+double attn_pairs(int n_seqs, const int* cu_host, const int* prefix_host) {
+    double pairs = 0;
+    for (int s = 0; s < n_seqs; ++s) {
+        const double n = cu_host[s + 1] - cu_host[s];
         pairs += n * (n + 1) / 2;
+        if (prefix_host && prefix_host[s] >= 0) pairs += n * (cu_host[prefix_host[s] + 1] - cu_host[prefix_host[s]]);
     }
-    TraceScope ts(kTraceAttnBwd, 10.0 * a.D * a.Hq * pairs, 0.0, stream);
+    return pairs;
+}
+
+int launch_attn_bwd(const AttnArgs& a, hipStream_t stream) {
+    TraceScope ts(kTraceAttnBwd, 10.0 * a.D * a.Hq * attn_pairs(a.n_seqs, a.cu_seqlens_host, a.prefix_host), 0.0, stream);
     if (attn_mfma_supported(a)) return launch_attn_bwd_mfma(a, stream);  // delta and RoPE backward fused
     ALCH_TRY(launch_attn_delta(a.dtype, a.dO, a.O, a.delta, a.T, a.Hq, a.D, stream));
     ALCH_TRY(launch_attn_bwd_generic(a, stream));
@@ -911,8 +929,8 @@ int alch_attention_forward(const alch_layer_shape* shape, const alch_batch* batc
     REQUIRE_ACT(Q, "Q", T); REQUIRE_ACT(K, "K", T); REQUIRE_ACT(V, "V", T); REQUIRE_ACT(O, "O", T);
     REQUIRE_ACT(LSE, "LSE", T);
     return launch_attn_fwd(shape->dtype, Q, K, V, O, LSE, T, batch->n_seqs, batch->max_seqlen, batch->cu_seqlens,
-                           batch->cu_seqlens_host, shape->n_q_heads, shape->n_kv_heads, shape->head_dim,
-                           static_cast<hipStream_t>(hip_stream));
+                           batch->cu_seqlens_host, batch->seq_prefix, batch->seq_prefix_host, 0, shape->n_q_heads,
+                           shape->n_kv_heads, shape->head_dim, static_cast<hipStream_t>(hip_stream));
 }
 
 size_t alch_layer_forward_workspace_bytes(const alch_layer_shape* shape, int32_t total_tokens, int32_t max_seqlen) {
@@ -921,12 +939,15 @@ size_t alch_layer_forward_workspace_bytes(const alch_layer_shape* shape, int32_t
     return plan_layer_fwd(*shape, total_tokens, nullptr, 0).bytes;
 }
 
-int alch_layer_forward(const alch_layer_shape* shape, const alch_batch* batch, const void* X,
-                       const alch_weights* w, void* Y, const alch_record_out* rec, void* workspace,
-                       size_t workspace_bytes, void* hip_stream) {
-    clear_error();
+// Forward of sequences seq_begin .. n_seqs-1 (rows r0 = cu[seq_begin] .. T-1 of every tensor); arguments validated.
+static int layer_forward_impl(const alch_layer_shape* shape, const alch_batch* batch, int seq_begin, const void* X,
+                              const alch_weights* w, void* Y, const alch_record_out* rec, void* workspace,
+                              size_t workspace_bytes, void* hip_stream) {
     ALCH_TRY(check_shape(shape));
     ALCH_TRY(check_batch(batch));
+    if (seq_begin < 0 || seq_begin > batch->n_seqs) return fail(ALCH_ERR_INVALID_ARG, "seq_begin %d outside 0..n_seqs", seq_begin);
+    if (seq_begin > 0 && batch->total_tokens > 0 && !batch->positions)
+        return fail(ALCH_ERR_INVALID_ARG, "positions must be given with seq_begin > 0");
     if (!w || !rec) return fail(ALCH_ERR_INVALID_ARG, "weights / record_out is NULL");
     REQUIRE_PTR(X, "X"); REQUIRE_PTR(Y, "Y");
     REQUIRE_PTR(w->Wq, "weights.Wq"); REQUIRE_PTR(w->Wk, "weights.Wk"); REQUIRE_PTR(w->Wv, "weights.Wv");
@@ -935,21 +956,33 @@ int alch_layer_forward(const alch_layer_shape* shape, const alch_batch* batch, c
     REQUIRE_PTR(rec->X, "record_out.X"); REQUIRE_PTR(rec->X2, "record_out.X2"); REQUIRE_PTR(rec->Q, "record_out.Q");
     REQUIRE_PTR(rec->K, "record_out.K"); REQUIRE_PTR(rec->V, "record_out.V"); REQUIRE_PTR(rec->O, "record_out.O");
     REQUIRE_PTR(rec->G, "record_out.G"); REQUIRE_PTR(rec->U, "record_out.U"); REQUIRE_PTR(rec->LSE, "record_out.LSE");
-    const size_t need = plan_layer_fwd(*shape, batch->total_tokens, nullptr, 0).bytes;
+    const int r0 = batch->cu_seqlens_host[seq_begin];
+    const int T = batch->total_tokens - r0;  // rows computed
+    const size_t need = plan_layer_fwd(*shape, T, nullptr, 0).bytes;
     if (!workspace || workspace_bytes < need) return fail(ALCH_ERR_WORKSPACE, "workspace %zu bytes < %zu needed", workspace_bytes, need);
     if (!aligned16(workspace)) return fail(ALCH_ERR_INVALID_ARG, "workspace is not 16-byte aligned");
+    if (T <= 0) return ALCH_OK;
 
     const alch_layer_shape& s = *shape;
-    const LayerFwdPlan p = plan_layer_fwd(s, batch->total_tokens, workspace, workspace_bytes);
+    const LayerFwdPlan p = plan_layer_fwd(s, T, workspace, workspace_bytes);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const alch_dtype dt = s.dtype;
-    const int T = batch->total_tokens, H = s.hidden, F = s.ffn, D = s.head_dim;
+    const size_t E = dtype_size(dt);
+    const int H = s.hidden, F = s.ffn, D = s.head_dim;
     const int QD = s.n_q_heads * D, KD = s.n_kv_heads * D;
+    // the computed rows of every [total_tokens, width] tensor
+    const void* Xr = at(X, (size_t)r0 * H, E);
+    void* Yr = at(Y, (size_t)r0 * H, E);
+    void *rX = at(rec->X, (size_t)r0 * H, E), *rX2 = at(rec->X2, (size_t)r0 * H, E), *rQ = at(rec->Q, (size_t)r0 * QD, E);
+    void *rK = at(rec->K, (size_t)r0 * KD, E), *rV = at(rec->V, (size_t)r0 * KD, E);
+    void *rG = at(rec->G, (size_t)r0 * F, E), *rU = at(rec->U, (size_t)r0 * F, E), *rO = at(rec->O, (size_t)r0 * QD, E);
+    // positions follow the rows; without them (seq_begin = 0 only) the kernels count inside each sequence
+    const int* pos = batch->positions ? batch->positions + r0 : nullptr;
 
-    if (rec->X != X) ALCH_TRY(launch_masked_copy(dt, X, nullptr, rec->X, T, H, st));
-    ALCH_TRY(launch_rmsnorm_fwd(dt, X, w->g1, p.Hn, T, H, s.rms_eps, st));
+    if (rX != Xr) ALCH_TRY(launch_masked_copy(dt, Xr, nullptr, rX, T, H, st));
+    ALCH_TRY(launch_rmsnorm_fwd(dt, Xr, w->g1, p.Hn, T, H, s.rms_eps, st));
     const void* Ws[3] = {w->Wq, w->Wk, w->Wv};
-    void* outs[3] = {rec->Q, rec->K, rec->V};
+    void* outs[3] = {rQ, rK, rV};
     const int widths[3] = {QD, KD, KD};
     for (int i = 0; i < 3; ++i) {
         GemmDesc d = gemm(dt, T, widths[i], true, true);
@@ -957,37 +990,53 @@ int alch_layer_forward(const alch_layer_shape* shape, const alch_batch* batch, c
         add_out(d, outs[i], 0, widths[i]);
         ALCH_TRY(launch_gemm(d, st));
     }
-    ALCH_TRY(launch_rope(dt, rec->Q, QD, T, s.n_q_heads, D, batch->positions, batch->cu_seqlens, batch->n_seqs, s.rope_base, 1.f, st));
-    ALCH_TRY(launch_rope(dt, rec->K, KD, T, s.n_kv_heads, D, batch->positions, batch->cu_seqlens, batch->n_seqs, s.rope_base, 1.f, st));
-    ALCH_TRY(launch_attn_fwd(dt, rec->Q, rec->K, rec->V, rec->O, rec->LSE, T, batch->n_seqs, batch->max_seqlen,
-                             batch->cu_seqlens, batch->cu_seqlens_host, s.n_q_heads, s.n_kv_heads, D, st));
+    ALCH_TRY(launch_rope(dt, rQ, QD, T, s.n_q_heads, D, pos, batch->cu_seqlens, batch->n_seqs, s.rope_base, 1.f, st));
+    ALCH_TRY(launch_rope(dt, rK, KD, T, s.n_kv_heads, D, pos, batch->cu_seqlens, batch->n_seqs, s.rope_base, 1.f, st));
+    // attention indexes whole-batch rows: the keys and values of a prefix sequence lie before r0
+    ALCH_TRY(launch_attn_fwd(dt, rec->Q, rec->K, rec->V, rec->O, rec->LSE, batch->total_tokens, batch->n_seqs,
+                             batch->max_seqlen, batch->cu_seqlens, batch->cu_seqlens_host, batch->seq_prefix,
+                             batch->seq_prefix_host, seq_begin, s.n_q_heads, s.n_kv_heads, D, st));
     {  // X2 = X + O Wo^T
-        ALCH_TRY(launch_masked_copy(dt, X, nullptr, rec->X2, T, H, st));
+        ALCH_TRY(launch_masked_copy(dt, Xr, nullptr, rX2, T, H, st));
         GemmDesc d = gemm(dt, T, H, true, true);
-        add_seg(d, rec->O, QD, w->Wo, QD, QD);
-        add_out(d, rec->X2, 0, H);
+        add_seg(d, rO, QD, w->Wo, QD, QD);
+        add_out(d, rX2, 0, H);
         d.accumulate = 1;
         ALCH_TRY(launch_gemm(d, st));
     }
-    ALCH_TRY(launch_rmsnorm_fwd(dt, rec->X2, w->g2, p.Hn, T, H, s.rms_eps, st));
+    ALCH_TRY(launch_rmsnorm_fwd(dt, rX2, w->g2, p.Hn, T, H, s.rms_eps, st));
     const void* Wm[2] = {w->Wg, w->Wu};
-    void* om[2] = {rec->G, rec->U};
+    void* om[2] = {rG, rU};
     for (int i = 0; i < 2; ++i) {
         GemmDesc d = gemm(dt, T, F, true, true);
         add_seg(d, p.Hn, H, Wm[i], H, H);
         add_out(d, om[i], 0, F);
         ALCH_TRY(launch_gemm(d, st));
     }
-    ALCH_TRY(launch_swiglu_act(dt, rec->G, rec->U, p.Act, (long long)T * F, st));
+    ALCH_TRY(launch_swiglu_act(dt, rG, rU, p.Act, (long long)T * F, st));
     {  // Y = X2 + Act Wd^T
-        ALCH_TRY(launch_masked_copy(dt, rec->X2, nullptr, Y, T, H, st));
+        ALCH_TRY(launch_masked_copy(dt, rX2, nullptr, Yr, T, H, st));
         GemmDesc d = gemm(dt, T, H, true, true);
         add_seg(d, p.Act, F, w->Wd, F, F);
-        add_out(d, Y, 0, H);
+        add_out(d, Yr, 0, H);
         d.accumulate = 1;
         ALCH_TRY(launch_gemm(d, st));
     }
     return ALCH_OK;
+}
+
+int alch_layer_forward(const alch_layer_shape* shape, const alch_batch* batch, const void* X,
+                       const alch_weights* w, void* Y, const alch_record_out* rec, void* workspace,
+                       size_t workspace_bytes, void* hip_stream) {
+    clear_error();
+    return layer_forward_impl(shape, batch, 0, X, w, Y, rec, workspace, workspace_bytes, hip_stream);
+}
+
+int alch_layer_forward_from(const alch_layer_shape* shape, const alch_batch* batch, int32_t seq_begin, const void* X,
+                            const alch_weights* w, void* Y, const alch_record_out* rec, void* workspace,
+                            size_t workspace_bytes, void* hip_stream) {
+    clear_error();
+    return layer_forward_impl(shape, batch, seq_begin, X, w, Y, rec, workspace, workspace_bytes, hip_stream);
 }
 
 }  // extern "C"

@@ -39,6 +39,8 @@ struct AttnMfmaParams {
     float* delta;  // written by the dQ kernel (row sums of dO*O), read by the dK/dV kernel
     __bf16 *dQ, *dK, *dV;
     const int* cu;
+    const int* prefix;     // null, or per sequence: -1 / the earlier sequence whose keys it also attends to
+    int n_seqs;
     const int* positions;  // RoPE positions per token, or null: index inside the sequence
     int Hq, Hkv;
     long long ldq, ldk, ldo;  // row strides (elements) of Q/dO, K/V, and of the outputs
@@ -159,6 +161,10 @@ __device__ __forceinline__ bf16x8 global_frag_d(const __bf16* base, long long ld
 
 // ---------------------------------------------------------------------------------------------
 // dK / dV
+// kPrefix: sequences may name an earlier sequence as their prefix.  The key block then also meets, after the
+// queries of its own sequence (causal), every query of every sequence that names this one (no mask but the
+// ends of the sequences): the tile stream is the concatenation of those, sequence by sequence.
+template <bool kPrefix>
 __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
     __shared__ __attribute__((aligned(1024))) char smem[3 * kStageBytes];
     const uint32_t lds0 = (uint32_t)(uintptr_t)ALCH_LDS(smem);
@@ -194,20 +200,45 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
     tile_voffsets(voff, p.ldq, wave, lane);
     const int qt0 = (kb * 128) / kTileRows;
     const int nqt = (len + kTileRows - 1) / kTileRows - qt0;
-    const int n_it = G * nqt;
+    int n_it = G * nqt;
+    if constexpr (kPrefix) {
+        for (int c = seq + 1; c < p.n_seqs; ++c)
+            if (p.prefix[c] == seq) n_it += G * ((p.cu[c + 1] - p.cu[c] + kTileRows - 1) / kTileRows);
+    }
     const float sl2 = p.scale * kLog2e;
 
-    // Tile `it` of the stream (query head it / nqt of the group, 64-query tile qt0 + it % nqt) goes to
-    // stage it % 3.  Beyond the end of the stream the loads are issued with zero extent: they move
-    // nothing and keep every wave's count of outstanding loads the same.
-    auto issue = [&](int it) {
-        const int h = kv * G + it / nqt, qt = qt0 + it % nqt;
-        const int row_first = qt * kTileRows, rows_valid = it < n_it ? len - row_first : 0;
+    // The tile stream: for the key block's own sequence and then (kPrefix) every sequence that names it as
+    // prefix, for every query head of the group, the 64-query tiles qt_first .. qt_end-1 of that sequence.
+    struct Cursor {
+        int c, row0, n;         // sequence of the queries, its first row in the batch, its length
+        int qt_first, qt_end;   // its tiles that this key block meets
+        int h, qt;              // query head and tile of the current position
+    };
+    auto advance = [&](Cursor& q) {
+        if (++q.qt < q.qt_end) return;
+        q.qt = q.qt_first;
+        if (++q.h < kv * G + G) return;
+        q.h = kv * G;
+        if constexpr (kPrefix) {
+            int c = q.c + 1;
+            while (c < p.n_seqs && !(p.prefix[c] == seq && p.cu[c + 1] > p.cu[c])) ++c;
+            if (c < p.n_seqs) {
+                q.c = c; q.row0 = p.cu[c]; q.n = p.cu[c + 1] - q.row0;
+                q.qt_first = q.qt = 0; q.qt_end = (q.n + kTileRows - 1) / kTileRows;
+            }
+        }
+        // (past the end of the stream the cursor wraps; its tiles are then loaded with zero extent)
+    };
+    // Tile `it` of the stream goes to stage it % 3.  Beyond the end of the stream the loads are issued with
+    // zero extent: they move nothing and keep every wave's count of outstanding loads the same.
+    auto issue = [&](const Cursor& q, int it) {
+        const int row_first = q.qt * kTileRows, rows_valid = it < n_it ? q.n - row_first : 0;
+        const long long row = (long long)(q.row0 + row_first);
         const uint32_t st = lds0 + (uint32_t)(it % 3) * kStageBytes;
-        issue_rows_tile(p.Q + (long long)(seq_start + row_first) * p.ldq + h * kD, p.ldq, rows_valid, st, wave, voff);
-        issue_rows_tile(p.dO + (long long)(seq_start + row_first) * p.ldq + h * kD, p.ldq, rows_valid, st + kTileBytes, wave, voff);
-        if (wave == 0) issue_row_scalars(p.LSE + (long long)(seq_start + row_first) * p.Hq + h, p.Hq, rows_valid, st + 2 * kTileBytes, lane);
-        if (wave == 1) issue_row_scalars(p.delta + (long long)(seq_start + row_first) * p.Hq + h, p.Hq, rows_valid, st + 2 * kTileBytes + 256, lane);
+        issue_rows_tile(p.Q + row * p.ldq + q.h * kD, p.ldq, rows_valid, st, wave, voff);
+        issue_rows_tile(p.dO + row * p.ldq + q.h * kD, p.ldq, rows_valid, st + kTileBytes, wave, voff);
+        if (wave == 0) issue_row_scalars(p.LSE + row * p.Hq + q.h, p.Hq, rows_valid, st + 2 * kTileBytes, lane);
+        if (wave == 1) issue_row_scalars(p.delta + row * p.Hq + q.h, p.Hq, rows_valid, st + 2 * kTileBytes + 256, lane);
     };
 
     // Software pipeline over the tile stream, three LDS stages.  Entering iteration `it`, of tile `it`
@@ -225,13 +256,24 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
     f32x16 S1, dP1;         // raw scores of block 1 of the current tile
     bf16x8 pf0[2], dsf0[2]; // P, dS of block 0 of the current tile
     const int jl = j0 + (lane & 31);  // this lane's key
-    const unsigned live = (unsigned)max(len - jl, 0);
+    const unsigned live_own = (unsigned)max(len - jl, 0);
     // P, dS of accumulator elements e0 .. e0+n-1 of one block, in place.  Element e is query row
     // i = i0 + 8*(e>>2) + 4*half + (e&3) against key column jl.  Pairs above the diagonal (jl > i) and rows
     // or keys past the end of the sequence get exponent -inf, i.e. p = 0 exactly: with rel = i - jl that
-    // is one unsigned test, rel >= max(len - jl, 0).  l, d: LSE and delta of the block's 16 rows of this lane.
-    auto softmax_part = [&](f32x16& s, f32x16& dp, const f32x4 (&l)[4], const f32x4 (&d)[4], int i0, int e0, int n) {
-        const int rel0 = i0 + 4 * half - jl;
+    // is one unsigned test, rel >= max(len - jl, 0).  Queries of a sequence that names this one as prefix
+    // see every key: rel = i and the bound is that sequence's length (0 for a key past the end).
+    // l, d: LSE and delta of the block's 16 rows of this lane.
+    struct Meta { int ibase, sub; unsigned live; };  // first query row of a tile; what rel subtracts; the bound
+    auto meta_of = [&](const Cursor& q) {
+        Meta m;
+        m.ibase = q.qt * kTileRows;
+        if (!kPrefix || q.c == seq) { m.sub = jl; m.live = live_own; }
+        else { m.sub = 0; m.live = jl < len ? (unsigned)q.n : 0u; }
+        return m;
+    };
+    auto softmax_part = [&](f32x16& s, f32x16& dp, const f32x4 (&l)[4], const f32x4 (&d)[4], const Meta& m, int blk, int e0, int n) {
+        const int rel0 = m.ibase + blk * 32 + 4 * half - (kPrefix ? m.sub : jl);
+        const unsigned live = kPrefix ? m.live : live_own;
 #pragma unroll
         for (int e = e0; e < e0 + n; ++e) {
             const unsigned rel = (unsigned)(rel0 + 8 * (e >> 2) + (e & 3));
@@ -251,8 +293,13 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
         }
     };
 
-    issue(0);
-    issue(1);
+    Cursor q_ld{seq, seq_start, len, qt0, qt0 + nqt, kv * G, qt0};
+    issue(q_ld, 0);
+    Meta m_cur = meta_of(q_ld);
+    advance(q_ld);
+    issue(q_ld, 1);
+    Meta m_nxt = meta_of(q_ld);
+    advance(q_ld);  // now at tile 2, the next one to load
     if (wave < 2)
         asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
     else
@@ -271,7 +318,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
         }
         f32x4 l[4], d[4];
         load_row_scalars(smem, 0, l, d);
-        softmax_part(S0, dP0, l, d, qt0 * kTileRows, 0, 16);
+        softmax_part(S0, dP0, l, d, m_cur, 0, 0, 16);
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             pf0[ks] = pack8(S0, ks);
@@ -279,16 +326,12 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
         }
     }
 
-    // stream state, advanced by one tile per iteration (no divisions in the loop):
-    // LDS byte offsets of the stages of tiles it, it+1, it+2 and (head, tile) of tile it and it+2
+    // stream state, advanced by one tile per iteration (no divisions in the loop): LDS byte offsets of the
+    // stages of tiles it, it+1, it+2; mask data of tiles it (m_cur) and it+1 (m_nxt); position of tile it+2 (q_ld)
     uint32_t s_cur = 0, s_nxt = kStageBytes, s_ld = 2 * kStageBytes;
-    int qt_cur = qt0;
-    int h_ld = kv * G + 2 / nqt, qt_ld = qt0 + 2 % nqt;
     for (int it = 0; it < n_it; ++it) {
         const char* tq = smem + s_cur;
         const char* tdo = tq + kTileBytes;
-        const int i00 = qt_cur * kTileRows;
-        const int qt_nxt = qt_cur + 1 == qt0 + nqt ? qt0 : qt_cur + 1;
         f32x4 l1[4], d1[4];  // LSE, delta of block 1 of this tile
         load_row_scalars(tq, 1, l1, d1);
 
@@ -297,10 +340,11 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
         __syncthreads();
         // Loads of tile it+2: descriptors now, the nine load instructions one per group below (a
         // burst of them would hold the wave at the issue stage for over a thousand cycles).
-        const int rows2 = it + 2 < n_it ? len - qt_ld * kTileRows : 0;
+        const int rows2 = it + 2 < n_it ? q_ld.n - q_ld.qt * kTileRows : 0;
         const uint32_t st2 = lds0 + s_ld;
         const long long ext2 = rows2 > 0 ? ((long long)(rows2 - 1) * p.ldq + kD) * 2 : 0;
-        const long long row2 = (long long)(seq_start + qt_ld * kTileRows);
+        const long long row2 = (long long)(q_ld.row0 + q_ld.qt * kTileRows);
+        const int h_ld = q_ld.h;
         const i32x4 rs_q = rsrc_of(p.Q + row2 * p.ldq + h_ld * kD, ext2);
         const i32x4 rs_do = rsrc_of(p.dO + row2 * p.ldq + h_ld * kD, ext2);
         const i32x4 rs_sc = rsrc_of((wave == 0 ? p.LSE : p.delta) + row2 * p.Hq + h_ld,
@@ -334,11 +378,11 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
             else if (g == 8 && wave < 2) dma4(rs_sc, st2 + 2 * kTileBytes + (uint32_t)wave * 256u, (uint32_t)(lane * p.Hq * 4));
             if (g + 2 < 16) fr[(g + 2) % 3] = load_group(g + 2);
             if (g < 8) {
-                softmax_part(S1, dP1, l1, d1, i00 + 32, 2 * g, 2);
+                softmax_part(S1, dP1, l1, d1, m_cur, 1, 2 * g, 2);
                 if (g == 3) { pf1[0] = pack8(S1, 0); dsf1[0] = pack8(dP1, 0); }
                 if (g == 7) { pf1[1] = pack8(S1, 1); dsf1[1] = pack8(dP1, 1); }
             } else {
-                softmax_part(Sn0, dPn0, ln, dn, qt_nxt * kTileRows, 2 * (g - 8), 2);
+                softmax_part(Sn0, dPn0, ln, dn, m_nxt, 0, 2 * (g - 8), 2);
                 if (g == 11) { pfn[0] = pack8(Sn0, 0); dsfn[0] = pack8(dPn0, 0); }
                 if (g == 15) { pfn[1] = pack8(Sn0, 1); dsfn[1] = pack8(dPn0, 1); }
             }
@@ -371,8 +415,9 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
         for (int ks = 0; ks < 2; ++ks) { pf0[ks] = pfn[ks]; dsf0[ks] = dsfn[ks]; }
         const uint32_t s_free = s_cur;
         s_cur = s_nxt; s_nxt = s_ld; s_ld = s_free;
-        qt_cur = qt_nxt;
-        if (++qt_ld == qt0 + nqt) { qt_ld = qt0; ++h_ld; }
+        m_cur = m_nxt;
+        m_nxt = meta_of(q_ld);
+        advance(q_ld);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
@@ -441,16 +486,23 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_dq_mfma(AttnMfmaParams p) {
     const uint32_t lane_d = frag_d_lane(lane), lane_r0 = frag_rows_lane(lane, 0), lane_r1 = frag_rows_lane(lane, 1);
     uint32_t voff[4];
     tile_voffsets(voff, p.ldk, wave, lane);
-    // key tiles 0 .. last tile that holds a key <= the work-group's last query
+    // key tiles: all tiles of the prefix sequence (if any), then own tiles 0 .. the last one that holds a
+    // key <= the work-group's last query
+    const int pre = p.prefix ? p.prefix[seq] : -1;
+    const int pre_start = pre >= 0 ? p.cu[pre] : 0, pre_len = pre >= 0 ? p.cu[pre + 1] - pre_start : 0;
+    const int npt = (pre_len + kTileRows - 1) / kTileRows;
     const int last_q = min(qb * 128 + 127, len - 1);
-    const int n_it = last_q / kTileRows + 1;
+    const int n_it = npt + last_q / kTileRows + 1;
     const float sl2 = p.scale * kLog2e;
 
     auto issue = [&](int it) {
-        const int row_first = it * kTileRows, rows_valid = len - row_first;
+        const bool in_pre = it < npt;
+        const int row_first = (in_pre ? it : it - npt) * kTileRows;
+        const int rows_valid = (in_pre ? pre_len : len) - row_first;
+        const long long row = (long long)((in_pre ? pre_start : seq_start) + row_first);
         const uint32_t st = lds0 + (uint32_t)(it & 1) * kStageBytes;
-        issue_rows_tile(p.K + (long long)(seq_start + row_first) * p.ldk + kv * kD, p.ldk, rows_valid, st, wave, voff);
-        issue_rows_tile(p.V + (long long)(seq_start + row_first) * p.ldk + kv * kD, p.ldk, rows_valid, st + kTileBytes, wave, voff);
+        issue_rows_tile(p.K + row * p.ldk + kv * kD, p.ldk, rows_valid, st, wave, voff);
+        issue_rows_tile(p.V + row * p.ldk + kv * kD, p.ldk, rows_valid, st + kTileBytes, wave, voff);
     };
 
     issue(0);
@@ -460,9 +512,14 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_dq_mfma(AttnMfmaParams p) {
         if (it + 1 < n_it) issue(it + 1);
         const char* tk = smem + (it & 1) * kStageBytes;
         const char* tv = tk + kTileBytes;
+        // keys of this tile count from 0 inside their own sequence; key j is visible to query i when
+        // j <= lim: the last prefix key for a prefix tile, i itself (the diagonal) for an own tile
+        const bool in_pre = it < npt;
+        const int jt = (in_pre ? it : it - npt) * kTileRows;
+        const int lim = in_pre ? pre_len - 1 : i, lim0 = in_pre ? pre_len - 1 : i0;
 #pragma unroll
         for (int jb = 0; jb < 2; ++jb) {
-            const int j0 = it * kTileRows + jb * 32;
+            const int j0 = jt + jb * 32;
             // (blocks wholly above the diagonal are computed and masked to zero, see the dK/dV kernel)
             const char* bk = tk + jb * 32 * 256;
             const char* bv = tv + jb * 32 * 256;
@@ -479,11 +536,11 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_dq_mfma(AttnMfmaParams p) {
                 const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(St[e], sl2, -lse2));
                 dPt[e] = pr * (dPt[e] - del);
             }
-            if (!i_ok || j0 + 31 > i0) {
+            if (!i_ok || j0 + 31 > lim0) {
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const int j = j0 + 8 * (e >> 2) + 4 * half + (e & 3);
-                    if (!i_ok || j > i) dPt[e] = 0.f;
+                    if (!i_ok || j > lim) dPt[e] = 0.f;
                 }
             }
 #pragma unroll
@@ -520,6 +577,8 @@ struct AttnFwdParams {
     __bf16* O;
     float* LSE;
     const int* cu;
+    const int* prefix;  // as in the backward
+    int seq_begin;      // first sequence whose queries are computed
     int Hq, Hkv;
     long long ldq, ldk;
     float scale;
@@ -528,7 +587,7 @@ struct AttnFwdParams {
 __global__ __launch_bounds__(256, 2) void k_attn_fwd_mfma(AttnFwdParams p) {
     __shared__ __attribute__((aligned(1024))) char smem[2 * kStageBytes];
     const uint32_t lds0 = (uint32_t)(uintptr_t)ALCH_LDS(smem);
-    const int seq = blockIdx.y, h = blockIdx.x;
+    const int seq = p.seq_begin + blockIdx.y, h = blockIdx.x;
     const int seq_start = p.cu[seq], len = p.cu[seq + 1] - seq_start;
     // heaviest (last) query blocks of every sequence and head first: blockIdx.z is the slowest index
     const int qb = (int)gridDim.z - 1 - (int)blockIdx.z;
@@ -553,15 +612,23 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd_mfma(AttnFwdParams p) {
     const uint32_t lane_d = frag_d_lane(lane), lane_r0 = frag_rows_lane(lane, 0), lane_r1 = frag_rows_lane(lane, 1);
     uint32_t voff[4];
     tile_voffsets(voff, p.ldk, wave, lane);
+    // key tiles: all tiles of the prefix sequence (if any), then the own tiles up to the diagonal; one
+    // running maximum and normaliser cover both, so O and LSE are those of the joint softmax
+    const int pre = p.prefix ? p.prefix[seq] : -1;
+    const int pre_start = pre >= 0 ? p.cu[pre] : 0, pre_len = pre >= 0 ? p.cu[pre + 1] - pre_start : 0;
+    const int npt = (pre_len + kTileRows - 1) / kTileRows;
     const int last_q = min(qb * 128 + 127, len - 1);
-    const int n_it = last_q / kTileRows + 1;
+    const int n_it = npt + last_q / kTileRows + 1;
     const float sl2 = p.scale * kLog2e;
 
     auto issue = [&](int it) {
-        const int row_first = it * kTileRows, rows_valid = len - row_first;
+        const bool in_pre = it < npt;
+        const int row_first = (in_pre ? it : it - npt) * kTileRows;
+        const int rows_valid = (in_pre ? pre_len : len) - row_first;
+        const long long row = (long long)((in_pre ? pre_start : seq_start) + row_first);
         const uint32_t st = lds0 + (uint32_t)(it & 1) * kStageBytes;
-        issue_rows_tile(p.K + (long long)(seq_start + row_first) * p.ldk + kv * kD, p.ldk, rows_valid, st, wave, voff);
-        issue_rows_tile(p.V + (long long)(seq_start + row_first) * p.ldk + kv * kD, p.ldk, rows_valid, st + kTileBytes, wave, voff);
+        issue_rows_tile(p.K + row * p.ldk + kv * kD, p.ldk, rows_valid, st, wave, voff);
+        issue_rows_tile(p.V + row * p.ldk + kv * kD, p.ldk, rows_valid, st + kTileBytes, wave, voff);
     };
 
     issue(0);
@@ -571,7 +638,9 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd_mfma(AttnFwdParams p) {
         if (it + 1 < n_it) issue(it + 1);
         const char* tk = smem + (it & 1) * kStageBytes;
         const char* tv = tk + kTileBytes;
-        const int jt = it * kTileRows;
+        const bool in_pre = it < npt;
+        const int jt = (in_pre ? it : it - npt) * kTileRows;  // first key of the tile inside its own sequence
+        const int lim = in_pre ? pre_len - 1 : i;             // last key of the tile's sequence this query sees
         // (a tile wholly above this wave's diagonal is computed and fully masked: p = 0, alpha = 1)
         f32x16 St[2];
 #pragma unroll
@@ -582,8 +651,8 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd_mfma(AttnFwdParams p) {
             for (int kk = 0; kk < 8; ++kk)
                 St[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_d(tk + jb * 32 * 256, lane_d, kk), qf[kk], St[jb], 0, 0, 0);
         }
-        // scores in the log2 domain, masked (key j = jt + jb*32 + 8b + 4*half + r must satisfy j <= i)
-        const bool need_mask = jt + 63 > i0;
+        // scores in the log2 domain, masked (key j = jt + jb*32 + 8b + 4*half + r must satisfy j <= lim)
+        const bool need_mask = jt + 63 > (in_pre ? pre_len - 1 : i0);
         float mx = m2;
 #pragma unroll
         for (int jb = 0; jb < 2; ++jb)
@@ -592,7 +661,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_fwd_mfma(AttnFwdParams p) {
                 float sv = St[jb][e] * sl2;
                 if (need_mask) {
                     const int j = jt + jb * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-                    if (j > i) sv = -INFINITY;
+                    if (j > lim) sv = -INFINITY;
                 }
                 St[jb][e] = sv;
                 mx = fmaxf(mx, sv);
@@ -652,40 +721,42 @@ int launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t stream) {
     p.O = (const __bf16*)a.O; p.LSE = a.LSE; p.delta = a.delta;
     p.positions = a.positions; p.rope_log2_base = a.rope_base > 0.f ? log2f(a.rope_base) : 0.f;
     p.dQ = (__bf16*)a.dQ; p.dK = (__bf16*)a.dK; p.dV = (__bf16*)a.dV;
-    p.cu = a.cu_seqlens; p.Hq = a.Hq; p.Hkv = a.Hkv;
+    p.cu = a.cu_seqlens; p.prefix = a.prefix; p.n_seqs = a.n_seqs; p.Hq = a.Hq; p.Hkv = a.Hkv;
     p.ldq = (long long)a.Hq * a.D; p.ldk = (long long)a.Hkv * a.D; p.ldo = a.ld_dqkv;
     p.scale = 1.0f / sqrtf((float)a.D);
     const int nb = ceil_div(a.max_seqlen, 128);
     if (nb <= 0 || a.n_seqs <= 0) return ALCH_OK;
     if (nb > 65535 || a.n_seqs > 65535) return fail(ALCH_ERR_UNSUPPORTED, "attention: more than 65535 sequences or 128-token blocks");
     k_attn_bwd_dq_mfma<<<dim3(a.Hq, a.n_seqs, nb), 256, 0, stream>>>(p);   // also writes delta
-    k_attn_bwd_dkv_mfma<<<dim3(a.Hkv, a.n_seqs, nb), 256, 0, stream>>>(p);
+    if (a.prefix)
+        k_attn_bwd_dkv_mfma<true><<<dim3(a.Hkv, a.n_seqs, nb), 256, 0, stream>>>(p);
+    else
+        k_attn_bwd_dkv_mfma<false><<<dim3(a.Hkv, a.n_seqs, nb), 256, 0, stream>>>(p);
     ALCH_HIP_TRY(hipGetLastError());
     return ALCH_OK;
 }
 
 int launch_attn_fwd(alch_dtype dt, const void* Q, const void* K, const void* V, void* O, float* LSE, int T,
-                    int n_seqs, int max_seqlen, const int* cu_seqlens, const int* cu_seqlens_host, int Hq,
-                    int Hkv, int D, hipStream_t stream) {
-    double pairs = 0;
-    for (int s = 0; s < n_seqs; ++s) {
-        const double n = cu_seqlens_host[s + 1] - cu_seqlens_host[s];
-        pairs += n * (n + 1) / 2;
-    }
+                    int n_seqs, int max_seqlen, const int* cu_seqlens, const int* cu_seqlens_host, const int* prefix,
+                    const int* prefix_host, int seq_begin, int Hq, int Hkv, int D, hipStream_t stream) {
+    if (seq_begin >= n_seqs) return ALCH_OK;
+    const double pairs = attn_pairs(n_seqs - seq_begin, cu_seqlens_host + seq_begin, nullptr) +
+                         (attn_pairs(n_seqs, cu_seqlens_host, prefix_host) - attn_pairs(n_seqs, cu_seqlens_host, nullptr));
     TraceScope ts(kTraceAttnFwd, 4.0 * D * Hq * pairs, 0.0, stream);
     if (dt == ALCH_BF16 && D == kD && T > 0 && aligned16(Q) && aligned16(K) && aligned16(V) && aligned16(O)) {
         AttnFwdParams p;
         p.Q = (const __bf16*)Q; p.K = (const __bf16*)K; p.V = (const __bf16*)V; p.O = (__bf16*)O; p.LSE = LSE;
-        p.cu = cu_seqlens; p.Hq = Hq; p.Hkv = Hkv; p.ldq = (long long)Hq * D; p.ldk = (long long)Hkv * D;
+        p.cu = cu_seqlens; p.prefix = prefix; p.seq_begin = seq_begin;
+        p.Hq = Hq; p.Hkv = Hkv; p.ldq = (long long)Hq * D; p.ldk = (long long)Hkv * D;
         p.scale = 1.0f / sqrtf((float)D);
         const int nb = ceil_div(max_seqlen, 128);
         if (nb <= 0 || n_seqs <= 0) return ALCH_OK;
         if (nb > 65535 || n_seqs > 65535) return fail(ALCH_ERR_UNSUPPORTED, "attention: more than 65535 sequences or 128-token blocks");
-        k_attn_fwd_mfma<<<dim3(Hq, n_seqs, nb), 256, 0, stream>>>(p);
+        k_attn_fwd_mfma<<<dim3(Hq, n_seqs - seq_begin, nb), 256, 0, stream>>>(p);
         ALCH_HIP_TRY(hipGetLastError());
         return ALCH_OK;
     }
-    return launch_attn_fwd_generic(dt, Q, K, V, O, LSE, T, n_seqs, cu_seqlens, Hq, Hkv, D, stream);
+    return launch_attn_fwd_generic(dt, Q, K, V, O, LSE, T, n_seqs, cu_seqlens, cu_seqlens_host, prefix, seq_begin, Hq, Hkv, D, stream);
 }
 
 }  // namespace alch

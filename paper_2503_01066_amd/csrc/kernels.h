@@ -127,6 +127,10 @@ struct AttnArgs {
     int T, n_seqs, max_seqlen, Hq, Hkv, D;
     const int* cu_seqlens;       // device
     const int* cu_seqlens_host;  // host
+    // shared prefixes: prefix[s] = -1 or the index of the earlier sequence whose keys and values every token
+    // of s also attends to (device / host copies, both null when no sequence has a prefix)
+    const int* prefix = nullptr;
+    const int* prefix_host = nullptr;
     const void *Q, *K, *V, *O, *dO;  // dense [T, heads*D]
     const float* LSE;                // [T, Hq]
     float* delta;                    // scratch [T, Hq]: row sums of dO*O, produced inside launch_attn_bwd
@@ -140,12 +144,16 @@ int launch_attn_bwd(const AttnArgs& a, hipStream_t stream);
 int launch_attn_bwd_generic(const AttnArgs& a, hipStream_t stream);
 bool attn_mfma_supported(const AttnArgs& a);
 int launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t stream);
+static constexpr int kMaxPrefixSeqs = 4096;  // sequences per batch when prefixes are shared
+double attn_pairs(int n_seqs, const int* cu_host, const int* prefix_host);
+// forward: writes O [T,Hq*D] and LSE [T,Hq] for the query rows of sequences seq_begin .. n_seqs-1 (keys and
+// values of a prefix sequence are read wherever it lies); prefix / prefix_host as in AttnArgs
 int launch_attn_fwd_generic(alch_dtype dt, const void* Q, const void* K, const void* V, void* O, float* LSE, int T,
-                            int n_seqs, const int* cu_seqlens, int Hq, int Hkv, int D, hipStream_t stream);
-// forward: writes O [T,Hq*D] and LSE [T,Hq]
+                            int n_seqs, const int* cu_seqlens, const int* cu_seqlens_host, const int* prefix,
+                            int seq_begin, int Hq, int Hkv, int D, hipStream_t stream);
 int launch_attn_fwd(alch_dtype dt, const void* Q, const void* K, const void* V, void* O, float* LSE, int T,
-                    int n_seqs, int max_seqlen, const int* cu_seqlens, const int* cu_seqlens_host, int Hq,
-                    int Hkv, int D, hipStream_t stream);
+                    int n_seqs, int max_seqlen, const int* cu_seqlens, const int* cu_seqlens_host, const int* prefix,
+                    const int* prefix_host, int seq_begin, int Hq, int Hkv, int D, hipStream_t stream);
 
 // ---- LM head + cross-entropy ---------------------------------------------------------------
 // n_counted[0] = #{t : labels[t] >= 0 and (mask == NULL or mask[t] != 0)}; row_loss[0..T) = 0

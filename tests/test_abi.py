@@ -166,6 +166,28 @@ def test_lora_entry_points_reject_bad_arguments():
     assert L.alch_stack_backward_lora(*sargs(None)) == -1
 
 
+def test_shared_prefix_batch_validation():
+    L = A.lib()
+    P = 0x10000
+    s = A.make_shape(256, 4, 4, 64, 1024, 1e-6, 1e4, "f32")
+    w, g = B.CWeights(*([P] * 9), 0), B.CWgrads(*([None] * 9), 0)
+    sv = B.CSaved(*([P] * 9), 0)
+    cu = np.asarray([0, 4, 6, 9], dtype=np.int32)
+
+    def call(prefix, positions=P, dev=P):
+        pre = None if prefix is None else np.asarray(prefix, dtype=np.int32)
+        b = B.CBatch(3, 9, 4, P, positions, cu.ctypes.data, dev if pre is not None else None,
+                     None if pre is None else pre.ctypes.data)
+        return L.alch_layer_backward(C.byref(s), C.byref(b), C.byref(sv), C.byref(w), P, None, P, C.byref(g), P, 1024, None)
+
+    assert call([-1, 0, 0]) == -3                      # valid: stops at the workspace check
+    assert call([-1, 0, 0], positions=None) == -1 and "positions" in _err()
+    assert call([-1, 1, 0]) == -2 and "earlier" in _err()       # a prefix must come before
+    assert call([-1, 0, 1]) == -2 and "prefix itself" in _err()  # and have no prefix of its own
+    assert call([-2, 0, 0]) == -2
+    assert call([-1, 0, 0], dev=None) == -1            # device and host copies go together
+
+
 def test_six_stream_record_passes_validation_but_missing_required_tensors_do_not():
     L = A.lib()
     P = 0x10000
