@@ -292,6 +292,39 @@ size_t alch_stack_backward_lora_workspace_bytes(const alch_layer_shape* shape, i
                                                 int32_t total_tokens, int32_t max_seqlen, int32_t rank);
 
 /*
+ * alch_stack_backward_dpo: alch_stack_backward[_lora] with the DPO loss (Section 6: the example loss of
+ * preference alignment) in place of cross-entropy, for batches whose responses share the saved prefill of
+ * their prompt (batch->seq_prefix, Section 4.1).
+ *
+ * A scored token is an item m: the log-probability of item_label[m] under the LM-head row computed from
+ * stack-output row item_row[m] adds to pi[item_slot[m]]; slots 2p and 2p+1 are the chosen and the rejected
+ * response of pair p.  The first token of a response is scored from the last row of its prompt, so that
+ * row carries one item per response.  With
+ *     z_p = beta * [(pi[2p] - ref_logp[2p]) - (pi[2p+1] - ref_logp[2p+1])]
+ * the loss is the mean over pairs of -log sigmoid(z_p); ref_logp are the same sums under the frozen
+ * reference model (an input).  Items with a label outside 0..vocab-1 or a slot outside 0..2*n_pairs-1
+ * score nothing.  item_row must be ascending (equal rows adjacent); item_row_host is its host copy, used
+ * for validation.  n_items <= total_tokens.  z_out (device [n_pairs]) may be NULL.
+ * lora / lora_grads may be NULL (no adapters); every other argument and the workspace size are those of
+ * alch_stack_backward_lora (alch_stack_backward when lora == NULL).
+ */
+typedef struct {
+    int32_t n_items, n_pairs;
+    const int32_t *item_row, *item_label, *item_slot; /* device [n_items] */
+    const int32_t* item_row_host;                      /* host [n_items] */
+    const float* ref_logp;                             /* device [2*n_pairs] */
+    float beta;
+    float* z_out;                                      /* device [n_pairs] or NULL */
+} alch_dpo;
+
+int alch_stack_backward_dpo(const alch_layer_shape* shape, int32_t n_layers, int32_t vocab,
+                            const alch_batch* batch, const alch_saved* saved, const alch_weights* weights,
+                            const alch_lora* lora, const void* X_final, const void* g_final, const void* W_lm,
+                            const alch_dpo* dpo, const alch_wgrads* wgrads, const alch_lora_grads* lora_grads,
+                            void* dg_final, void* dW_lm, void* dX_embed, float* loss_out, const alch_hooks* hooks,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * alch_layer_forward: the forward pass of one layer, writing Y and the full record.
  * It is the producer side of the record (what serving prefill computes, Section 4.1) and
  * the "recompute" leg of the comparison in Section 6; record_out members are written,

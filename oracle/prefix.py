@@ -201,3 +201,24 @@ def stack_backward_dpo(shape, cu_seqlens, prefix, recs, layers_W, X_final, g_fin
         dX = g["dX"]
         per_layer[l] = g
     return dict(loss=loss, z=z, dX_embed=dX, dg_final=dg_final, dW_lm=dW_lm, layers=per_layer)
+
+
+def stack_backward_dpo_lora(shape, cu_seqlens, prefix, recs, layers_W, layers_lora, scale, X_final, g_final, W_lm,
+                            item_row, item_label, item_slot, ref_logp, beta):
+    """stack_backward_dpo for layers that carry low-rank adapters (Section 6: the evaluated models carry a
+    rank-8 adapter).  Same definition as the adapter oracle of the plain layer: the adapted projection is the
+    plain one at W' = W + scale * B A, so dA = scale * B^T dW', dB = scale * dW' A^T with dW' the weight
+    gradient of the shared-prefix layer at W'.  The head carries no adapter."""
+    from .lora import merged_weights
+    loss, dX, dg_final, dW_lm, z = dpo_head(shape, X_final, g_final, W_lm, item_row, item_label, item_slot,
+                                            ref_logp, beta)
+    per_layer = [None] * len(layers_W)
+    for l in range(len(layers_W) - 1, -1, -1):
+        g = layer_backward_reuse_prefix(shape, cu_seqlens, prefix, recs[l], merged_weights(layers_W[l], layers_lora[l], scale), dX)
+        for p, (A, B) in layers_lora[l].items():
+            dWm = g["dW" + p]
+            g["dA" + p] = scale * np.asarray(B, dtype=np.float64).T @ dWm
+            g["dB" + p] = scale * dWm @ np.asarray(A, dtype=np.float64).T
+        dX = g["dX"]
+        per_layer[l] = g
+    return dict(loss=loss, z=z, dX_embed=dX, dg_final=dg_final, dW_lm=dW_lm, layers=per_layer)

@@ -142,6 +142,12 @@ def lib():
     L.alch_layer_forward.restype = C.c_int
     L.alch_layer_forward.argtypes = [C.POINTER(LayerShape), C.POINTER(CBatch), C.c_void_p, C.POINTER(CWeights),
                                      C.c_void_p, C.POINTER(CRecordOut), C.c_void_p, C.c_size_t, C.c_void_p]
+    L.alch_stack_backward_dpo.restype = C.c_int
+    L.alch_stack_backward_dpo.argtypes = [C.POINTER(LayerShape), C.c_int32, C.c_int32, C.POINTER(CBatch),
+                                          C.POINTER(CSaved), C.POINTER(CWeights), C.POINTER(CLora), C.c_void_p,
+                                          C.c_void_p, C.c_void_p, C.POINTER(CDpo), C.POINTER(CWgrads),
+                                          C.POINTER(CLoraGrads), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.POINTER(CHooks), C.c_void_p, C.c_size_t, C.c_void_p]
     L.alch_layer_forward_from.restype = C.c_int
     L.alch_layer_forward_from.argtypes = [C.POINTER(LayerShape), C.POINTER(CBatch), C.c_int32, C.c_void_p,
                                           C.POINTER(CWeights), C.c_void_p, C.POINTER(CRecordOut), C.c_void_p,
@@ -416,6 +422,76 @@ def alch_stack_backward_lora(shape, batch, saved_layers, weights_layers, lora_la
         d.update(lg)
         layers.append(d)
     return dict(loss=loss, dX_embed=dX_embed, dg_final=dg_final, dW_lm=dW_lm, layers=layers)
+
+
+class CDpo(C.Structure):
+    _fields_ = [("n_items", C.c_int32), ("n_pairs", C.c_int32), ("item_row", C.c_void_p), ("item_label", C.c_void_p),
+                ("item_slot", C.c_void_p), ("item_row_host", C.c_void_p), ("ref_logp", C.c_void_p), ("beta", C.c_float),
+                ("z_out", C.c_void_p)]
+
+
+def alch_stack_backward_dpo(shape, batch, saved_layers, weights_layers, X_final, g_final, W_lm, item_row, item_label,
+                            item_slot, ref_logp, beta, lora_layers=None, rank=0, scale=1.0, want=WEIGHT_KEYS,
+                            want_head=True, lora_grads_layers=None, grads_layers=None, accumulate=False, hooks=None,
+                            workspace=None, stream=None):
+    """Stack backward under the DPO loss.  item_row / item_label / item_slot: int32 numpy arrays, one entry per
+    scored token, rows ascending; ref_logp: float32 [2 * n_pairs] (numpy or device tensor).  lora_layers: None, or
+    per layer a dict projection -> (A, B).  Returns the dict of alch_stack_backward plus z (device [n_pairs])."""
+    L = lib()
+    dev = X_final.device
+    n_layers = len(saved_layers)
+    vocab = W_lm.shape[0]
+    rows_host = np.ascontiguousarray(item_row, dtype=np.int32)
+    n_items = int(rows_host.shape[0])
+    i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
+    d_row, d_label, d_slot = i32(rows_host), i32(item_label), i32(item_slot)
+    ref = ref_logp if torch.is_tensor(ref_logp) else torch.from_numpy(np.ascontiguousarray(ref_logp, dtype=np.float32)).to(dev)
+    n_pairs = int(ref.numel() // 2)
+    z = torch.empty(max(n_pairs, 1), dtype=torch.float32, device=dev)
+    dpo = CDpo(n_items, n_pairs, d_row.data_ptr(), d_label.data_ptr(), d_slot.data_ptr(), rows_host.ctypes.data,
+               ref.data_ptr(), beta, z.data_ptr())
+    if grads_layers is None:
+        grads_layers = [{"d" + k: torch.empty_like(w[k]) for k in want} for w in weights_layers]
+    n = max(n_layers, 1)
+    SA = (CSaved * n)(*[_saved_struct(s_, 0) for s_ in saved_layers])
+    WA = (CWeights * n)(*[_weights_struct(w, 0) for w in weights_layers])
+    GA = (CWgrads * n)(*[_wgrads_struct(g, accumulate) for g in grads_layers])
+    LA = LG = None
+    if lora_layers is not None:
+        if lora_grads_layers is None:
+            lora_grads_layers = []
+            for lo in lora_layers:
+                g = {}
+                for p_, (A_, B_) in lo.items():
+                    g["dA" + p_], g["dB" + p_] = torch.empty_like(A_), torch.empty_like(B_)
+                lora_grads_layers.append(g)
+        pairs = [_lora_structs(lo, lg, rank, scale, accumulate) for lo, lg in zip(lora_layers, lora_grads_layers)]
+        LA = (CLora * n)(*[p_[0] for p_ in pairs])
+        LG = (CLoraGrads * n)(*[p_[1] for p_ in pairs])
+        need = L.alch_stack_backward_lora_workspace_bytes(C.byref(shape), n_layers, vocab, batch.total_tokens,
+                                                          batch.max_seqlen, rank)
+    else:
+        need = L.alch_stack_backward_workspace_bytes(C.byref(shape), n_layers, vocab, batch.total_tokens, batch.max_seqlen)
+    dg_final = torch.empty_like(g_final) if want_head else None
+    dW_lm = torch.empty_like(W_lm) if want_head else None
+    dX_embed = torch.empty_like(X_final)
+    loss = torch.empty(1, dtype=torch.float32, device=dev)
+    ws = workspace if workspace is not None else _workspace(need, dev)
+    hk = None
+    if hooks is not None:
+        ready, preempt = hooks
+        hk = CHooks(HOOK_FN(ready) if ready else HOOK_FN(), HOOK_FN(preempt) if preempt else HOOK_FN(), None)
+    _check(L.alch_stack_backward_dpo(C.byref(shape), n_layers, vocab, C.byref(batch.c), SA, WA, LA, _ptr(X_final),
+                                     _ptr(g_final), _ptr(W_lm), C.byref(dpo), GA, LG, _ptr(dg_final), _ptr(dW_lm),
+                                     _ptr(dX_embed), _ptr(loss), C.byref(hk) if hk else None, _ptr(ws), ws.numel(),
+                                     _stream_handle(stream)))
+    layers = []
+    for i, g in enumerate(grads_layers):
+        d = dict(g)
+        if lora_grads_layers is not None:
+            d.update(lora_grads_layers[i])
+        layers.append(d)
+    return dict(loss=loss, z=z[:n_pairs], dX_embed=dX_embed, dg_final=dg_final, dW_lm=dW_lm, layers=layers)
 
 
 def alch_gemm(M, N, terms, a_kmajor, b_kmajor, out=None, accumulate=False, stream=None):

@@ -13,7 +13,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "lib", "libalch.so")
 SOURCES = ["api.hip", "pack.hip", "gemm_mfma.hip", "gemm_generic.hip", "rowops.hip", "attn_generic.hip",
-           "attn_mfma.hip", "lmhead.hip", "lora.hip"]
+           "attn_mfma.hip", "lmhead.hip", "lora.hip", "dpo.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-inline-asm", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]

@@ -193,6 +193,8 @@ struct StackPlan {
     uint8_t* h_counted;
     void *h_Hf, *h_dHf, *h_packws;
     int *h_labels, *h_index, *h_inv, *h_cu, *h_n, *h_chunk_rows;
+    // DPO head: log-probability and log-normaliser per item, sum and weight per slot
+    float *dpo_logp, *dpo_logz, *dpo_pi, *dpo_w;
     size_t layer_ws_bytes, bytes;
 };
 static StackPlan plan_stack(const alch_layer_shape& s, int vocab, int T, void* ws, size_t ws_bytes, int lora_rank = 0) {
@@ -218,6 +220,10 @@ static StackPlan plan_stack(const alch_layer_shape& s, int vocab, int T, void* w
     p.h_cu = static_cast<int*>(a.take(256));
     p.h_n = static_cast<int*>(a.take(256));
     p.h_chunk_rows = static_cast<int*>(a.take(((t + kHeadChunkRows - 1) / kHeadChunkRows) * sizeof(int)));
+    p.dpo_logp = static_cast<float*>(a.take(t * sizeof(float)));
+    p.dpo_logz = static_cast<float*>(a.take(t * sizeof(float)));
+    p.dpo_pi = static_cast<float*>(a.take(t * sizeof(float)));
+    p.dpo_w = static_cast<float*>(a.take(t * sizeof(float)));
     p.layer_ws_bytes = plan_layer_bwd(s, T, nullptr, 0, lora_rank).bytes;
     p.layer_ws = a.take(p.layer_ws_bytes);
     p.bytes = round_up(a.used, 256);
@@ -767,12 +773,13 @@ size_t alch_stack_backward_workspace_bytes(const alch_layer_shape* shape, int32_
     return plan_stack(*shape, vocab, total_tokens, nullptr, 0).bytes;
 }
 
+// The head is cross-entropy on `labels` (dpo == nullptr) or DPO on the scored items of `dpo`.
 static int stack_backward_impl(const alch_layer_shape* shape, int32_t n_layers, int32_t vocab, const alch_batch* batch,
                                const alch_saved* saved, const alch_weights* weights, const alch_lora* lora,
                                const void* X_final, const void* g_final, const void* W_lm, const int32_t* labels,
                                const uint8_t* loss_mask, const alch_wgrads* wgrads, const alch_lora_grads* lora_grads,
                                void* dg_final, void* dW_lm, void* dX_embed, float* loss_out, const alch_hooks* hooks,
-                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+                               void* workspace, size_t workspace_bytes, void* hip_stream, const alch_dpo* dpo = nullptr) {
     clear_error();
     ALCH_TRY(check_shape(shape));
     ALCH_TRY(check_batch(batch));
@@ -790,8 +797,21 @@ static int stack_backward_impl(const alch_layer_shape* shape, int32_t n_layers, 
     const int rank = (lora && n_layers > 0) ? lora[0].rank : 0;
     REQUIRE_ACT(X_final, "X_final", batch->total_tokens); REQUIRE_PTR(g_final, "g_final"); REQUIRE_PTR(W_lm, "W_lm");
     REQUIRE_ACT(dX_embed, "dX_embed", batch->total_tokens);
-    if ((batch->total_tokens > 0 && !labels) || !loss_out) return fail(ALCH_ERR_INVALID_ARG, "labels / loss_out is NULL");
+    if ((!dpo && batch->total_tokens > 0 && !labels) || !loss_out) return fail(ALCH_ERR_INVALID_ARG, "labels / loss_out is NULL");
     OPTIONAL_PTR(dg_final, "dg_final"); OPTIONAL_PTR(dW_lm, "dW_lm");
+    if (dpo) {
+        if (dpo->n_items < 0 || dpo->n_pairs < 0) return fail(ALCH_ERR_INVALID_ARG, "dpo: negative n_items / n_pairs");
+        if (dpo->n_items > batch->total_tokens) return fail(ALCH_ERR_SHAPE, "dpo: %d items > %d tokens", dpo->n_items, batch->total_tokens);
+        if (2 * (long long)dpo->n_pairs > batch->total_tokens) return fail(ALCH_ERR_SHAPE, "dpo: %d pairs need more slots than there are tokens", dpo->n_pairs);
+        if (dpo->n_items > 0 && (!dpo->item_row || !dpo->item_label || !dpo->item_slot || !dpo->item_row_host))
+            return fail(ALCH_ERR_INVALID_ARG, "dpo: item_row / item_label / item_slot / item_row_host is NULL");
+        if (dpo->n_pairs > 0 && !dpo->ref_logp) return fail(ALCH_ERR_INVALID_ARG, "dpo: ref_logp is NULL");
+        for (int m = 0; m < dpo->n_items; ++m) {
+            const int r = dpo->item_row_host[m];
+            if (r < 0 || r >= batch->total_tokens) return fail(ALCH_ERR_SHAPE, "dpo: item_row[%d] = %d outside the batch", m, r);
+            if (m > 0 && r < dpo->item_row_host[m - 1]) return fail(ALCH_ERR_SHAPE, "dpo: item_row is not ascending at item %d", m);
+        }
+    }
     const size_t need = plan_stack(*shape, vocab, batch->total_tokens, nullptr, 0, rank).bytes;
     if (!workspace || workspace_bytes < need) return fail(ALCH_ERR_WORKSPACE, "workspace %zu bytes < %zu needed", workspace_bytes, need);
     if (!aligned16(workspace)) return fail(ALCH_ERR_INVALID_ARG, "workspace is not 16-byte aligned");
@@ -804,65 +824,119 @@ static int stack_backward_impl(const alch_layer_shape* shape, int32_t n_layers, 
     const int T = batch->total_tokens, H = s.hidden;
     const int acc = wgrads ? (wgrads[0].accumulate != 0) : 0;
 
-    // LM head + cross-entropy in row chunks: logits -> dlogits in place, never stored whole.
-    // With a loss mask (bf16, matrix-core shapes) only the counted tokens -- label >= 0 and mask byte nonzero --
-    // go through the head: their Hf rows and labels are gathered, the three products and the cross-entropy
-    // take their row counts from device memory, and dHf is scattered back into a zero-filled [T, H].
-    const bool compact_head = loss_mask && T > 0 && dt == ALCH_BF16 && H % 64 == 0 && vocab % 64 == 0;
-    ALCH_TRY(launch_count_labels(labels, loss_mask, T, p.n_counted, p.row_loss, st));
-    ALCH_TRY(launch_rmsnorm_fwd(dt, X_final, g_final, p.Hf, T, H, s.rms_eps, st));
-    const void* head_in = p.Hf;
-    void* head_out = p.dHf;
-    const int* head_labels = labels;
-    const uint8_t* head_mask = loss_mask;
-    if (compact_head) {
-        ALCH_TRY(launch_counted_mask(labels, loss_mask, T, p.h_counted, st));
-        const alch_stream rows1[1] = {{p.Hf, p.h_Hf, (size_t)H * E, (size_t)H * E}};
-        ALCH_TRY(launch_pack(p.h_counted, T, batch->cu_seqlens, 0, 1, rows1, T, p.h_index, p.h_cu, p.h_n, p.h_packws, st, false));
-        ALCH_TRY(launch_gather_int(labels, p.h_index, p.h_n, p.h_labels, T, st));
-        ALCH_TRY(launch_rank_of_kept(p.h_index, p.h_n, p.h_inv, T, st));
-        ALCH_TRY(launch_chunk_rows(p.h_n, ceil_div(T, kHeadChunkRows), kHeadChunkRows, p.h_chunk_rows, st));
-        head_in = p.h_Hf; head_out = p.h_dHf; head_labels = p.h_labels; head_mask = nullptr;
-    }
-    bool first = true;
-    for (int r0 = 0; r0 < T; r0 += kHeadChunkRows) {
-        const int rows = T - r0 < kHeadChunkRows ? T - r0 : kHeadChunkRows;
-        const int* rows_dev = compact_head ? p.h_chunk_rows + r0 / kHeadChunkRows : nullptr;
-        const void* hf = at(head_in, (size_t)r0 * H, E);
-        {  // logits = Hf W_lm^T
+    bool compact_head = false;
+    if (dpo) {
+        // DPO head: the stack-output rows of the scored tokens are gathered into [n_items, H]; pass 1 turns each
+        // chunk of their logits into log-probabilities, the slot sums give z, the loss and a weight per slot;
+        // pass 2 forms the logits gradient (recomputing the logits unless one chunk holds them all) and the two
+        // products; the row gradients are summed back into a zero-filled [T, H] (a row may score several tokens).
+        const int M = dpo->n_items, n_slots = 2 * dpo->n_pairs;
+        ALCH_TRY(launch_rmsnorm_fwd(dt, X_final, g_final, p.Hf, T, H, s.rms_eps, st));
+        if (M > 0) ALCH_TRY(launch_scatter_rows(p.Hf, dpo->item_row, p.h_Hf, M, (size_t)H * E, st));  // h_Hf[m] = Hf[item_row[m]]
+        const bool one_chunk = M <= kHeadChunkRows;
+        auto logits_of = [&](int r0, int rows) {
             GemmDesc d = gemm(dt, rows, vocab, true, true);
-            add_seg(d, hf, H, W_lm, H, H);
+            add_seg(d, at(p.h_Hf, (size_t)r0 * H, E), H, W_lm, H, H);
             add_out(d, p.logits, 0, vocab);
-            d.m_dev = rows_dev;
-            ALCH_TRY(launch_gemm(d, st));
+            return launch_gemm(d, st);
+        };
+        for (int r0 = 0; r0 < M; r0 += kHeadChunkRows) {
+            const int rows = M - r0 < kHeadChunkRows ? M - r0 : kHeadChunkRows;
+            ALCH_TRY(logits_of(r0, rows));
+            ALCH_TRY(launch_dpo_logp(dt, p.logits, vocab, rows, vocab, dpo->item_label + r0, p.dpo_logp + r0, p.dpo_logz + r0, st));
         }
-        ALCH_TRY(launch_ce_chunk(dt, p.logits, vocab, rows, vocab, head_labels + r0, head_mask ? head_mask + r0 : nullptr,
-                                 p.n_counted, p.row_loss + r0, st, rows_dev));
-        {  // dHf = dlogits W_lm
-            GemmDesc d = gemm(dt, rows, H, true, false);
-            add_seg(d, p.logits, vocab, W_lm, H, vocab);
-            add_out(d, const_cast<char*>(at(head_out, (size_t)r0 * H, E)), 0, H);
-            d.m_dev = rows_dev;
-            ALCH_TRY(launch_gemm(d, st));
+        ALCH_TRY(launch_dpo_weights(p.dpo_logp, dpo->item_slot, dpo->item_label, M, vocab, dpo->ref_logp, dpo->n_pairs,
+                                    dpo->beta, p.dpo_pi, p.dpo_w, dpo->z_out, loss_out, st));
+        bool first = true;
+        for (int r0 = 0; r0 < M; r0 += kHeadChunkRows) {
+            const int rows = M - r0 < kHeadChunkRows ? M - r0 : kHeadChunkRows;
+            if (!one_chunk) ALCH_TRY(logits_of(r0, rows));
+            ALCH_TRY(launch_dpo_grad(dt, p.logits, vocab, rows, vocab, dpo->item_label + r0, dpo->item_slot + r0,
+                                     p.dpo_logz + r0, p.dpo_w, n_slots, st));
+            {  // gradient of the gathered rows = dlogits W_lm
+                GemmDesc d = gemm(dt, rows, H, true, false);
+                add_seg(d, p.logits, vocab, W_lm, H, vocab);
+                add_out(d, at(p.h_dHf, (size_t)r0 * H, E), 0, H);
+                ALCH_TRY(launch_gemm(d, st));
+            }
+            if (dW_lm) {  // dW_lm (+)= dlogits^T Hf
+                GemmDesc d = gemm(dt, vocab, H, false, false);
+                add_seg(d, p.logits, vocab, at(p.h_Hf, (size_t)r0 * H, E), H, rows);
+                add_out(d, dW_lm, 0, H);
+                d.accumulate = first ? acc : 1;
+                ALCH_TRY(launch_gemm(d, st));
+            }
+            first = false;
         }
-        if (dW_lm) {  // dW_lm (+)= dlogits^T Hf
-            GemmDesc d = gemm(dt, vocab, H, false, false);
-            add_seg(d, p.logits, vocab, hf, H, rows);
+        if (M == 0 && dW_lm && !acc) {
+            GemmDesc d = gemm(dt, vocab, H, false, false);  // zero rows contracted: writes zeros
+            add_seg(d, p.logits, vocab, p.Hf, H, 0);
             add_out(d, dW_lm, 0, H);
-            d.accumulate = first ? acc : 1;
-            d.k_dev = rows_dev;
-            ALCH_TRY(launch_gemm(d, st));
+            ALCH_TRY(launch_gemm_generic(d, st));
         }
-        first = false;
+        ALCH_TRY(launch_dpo_scatter(dt, p.h_dHf, dpo->item_row, M, p.dHf, T, H, st));
+    } else {
+        // LM head + cross-entropy in row chunks: logits -> dlogits in place, never stored whole.
+        // With a loss mask (bf16, matrix-core shapes) only the counted tokens -- label >= 0 and mask byte nonzero --
+        // go through the head: their Hf rows and labels are gathered, the three products and the cross-entropy
+        // take their row counts from device memory, and dHf is scattered back into a zero-filled [T, H].
+        compact_head = loss_mask && T > 0 && dt == ALCH_BF16 && H % 64 == 0 && vocab % 64 == 0;
+        ALCH_TRY(launch_count_labels(labels, loss_mask, T, p.n_counted, p.row_loss, st));
+        ALCH_TRY(launch_rmsnorm_fwd(dt, X_final, g_final, p.Hf, T, H, s.rms_eps, st));
+        const void* head_in = p.Hf;
+        void* head_out = p.dHf;
+        const int* head_labels = labels;
+        const uint8_t* head_mask = loss_mask;
+        if (compact_head) {
+            ALCH_TRY(launch_counted_mask(labels, loss_mask, T, p.h_counted, st));
+            const alch_stream rows1[1] = {{p.Hf, p.h_Hf, (size_t)H * E, (size_t)H * E}};
+            ALCH_TRY(launch_pack(p.h_counted, T, batch->cu_seqlens, 0, 1, rows1, T, p.h_index, p.h_cu, p.h_n, p.h_packws, st, false));
+            ALCH_TRY(launch_gather_int(labels, p.h_index, p.h_n, p.h_labels, T, st));
+            ALCH_TRY(launch_rank_of_kept(p.h_index, p.h_n, p.h_inv, T, st));
+            ALCH_TRY(launch_chunk_rows(p.h_n, ceil_div(T, kHeadChunkRows), kHeadChunkRows, p.h_chunk_rows, st));
+            head_in = p.h_Hf; head_out = p.h_dHf; head_labels = p.h_labels; head_mask = nullptr;
+        }
+        bool first = true;
+        for (int r0 = 0; r0 < T; r0 += kHeadChunkRows) {
+            const int rows = T - r0 < kHeadChunkRows ? T - r0 : kHeadChunkRows;
+            const int* rows_dev = compact_head ? p.h_chunk_rows + r0 / kHeadChunkRows : nullptr;
+            const void* hf = at(head_in, (size_t)r0 * H, E);
+            {  // logits = Hf W_lm^T
+                GemmDesc d = gemm(dt, rows, vocab, true, true);
+                add_seg(d, hf, H, W_lm, H, H);
+                add_out(d, p.logits, 0, vocab);
+                d.m_dev = rows_dev;
+                ALCH_TRY(launch_gemm(d, st));
+            }
+            ALCH_TRY(launch_ce_chunk(dt, p.logits, vocab, rows, vocab, head_labels + r0, head_mask ? head_mask + r0 : nullptr,
+                                     p.n_counted, p.row_loss + r0, st, rows_dev));
+            {  // dHf = dlogits W_lm
+                GemmDesc d = gemm(dt, rows, H, true, false);
+                add_seg(d, p.logits, vocab, W_lm, H, vocab);
+                add_out(d, const_cast<char*>(at(head_out, (size_t)r0 * H, E)), 0, H);
+                d.m_dev = rows_dev;
+                ALCH_TRY(launch_gemm(d, st));
+            }
+            if (dW_lm) {  // dW_lm (+)= dlogits^T Hf
+                GemmDesc d = gemm(dt, vocab, H, false, false);
+                add_seg(d, p.logits, vocab, hf, H, rows);
+                add_out(d, dW_lm, 0, H);
+                d.accumulate = first ? acc : 1;
+                d.k_dev = rows_dev;
+                ALCH_TRY(launch_gemm(d, st));
+            }
+            first = false;
+        }
+        if (compact_head) ALCH_TRY(launch_scatter_rows(p.h_dHf, p.h_inv, p.dHf, T, (size_t)H * E, st));
+        if (T == 0 && dW_lm && !acc) {
+            GemmDesc d = gemm(dt, vocab, H, false, false);  // zero rows contracted: writes zeros
+            add_seg(d, p.logits, vocab, p.Hf, H, 0);
+            add_out(d, dW_lm, 0, H);
+            ALCH_TRY(launch_gemm_generic(d, st));
+        }
+        ALCH_TRY(launch_finish_loss(p.row_loss, p.n_counted, loss_out, T, st));
+
     }
-    if (compact_head) ALCH_TRY(launch_scatter_rows(p.h_dHf, p.h_inv, p.dHf, T, (size_t)H * E, st));
-    if (T == 0 && dW_lm && !acc) {
-        GemmDesc d = gemm(dt, vocab, H, false, false);  // zero rows contracted: writes zeros
-        add_seg(d, p.logits, vocab, p.Hf, H, 0);
-        add_out(d, dW_lm, 0, H);
-        ALCH_TRY(launch_gemm_generic(d, st));
-    }
-    ALCH_TRY(launch_finish_loss(p.row_loss, p.n_counted, loss_out, T, st));
 
     // final RMSNorm backward -> gradient w.r.t. the last layer's output
     void* cur = n_layers == 0 ? dX_embed : p.ping;
@@ -918,6 +992,21 @@ int alch_stack_backward_lora(const alch_layer_shape* shape, int32_t n_layers, in
     return stack_backward_impl(shape, n_layers, vocab, batch, saved, weights, lora, X_final, g_final, W_lm, labels,
                                loss_mask, wgrads, lora_grads, dg_final, dW_lm, dX_embed, loss_out, hooks, workspace,
                                workspace_bytes, hip_stream);
+}
+
+int alch_stack_backward_dpo(const alch_layer_shape* shape, int32_t n_layers, int32_t vocab, const alch_batch* batch,
+                            const alch_saved* saved, const alch_weights* weights, const alch_lora* lora,
+                            const void* X_final, const void* g_final, const void* W_lm, const alch_dpo* dpo,
+                            const alch_wgrads* wgrads, const alch_lora_grads* lora_grads, void* dg_final, void* dW_lm,
+                            void* dX_embed, float* loss_out, const alch_hooks* hooks, void* workspace,
+                            size_t workspace_bytes, void* hip_stream) {
+    if (!dpo) {
+        clear_error();
+        return fail(ALCH_ERR_INVALID_ARG, "dpo is NULL");
+    }
+    return stack_backward_impl(shape, n_layers, vocab, batch, saved, weights, lora, X_final, g_final, W_lm, nullptr,
+                               nullptr, wgrads, lora ? lora_grads : nullptr, dg_final, dW_lm, dX_embed, loss_out, hooks,
+                               workspace, workspace_bytes, hip_stream, dpo);
 }
 
 int alch_attention_forward(const alch_layer_shape* shape, const alch_batch* batch, const void* Q, const void* K,

@@ -169,6 +169,20 @@ int launch_counted_mask(const int* labels, const uint8_t* loss_mask, int T, uint
 int launch_chunk_rows(const int* n_rows, int n_chunks, int chunk, int* chunk_rows, hipStream_t stream);
 // dst[r] = src[index[r]] for r < min(*n_rows, T)
 int launch_gather_int(const int* src, const int* index, const int* n_rows, int* dst, int T, hipStream_t stream);
+// ---- DPO head on scored tokens (items) -----------------------------------------------------
+// logp[m], logz[m] of a chunk of item logits rows
+int launch_dpo_logp(alch_dtype dt, const void* logits, long long ld, int rows, int vocab, const int* labels, float* logp,
+                    float* logz, hipStream_t stream);
+// pi[slot] = sum of logp; z, loss, weight of every slot (w_slot [2 n_pairs]); z_out may be null
+int launch_dpo_weights(const float* logp, const int* slots, const int* labels, int n_items, int vocab, const float* ref,
+                       int n_pairs, float beta, float* pi, float* w_slot, float* z_out, float* loss_out, hipStream_t stream);
+// a chunk of item logits rows -> their gradient, in place
+int launch_dpo_grad(alch_dtype dt, void* logits, long long ld, int rows, int vocab, const int* labels, const int* slots,
+                    const float* logz, const float* w_slot, int n_slots, hipStream_t stream);
+// out [T, width] = 0, then out[item_row[m]] += src[m] (items sorted by row; fixed order)
+int launch_dpo_scatter(alch_dtype dt, const void* src, const int* item_row, int n_items, void* out, int T, int width,
+                       hipStream_t stream);
+
 // loss_out[0] = sum(row_loss) / max(N, 1)   (fixed summation order)
 int launch_finish_loss(const float* row_loss, const int* n_counted, float* loss_out, int T, hipStream_t stream);
 

@@ -99,3 +99,125 @@ def test_whole_batch_forward_with_prefixes_equals_the_oracle():
     assert rel_err(to_np(Y), Y64) <= TOL[dtype]
     for k in REC + ("LSE",):
         assert rel_err(to_np(drec[k]), rec64[k]) <= TOL[dtype], k
+
+
+# ---- DPO head and the stack under it ------------------------------------------------------------
+from oracle.prefix import stack_forward_prefix, stack_backward_dpo
+
+
+def make_dpo_stack(dtype, shape_name, prompts, responses, L, V, seed):
+    shp = synth.shape_dict(shape_name)
+    osh = oracle_shape(shp)
+    b = synth.preference_batch(prompts, responses, V, seed)
+    T = int(b["cu"][-1])
+    wstd = 0.3 if shape_name == "tiny" else 0.05
+    Ws = [synth.layer_weights(shp, seed + 10 * l, dtype, std=wstd, gain_std=0.1) for l in range(L)]
+    rng = np.random.default_rng(seed + 1000)
+    X0 = synth.normal(rng, (T, shp["hidden"]), 1.0, dtype)
+    gf = synth.quantize(1.0 + 0.1 * rng.standard_normal(shp["hidden"]).astype(np.float32), dtype)
+    Wlm = synth.normal(rng, (V, shp["hidden"]), wstd, dtype)
+    n_slots = sum(len(r) for r in responses)
+    ref = rng.normal(-3.0, 1.0, n_slots).astype(np.float32)
+    Xf64, recs64 = stack_forward_prefix(osh, b["cu"], b["prefix"], X0.astype(np.float64), [f64(W) for W in Ws])
+    recs = []
+    for r in recs64:
+        q = {k: synth.quantize(r[k].astype(np.float32), dtype) for k in REC}
+        q["LSE"] = r["LSE"].astype(np.float32)
+        recs.append(q)
+    Xf = synth.quantize(Xf64.astype(np.float32), dtype)
+    return shp, osh, b, Ws, recs, Xf, gf, Wlm, ref
+
+
+@pytest.mark.parametrize("dtype,shape_name,prompts,responses,V", [
+    ("f32", "tiny", [4, 3], [[3, 2], [2, 5]], 53),
+    ("bf16", "medium", [150, 70], [[60, 33], [129, 20]], 1024),
+    ("bf16", "medium64", [90], [[40, 40]], 512)])
+def test_stack_backward_dpo_matches_oracle(dtype, shape_name, prompts, responses, V):
+    import paper_2503_01066_amd as A
+    L, beta = 2, 0.5
+    shp, osh, b, Ws, recs, Xf, gf, Wlm, ref = make_dpo_stack(dtype, shape_name, prompts, responses, L, V, 3)
+    want = stack_backward_dpo(osh, b["cu"], b["prefix"], [f64(r) for r in recs], [f64(W) for W in Ws], Xf.astype(np.float64),
+                              gf.astype(np.float64), Wlm.astype(np.float64), b["item_row"], b["item_label"], b["item_slot"],
+                              ref.astype(np.float64), beta)
+    batch = A.Batch(b["cu"], positions=b["positions"], prefix=b["prefix"])
+    out = A.alch_stack_backward_dpo(alch_shape(shp, dtype), batch, [dev_record(r, dtype) for r in recs],
+                                    [{k: to_dev(v, dtype) for k, v in W.items()} for W in Ws], to_dev(Xf, dtype),
+                                    to_dev(gf, dtype), to_dev(Wlm, dtype), b["item_row"], b["item_label"], b["item_slot"],
+                                    ref, beta)
+    torch.cuda.synchronize()
+    tol = TOL[dtype]
+    # z and the loss come from sums of log-probabilities over up to a hundred tokens: absolute bar on that scale
+    zscale = max(1.0, np.abs(want["z"]).max())
+    assert np.abs(to_np(out["z"]) - want["z"]).max() <= tol * zscale * 5, (to_np(out["z"]), want["z"])
+    assert abs(out["loss"].item() - want["loss"]) <= tol * max(1.0, abs(want["loss"])) * 5
+    for k in ("dX_embed", "dg_final", "dW_lm"):
+        assert rel_err(to_np(out[k]), want[k]) <= tol * (3 if dtype == "bf16" else 1), (k, rel_err(to_np(out[k]), want[k]))
+    for l in range(L):
+        for k in WEIGHT_KEYS:
+            e = rel_err(to_np(out["layers"][l]["d" + k]), want["layers"][l]["d" + k])
+            assert e <= tol * (3 if dtype == "bf16" else 1), (l, k, e)
+
+
+def test_dpo_without_pairs_gives_zero():
+    import paper_2503_01066_amd as A
+    dtype = "f32"
+    shp, osh, b, Ws, recs, Xf, gf, Wlm, ref = make_dpo_stack(dtype, "tiny", [4], [[]], 1, 17, 1)
+    batch = A.Batch(b["cu"], positions=b["positions"], prefix=b["prefix"])
+    out = A.alch_stack_backward_dpo(alch_shape(shp, dtype), batch, [dev_record(r, dtype) for r in recs],
+                                    [{k: to_dev(v, dtype) for k, v in W.items()} for W in Ws], to_dev(Xf, dtype),
+                                    to_dev(gf, dtype), to_dev(Wlm, dtype), b["item_row"], b["item_label"], b["item_slot"],
+                                    np.zeros(0, np.float32), 0.5)
+    torch.cuda.synchronize()
+    assert out["loss"].item() == 0.0
+    for k in ("dX_embed", "dg_final", "dW_lm"):
+        assert float(out[k].abs().max()) == 0.0, k
+
+
+def test_stack_backward_dpo_with_adapters_on_a_frozen_base():
+    # the paper's training setting (Section 6): rank-8 adapters, frozen base and head, DPO loss
+    import paper_2503_01066_amd as A
+    from oracle.lora import merged_weights
+    from oracle.prefix import stack_backward_dpo_lora
+    dtype, L, V, beta, rank, scale = "bf16", 2, 1024, 0.5, 8, 2.0
+    shp = synth.shape_dict("medium")
+    osh = oracle_shape(shp)
+    b = synth.preference_batch([150, 70], [[60, 33], [129, 20]], V, 4)
+    T = int(b["cu"][-1])
+    Ws = [synth.layer_weights(shp, 4 + 10 * l, dtype, std=0.05, gain_std=0.1) for l in range(L)]
+    loras = [synth.lora_adapters(shp, rank, 70 + l, dtype, projections=pj) for l, pj in
+             enumerate((synth.PROJECTIONS, ("q", "v", "d")))]
+    rng = np.random.default_rng(1004)
+    X0 = synth.normal(rng, (T, shp["hidden"]), 1.0, dtype)
+    gf = synth.quantize(1.0 + 0.1 * rng.standard_normal(shp["hidden"]).astype(np.float32), dtype)
+    Wlm = synth.normal(rng, (V, shp["hidden"]), 0.05, dtype)
+    ref = rng.normal(-3.0, 1.0, 4).astype(np.float32)
+    merged = [merged_weights(f64(W), {p: (a.astype(np.float64), bb.astype(np.float64)) for p, (a, bb) in lo.items()}, scale)
+              for W, lo in zip(Ws, loras)]
+    Xf64, recs64 = stack_forward_prefix(osh, b["cu"], b["prefix"], X0.astype(np.float64), merged)
+    recs = []
+    for r in recs64:
+        q = {k: synth.quantize(r[k].astype(np.float32), dtype) for k in REC}
+        q["LSE"] = r["LSE"].astype(np.float32)
+        recs.append(q)
+    Xf = synth.quantize(Xf64.astype(np.float32), dtype)
+    lo64 = [{p: (a.astype(np.float64), bb.astype(np.float64)) for p, (a, bb) in lo.items()} for lo in loras]
+    want = stack_backward_dpo_lora(osh, b["cu"], b["prefix"], [f64(r) for r in recs], [f64(W) for W in Ws], lo64, scale,
+                                   Xf.astype(np.float64), gf.astype(np.float64), Wlm.astype(np.float64), b["item_row"],
+                                   b["item_label"], b["item_slot"], ref.astype(np.float64), beta)
+    batch = A.Batch(b["cu"], positions=b["positions"], prefix=b["prefix"])
+    dlo = [{p: (to_dev(a, dtype), to_dev(bb, dtype)) for p, (a, bb) in lo.items()} for lo in loras]
+    out = A.alch_stack_backward_dpo(alch_shape(shp, dtype), batch, [dev_record(r, dtype) for r in recs],
+                                    [{k: to_dev(v, dtype) for k, v in W.items()} for W in Ws], to_dev(Xf, dtype),
+                                    to_dev(gf, dtype), to_dev(Wlm, dtype), b["item_row"], b["item_label"], b["item_slot"],
+                                    ref, beta, lora_layers=dlo, rank=rank, scale=scale, want=(), want_head=False)
+    torch.cuda.synchronize()
+    tol = TOL[dtype] * 3
+    assert abs(out["loss"].item() - want["loss"]) <= tol * max(1.0, abs(want["loss"]))
+    assert out["dW_lm"] is None and out["dg_final"] is None
+    assert rel_err(to_np(out["dX_embed"]), want["dX_embed"]) <= tol
+    for l, lo in enumerate(loras):
+        assert not any(k.startswith("dW") for k in out["layers"][l])
+        for p in lo:
+            for k in ("dA" + p, "dB" + p):
+                e = rel_err(to_np(out["layers"][l][k]), want["layers"][l][k])
+                assert e <= tol, (l, k, e)

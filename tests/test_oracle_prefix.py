@@ -233,3 +233,44 @@ def test_stack_dpo_finite_differences_through_the_shared_prompt():
             fm = loss()
             Pm[i] = old
             assert abs((fp - fm) / (2 * h) - an[i]) <= 1e-5 * ref_mag, i
+
+
+def test_stack_dpo_adapter_gradients_by_finite_differences():
+    # adapters on both layers; the loss is evaluated by the shared-prefix forward at the merged weights
+    from oracle.lora import merged_weights
+    from oracle.prefix import stack_backward_dpo_lora
+    rng = np.random.default_rng(18)
+    b, _, gf, Wlm, ref = head_case(7)
+    cu, prefix = b["cu"], b["prefix"]
+    T = int(cu[-1])
+    Ws = [weights(rng, SHAPE), weights(rng, SHAPE)]
+    r = 2
+    loras = [{p: (rng.normal(0, 0.4, (r, W["W" + p].shape[1])), rng.normal(0, 0.4, (W["W" + p].shape[0], r)))
+              for p in proj} for W, proj in zip(Ws, (("q", "k", "d"), ("v", "o", "g", "u")))]
+    X0 = rng.normal(size=(T, 16))
+    items = (b["item_row"], b["item_label"], b["item_slot"])
+    scale = 0.6
+
+    def forward():
+        return stack_forward_prefix(SHAPE, cu, prefix, X0, [merged_weights(W, lo, scale) for W, lo in zip(Ws, loras)])
+
+    def loss():
+        return dpo_head(SHAPE, forward()[0], gf, Wlm, *items, ref, 0.5)[0]
+
+    Xf, recs = forward()
+    g = stack_backward_dpo_lora(SHAPE, cu, prefix, recs, Ws, loras, scale, Xf, gf, Wlm, *items, ref, 0.5)
+    h = 1e-5
+    for l, lo in enumerate(loras):
+        for p, (A, B) in lo.items():
+            for name, Pm in (("dA" + p, A), ("dB" + p, B)):
+                an = g["layers"][l][name]
+                ref_mag = max(np.abs(an).max(), 1e-30)
+                idx = list(np.ndindex(*Pm.shape))
+                for i in [idx[k] for k in rng.choice(len(idx), min(8, len(idx)), replace=False)]:
+                    old = Pm[i]
+                    Pm[i] = old + h
+                    fp = loss()
+                    Pm[i] = old - h
+                    fm = loss()
+                    Pm[i] = old
+                    assert abs((fp - fm) / (2 * h) - an[i]) <= 1e-5 * ref_mag, (l, name, i)
