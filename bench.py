@@ -33,7 +33,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config2", choices=["config2", "config3", "config4", "config5", "copy"])
+    ap.add_argument("--workload", default="config2", choices=["config2", "config3", "config4", "config5", "dpo", "copy"])
     ap.add_argument("--layers", type=int, default=32, help="config4: number of layers")
     ap.add_argument("--loss-mask", action="store_true", help="config5: zero dY rows with a Bernoulli(0.25) loss mask")
     ap.add_argument("--lora-rank", type=int, default=0,
@@ -417,6 +417,152 @@ def run_config4(args, torch, A):
     return res
 
 
+def run_dpo(args, torch, A):
+    """Preference alignment on shared prefills (Section 4.1, Section 6 of the paper): 8 prompts x 2048 tokens whose
+    records a serving prefill left behind, each with a chosen and a rejected response of 128 tokens.  A step =
+    forward of the response tokens alone on the prompts' saved K/V (every layer) + DPO loss + backward through
+    prompts and responses.  Compared with the path without reuse: prefill of prompt + response twice
+    (16 sequences x 2176 tokens), the same loss, the same backward."""
+    import ctypes
+    import synth_inputs as synth
+    dev, bf = "cuda", torch.bfloat16
+    shp = synth.shape_dict("llama8b")
+    shape = A.make_shape(*[shp[k] for k in synth.SHAPE_FIELDS], "bf16")
+    H, QD, KD, F = shp["hidden"], shp["n_q_heads"] * shp["head_dim"], shp["n_kv_heads"] * shp["head_dim"], shp["ffn"]
+    L, NP, P, R, V, beta = args.layers, 8, 2048, 128, 128256, 0.1
+    b = synth.preference_batch([P] * NP, [[R, R]] * NP, V, 0)
+    T, Tp = int(b["cu"][-1]), NP * P
+    g = torch.Generator(device=dev).manual_seed(0)
+    rnd = lambda shape_, std: (torch.randn(shape_, generator=g, device=dev, dtype=torch.float32) * std).to(bf)
+    Ws = [{"Wq": rnd((QD, H), 0.02), "Wk": rnd((KD, H), 0.02), "Wv": rnd((KD, H), 0.02), "Wo": rnd((H, QD), 0.02),
+           "Wg": rnd((F, H), 0.02), "Wu": rnd((F, H), 0.02), "Wd": rnd((H, F), 0.02),
+           "g1": torch.ones(H, device=dev, dtype=bf), "g2": torch.ones(H, device=dev, dtype=bf)} for _ in range(L)]
+    W_lm, g_final = rnd((V, H), 0.02), torch.ones(H, device=dev, dtype=bf)
+    emb = rnd((V, H), 0.02)
+    X0 = emb[torch.from_numpy(b["tokens"]).to(dev).long()]
+    del emb
+    ref = torch.full((2 * NP,), -float(R) * float(np.log(V)), dtype=torch.float32, device=dev)  # a uniform reference model
+    r = args.lora_rank
+    frozen = args.frozen_base
+    loras = None
+    if r:
+        dims = dict(q=(QD, H), k=(KD, H), v=(KD, H), o=(H, QD), g=(F, H), u=(F, H), d=(H, F))
+        loras = [{p: (rnd((r, i), 0.05), torch.zeros((o, r), device=dev, dtype=bf)) for p, (o, i) in dims.items()}
+                 for _ in range(L)]
+    want = () if frozen else A.WEIGHT_KEYS
+    grads = [({} if frozen else {"d" + k: torch.empty_like(v) for k, v in W.items()}) for W in Ws]
+    lgrads = None if not r else [{"d" + m + p: torch.empty_like(ab[0] if m == "A" else ab[1]) for p, ab in lo.items()
+                                  for m in "AB"} for lo in loras]
+    if r:
+        need = A.lib().alch_stack_backward_lora_workspace_bytes(ctypes.byref(shape), L, V, 16 * (P + R), P + R, r)
+    else:
+        need = A.stack_backward_workspace_bytes(shape, L, V, 16 * (P + R), P + R)
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    ws_fwd = torch.empty(A.lib().alch_layer_forward_workspace_bytes(ctypes.byref(shape), 16 * (P + R), P + R),
+                         dtype=torch.uint8, device=dev)
+
+    def backward(batch, recs, xf, items):
+        return A.alch_stack_backward_dpo(shape, batch, recs, Ws, xf, g_final, W_lm, items[0], items[1], items[2], ref, beta,
+                                         lora_layers=loras, rank=r, scale=2.0, want=want, want_head=not frozen,
+                                         lora_grads_layers=lgrads, grads_layers=grads, workspace=ws)
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            out = fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps, out
+
+    # ---- reuse: the prompts' rows of every record exist (written once, untimed: the serving prefill) ----
+    batch = A.Batch(b["cu"], positions=b["positions"], prefix=b["prefix"])
+    prompts_only = A.Batch(b["cu"][:NP + 1])
+    acts, recs = [X0], []
+    widths = dict(X=H, X2=H, Q=QD, K=KD, V=KD, O=QD, G=F, U=F)
+    for l in range(L):
+        rec = {k: torch.empty((T, w), dtype=bf, device=dev) for k, w in widths.items() if k != "X"}
+        rec["X"] = acts[l]
+        rec["LSE"] = torch.empty((T, shp["n_q_heads"]), dtype=torch.float32, device=dev)
+        Y = torch.empty((T, H), dtype=bf, device=dev)
+        A.alch_layer_forward(shape, prompts_only, acts[l], Ws[l], workspace=ws_fwd, rec=rec, Y=Y)   # rows of the prompts
+        recs.append(rec)
+        acts.append(Y)
+    items = (b["item_row"], b["item_label"], b["item_slot"])
+
+    def reuse_step():
+        for l in range(L):   # the responses alone, on the prompts' saved keys and values
+            A.alch_layer_forward(shape, batch, acts[l], Ws[l], workspace=ws_fwd, seq_begin=NP, rec=recs[l], Y=acts[l + 1])
+        return backward(batch, recs, acts[L], items)
+
+    A.alch_trace_enable(True)
+    t_reuse, out = timed(reuse_step, args.steps, args.warmup)
+    A.alch_trace_enable(False)
+    trace = A.alch_trace_collect()
+    loss = float(out["loss"].item())
+    rec_bytes = sum(t.numel() * t.element_size() for rec in recs for t in rec.values())
+    del recs, acts
+    torch.cuda.empty_cache()
+
+    # ---- no reuse: prompt + response prefilled once per response ----
+    cu_d = synth.uniform_cu(2 * NP, P + R)
+    src = np.concatenate([np.concatenate([np.arange(g_ * P, (g_ + 1) * P), np.arange(Tp + k * R, Tp + (k + 1) * R)])
+                          for g_ in range(NP) for k in (2 * g_, 2 * g_ + 1)])
+    X0d = X0[torch.from_numpy(src).to(dev)]
+    Td = int(cu_d[-1])
+    rows, labels, slots = [], [], []
+    tok = b["tokens"]
+    for k in range(2 * NP):
+        a = k * (P + R)
+        rows += list(range(a + P - 1, a + P + R - 1))
+        labels += list(tok[Tp + k * R: Tp + (k + 1) * R])
+        slots += [k] * R
+    items_d = (np.asarray(rows, np.int32), np.asarray(labels, np.int32), np.asarray(slots, np.int32))
+    batch_d = A.Batch(cu_d)
+
+    def dup_step():
+        X, rs = X0d, []
+        for l in range(L):
+            X, rec = A.alch_layer_forward(shape, batch_d, X, Ws[l], workspace=ws_fwd)
+            rs.append(rec)
+        return backward(batch_d, rs, X, items_d), rs
+
+    t_dup, (out_d, rs) = timed(dup_step, max(1, args.steps // 2), 1)
+    loss_d = float(out_d["loss"].item())
+    rec_bytes_d = sum(t.numel() * t.element_size() for rec in rs for t in rec.values())
+    del rs
+
+    gm = [x for x in trace if x[0] == "gemm_mfma"]
+    gm_ms = sum(x[3] for x in gm)
+    achieved_tf = sum(x[1] for x in gm) / (gm_ms * 1e-3) / 1e12
+    n_traced = args.steps + args.warmup
+    by = {}
+    for kind, fl, nb, ms in trace:
+        by[kind] = by.get(kind, 0.0) + ms
+    mode = ("rank-%d adapters on a %s base" % (r, "frozen" if frozen else "trained")) if r else \
+           ("data gradients only (frozen base and head)" if frozen else "full weight gradients")
+    return {
+        "metric": METRIC, "value": T / t_reuse, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": t_reuse * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "dpo: %d-layer Llama-3-8B-shaped stack, bf16, %d prompts x %d tokens (records reused) + "
+                               "chosen and rejected response of %d tokens each on the shared prompt K/V, vocab %d, DPO "
+                               "loss, %s" % (L, NP, P, R, V, mode),
+                   "layers": L, "tokens": T, "prompt_len": P, "response_len": R, "vocab": V},
+        "loss": loss, "loss_without_reuse": loss_d,
+        "without_reuse_ms_per_step": t_dup * 1e3, "without_reuse_tokens_per_s": T / t_dup,
+        "reuse_speedup": t_dup / t_reuse,
+        "record_bytes_shared_prompt": rec_bytes, "record_bytes_without_reuse": rec_bytes_d,
+        "record_memory_saving": 1.0 - rec_bytes / rec_bytes_d,
+        "roofline": {"kernel": "k_gemm_mfma (all contractions of the response forward and the backward)", "bound": "mfma",
+                     "achieved": achieved_tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved_tf / PEAK_BF16_TFLOPS, "traffic": None,
+                     "launches_per_step": len(gm) / n_traced, "avg_launch_ms": gm_ms / max(len(gm), 1)},
+        "kernel_ms_per_step": {k: v / n_traced for k, v in by.items()},
+    }
+
+
 def run_config3(args, torch, A):
     import synth_inputs as synth
     dev = "cuda"
@@ -510,7 +656,7 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     out = {"config2": run_layer, "config5": run_layer, "config3": run_config3, "config4": run_config4,
-           "copy": run_copy}[args.workload](args, torch, A)
+           "dpo": run_dpo, "copy": run_copy}[args.workload](args, torch, A)
     if not args.no_cpu_baseline and args.workload == "config4":
         # extrapolated, and labelled so: one layer on 4 x 2048 tokens, scaled by flops
         b = cpu_baseline_layer("config2")
@@ -519,7 +665,7 @@ def main():
         b["value"] = b["value"] * P_tok / per_tok
         b["sample"] = "EXTRAPOLATED by flop count from: " + b["sample"]
         out["cpu_baseline"] = b
-    elif not args.no_cpu_baseline and args.workload != "copy":
+    elif not args.no_cpu_baseline and args.workload not in ("copy", "dpo"):
         out["cpu_baseline"] = cpu_baseline_config3() if args.workload == "config3" else cpu_baseline_layer(args.workload)
     print(json.dumps(out))
 

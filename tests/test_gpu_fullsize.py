@@ -216,3 +216,77 @@ def test_config2_full_size_adapter_mode_sampled_outputs():
     assert np.abs(dBg[ff] - want).max() <= 2e-2 * max(np.abs(want).max(), np.abs(dBg).max())
     for k, v in out.items():
         assert torch.isfinite(v.float()).all(), k
+
+
+def test_shared_prompt_equals_duplicated_prefill_at_real_width():
+    # Property that holds at any size (Section 4.1: chosen and rejected share the prompt's prefill): the DPO step on
+    # [prompts | responses with a prefix] gives the loss and gradients of the step that prefills prompt + response
+    # once per response.  Llama-3-8B-shaped layers, two prompts of 2048 and 700 tokens, responses of 128 tokens.
+    import paper_2503_01066_amd as A
+    dev, bf = "cuda", torch.bfloat16
+    shp = synth.shape_dict("llama8b")
+    shape = alch_shape(shp, "bf16")
+    H, V, L, R = shp["hidden"], 4096, 2, 128
+    prompts = [2048, 700]
+    b = synth.preference_batch(prompts, [[R, R], [R, R]], V, 3)
+    T, Tp = int(b["cu"][-1]), sum(prompts)
+    g = torch.Generator(device=dev).manual_seed(1)
+    rnd = lambda s_, std: (torch.randn(s_, generator=g, device=dev, dtype=torch.float32) * std).to(bf)
+    QD, KD, F = shp["n_q_heads"] * shp["head_dim"], shp["n_kv_heads"] * shp["head_dim"], shp["ffn"]
+    Ws = [{"Wq": rnd((QD, H), 0.02), "Wk": rnd((KD, H), 0.02), "Wv": rnd((KD, H), 0.02), "Wo": rnd((H, QD), 0.02),
+           "Wg": rnd((F, H), 0.02), "Wu": rnd((F, H), 0.02), "Wd": rnd((H, F), 0.02),
+           "g1": torch.ones(H, device=dev, dtype=bf), "g2": torch.ones(H, device=dev, dtype=bf)} for _ in range(L)]
+    W_lm, g_final = rnd((V, H), 0.02), torch.ones(H, device=dev, dtype=bf)
+    X0 = rnd((T, H), 1.0)
+    ref = np.full(4, -R * np.log(V), np.float32)
+
+    # shared: prompts first (as serving would), then the responses alone on their K/V
+    batch = A.Batch(b["cu"], positions=b["positions"], prefix=b["prefix"])
+    X, recs = X0, []
+    for l in range(L):
+        rec = {k: torch.empty((T, w), dtype=bf, device=dev) for k, w in dict(X=H, X2=H, Q=QD, K=KD, V=KD, O=QD, G=F, U=F).items()}
+        rec["LSE"] = torch.empty((T, shp["n_q_heads"]), dtype=torch.float32, device=dev)
+        Y, rec = A.alch_layer_forward(shape, A.Batch(b["cu"][:3]), X, Ws[l], rec=rec, Y=torch.empty((T, H), dtype=bf, device=dev))
+        A.alch_layer_forward(shape, batch, X, Ws[l], seq_begin=2, rec=rec, Y=Y)
+        recs.append(rec)
+        X = Y
+    out = A.alch_stack_backward_dpo(shape, batch, recs, Ws, X, g_final, W_lm, b["item_row"], b["item_label"], b["item_slot"], ref, 0.1)
+
+    # duplicated: [prompt; response] per response
+    lens = [prompts[0] + R, prompts[0] + R, prompts[1] + R, prompts[1] + R]
+    cu_d = synth.ragged_cu(lens)
+    src, rows, labels, slots = [], [], [], []
+    tok = b["tokens"]
+    for k in range(4):
+        gq = k // 2
+        p0 = int(b["cu"][gq])
+        src += list(range(p0, p0 + prompts[gq])) + list(range(Tp + k * R, Tp + (k + 1) * R))
+        a = int(cu_d[k])
+        rows += list(range(a + prompts[gq] - 1, a + prompts[gq] + R - 1))
+        labels += list(tok[Tp + k * R: Tp + (k + 1) * R])
+        slots += [k] * R
+    src_t = torch.tensor(src, device=dev)
+    batch_d = A.Batch(cu_d)
+    Xd, recs_d = X0[src_t], []
+    for l in range(L):
+        Xd, rec = A.alch_layer_forward(shape, batch_d, Xd, Ws[l])
+        recs_d.append(rec)
+    out_d = A.alch_stack_backward_dpo(shape, batch_d, recs_d, Ws, Xd, g_final, W_lm, np.asarray(rows, np.int32),
+                                      np.asarray(labels, np.int32), np.asarray(slots, np.int32), ref, 0.1)
+    torch.cuda.synchronize()
+
+    # (700 is no multiple of the 64-key tile: the two paths split the softmax sums differently, so they agree to
+    # bf16 rounding of the logits, not bit for bit)
+    assert abs(out["loss"].item() - out_d["loss"].item()) <= 2e-2 * max(1.0, abs(out_d["loss"].item()))
+    assert rel_err(to_np(out["z"]), to_np(out_d["z"])) <= 2e-2
+    # gradient w.r.t. the embeddings: duplicated rows of a prompt add up
+    want = torch.zeros((T, H), dtype=torch.float32, device=dev)
+    want.index_add_(0, src_t, out_d["dX_embed"].float())
+    assert rel_err(to_np(out["dX_embed"]), to_np(want)) <= 2e-2
+    assert float(out["dX_embed"][:Tp].abs().max()) > 0
+    for k in ("dW_lm", "dg_final"):
+        assert rel_err(to_np(out[k]), to_np(out_d[k])) <= 2e-2, k
+    for l in range(L):
+        for k in out["layers"][l]:
+            e = rel_err(to_np(out["layers"][l][k]), to_np(out_d["layers"][l][k]))
+            assert e <= 2e-2, (l, k, e)
