@@ -80,6 +80,38 @@ def cpu_baseline_layer(workload, seed=0):
                       % (n_seq, S, shape_name, dt)}
 
 
+def cpu_baseline_dpo(layers, seed=0):
+    """The shared-prefix oracle, as it stands, on a bounded sample of the dpo workload: one layer of the same shape,
+    one prompt of 1024 tokens with two responses of 128 tokens (response rows forward + layer backward); the
+    figure is scaled to the stack by the layer count and labelled so."""
+    import synth_inputs as synth
+    from oracle import LayerShape
+    from oracle.prefix import layer_forward_prefix, layer_backward_reuse_prefix
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count()
+    shp = synth.shape_dict("llama8b")
+    osh = LayerShape(*[shp[k] for k in synth.SHAPE_FIELDS])
+    b = synth.preference_batch([1024], [[128, 128]], 1000, seed)
+    T = int(b["cu"][-1])
+    W = {k: v.astype(np.float64) for k, v in synth.layer_weights(shp, seed, "bf16").items()}
+    X = synth.activations(T, shp["hidden"], seed + 1, "bf16").astype(np.float64)
+    dY = synth.activations(T, shp["hidden"], seed + 2, "bf16", std=0.01).astype(np.float64)
+    _, rec = layer_forward_prefix(osh, b["cu"], b["prefix"], X, W)     # untimed: the serving prefill
+    t0 = time.perf_counter()
+    # the oracle has no response-only forward: the whole-batch forward is timed and charged by the response share
+    layer_forward_prefix(osh, b["cu"], b["prefix"], X, W)
+    t_fwd = (time.perf_counter() - t0) * 256.0 / T
+    t1 = time.perf_counter()
+    layer_backward_reuse_prefix(osh, b["cu"], b["prefix"], rec, W, dY)
+    dt = t_fwd + time.perf_counter() - t1
+    return {"value": T / dt / layers, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": "EXTRAPOLATED to %d layers (LM head left out) from one llama8b-shaped layer on 1 prompt x 1024 + 2 "
+                      "responses x 128 tokens: response share of the forward + full backward, fp64 numpy, %.1f s" % (layers, dt)}
+
+
 def cpu_baseline_config3(seed=0, layers=3):
     """The gather oracle, as it stands, on the config-3 batch for a bounded number of layers."""
     import synth_inputs as synth
@@ -665,7 +697,9 @@ def main():
         b["value"] = b["value"] * P_tok / per_tok
         b["sample"] = "EXTRAPOLATED by flop count from: " + b["sample"]
         out["cpu_baseline"] = b
-    elif not args.no_cpu_baseline and args.workload not in ("copy", "dpo"):
+    elif not args.no_cpu_baseline and args.workload == "dpo":
+        out["cpu_baseline"] = cpu_baseline_dpo(args.layers)
+    elif not args.no_cpu_baseline and args.workload != "copy":
         out["cpu_baseline"] = cpu_baseline_config3() if args.workload == "config3" else cpu_baseline_layer(args.workload)
     print(json.dumps(out))
 

@@ -17,6 +17,7 @@ REC = ("X", "X2", "Q", "K", "V", "O", "G", "U")
 # plain kernels, bf16 / head_dim 128 the matrix-core kernels (prompts and responses spanning several 64- and
 # 128-row tiles, ragged tails, a prompt without responses, an empty response, three responses on one prompt)
 CASES = [("f32", "tiny", [4, 2, 3], [[3, 2], [1, 4], []]),
+         ("f32", "tiny", [0, 3], [[2], [1, 1]]),            # an empty prompt: its response stands alone
          ("bf16", "medium64", [130, 61], [[40, 75], [20, 20]]),
          ("bf16", "medium", [300, 65, 128], [[70, 129], [1, 0, 200], []]),
          ("bf16", "medium", [257], [[64, 64]]),
@@ -87,6 +88,33 @@ def test_forward_over_the_responses_alone(dtype, shape_name, prompts, responses)
     assert np.all(to_np(Y)[:n_p] == marker)
     if T > n_p:
         assert rel_err(to_np(Y)[n_p:], Y64[n_p:]) <= tol
+
+
+@pytest.mark.parametrize("dtype,shape_name,prompts,responses", [CASES[0], CASES[3]])
+def test_partial_record_with_shared_prefixes(dtype, shape_name, prompts, responses):
+    # X, Q, K, V only: O and LSE are recomputed by the shared-prefix attention forward, then X2, G, U
+    import paper_2503_01066_amd as A
+    shp, osh, b, W, X, _, rec64, rec, dY = make(dtype, shape_name, prompts, responses, 21)
+    four = {k: rec[k] for k in ("X", "Q", "K", "V")}
+    # the oracle completes the same rounded tensors: attention over the visibility of the batch
+    from oracle.prefix import _attention, visibility
+    from oracle.layer import _rms_norm
+    T = X.shape[0]
+    Hq, Hkv, D = osh.n_q_heads, osh.n_kv_heads, osh.head_dim
+    W64 = f64(W)
+    Q, K, V = (np.asarray(four[k], dtype=np.float64) for k in ("Q", "K", "V"))
+    O, LSE = _attention(osh, visibility(b["cu"], b["prefix"]), Q.reshape(T, Hq, D), K.reshape(T, Hkv, D), V.reshape(T, Hkv, D))
+    full = dict(f64(four), O=O.reshape(T, Hq * D), LSE=LSE)
+    full["X2"] = full["X"] + full["O"] @ W64["Wo"].T
+    H2, _ = _rms_norm(full["X2"], W64["g2"], osh.rms_eps)
+    full["G"], full["U"] = H2 @ W64["Wg"].T, H2 @ W64["Wu"].T
+    ref = layer_backward_reuse_prefix(osh, b["cu"], b["prefix"], full, W64, dY)
+    batch = A.Batch(b["cu"], positions=b["positions"], prefix=b["prefix"])
+    out = A.alch_layer_backward(alch_shape(shp, dtype), batch, {k: to_dev(v, dtype) for k, v in four.items()},
+                                {k: to_dev(v, dtype) for k, v in W.items()}, to_dev(dY, dtype))
+    torch.cuda.synchronize()
+    for k in ["dX"] + ["d" + w for w in WEIGHT_KEYS]:
+        assert rel_err(to_np(out[k]), ref[k]) <= TOL[dtype], (k, rel_err(to_np(out[k]), ref[k]))
 
 
 def test_whole_batch_forward_with_prefixes_equals_the_oracle():
