@@ -430,26 +430,38 @@ class CDpo(C.Structure):
                 ("z_out", C.c_void_p)]
 
 
+class DpoItems:
+    """The scored tokens of a DPO step, uploaded once: device copies of item_row / item_label / item_slot and of the
+    reference sums, plus the host copy of item_row the library validates.  Pass it as `item_row` to
+    alch_stack_backward_dpo (the other item arguments are then ignored) to keep the call free of host-to-device
+    copies, e.g. under graph capture."""
+
+    def __init__(self, item_row, item_label, item_slot, ref_logp, device="cuda"):
+        self.rows_host = np.ascontiguousarray(item_row, dtype=np.int32)
+        i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(device)
+        self.row, self.label, self.slot = i32(self.rows_host), i32(item_label), i32(item_slot)
+        self.ref = ref_logp if torch.is_tensor(ref_logp) else \
+            torch.from_numpy(np.ascontiguousarray(ref_logp, dtype=np.float32)).to(device)
+        self.n_items, self.n_pairs = int(self.rows_host.shape[0]), int(self.ref.numel() // 2)
+        self.z = torch.empty(max(self.n_pairs, 1), dtype=torch.float32, device=device)
+
+
 def alch_stack_backward_dpo(shape, batch, saved_layers, weights_layers, X_final, g_final, W_lm, item_row, item_label,
                             item_slot, ref_logp, beta, lora_layers=None, rank=0, scale=1.0, want=WEIGHT_KEYS,
                             want_head=True, lora_grads_layers=None, grads_layers=None, accumulate=False, hooks=None,
                             workspace=None, stream=None):
     """Stack backward under the DPO loss.  item_row / item_label / item_slot: int32 numpy arrays, one entry per
-    scored token, rows ascending; ref_logp: float32 [2 * n_pairs] (numpy or device tensor).  lora_layers: None, or
+    scored token, rows ascending; ref_logp: float32 [2 * n_pairs] (numpy or device tensor); or item_row = a DpoItems
+    holding all four.  lora_layers: None, or
     per layer a dict projection -> (A, B).  Returns the dict of alch_stack_backward plus z (device [n_pairs])."""
     L = lib()
     dev = X_final.device
     n_layers = len(saved_layers)
     vocab = W_lm.shape[0]
-    rows_host = np.ascontiguousarray(item_row, dtype=np.int32)
-    n_items = int(rows_host.shape[0])
-    i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
-    d_row, d_label, d_slot = i32(rows_host), i32(item_label), i32(item_slot)
-    ref = ref_logp if torch.is_tensor(ref_logp) else torch.from_numpy(np.ascontiguousarray(ref_logp, dtype=np.float32)).to(dev)
-    n_pairs = int(ref.numel() // 2)
-    z = torch.empty(max(n_pairs, 1), dtype=torch.float32, device=dev)
-    dpo = CDpo(n_items, n_pairs, d_row.data_ptr(), d_label.data_ptr(), d_slot.data_ptr(), rows_host.ctypes.data,
-               ref.data_ptr(), beta, z.data_ptr())
+    it = item_row if isinstance(item_row, DpoItems) else DpoItems(item_row, item_label, item_slot, ref_logp, dev)
+    n_pairs, z = it.n_pairs, it.z
+    dpo = CDpo(it.n_items, n_pairs, it.row.data_ptr(), it.label.data_ptr(), it.slot.data_ptr(), it.rows_host.ctypes.data,
+               it.ref.data_ptr(), beta, z.data_ptr())
     if grads_layers is None:
         grads_layers = [{"d" + k: torch.empty_like(w[k]) for k in want} for w in weights_layers]
     n = max(n_layers, 1)

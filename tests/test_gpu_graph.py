@@ -145,3 +145,69 @@ def test_graph_with_loss_mask_compaction_and_adapters():
     assert not torch.equal(again["dWd"], eager["dWd"])
     for k in again:
         assert torch.equal(got[k], again[k]), k
+
+
+def test_graph_of_the_preference_alignment_step():
+    # forward of the responses alone on the prompts' saved K/V + DPO head + backward through the shared prompt,
+    # captured once; replays follow new response embeddings written to the same addresses
+    import paper_2503_01066_amd as A
+    shp = synth.shape_dict("medium")
+    shape = alch_shape(shp, "bf16")
+    H, V, L = shp["hidden"], 512, 2
+    b = synth.preference_batch([150, 70], [[60, 33], [129, 20]], V, 2)
+    T, n_p = int(b["cu"][-1]), int(b["cu"][2])
+    batch = A.Batch(b["cu"], positions=b["positions"], prefix=b["prefix"])
+    Ws = [{k: to_dev(v, "bf16") for k, v in synth.layer_weights(shp, 10 * l, "bf16", std=0.05).items()} for l in range(L)]
+    rng = np.random.default_rng(3)
+    Wlm, gf = to_dev(synth.normal(rng, (V, H), 0.05, "bf16"), "bf16"), torch.ones(H, dtype=torch.bfloat16, device="cuda")
+    acts = [to_dev(synth.normal(rng, (T, H), 1.0, "bf16"), "bf16")] + [torch.empty((T, H), dtype=torch.bfloat16, device="cuda") for _ in range(L)]
+    QD, KD, F = shp["n_q_heads"] * shp["head_dim"], shp["n_kv_heads"] * shp["head_dim"], shp["ffn"]
+    recs = []
+    for l in range(L):   # the prompts' rows: the serving prefill
+        rec = {k: torch.empty((T, w), dtype=torch.bfloat16, device="cuda") for k, w in dict(X2=H, Q=QD, K=KD, V=KD, O=QD, G=F, U=F).items()}
+        rec["X"] = acts[l]
+        rec["LSE"] = torch.empty((T, shp["n_q_heads"]), dtype=torch.float32, device="cuda")
+        A.alch_layer_forward(shape, A.Batch(b["cu"][:3]), acts[l], Ws[l], rec=rec, Y=acts[l + 1])
+        recs.append(rec)
+    items = A.DpoItems(b["item_row"], b["item_label"], b["item_slot"], rng.normal(-3, 1, 4).astype(np.float32))
+    grads = [{"d" + k: torch.empty_like(v) for k, v in W.items()} for W in Ws]
+    ws = torch.empty(A.stack_backward_workspace_bytes(shape, L, V, T, 150), dtype=torch.uint8, device="cuda")
+    import ctypes
+    ws_f = torch.empty(A.lib().alch_layer_forward_workspace_bytes(ctypes.byref(shape), T, 150), dtype=torch.uint8, device="cuda")
+    holder = {}
+
+    def step():
+        for l in range(L):
+            A.alch_layer_forward(shape, batch, acts[l], Ws[l], workspace=ws_f, seq_begin=2, rec=recs[l], Y=acts[l + 1])
+        holder["out"] = A.alch_stack_backward_dpo(shape, batch, recs, Ws, acts[L], gf, Wlm, items, None, None, None, 0.5,
+                                                  grads_layers=grads, workspace=ws)
+
+    def outputs():
+        o = holder["out"]
+        d = {"loss": o["loss"], "z": o["z"], "dX_embed": o["dX_embed"], "dW_lm": o["dW_lm"]}
+        for l in range(L):
+            d.update({"%d.%s" % (l, k): v for k, v in grads[l].items()})
+        return d
+
+    step()
+    eager = snapshot(outputs())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for rep in range(2):
+        for v in outputs().values():
+            v.fill_(float(rep))
+        torch.cuda.synchronize()
+        g.replay()
+        got = snapshot(outputs())
+        for k in eager:
+            assert torch.equal(got[k], eager[k]), (rep, k)
+    acts[0][n_p:].mul_(0.5)      # other responses at the same addresses
+    torch.cuda.synchronize()
+    g.replay()
+    got = snapshot(outputs())
+    step()
+    again = snapshot(outputs())
+    assert not torch.equal(again["loss"], eager["loss"])
+    for k in again:
+        assert torch.equal(got[k], again[k]), k
