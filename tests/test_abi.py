@@ -188,6 +188,45 @@ def test_shared_prefix_batch_validation():
     assert call([-1, 0, 0], dev=None) == -1            # device and host copies go together
 
 
+def test_forward_from_and_dpo_validation():
+    L = A.lib()
+    P = 0x10000
+    s = A.make_shape(256, 4, 4, 64, 1024, 1e-6, 1e4, "f32")
+    w = B.CWeights(*([P] * 9), 0)
+    ro = B.CRecordOut(*([P] * 9))
+    cu = np.asarray([0, 4, 6, 9], dtype=np.int32)
+    pre = np.asarray([-1, 0, 0], dtype=np.int32)
+    b = B.CBatch(3, 9, 4, P, P, cu.ctypes.data, P, pre.ctypes.data)
+    fwd = lambda batch, seq_begin, ws=1024: L.alch_layer_forward_from(C.byref(s), C.byref(batch), seq_begin, P, C.byref(w), P,
+                                                                       C.byref(ro), P, ws, None)
+    assert fwd(b, 1) == -3                                   # valid: stops at the workspace check
+    assert fwd(b, 3, 1 << 30) == 0                           # no sequence left: nothing is launched
+    assert fwd(b, 4) == -1 and "seq_begin" in _err()
+    assert fwd(b, -1) == -1
+    nopos = B.CBatch(3, 9, 4, P, None, cu.ctypes.data, None, None)
+    assert fwd(nopos, 1) == -1 and "positions" in _err()
+    assert fwd(nopos, 0) == -3
+
+    sv, g = B.CSaved(*([P] * 9), 0), B.CWgrads(*([None] * 9), 0)
+    rows = np.asarray([3, 3, 4, 6], dtype=np.int32)
+
+    def dpo_call(d):
+        return L.alch_stack_backward_dpo(C.byref(s), 1, 100, C.byref(b), C.byref(sv), C.byref(w), None, P, P, P,
+                                         C.byref(d) if d is not None else None, C.byref(g), None, None, None, P, P, None,
+                                         P, 1024, None)
+    ok = B.CDpo(4, 1, P, P, P, rows.ctypes.data, P, 0.1, None)
+    assert dpo_call(ok) == -3
+    assert dpo_call(None) == -1 and "dpo is NULL" in _err()
+    assert dpo_call(B.CDpo(4, 1, P, P, P, None, P, 0.1, None)) == -1
+    assert dpo_call(B.CDpo(4, 1, P, P, P, rows.ctypes.data, None, 0.1, None)) == -1 and "ref_logp" in _err()
+    assert dpo_call(B.CDpo(10, 1, P, P, P, rows.ctypes.data, P, 0.1, None)) == -2      # more items than tokens
+    bad = np.asarray([3, 2, 4, 6], dtype=np.int32)
+    assert dpo_call(B.CDpo(4, 1, P, P, P, bad.ctypes.data, P, 0.1, None)) == -2 and "ascending" in _err()
+    far = np.asarray([3, 3, 4, 9], dtype=np.int32)
+    assert dpo_call(B.CDpo(4, 1, P, P, P, far.ctypes.data, P, 0.1, None)) == -2 and "outside" in _err()
+    assert dpo_call(B.CDpo(0, 0, None, None, None, None, None, 0.1, None)) == -3       # nothing scored is legal
+
+
 def test_six_stream_record_passes_validation_but_missing_required_tensors_do_not():
     L = A.lib()
     P = 0x10000
