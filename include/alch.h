@@ -379,6 +379,19 @@ int alch_gemm(alch_dtype dtype, int32_t M, int32_t N, int32_t a_kmajor, int32_t 
               const alch_gemm_term* terms, void* C, int64_t ldc, int32_t accumulate, void* hip_stream);
 
 /*
+ * alch_gemm_ws: alch_gemm with device scratch of alch_gemm_workspace_bytes() bytes (16-byte aligned; NULL
+ * gives alch_gemm).  The matrix-core kernel walks the 256x256 output tiles in rounds of one tile per compute
+ * unit; with scratch, a single-term product whose last round holds tiles for at most half of the compute
+ * units splits each of those tiles along the contraction over several work-groups (fp32 partial tiles in the
+ * scratch, added in a fixed order by a second kernel), as the weight-gradient products of the backward entry
+ * points do.  The result is deterministic; it differs from alch_gemm's only in fp32 summation order.
+ */
+int alch_gemm_ws(alch_dtype dtype, int32_t M, int32_t N, int32_t a_kmajor, int32_t b_kmajor, int32_t n_terms,
+                 const alch_gemm_term* terms, void* C, int64_t ldc, int32_t accumulate, void* workspace,
+                 size_t workspace_bytes, void* hip_stream);
+size_t alch_gemm_workspace_bytes(void);
+
+/*
  * alch_attention_forward: causal grouped-query attention over saved (post-RoPE) Q, K and V,
  * writing O [T,Hq*D] and LSE fp32 [T,Hq].  It is the step of the prefill that defines the LSE
  * and O members of the record (Section 4.1); exposed so that a record can be completed from

@@ -155,6 +155,11 @@ def lib():
     L.alch_gemm.restype = C.c_int
     L.alch_gemm.argtypes = [C.c_int, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(CGemmTerm),
                             C.c_void_p, C.c_int64, C.c_int32, C.c_void_p]
+    L.alch_gemm_ws.restype = C.c_int
+    L.alch_gemm_ws.argtypes = [C.c_int, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(CGemmTerm),
+                               C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.alch_gemm_workspace_bytes.restype = C.c_size_t
+    L.alch_gemm_workspace_bytes.argtypes = []
     L.alch_attention_forward.restype = C.c_int
     L.alch_attention_forward.argtypes = [C.POINTER(LayerShape), C.POINTER(CBatch), C.c_void_p, C.c_void_p, C.c_void_p,
                                          C.c_void_p, C.c_void_p, C.c_void_p]
@@ -506,8 +511,9 @@ def alch_stack_backward_dpo(shape, batch, saved_layers, weights_layers, X_final,
     return dict(loss=loss, z=z[:n_pairs], dX_embed=dX_embed, dg_final=dg_final, dW_lm=dW_lm, layers=layers)
 
 
-def alch_gemm(M, N, terms, a_kmajor, b_kmajor, out=None, accumulate=False, stream=None):
-    """terms: list of (A, B, K) device tensors (2-D, last dim contiguous).  Returns C [M, N]."""
+def alch_gemm(M, N, terms, a_kmajor, b_kmajor, out=None, accumulate=False, stream=None, workspace=None):
+    """terms: list of (A, B, K) device tensors (2-D, last dim contiguous).  Returns C [M, N].  workspace: optional
+    uint8 device tensor of lib().alch_gemm_workspace_bytes() bytes (lets the last round of tiles be split)."""
     L = lib()
     A0 = terms[0][0]
     code = ALCH_BF16 if A0.dtype == torch.bfloat16 else ALCH_F32
@@ -515,8 +521,9 @@ def alch_gemm(M, N, terms, a_kmajor, b_kmajor, out=None, accumulate=False, strea
         out = torch.empty((M, N), dtype=A0.dtype, device=A0.device)
     arr = (CGemmTerm * len(terms))(*[CGemmTerm(a.data_ptr(), b.data_ptr(), k, a.stride(0), b.stride(0))
                                      for a, b, k in terms])
-    _check(L.alch_gemm(code, M, N, 1 if a_kmajor else 0, 1 if b_kmajor else 0, len(terms), arr, _ptr(out),
-                       out.stride(0), 1 if accumulate else 0, _stream_handle(stream)))
+    _check(L.alch_gemm_ws(code, M, N, 1 if a_kmajor else 0, 1 if b_kmajor else 0, len(terms), arr, _ptr(out),
+                          out.stride(0), 1 if accumulate else 0, _ptr(workspace),
+                          0 if workspace is None else workspace.numel(), _stream_handle(stream)))
     return out
 
 

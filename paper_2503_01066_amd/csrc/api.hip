@@ -121,6 +121,7 @@ struct LayerBwdPlan {
     void *Ap_d = nullptr, *Ap_gu = nullptr, *Ap_o = nullptr, *Ap_qkv = nullptr;  // [64,F] [128,H] [64,QD] [192,H]
     void* Bt[ALCH_N_PROJ] = {};                                                  // B_p transposed: [rank, out_p]
     float* up_scratch = nullptr;
+    void* gemm_ws = nullptr;  // fp32 partial tiles of a weight-gradient product whose last round of tiles is split
     size_t bytes;
 };
 
@@ -151,6 +152,7 @@ static LayerBwdPlan plan_layer_bwd(const alch_layer_shape& s, int T, void* ws, s
     p.c_inv = static_cast<int*>(a.take(t * sizeof(int)));
     p.c_cu = static_cast<int*>(a.take(256));
     p.c_n = static_cast<int*>(a.take(256));
+    p.gemm_ws = a.take(kGemmSplitWsBytes);
     if (lora_rank > 0) {
         const size_t wmax = std::max(std::max(H, QD), F);
         p.T1 = a.take(t * kLoraSlot * E);
@@ -441,6 +443,7 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
     }
     if (g.dWd) {  // dWd = dY^T Act
         GemmDesc d = gemm(dt, H, F, false, false);
+        d.split_ws = p.gemm_ws; d.split_ws_bytes = kGemmSplitWsBytes;
         d.k_dev = ndev;
         add_seg(d, mY, H, p.Act, F, T);
         add_out(d, g.dWd, 0, F);
@@ -470,6 +473,7 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
     if (g.dWg || g.dWu) {  // [dWg; dWu] = [dG | dU]^T H2
         if (g.dWg && g.dWu) {
             GemmDesc d = gemm(dt, 2 * F, H, false, false);
+            d.split_ws = p.gemm_ws; d.split_ws_bytes = kGemmSplitWsBytes;
         d.k_dev = ndev;
             add_seg(d, p.dGU, 2 * (long long)F, p.Hn, H, T);
             add_out(d, g.dWg, 0, H);
@@ -485,6 +489,7 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
             }
         } else {
             GemmDesc d = gemm(dt, F, H, false, false);
+            d.split_ws = p.gemm_ws; d.split_ws_bytes = kGemmSplitWsBytes;
         d.k_dev = ndev;
             add_seg(d, g.dWg ? p.dGU : at(p.dGU, F, E), 2 * (long long)F, p.Hn, H, T);
             add_out(d, g.dWg ? g.dWg : g.dWu, 0, H);
@@ -511,6 +516,7 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
     ALCH_TRY(adapter_grads(ALCH_PROJ_O, 0, mO, QD, QD, mdX2, H, H));
     if (g.dWo) {  // dWo = dX2^T O
         GemmDesc d = gemm(dt, H, QD, false, false);
+        d.split_ws = p.gemm_ws; d.split_ws_bytes = kGemmSplitWsBytes;
         d.k_dev = ndev;
         add_seg(d, mdX2, H, mO, QD, T);
         add_out(d, g.dWo, 0, QD);
@@ -559,6 +565,7 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
     if (g.dWq || g.dWk || g.dWv) {  // dW{q,k,v} = d{Q,K,V}^T H1
         if (g.dWq && g.dWk && g.dWv && QD % 256 == 0 && KD % 256 == 0) {
             GemmDesc d = gemm(dt, QKV, H, false, false);
+            d.split_ws = p.gemm_ws; d.split_ws_bytes = kGemmSplitWsBytes;
             add_seg(d, p.dQKV, QKV, p.Hn, H, T);
             add_out(d, g.dWq, 0, H);
             add_out(d, g.dWk, QD, H);
@@ -571,6 +578,7 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
             for (int i = 0; i < 3; ++i) {
                 if (!outs[i]) continue;
                 GemmDesc d = gemm(dt, rows[i], H, false, false);
+                d.split_ws = p.gemm_ws; d.split_ws_bytes = kGemmSplitWsBytes;
                 add_seg(d, at(p.dQKV, off[i], E), QKV, p.Hn, H, T);
                 add_out(d, outs[i], 0, H);
                 d.accumulate = acc;
@@ -641,9 +649,18 @@ int alch_trace_collect(alch_trace_record* out, int32_t max_records, int32_t* n_o
 const char* alch_last_error(void) { return g_error; }
 const char* alch_version(void) { return "alch 0.1 (gfx950)"; }
 
+size_t alch_gemm_workspace_bytes(void) { return kGemmSplitWsBytes; }
+
 int alch_gemm(alch_dtype dtype, int32_t M, int32_t N, int32_t a_kmajor, int32_t b_kmajor, int32_t n_terms,
               const alch_gemm_term* terms, void* C, int64_t ldc, int32_t accumulate, void* hip_stream) {
+    return alch_gemm_ws(dtype, M, N, a_kmajor, b_kmajor, n_terms, terms, C, ldc, accumulate, nullptr, 0, hip_stream);
+}
+
+int alch_gemm_ws(alch_dtype dtype, int32_t M, int32_t N, int32_t a_kmajor, int32_t b_kmajor, int32_t n_terms,
+                 const alch_gemm_term* terms, void* C, int64_t ldc, int32_t accumulate, void* workspace,
+                 size_t workspace_bytes, void* hip_stream) {
     clear_error();
+    if (workspace && !aligned16(workspace)) return fail(ALCH_ERR_INVALID_ARG, "workspace is not 16-byte aligned");
     if (dtype != ALCH_F32 && dtype != ALCH_BF16) return fail(ALCH_ERR_INVALID_ARG, "bad dtype %d", (int)dtype);
     if (M < 0 || N < 0) return fail(ALCH_ERR_SHAPE, "negative M or N");
     if (n_terms < 1 || n_terms > kMaxGemmSegs || !terms) return fail(ALCH_ERR_INVALID_ARG, "n_terms must be 1..%d and terms non-NULL", kMaxGemmSegs);
@@ -659,6 +676,8 @@ int alch_gemm(alch_dtype dtype, int32_t M, int32_t N, int32_t a_kmajor, int32_t 
     }
     add_out(d, C, 0, ldc);
     d.accumulate = accumulate != 0;
+    d.split_ws = workspace;
+    d.split_ws_bytes = workspace ? workspace_bytes : 0;
     return launch_gemm(d, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -861,6 +880,7 @@ static int stack_backward_impl(const alch_layer_shape* shape, int32_t n_layers, 
             }
             if (dW_lm) {  // dW_lm (+)= dlogits^T Hf
                 GemmDesc d = gemm(dt, vocab, H, false, false);
+                d.split_ws = p.layer_ws; d.split_ws_bytes = p.layer_ws_bytes;  // the layers' workspace is idle during the head
                 add_seg(d, p.logits, vocab, at(p.h_Hf, (size_t)r0 * H, E), H, rows);
                 add_out(d, dW_lm, 0, H);
                 d.accumulate = first ? acc : 1;
@@ -919,6 +939,7 @@ static int stack_backward_impl(const alch_layer_shape* shape, int32_t n_layers, 
             }
             if (dW_lm) {  // dW_lm (+)= dlogits^T Hf
                 GemmDesc d = gemm(dt, vocab, H, false, false);
+                d.split_ws = p.layer_ws; d.split_ws_bytes = p.layer_ws_bytes;  // the layers' workspace is idle during the head
                 add_seg(d, p.logits, vocab, hf, H, rows);
                 add_out(d, dW_lm, 0, H);
                 d.accumulate = first ? acc : 1;

@@ -20,6 +20,12 @@
 //     load's range check; stores are predicated.
 //   * Work-groups are numbered so that each of the 8 XCDs (one L2 each) works on a
 //     compact patch of output tiles.
+//   * The grid is persistent, one work-group per compute unit, each walking its share of the tiles
+//     round by round.  When the last round would hold tiles for at most half of the compute units, it
+//     is left to a second launch (the kSplit instantiation) in which s work-groups of the same XCD
+//     share a tile, each taking 1/s of the contraction and leaving an fp32 partial tile in a scratch
+//     buffer; k_gemm_split_finish adds the s partials in a fixed order and writes the output
+//     (deterministic, no atomics).
 #include "kernels.h"
 
 namespace alch {
@@ -27,6 +33,7 @@ namespace alch {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 #define ALCH_LDS(p) ((__attribute__((address_space(3))) void*)(p))
 
@@ -56,6 +63,12 @@ struct MfmaGemmParams {
     const __bf16* U;
     long long ldgu;
     __bf16* act_out;
+    // Tiles q < q_end of every XCD's share are computed whole by the plain instantiation.  The kSplit
+    // instantiation computes the tiles q_end .. of the share, split_s work-groups per tile, partial tiles
+    // [tile of the split round][part][256][256] fp32 in split_ws.
+    int q_end;
+    float* split_ws;
+    int split_s;
 };
 
 typedef __attribute__((ext_vector_type(4))) int i32x4;
@@ -157,7 +170,7 @@ template <typename F> __device__ __forceinline__ void static_for4(F&& f) {
     f(IntC<3>{});
 }
 
-template <bool AK, bool BKM>
+template <bool AK, bool BKM, bool kSplit = false>
 __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
     // kStages pipeline stages of [A tile 16 KB | B tile 16 KB]
     __shared__ __attribute__((aligned(1024))) char smem[kStages * 2 * kOperandStageBytes];
@@ -174,7 +187,11 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave >> 1, wn = wave & 1;
-    for (int q = blockIdx.x / 8; q < per_xcd; q += gridDim.x / 8) {
+    // kSplit: one tile per work-group; work-group w of an XCD takes part w / rem of tile q_end + w % rem
+    const int rem = per_xcd - p.q_end;
+    const int ks = kSplit ? (int)(blockIdx.x / 8) / rem : 0;
+    for (int q = kSplit ? p.q_end + (int)(blockIdx.x / 8) % rem : (int)(blockIdx.x / 8); q < (kSplit ? per_xcd : p.q_end);
+         q += kSplit ? per_xcd : (int)(gridDim.x / 8)) {
     const int t = (blockIdx.x % 8) * per_xcd + q;
     if (t >= nt) break;
     const int band_tiles = kGroupM * p.tiles_n;
@@ -195,7 +212,7 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
     for (int seg = 0; seg < p.n_seg; ++seg) {
         const long long lda = p.lda[seg], ldb = p.ldb[seg];
         const int K = p.k_dev ? min(__builtin_amdgcn_readfirstlane(*p.k_dev), p.K[seg]) : p.K[seg];
-        const int nk = (K + BK - 1) / BK;
+        int nk = (K + BK - 1) / BK;
         const char *pa, *pb, *enda, *endb;
         long long stepa, stepb;
         if (AK) {
@@ -215,6 +232,12 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
             pb = (const char*)(p.B[seg] + n0);
             endb = (const char*)(p.B[seg] + (long long)(K - 1) * ldb + p.N);
             stepb = (long long)BK * ldb * 2;
+        }
+        if (kSplit) {  // this work-group's share of the k-tiles
+            const int per = (nk + p.split_s - 1) / p.split_s, kt0 = ks * per;
+            nk = max(0, min(per, nk - kt0));
+            pa += (long long)kt0 * stepa;
+            pb += (long long)kt0 * stepb;
         }
         uint32_t va[4], vb[4];
         tile_offsets<AK>(va, wave, lane, lda, Mv - m0);
@@ -318,6 +341,24 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
 #undef ALCH_RB
     }
 
+    if constexpr (kSplit) {
+        // fp32 partial tile, row-major [256][256]: block (i, j) holds (see below) row i*32 + (lane&31) and, in
+        // registers 4b..4b+3, columns j*32 + 8b + 4*(lane>>5) + 0..3 of the wave's 128x128 quarter
+        float* ws = p.split_ws + ((size_t)(((blockIdx.x % 8) * rem + (q - p.q_end)) * p.split_s + ks)) * (BM * BN) +
+                    (wm * 128 + (lane & 31)) * BN + wn * 128 + 4 * (lane >> 5);
+        static_for4([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    f32x4 v;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) v[r] = acc[i][j][4 * b + r];
+                    *reinterpret_cast<f32x4*>(ws + i * 32 * BN + j * 32 + 8 * b) = v;
+                }
+        });
+    } else {
     // ---- epilogue.  The MFMAs were issued with the operand roles swapped, so block (i, j) holds
     // the transposed 32x32 result: this lane owns output row m = .. + i*32 + (lane&31) and, in
     // registers 4b..4b+3, the four consecutive columns n = .. + j*32 + 8b + 4*(lane>>5) + 0..3.
@@ -429,7 +470,53 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
                 }
         });
     }
+    }  // plain epilogue
     }  // tiles of this work-group
+}
+
+// Sum of the partial tiles of the split round -> output.  blockIdx.x: tile of that round (same tile numbering as
+// the GEMM kernel), blockIdx.y: slab of 16 rows; a thread handles four consecutive columns of four rows.
+__global__ __launch_bounds__(256) void k_gemm_split_finish(MfmaGemmParams p, int per_xcd, int nt) {
+    const int rem = per_xcd - p.q_end;
+    const int t = (blockIdx.x / rem) * per_xcd + p.q_end + blockIdx.x % rem;
+    if (t >= nt) return;
+    const int band_tiles = kGroupM * p.tiles_n;
+    const int band = t / band_tiles, in_band = t % band_tiles;
+    const int band_rows = min(kGroupM, p.tiles_m - band * kGroupM);
+    const int m0 = (band * kGroupM + in_band % band_rows) * BM, n0 = (in_band / band_rows) * BN;
+    int oseg = 0;
+#pragma unroll
+    for (int s = 1; s < 3; ++s)
+        if (s < p.n_out && m0 >= p.m_begin[s]) oseg = s;
+    __bf16* __restrict__ C = p.C[oseg];
+    const long long ldc = p.ldc[oseg];
+    const int mrel0 = m0 - p.m_begin[oseg];
+    const int m_end = (oseg + 1 < p.n_out ? min(p.m_begin[oseg + 1], p.M) : p.M);
+    const float* ws = p.split_ws + (size_t)blockIdx.x * p.split_s * (BM * BN);
+    const int col = 4 * (threadIdx.x & 63), n = n0 + col;
+    if (n >= p.N) return;  // (N is a multiple of 8: a thread's four columns are all inside or all outside)
+    const int r0 = blockIdx.y * 16 + (threadIdx.x >> 6);
+    f32x4 v[4];
+    bf16x4 old[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {  // all loads first
+        const int r = r0 + 4 * i;
+        v[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (m0 + r < m_end) {
+            for (int k = 0; k < p.split_s; ++k) v[i] += *reinterpret_cast<const f32x4*>(ws + (size_t)k * (BM * BN) + r * BN + col);
+            if (p.accumulate) old[i] = *reinterpret_cast<const bf16x4*>(C + (long long)(mrel0 + r) * ldc + n);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = r0 + 4 * i;
+        if (m0 + r < m_end) {
+            bf16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = (__bf16)(p.accumulate ? v[i][e] + bf2f(old[i][e]) : v[i][e]);
+            *reinterpret_cast<bf16x4*>(C + (long long)(mrel0 + r) * ldc + n) = o;
+        }
+    }
 }
 
 bool gemm_mfma_supported(const GemmDesc& d) {
@@ -497,14 +584,37 @@ int launch_gemm_mfma(const GemmDesc& d, hipStream_t stream) {
         n_cu = v > 8 ? v / 8 * 8 : 8;
     }
     const int grid = ceil_div(nt, 8) * 8 < n_cu ? ceil_div(nt, 8) * 8 : n_cu;
-    if (d.a_kmajor && d.b_kmajor)
+    // split of the last round (see the header): one operand pair, plain epilogue, host-known sizes, and a
+    // contraction long enough that every part still runs the pipeline for a while
+    const int per_xcd = ceil_div(nt, 8), wgx = grid / 8;
+    const int full_q = per_xcd / wgx * wgx, rem = per_xcd - full_q;
+    p.q_end = per_xcd;
+    p.split_ws = nullptr;
+    p.split_s = 1;
+    if (d.split_ws && aligned16(d.split_ws) && d.n_seg == 1 && d.epilogue == kEpiNone && !d.m_dev && !d.k_dev && grid == n_cu &&
+        full_q > 0 && rem > 0 && 2 * rem <= wgx) {
+        const int s = wgx / rem < 8 ? wgx / rem : 8;
+        if (ceil_div(d.seg[0].K, BK) >= 16 * s && (size_t)8 * rem * s * BM * BN * sizeof(float) <= d.split_ws_bytes) {
+            p.q_end = full_q;
+            p.split_ws = static_cast<float*>(d.split_ws);
+            p.split_s = s;
+        }
+    }
+    const int grid_split = 8 * rem * p.split_s;
+    if (d.a_kmajor && d.b_kmajor) {
         k_gemm_mfma<true, true><<<grid, 256, 0, stream>>>(p);
-    else if (d.a_kmajor && !d.b_kmajor)
+        if (p.split_s > 1) k_gemm_mfma<true, true, true><<<grid_split, 256, 0, stream>>>(p);
+    } else if (d.a_kmajor && !d.b_kmajor) {
         k_gemm_mfma<true, false><<<grid, 256, 0, stream>>>(p);
-    else if (!d.a_kmajor && !d.b_kmajor)
+        if (p.split_s > 1) k_gemm_mfma<true, false, true><<<grid_split, 256, 0, stream>>>(p);
+    } else if (!d.a_kmajor && !d.b_kmajor) {
         k_gemm_mfma<false, false><<<grid, 256, 0, stream>>>(p);
-    else
+        if (p.split_s > 1) k_gemm_mfma<false, false, true><<<grid_split, 256, 0, stream>>>(p);
+    } else {
         k_gemm_mfma<false, true><<<grid, 256, 0, stream>>>(p);
+        if (p.split_s > 1) k_gemm_mfma<false, true, true><<<grid_split, 256, 0, stream>>>(p);
+    }
+    if (p.split_s > 1) k_gemm_split_finish<<<dim3(8 * rem, BM / 16), 256, 0, stream>>>(p, per_xcd, nt);
     ALCH_HIP_TRY(hipGetLastError());
     return ALCH_OK;
 }

@@ -54,7 +54,13 @@ struct GemmDesc {
     // every operand pair = min(*k_dev, K).  Rows / contraction steps beyond them are neither read nor written.
     const int* m_dev = nullptr;
     const int* k_dev = nullptr;
+    // optional scratch (matrix-core kernel only): when the last round of tiles would leave at least half of the
+    // compute units idle, every tile of that round is split along the contraction over s work-groups, which
+    // write fp32 partial tiles here; a second kernel adds them in a fixed order.  kGemmSplitWsBytes always suffices.
+    void* split_ws = nullptr;
+    size_t split_ws_bytes = 0;
 };
+static constexpr size_t kGemmSplitWsBytes = (size_t)64 << 20;
 int launch_gemm(const GemmDesc& d, hipStream_t stream);
 // used by launch_gemm
 bool gemm_mfma_supported(const GemmDesc& d);

@@ -45,7 +45,8 @@ def test_workspace_queries():
     s = A.make_shape(4096, 32, 8, 128, 14336, 1e-5, 5e5, "bf16")
     n = L.alch_layer_backward_workspace_bytes(C.byref(s), 8192, 2048)
     # dominated by [T, 2F] + [T, F] bf16, plus the compacted copies of G, U (loss-mask mode) and the [T, H]-sized rest
-    assert 8192 * 3 * 14336 * 2 < n < 3 * 8192 * 3 * 14336 * 2
+    # and the fixed 64 MiB scratch of the split weight-gradient products
+    assert 8192 * 3 * 14336 * 2 < n < 3 * 8192 * 3 * 14336 * 2 + (64 << 20)
     assert L.alch_layer_backward_workspace_bytes(C.byref(s), 0, 0) > 0
     bad = A.make_shape(4096, 32, 7, 128, 14336, 1e-5, 5e5, "bf16")
     assert L.alch_layer_backward_workspace_bytes(C.byref(bad), 8192, 2048) == 0

@@ -49,3 +49,29 @@ def test_gemm_terms_accumulate_and_fp32():
     C = A_.alch_gemm(70, 45, [(to_dev(A3, "f32"), to_dev(B3, "f32"), 33)], False, False)
     torch.cuda.synchronize()
     assert rel_err(to_np(C), r3) < 1e-5
+
+
+@pytest.mark.parametrize("a_k,b_k", [(False, False), (True, False), (True, True)])
+@pytest.mark.parametrize("M,N,K,acc", [(6144, 4096, 2048, False),     # 384 tiles: last round of 128, two parts each
+                                       (2040, 10232, 4096, True),     # 320 tiles with ragged edges: last round of 64, four parts
+                                       (2048, 10240, 1024, False)])   # contraction too short for four parts: not split
+def test_gemm_split_last_round(a_k, b_k, M, N, K, acc):
+    # with scratch the tiles of a half-empty last round are split along K; the result is that of the plain launch
+    # up to fp32 summation order, and both agree with fp64
+    import paper_2503_01066_amd as A_
+    rng = np.random.default_rng(M + N + K)
+    A, B, ref = operands(rng, M, N, K, a_k, b_k, "bf16")
+    C0 = synth.quantize(rng.standard_normal((M, N)).astype(np.float32) * 30, "bf16")
+    dA, dB = to_dev(A, "bf16"), to_dev(B, "bf16")
+    ws = torch.empty(A_.lib().alch_gemm_workspace_bytes(), dtype=torch.uint8, device="cuda")
+    outs = []
+    for w in (None, ws, ws):
+        C = to_dev(C0, "bf16")
+        A_.alch_gemm(M, N, [(dA, dB, K)], a_k, b_k, out=C, accumulate=acc, workspace=w)
+        torch.cuda.synchronize()
+        outs.append(to_np(C))
+    want = ref + C0 if acc else ref
+    assert rel_err(outs[0], want) < 6e-3
+    assert rel_err(outs[1], want) < 6e-3
+    assert np.array_equal(outs[1], outs[2])                      # deterministic
+    assert rel_err(outs[1], outs[0]) < 1e-2                      # at most a last-bit difference of the rounded output
