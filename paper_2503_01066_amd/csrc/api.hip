@@ -170,7 +170,7 @@ static LayerBwdPlan plan_layer_bwd(const alch_layer_shape& s, int T, void* ws, s
 }
 
 struct LayerFwdPlan {
-    void *Hn, *Act;
+    void *Hn, *Act, *gemm_ws;
     size_t bytes;
 };
 static LayerFwdPlan plan_layer_fwd(const alch_layer_shape& s, int T, void* ws, size_t ws_bytes) {
@@ -179,6 +179,7 @@ static LayerFwdPlan plan_layer_fwd(const alch_layer_shape& s, int T, void* ws, s
     LayerFwdPlan p;
     p.Hn = a.take(t * s.hidden * E);
     p.Act = a.take(t * s.ffn * E);
+    p.gemm_ws = a.take(kGemmSplitWsBytes);
     p.bytes = round_up(a.used, 256);
     return p;
 }
@@ -287,6 +288,13 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
     const size_t E = dtype_size(dt);
     const int T = b.total_tokens, H = s.hidden, F = s.ffn, D = s.head_dim;
     const int QD = s.n_q_heads * D, KD = s.n_kv_heads * D, QKV = QD + 2 * KD;
+    // every product may split a half-empty last round of tiles (short batches: all tiles) into the plan's scratch
+    auto gemm_ws = [&](alch_dtype t, int M, int N, bool a_k, bool b_k) {
+        GemmDesc d = gemm(t, M, N, a_k, b_k);
+        d.split_ws = p.gemm_ws;
+        d.split_ws_bytes = kGemmSplitWsBytes;
+        return d;
+    };
 
     // A record without O / LSE / X2 (Section 4.3.2: recompute instead of load): attention forward on the saved
     // post-RoPE Q, K, V gives O and LSE; X2 = X + O Wo^T (sum in fp32, one rounding, as the forward does).
@@ -431,7 +439,7 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
         ALCH_TRY(down_t2(ALCH_PROJ_D, 1, dys, H, outs1));
     }
     {
-        GemmDesc d = gemm(dt, T, F, true, false);
+        GemmDesc d = gemm_ws(dt, T, F, true, false);
         d.m_dev = ndev;
         add_seg(d, mY, H, w.Wd, F, H);
         if (has(ALCH_PROJ_D)) add_seg(d, p.T2, ldt2, p.Ap_d, F, kLoraSlot);
@@ -442,8 +450,7 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
         ALCH_TRY(launch_gemm(d, st));
     }
     if (g.dWd) {  // dWd = dY^T Act
-        GemmDesc d = gemm(dt, H, F, false, false);
-        d.split_ws = p.gemm_ws; d.split_ws_bytes = kGemmSplitWsBytes;
+        GemmDesc d = gemm_ws(dt, H, F, false, false);
         d.k_dev = ndev;
         add_seg(d, mY, H, p.Act, F, T);
         add_out(d, g.dWd, 0, F);
@@ -458,7 +465,7 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
         ALCH_TRY(down_t2(ALCH_PROJ_G, 2, dys, 2 * (long long)F, outs2));
     }
     {  // dH2 = dG Wg + dU Wu
-        GemmDesc d = gemm(dt, T, H, true, false);
+        GemmDesc d = gemm_ws(dt, T, H, true, false);
         d.m_dev = ndev;
         add_seg(d, p.dGU, 2 * (long long)F, w.Wg, H, F);
         add_seg(d, at(p.dGU, F, E), 2 * (long long)F, w.Wu, H, F);
@@ -472,8 +479,7 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
     ALCH_TRY(adapter_grads(ALCH_PROJ_U, 1, p.Hn, H, H, at(p.dGU, F, E), 2 * (long long)F, F));
     if (g.dWg || g.dWu) {  // [dWg; dWu] = [dG | dU]^T H2
         if (g.dWg && g.dWu) {
-            GemmDesc d = gemm(dt, 2 * F, H, false, false);
-            d.split_ws = p.gemm_ws; d.split_ws_bytes = kGemmSplitWsBytes;
+            GemmDesc d = gemm_ws(dt, 2 * F, H, false, false);
         d.k_dev = ndev;
             add_seg(d, p.dGU, 2 * (long long)F, p.Hn, H, T);
             add_out(d, g.dWg, 0, H);
@@ -488,8 +494,7 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
                 ALCH_TRY(launch_gemm(d, st));
             }
         } else {
-            GemmDesc d = gemm(dt, F, H, false, false);
-            d.split_ws = p.gemm_ws; d.split_ws_bytes = kGemmSplitWsBytes;
+            GemmDesc d = gemm_ws(dt, F, H, false, false);
         d.k_dev = ndev;
             add_seg(d, g.dWg ? p.dGU : at(p.dGU, F, E), 2 * (long long)F, p.Hn, H, T);
             add_out(d, g.dWg ? g.dWg : g.dWu, 0, H);
@@ -506,7 +511,7 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
         ALCH_TRY(down_t2(ALCH_PROJ_O, 1, dys, H, outs1));
     }
     {  // dO = dX2 Wo
-        GemmDesc d = gemm(dt, T, QD, true, false);
+        GemmDesc d = gemm_ws(dt, T, QD, true, false);
         d.m_dev = ndev;
         add_seg(d, mdX2, H, w.Wo, QD, H);
         if (has(ALCH_PROJ_O)) add_seg(d, p.T2, ldt2, p.Ap_o, QD, kLoraSlot);
@@ -515,8 +520,7 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
     }
     ALCH_TRY(adapter_grads(ALCH_PROJ_O, 0, mO, QD, QD, mdX2, H, H));
     if (g.dWo) {  // dWo = dX2^T O
-        GemmDesc d = gemm(dt, H, QD, false, false);
-        d.split_ws = p.gemm_ws; d.split_ws_bytes = kGemmSplitWsBytes;
+        GemmDesc d = gemm_ws(dt, H, QD, false, false);
         d.k_dev = ndev;
         add_seg(d, mdX2, H, mO, QD, T);
         add_out(d, g.dWo, 0, QD);
@@ -549,7 +553,7 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
         ALCH_TRY(down_t2(ALCH_PROJ_Q, 3, dys, QKV, outs3));
     }
     {  // dH1 = dQ Wq + dK Wk + dV Wv
-        GemmDesc d = gemm(dt, T, H, true, false);
+        GemmDesc d = gemm_ws(dt, T, H, true, false);
         add_seg(d, p.dQKV, QKV, w.Wq, H, QD);
         add_seg(d, at(p.dQKV, QD, E), QKV, w.Wk, H, KD);
         add_seg(d, at(p.dQKV, QD + KD, E), QKV, w.Wv, H, KD);
@@ -564,8 +568,7 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
     ALCH_TRY(adapter_grads(ALCH_PROJ_V, 2, p.Hn, H, H, at(p.dQKV, QD + KD, E), QKV, KD));
     if (g.dWq || g.dWk || g.dWv) {  // dW{q,k,v} = d{Q,K,V}^T H1
         if (g.dWq && g.dWk && g.dWv && QD % 256 == 0 && KD % 256 == 0) {
-            GemmDesc d = gemm(dt, QKV, H, false, false);
-            d.split_ws = p.gemm_ws; d.split_ws_bytes = kGemmSplitWsBytes;
+            GemmDesc d = gemm_ws(dt, QKV, H, false, false);
             add_seg(d, p.dQKV, QKV, p.Hn, H, T);
             add_out(d, g.dWq, 0, H);
             add_out(d, g.dWk, QD, H);
@@ -577,8 +580,7 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
             const int off[3] = {0, QD, QD + KD}, rows[3] = {QD, KD, KD};
             for (int i = 0; i < 3; ++i) {
                 if (!outs[i]) continue;
-                GemmDesc d = gemm(dt, rows[i], H, false, false);
-                d.split_ws = p.gemm_ws; d.split_ws_bytes = kGemmSplitWsBytes;
+                GemmDesc d = gemm_ws(dt, rows[i], H, false, false);
                 add_seg(d, at(p.dQKV, off[i], E), QKV, p.Hn, H, T);
                 add_out(d, outs[i], 0, H);
                 d.accumulate = acc;
@@ -842,6 +844,13 @@ static int stack_backward_impl(const alch_layer_shape* shape, int32_t n_layers, 
     const size_t E = dtype_size(dt);
     const int T = batch->total_tokens, H = s.hidden;
     const int acc = wgrads ? (wgrads[0].accumulate != 0) : 0;
+    // scratch of split products in the head: the layers' workspace, idle until the walk starts
+    auto gemm_ws = [&](alch_dtype t, int M, int N, bool a_k, bool b_k) {
+        GemmDesc d = gemm(t, M, N, a_k, b_k);
+        d.split_ws = p.layer_ws;
+        d.split_ws_bytes = p.layer_ws_bytes;
+        return d;
+    };
 
     bool compact_head = false;
     if (dpo) {
@@ -854,7 +863,7 @@ static int stack_backward_impl(const alch_layer_shape* shape, int32_t n_layers, 
         if (M > 0) ALCH_TRY(launch_scatter_rows(p.Hf, dpo->item_row, p.h_Hf, M, (size_t)H * E, st));  // h_Hf[m] = Hf[item_row[m]]
         const bool one_chunk = M <= kHeadChunkRows;
         auto logits_of = [&](int r0, int rows) {
-            GemmDesc d = gemm(dt, rows, vocab, true, true);
+            GemmDesc d = gemm_ws(dt, rows, vocab, true, true);
             add_seg(d, at(p.h_Hf, (size_t)r0 * H, E), H, W_lm, H, H);
             add_out(d, p.logits, 0, vocab);
             return launch_gemm(d, st);
@@ -873,14 +882,13 @@ static int stack_backward_impl(const alch_layer_shape* shape, int32_t n_layers, 
             ALCH_TRY(launch_dpo_grad(dt, p.logits, vocab, rows, vocab, dpo->item_label + r0, dpo->item_slot + r0,
                                      p.dpo_logz + r0, p.dpo_w, n_slots, st));
             {  // gradient of the gathered rows = dlogits W_lm
-                GemmDesc d = gemm(dt, rows, H, true, false);
+                GemmDesc d = gemm_ws(dt, rows, H, true, false);
                 add_seg(d, p.logits, vocab, W_lm, H, vocab);
                 add_out(d, at(p.h_dHf, (size_t)r0 * H, E), 0, H);
                 ALCH_TRY(launch_gemm(d, st));
             }
             if (dW_lm) {  // dW_lm (+)= dlogits^T Hf
-                GemmDesc d = gemm(dt, vocab, H, false, false);
-                d.split_ws = p.layer_ws; d.split_ws_bytes = p.layer_ws_bytes;  // the layers' workspace is idle during the head
+                GemmDesc d = gemm_ws(dt, vocab, H, false, false);
                 add_seg(d, p.logits, vocab, at(p.h_Hf, (size_t)r0 * H, E), H, rows);
                 add_out(d, dW_lm, 0, H);
                 d.accumulate = first ? acc : 1;
@@ -889,7 +897,7 @@ static int stack_backward_impl(const alch_layer_shape* shape, int32_t n_layers, 
             first = false;
         }
         if (M == 0 && dW_lm && !acc) {
-            GemmDesc d = gemm(dt, vocab, H, false, false);  // zero rows contracted: writes zeros
+            GemmDesc d = gemm_ws(dt, vocab, H, false, false);  // zero rows contracted: writes zeros
             add_seg(d, p.logits, vocab, p.Hf, H, 0);
             add_out(d, dW_lm, 0, H);
             ALCH_TRY(launch_gemm_generic(d, st));
@@ -922,7 +930,7 @@ static int stack_backward_impl(const alch_layer_shape* shape, int32_t n_layers, 
             const int* rows_dev = compact_head ? p.h_chunk_rows + r0 / kHeadChunkRows : nullptr;
             const void* hf = at(head_in, (size_t)r0 * H, E);
             {  // logits = Hf W_lm^T
-                GemmDesc d = gemm(dt, rows, vocab, true, true);
+                GemmDesc d = gemm_ws(dt, rows, vocab, true, true);
                 add_seg(d, hf, H, W_lm, H, H);
                 add_out(d, p.logits, 0, vocab);
                 d.m_dev = rows_dev;
@@ -931,15 +939,14 @@ static int stack_backward_impl(const alch_layer_shape* shape, int32_t n_layers, 
             ALCH_TRY(launch_ce_chunk(dt, p.logits, vocab, rows, vocab, head_labels + r0, head_mask ? head_mask + r0 : nullptr,
                                      p.n_counted, p.row_loss + r0, st, rows_dev));
             {  // dHf = dlogits W_lm
-                GemmDesc d = gemm(dt, rows, H, true, false);
+                GemmDesc d = gemm_ws(dt, rows, H, true, false);
                 add_seg(d, p.logits, vocab, W_lm, H, vocab);
                 add_out(d, const_cast<char*>(at(head_out, (size_t)r0 * H, E)), 0, H);
                 d.m_dev = rows_dev;
                 ALCH_TRY(launch_gemm(d, st));
             }
             if (dW_lm) {  // dW_lm (+)= dlogits^T Hf
-                GemmDesc d = gemm(dt, vocab, H, false, false);
-                d.split_ws = p.layer_ws; d.split_ws_bytes = p.layer_ws_bytes;  // the layers' workspace is idle during the head
+                GemmDesc d = gemm_ws(dt, vocab, H, false, false);
                 add_seg(d, p.logits, vocab, hf, H, rows);
                 add_out(d, dW_lm, 0, H);
                 d.accumulate = first ? acc : 1;
@@ -950,7 +957,7 @@ static int stack_backward_impl(const alch_layer_shape* shape, int32_t n_layers, 
         }
         if (compact_head) ALCH_TRY(launch_scatter_rows(p.h_dHf, p.h_inv, p.dHf, T, (size_t)H * E, st));
         if (T == 0 && dW_lm && !acc) {
-            GemmDesc d = gemm(dt, vocab, H, false, false);  // zero rows contracted: writes zeros
+            GemmDesc d = gemm_ws(dt, vocab, H, false, false);  // zero rows contracted: writes zeros
             add_seg(d, p.logits, vocab, p.Hf, H, 0);
             add_out(d, dW_lm, 0, H);
             ALCH_TRY(launch_gemm_generic(d, st));
@@ -1080,6 +1087,12 @@ static int layer_forward_impl(const alch_layer_shape* shape, const alch_batch* b
     const size_t E = dtype_size(dt);
     const int H = s.hidden, F = s.ffn, D = s.head_dim;
     const int QD = s.n_q_heads * D, KD = s.n_kv_heads * D;
+    auto gemm_ws = [&](alch_dtype t, int M, int N, bool a_k, bool b_k) {
+        GemmDesc d = gemm(t, M, N, a_k, b_k);
+        d.split_ws = p.gemm_ws;
+        d.split_ws_bytes = kGemmSplitWsBytes;
+        return d;
+    };
     // the computed rows of every [total_tokens, width] tensor
     const void* Xr = at(X, (size_t)r0 * H, E);
     void* Yr = at(Y, (size_t)r0 * H, E);
@@ -1095,7 +1108,7 @@ static int layer_forward_impl(const alch_layer_shape* shape, const alch_batch* b
     void* outs[3] = {rQ, rK, rV};
     const int widths[3] = {QD, KD, KD};
     for (int i = 0; i < 3; ++i) {
-        GemmDesc d = gemm(dt, T, widths[i], true, true);
+        GemmDesc d = gemm_ws(dt, T, widths[i], true, true);
         add_seg(d, p.Hn, H, Ws[i], H, H);
         add_out(d, outs[i], 0, widths[i]);
         ALCH_TRY(launch_gemm(d, st));
@@ -1108,7 +1121,7 @@ static int layer_forward_impl(const alch_layer_shape* shape, const alch_batch* b
                              batch->seq_prefix_host, seq_begin, s.n_q_heads, s.n_kv_heads, D, st));
     {  // X2 = X + O Wo^T
         ALCH_TRY(launch_masked_copy(dt, Xr, nullptr, rX2, T, H, st));
-        GemmDesc d = gemm(dt, T, H, true, true);
+        GemmDesc d = gemm_ws(dt, T, H, true, true);
         add_seg(d, rO, QD, w->Wo, QD, QD);
         add_out(d, rX2, 0, H);
         d.accumulate = 1;
@@ -1118,7 +1131,7 @@ static int layer_forward_impl(const alch_layer_shape* shape, const alch_batch* b
     const void* Wm[2] = {w->Wg, w->Wu};
     void* om[2] = {rG, rU};
     for (int i = 0; i < 2; ++i) {
-        GemmDesc d = gemm(dt, T, F, true, true);
+        GemmDesc d = gemm_ws(dt, T, F, true, true);
         add_seg(d, p.Hn, H, Wm[i], H, H);
         add_out(d, om[i], 0, F);
         ALCH_TRY(launch_gemm(d, st));
@@ -1126,7 +1139,7 @@ static int layer_forward_impl(const alch_layer_shape* shape, const alch_batch* b
     ALCH_TRY(launch_swiglu_act(dt, rG, rU, p.Act, (long long)T * F, st));
     {  // Y = X2 + Act Wd^T
         ALCH_TRY(launch_masked_copy(dt, rX2, nullptr, Yr, T, H, st));
-        GemmDesc d = gemm(dt, T, H, true, true);
+        GemmDesc d = gemm_ws(dt, T, H, true, true);
         add_seg(d, p.Act, F, w->Wd, F, F);
         add_out(d, Yr, 0, H);
         d.accumulate = 1;

@@ -68,7 +68,7 @@ struct MfmaGemmParams {
     // [tile of the split round][part][256][256] fp32 in split_ws.
     int q_end;
     float* split_ws;
-    int split_s;
+    int split_s, split_per;  // parts per tile; k-tiles per part (counted over all operand pairs in order)
 };
 
 typedef __attribute__((ext_vector_type(4))) int i32x4;
@@ -209,6 +209,7 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+    int seg_kt0 = 0;  // kSplit: k-tiles of the operand pairs before this one
     for (int seg = 0; seg < p.n_seg; ++seg) {
         const long long lda = p.lda[seg], ldb = p.ldb[seg];
         const int K = p.k_dev ? min(__builtin_amdgcn_readfirstlane(*p.k_dev), p.K[seg]) : p.K[seg];
@@ -233,11 +234,13 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
             endb = (const char*)(p.B[seg] + (long long)(K - 1) * ldb + p.N);
             stepb = (long long)BK * ldb * 2;
         }
-        if (kSplit) {  // this work-group's share of the k-tiles
-            const int per = (nk + p.split_s - 1) / p.split_s, kt0 = ks * per;
-            nk = max(0, min(per, nk - kt0));
-            pa += (long long)kt0 * stepa;
-            pb += (long long)kt0 * stepb;
+        if (kSplit) {  // this work-group's share [ks*per, (ks+1)*per) of the k-tiles of all pairs, cut to this pair
+            const int lo = min(max(ks * p.split_per - seg_kt0, 0), nk), hi = min(max((ks + 1) * p.split_per - seg_kt0, 0), nk);
+            seg_kt0 += nk;
+            if (hi <= lo) continue;
+            nk = hi - lo;
+            pa += (long long)lo * stepa;
+            pb += (long long)lo * stepb;
         }
         uint32_t va[4], vb[4];
         tile_offsets<AK>(va, wave, lane, lda, Mv - m0);
@@ -496,6 +499,33 @@ __global__ __launch_bounds__(256) void k_gemm_split_finish(MfmaGemmParams p, int
     const int col = 4 * (threadIdx.x & 63), n = n0 + col;
     if (n >= p.N) return;  // (N is a multiple of 8: a thread's four columns are all inside or all outside)
     const int r0 = blockIdx.y * 16 + (threadIdx.x >> 6);
+    if (p.epilogue == kEpiSwigluBwd) {
+        // the summed product is dAct (rounded to bf16 as the fused epilogue of the unsplit kernel does); with the
+        // saved G, U: dG = dAct U s'(G), dU = dAct silu(G), Act = silu(G) U
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int m = m0 + r0 + 4 * i;
+            if (m >= p.M) continue;
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+            for (int k = 0; k < p.split_s; ++k) v += *reinterpret_cast<const f32x4*>(ws + (size_t)k * (BM * BN) + (r0 + 4 * i) * BN + col);
+            const bf16x4 g4 = *reinterpret_cast<const bf16x4*>(p.G + (long long)m * p.ldgu + n);
+            const bf16x4 u4 = *reinterpret_cast<const bf16x4*>(p.U + (long long)m * p.ldgu + n);
+            bf16x4 dg4, du4, a4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float g = bf2f(g4[e]), u = bf2f(u4[e]), dd = bf2f((__bf16)v[e]);
+                const float sg = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g));
+                const float silu = g * sg;
+                dg4[e] = (__bf16)(dd * u * sg * (1.f + g * (1.f - sg)));
+                du4[e] = (__bf16)(dd * silu);
+                a4[e] = (__bf16)(silu * u);
+            }
+            *reinterpret_cast<bf16x4*>(C + (long long)m * ldc + n) = dg4;
+            *reinterpret_cast<bf16x4*>(C + (long long)m * ldc + p.N + n) = du4;
+            if (p.act_out) *reinterpret_cast<bf16x4*>(p.act_out + (long long)m * p.N + n) = a4;
+        }
+        return;
+    }
     f32x4 v[4];
     bf16x4 old[4];
 #pragma unroll
@@ -584,34 +614,39 @@ int launch_gemm_mfma(const GemmDesc& d, hipStream_t stream) {
         n_cu = v > 8 ? v / 8 * 8 : 8;
     }
     const int grid = ceil_div(nt, 8) * 8 < n_cu ? ceil_div(nt, 8) * 8 : n_cu;
-    // split of the last round (see the header): one operand pair, plain epilogue, host-known sizes, and a
-    // contraction long enough that every part still runs the pipeline for a while
-    const int per_xcd = ceil_div(nt, 8), wgx = grid / 8;
+    // Split of the last round (see the header): host-known sizes and a contraction long enough that every part
+    // still runs the pipeline for a while (the finish kernel carries the SwiGLU-gradient epilogue if there is one).  A product with tiles for at most half of the compute
+    // units (a short batch) has no other round: every tile is split.
+    const int per_xcd = ceil_div(nt, 8), wgx = n_cu / 8;
     const int full_q = per_xcd / wgx * wgx, rem = per_xcd - full_q;
     p.q_end = per_xcd;
     p.split_ws = nullptr;
     p.split_s = 1;
-    if (d.split_ws && aligned16(d.split_ws) && d.n_seg == 1 && d.epilogue == kEpiNone && !d.m_dev && !d.k_dev && grid == n_cu &&
-        full_q > 0 && rem > 0 && 2 * rem <= wgx) {
-        const int s = wgx / rem < 8 ? wgx / rem : 8;
-        if (ceil_div(d.seg[0].K, BK) >= 16 * s && (size_t)8 * rem * s * BM * BN * sizeof(float) <= d.split_ws_bytes) {
+    p.split_per = 0;
+    int nk_total = 0;
+    for (int s = 0; s < d.n_seg; ++s) nk_total += ceil_div(d.seg[s].K, BK);
+    if (d.split_ws && aligned16(d.split_ws) && !d.m_dev && !d.k_dev && rem > 0 && 2 * rem <= wgx) {
+        int s = wgx / rem < 16 ? wgx / rem : 16;
+        if (s > nk_total / 16) s = nk_total / 16;
+        if (s > 1 && (size_t)8 * rem * s * BM * BN * sizeof(float) <= d.split_ws_bytes) {
             p.q_end = full_q;
             p.split_ws = static_cast<float*>(d.split_ws);
             p.split_s = s;
+            p.split_per = ceil_div(nk_total, s);
         }
     }
     const int grid_split = 8 * rem * p.split_s;
     if (d.a_kmajor && d.b_kmajor) {
-        k_gemm_mfma<true, true><<<grid, 256, 0, stream>>>(p);
+        if (p.q_end > 0) k_gemm_mfma<true, true><<<grid, 256, 0, stream>>>(p);
         if (p.split_s > 1) k_gemm_mfma<true, true, true><<<grid_split, 256, 0, stream>>>(p);
     } else if (d.a_kmajor && !d.b_kmajor) {
-        k_gemm_mfma<true, false><<<grid, 256, 0, stream>>>(p);
+        if (p.q_end > 0) k_gemm_mfma<true, false><<<grid, 256, 0, stream>>>(p);
         if (p.split_s > 1) k_gemm_mfma<true, false, true><<<grid_split, 256, 0, stream>>>(p);
     } else if (!d.a_kmajor && !d.b_kmajor) {
-        k_gemm_mfma<false, false><<<grid, 256, 0, stream>>>(p);
+        if (p.q_end > 0) k_gemm_mfma<false, false><<<grid, 256, 0, stream>>>(p);
         if (p.split_s > 1) k_gemm_mfma<false, false, true><<<grid_split, 256, 0, stream>>>(p);
     } else {
-        k_gemm_mfma<false, true><<<grid, 256, 0, stream>>>(p);
+        if (p.q_end > 0) k_gemm_mfma<false, true><<<grid, 256, 0, stream>>>(p);
         if (p.split_s > 1) k_gemm_mfma<false, true, true><<<grid_split, 256, 0, stream>>>(p);
     }
     if (p.split_s > 1) k_gemm_split_finish<<<dim3(8 * rem, BM / 16), 256, 0, stream>>>(p, per_xcd, nt);

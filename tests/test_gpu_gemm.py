@@ -75,3 +75,26 @@ def test_gemm_split_last_round(a_k, b_k, M, N, K, acc):
     assert rel_err(outs[1], want) < 6e-3
     assert np.array_equal(outs[1], outs[2])                      # deterministic
     assert rel_err(outs[1], outs[0]) < 1e-2                      # at most a last-bit difference of the rounded output
+
+
+@pytest.mark.parametrize("a_k,b_k,M,N,Ks", [(True, False, 256, 4096, (4096, 2048)),      # 16 tiles, two operand pairs, 12 parts
+                                            (True, False, 300, 4096, (1024, 512, 6144)),  # ragged rows, parts crossing pair boundaries
+                                            (True, True, 512, 1024, (8192,)),              # 8 tiles, 16 parts
+                                            (False, False, 2048, 1024, (2048,))])          # 32 tiles, 4 parts
+def test_gemm_split_short_batches(a_k, b_k, M, N, Ks):
+    # a product with tiles for at most half of the compute units splits every tile along the contraction,
+    # across the operand pairs in order
+    import paper_2503_01066_amd as A_
+    rng = np.random.default_rng(M + N + sum(Ks))
+    terms, ref = [], 0.0
+    for K in Ks:
+        A, B, r = operands(rng, M, N, K, a_k, b_k, "bf16")
+        terms.append((to_dev(A, "bf16"), to_dev(B, "bf16"), K))
+        ref = ref + r
+    ws = torch.empty(A_.lib().alch_gemm_workspace_bytes(), dtype=torch.uint8, device="cuda")
+    C0 = A_.alch_gemm(M, N, terms, a_k, b_k)
+    C1 = A_.alch_gemm(M, N, terms, a_k, b_k, workspace=ws)
+    C2 = A_.alch_gemm(M, N, terms, a_k, b_k, workspace=ws)
+    torch.cuda.synchronize()
+    assert rel_err(to_np(C0), ref) < 6e-3 and rel_err(to_np(C1), ref) < 6e-3
+    assert torch.equal(C1, C2)
