@@ -33,7 +33,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config2", choices=["config2", "config3", "config4", "config5", "dpo", "copy"])
+    ap.add_argument("--workload", default="config2", choices=["config2", "config3", "config4", "config5", "dpo", "short", "copy"])
     ap.add_argument("--layers", type=int, default=32, help="config4: number of layers")
     ap.add_argument("--loss-mask", action="store_true", help="config5: zero dY rows with a Bernoulli(0.25) loss mask")
     ap.add_argument("--lora-rank", type=int, default=0,
@@ -65,7 +65,7 @@ def cpu_baseline_layer(workload, seed=0):
     shp = synth.shape_dict(shape_name)
     osh = LayerShape(*[shp[k] for k in synth.SHAPE_FIELDS])
     # a bounded sample (10-20 s of host time): config 2 in full (4 x 2048); of config 5, 2 sequences of 512 tokens
-    n_seq, S = (4, 2048) if workload == "config2" else (2, 512)
+    n_seq, S = (4, 2048) if workload == "config2" else ((1, 512) if workload == "short" else (2, 512))
     cu = np.arange(n_seq + 1) * S
     Ttot = n_seq * S
     W = {k: v.astype(np.float64) for k, v in synth.layer_weights(shp, seed, "bf16").items()}
@@ -148,6 +148,10 @@ LAYER_WORKLOADS = {
                 "(packed out of 16 x 2048 prefilled), capture/pack + full layer backward"),
     "config5": ("llama70b", 8, 4096, 2, "config5: one Llama-3-70B-shaped layer, bf16, 2 x 4096 trained tokens "
                 "(packed out of 8 x 4096 prefilled), capture/pack + full layer backward"),
+    # per-query training right after serving (Section 4.4 of the paper caches one query of a batch): a short batch,
+    # whose products have too few output tiles to fill the chip unless they are split along the contraction
+    "short": ("llama8b", 4, 512, 1, "short: one Llama-3-8B-shaped layer, bf16, 1 x 512 trained tokens "
+              "(packed out of 4 x 512 prefilled), capture/pack + full layer backward"),
 }
 
 
@@ -687,7 +691,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
-    out = {"config2": run_layer, "config5": run_layer, "config3": run_config3, "config4": run_config4,
+    out = {"config2": run_layer, "config5": run_layer, "short": run_layer, "config3": run_config3, "config4": run_config4,
            "dpo": run_dpo, "copy": run_copy}[args.workload](args, torch, A)
     if not args.no_cpu_baseline and args.workload == "config4":
         # extrapolated, and labelled so: one layer on 4 x 2048 tokens, scaled by flops
