@@ -114,7 +114,7 @@ struct LayerBwdPlan {
     // per-sequence counts, {n_kept, overflow}; scratch of the mask scan
     void *c_dY, *c_X2, *c_O, *c_G, *c_U, *c_dX2, *c_dO, *c_packws;
     int *c_index, *c_inv, *c_cu, *c_n;
-    // adapters (rank > 0): t1 = s x A^T [T, 64]; t2 = s dy B, three zero-padded 64-column slots [T, 192];
+    // adapters (rank > 0): t1 = s x A^T and t2 = s dy B, three zero-padded 64-column slots [T, 192] each;
     // the adapters' A matrices zero-padded to 64 rows and stacked per product; B transposed; partial sums of
     // the adapter gradients
     void *T1 = nullptr, *T2 = nullptr;
@@ -154,8 +154,7 @@ static LayerBwdPlan plan_layer_bwd(const alch_layer_shape& s, int T, void* ws, s
     p.c_n = static_cast<int*>(a.take(256));
     p.gemm_ws = a.take(kGemmSplitWsBytes);
     if (lora_rank > 0) {
-        const size_t wmax = std::max(std::max(H, QD), F);
-        p.T1 = a.take(t * kLoraSlot * E);
+        p.T1 = a.take(t * 3 * kLoraSlot * E);
         p.T2 = a.take(t * 3 * kLoraSlot * E);
         p.Ap_d = a.take(kLoraSlot * F * E);
         p.Ap_gu = a.take(2 * kLoraSlot * H * E);
@@ -163,7 +162,10 @@ static LayerBwdPlan plan_layer_bwd(const alch_layer_shape& s, int T, void* ws, s
         p.Ap_qkv = a.take(3 * kLoraSlot * H * E);
         const size_t outs[ALCH_N_PROJ] = {QD, KD, KD, H, F, F, H};
         for (int i = 0; i < ALCH_N_PROJ; ++i) p.Bt[i] = a.take((size_t)lora_rank * outs[i] * E);
-        p.up_scratch = static_cast<float*>(a.take(lora_up_scratch_bytes(lora_rank, (int)wmax)));
+        // the widest group of adapter gradients formed by one launch: gate + up (dA on H twice, dB on F twice) or
+        // q + k + v (dA on H three times, dB on QD + 2 KD)
+        const size_t n_sum = std::max(2 * (H + F), std::max(3 * H + QD + 2 * KD, std::max(F + H, QD + H)));
+        p.up_scratch = static_cast<float*>(a.take(lora_up_scratch_bytes(lora_rank, (int)n_sum)));
     }
     p.bytes = round_up(a.used, 256);
     return p;
@@ -381,17 +383,27 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
             if (has(pj)) pp.job[nj++] = LoraPrepJob{lo->B[pj], p.Bt[pj], r, outs[pj], r, 1};
         ALCH_TRY(launch_lora_prep(dt, pp, nj, st));
     }
-    auto adapter_grads = [&](int pj, int slot, const void* x, long long ldx, int in_p, const void* dy, long long lddy,
-                             int out_p) -> int {
-        if (!wants(pj)) return ALCH_OK;
-        if (lg->dB[pj]) {
-            const LoraDown job{x, ldx, in_p, lo->A[pj], in_p, r, p.T1};
-            ALCH_TRY(launch_lora_down(dt, &job, 1, T, lo->scale, kLoraSlot, kLoraSlot, st));
-            ALCH_TRY(launch_lora_up(dt, p.T1, kLoraSlot, dy, lddy, T, out_p, r, 1.f, lg->dB[pj], r, true, lacc, p.up_scratch, st));
+    // Adapter gradients of the n <= 3 projections pj0, pj0+1, .. that share the input x [T, in_p]; dy[i] [T, out_p[i]]
+    // with row stride lddy; t2 of projection pj0+i sits in slot i.  One launch forms the t1 of all of them, one pair
+    // of launches all their dA and dB.
+    auto adapter_grads = [&](int pj0, int n, const void* x, long long ldx, int in_p, const void* const* dy, long long lddy,
+                             const int* out_p) -> int {
+        LoraDown dj[3];
+        LoraUp uj[kLoraUpJobs];
+        int nd = 0, nu = 0;
+        const long long ldt1 = 3 * kLoraSlot;
+        for (int i = 0; i < n; ++i) {
+            const int pj = pj0 + i;
+            if (!wants(pj)) continue;
+            if (lg->dB[pj]) {
+                char* t1 = at(p.T1, (size_t)nd * kLoraSlot, E);
+                dj[nd++] = LoraDown{x, ldx, in_p, lo->A[pj], in_p, r, t1};
+                uj[nu++] = LoraUp{t1, ldt1, dy[i], lddy, out_p[i], lg->dB[pj], r, 1};
+            }
+            if (lg->dA[pj]) uj[nu++] = LoraUp{at(p.T2, (size_t)i * kLoraSlot, E), ldt2, x, ldx, in_p, lg->dA[pj], in_p, 0};
         }
-        if (lg->dA[pj])
-            ALCH_TRY(launch_lora_up(dt, at(p.T2, (size_t)slot * kLoraSlot, E), ldt2, x, ldx, T, in_p, r, 1.f, lg->dA[pj], in_p,
-                                    false, lacc, p.up_scratch, st));
+        if (nd) ALCH_TRY(launch_lora_down(dt, dj, nd, T, lo->scale, ldt1, kLoraSlot, st));
+        if (nu) ALCH_TRY(launch_lora_up(dt, uj, nu, T, r, 1.f, lacc, p.up_scratch, st));
         return ALCH_OK;
     };
 
@@ -457,7 +469,11 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
         d.accumulate = acc;
         ALCH_TRY(launch_gemm(d, st));
     }
-    ALCH_TRY(adapter_grads(ALCH_PROJ_D, 0, p.Act, F, F, mY, H, H));
+    {
+        const void* dys[1] = {mY};
+        const int outs1[1] = {H};
+        ALCH_TRY(adapter_grads(ALCH_PROJ_D, 1, p.Act, F, F, dys, H, outs1));
+    }
     const bool lora_gu = has(ALCH_PROJ_G) || has(ALCH_PROJ_U);
     if (lora_gu) {
         const void* dys[2] = {p.dGU, at(p.dGU, F, E)};
@@ -475,8 +491,11 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
     }
     if (!hn_ready && (g.dWg || g.dWu || wants(ALCH_PROJ_G) || wants(ALCH_PROJ_U)))
         ALCH_TRY(launch_rmsnorm_fwd(dt, mX2, w.g2, p.Hn, T, H, s.rms_eps, st, ndev));
-    ALCH_TRY(adapter_grads(ALCH_PROJ_G, 0, p.Hn, H, H, p.dGU, 2 * (long long)F, F));
-    ALCH_TRY(adapter_grads(ALCH_PROJ_U, 1, p.Hn, H, H, at(p.dGU, F, E), 2 * (long long)F, F));
+    {
+        const void* dys[2] = {p.dGU, at(p.dGU, F, E)};
+        const int outs2[2] = {F, F};
+        ALCH_TRY(adapter_grads(ALCH_PROJ_G, 2, p.Hn, H, H, dys, 2 * (long long)F, outs2));
+    }
     if (g.dWg || g.dWu) {  // [dWg; dWu] = [dG | dU]^T H2
         if (g.dWg && g.dWu) {
             GemmDesc d = gemm_ws(dt, 2 * F, H, false, false);
@@ -518,7 +537,11 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
         add_out(d, mdO, 0, QD);
         ALCH_TRY(launch_gemm(d, st));
     }
-    ALCH_TRY(adapter_grads(ALCH_PROJ_O, 0, mO, QD, QD, mdX2, H, H));
+    {
+        const void* dys[1] = {mdX2};
+        const int outs1[1] = {H};
+        ALCH_TRY(adapter_grads(ALCH_PROJ_O, 1, mO, QD, QD, dys, H, outs1));
+    }
     if (g.dWo) {  // dWo = dX2^T O
         GemmDesc d = gemm_ws(dt, H, QD, false, false);
         d.k_dev = ndev;
@@ -563,9 +586,11 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
     }
     if (g.dWq || g.dWk || g.dWv || wants(ALCH_PROJ_Q) || wants(ALCH_PROJ_K) || wants(ALCH_PROJ_V))
         ALCH_TRY(launch_rmsnorm_fwd(dt, sv.X, w.g1, p.Hn, T, H, s.rms_eps, st));
-    ALCH_TRY(adapter_grads(ALCH_PROJ_Q, 0, p.Hn, H, H, p.dQKV, QKV, QD));
-    ALCH_TRY(adapter_grads(ALCH_PROJ_K, 1, p.Hn, H, H, at(p.dQKV, QD, E), QKV, KD));
-    ALCH_TRY(adapter_grads(ALCH_PROJ_V, 2, p.Hn, H, H, at(p.dQKV, QD + KD, E), QKV, KD));
+    {
+        const void* dys[3] = {p.dQKV, at(p.dQKV, QD, E), at(p.dQKV, QD + KD, E)};
+        const int outs3[3] = {QD, KD, KD};
+        ALCH_TRY(adapter_grads(ALCH_PROJ_Q, 3, p.Hn, H, H, dys, QKV, outs3));
+    }
     if (g.dWq || g.dWk || g.dWv) {  // dW{q,k,v} = d{Q,K,V}^T H1
         if (g.dWq && g.dWk && g.dWv && QD % 256 == 0 && KD % 256 == 0) {
             GemmDesc d = gemm_ws(dt, QKV, H, false, false);

@@ -113,11 +113,19 @@ struct LoraDown {
 int launch_lora_down(alch_dtype dt, const LoraDown* jobs, int n_jobs, int Trows, float alpha, long long ldy,
                      int slot_cols, hipStream_t stream);
 // C(j, n) (+)= alpha * sum_t S[t*lds + j] * X[t*ldx + n], j < r, n < N; stored C[j*ldc + n], or C[n*ldc + j]
-// when transposed.  scratch: lora_up_scratch_bytes(r, N) bytes of fp32 partial sums.
-size_t lora_up_scratch_bytes(int rank, int n_max);
-int launch_lora_up(alch_dtype dt, const void* S, long long lds, const void* X, long long ldx, int Trows, int N, int r,
-                   float alpha, void* C, long long ldc, bool transposed, int accumulate, float* scratch,
-                   hipStream_t stream);
+// when transposed.  Up to kLoraUpJobs problems per launch pair, all with Trows rows, the same r, alpha and
+// accumulate.  scratch: lora_up_scratch_bytes(r, sum of the N of the jobs) bytes of fp32 partial sums.
+static constexpr int kLoraUpJobs = 6;
+struct LoraUp {
+    const void* S; long long lds;
+    const void* X; long long ldx;
+    int N;
+    void* C; long long ldc;
+    int transposed;
+};
+size_t lora_up_scratch_bytes(int rank, int n_sum);
+int launch_lora_up(alch_dtype dt, const LoraUp* jobs, int n_jobs, int Trows, int r, float alpha, int accumulate,
+                   float* scratch, hipStream_t stream);
 // Operand preparation: job i writes dst [rows_out, cols] = src [r, cols] (or, transpose, src [cols, r]
 // transposed) followed by zero rows; src null: all zeros.
 struct LoraPrepJob {

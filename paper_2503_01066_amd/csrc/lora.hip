@@ -206,14 +206,37 @@ __device__ __forceinline__ void up_step(const __bf16* xr, const __bf16* sr, long
 template <typename T> struct UpStep { static constexpr int kTokens = 1; };
 template <> struct UpStep<__bf16> { static constexpr int kTokens = 2; };
 
+struct LoraUpJob {
+    const void* S; long long lds;
+    const void* X; long long ldx;
+    int N, nsplit, rows_per_split;
+    void* C; long long ldc;
+    int transposed;
+    long long scratch_off;  // floats
+};
+struct LoraUpParams {
+    LoraUpJob job[kLoraUpJobs];
+    int Trows, r, accumulate;
+    float alpha;
+    float* scratch;
+};
+
+// blockIdx.z = job * (r / 8) + chunk of eight rank rows; work-groups beyond a job's column slabs or row splits exit
 template <typename T>
-__global__ __launch_bounds__(256) void k_lora_up_partial(const T* __restrict__ S, long long lds, const T* __restrict__ X,
-                                                         long long ldx, int Trows, int N, int rows_per_split,
-                                                         float* __restrict__ partial) {
+__global__ __launch_bounds__(256) void k_lora_up_partial(LoraUpParams p) {
     __shared__ float red[3][64][65];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int chunks = p.r >> 3;
+    const LoraUpJob jb = p.job[blockIdx.z / chunks];
+    const int jc = blockIdx.z % chunks;
+    const int N = jb.N, nsplit = jb.nsplit, split = blockIdx.y;
+    if ((int)blockIdx.x * 512 >= N || split >= nsplit) return;
+    const T* __restrict__ S = static_cast<const T*>(jb.S);
+    const T* __restrict__ X = static_cast<const T*>(jb.X);
+    const long long lds = jb.lds, ldx = jb.ldx;
+    const int Trows = p.Trows, rows_per_split = jb.rows_per_split;
+    float* __restrict__ partial = p.scratch + jb.scratch_off;
     const int n0 = blockIdx.x * 512 + lane * 8;
-    const int split = blockIdx.y, nsplit = gridDim.y, jc = blockIdx.z;
     const long long r0 = (long long)split * rows_per_split;
     const long long r1 = r0 + rows_per_split < Trows ? r0 + rows_per_split : Trows;
     constexpr int kTok = UpStep<T>::kTokens;
@@ -253,19 +276,23 @@ __global__ __launch_bounds__(256) void k_lora_up_partial(const T* __restrict__ S
 // ---- up, pass 2: C(j, n) (+)= alpha * sum over splits, written as C[j*ldc + n] or transposed C[n*ldc + j].
 // Eight lanes share one output: lane q adds splits q, q+8, ... and the eight sums are folded in a fixed order.
 template <typename T>
-__global__ __launch_bounds__(256) void k_lora_up_finish(const float* __restrict__ partial, int nsplit, int N, int r,
-                                                        float alpha, T* __restrict__ C, long long ldc, int transposed,
-                                                        int accumulate) {
+__global__ __launch_bounds__(256) void k_lora_up_finish(LoraUpParams p) {
+    const LoraUpJob jb = p.job[blockIdx.y];
+    const int N = jb.N, nsplit = jb.nsplit, r = p.r, transposed = jb.transposed, accumulate = p.accumulate;
+    const float alpha = p.alpha;
+    const float* __restrict__ partial = p.scratch + jb.scratch_off;
+    T* __restrict__ C = static_cast<T*>(jb.C);
+    const long long ldc = jb.ldc;
     const long long idx = ((long long)blockIdx.x * 256 + threadIdx.x) >> 3;
     const int q = threadIdx.x & 7;
     const bool live = idx < (long long)N * r;
     // consecutive outputs walk n: the partial sums are read in order (C itself is small)
     const int jj = !live ? 0 : (int)(idx / N);
     const int n = !live ? 0 : (int)(idx % N);
-    const float* p = partial + ((long long)(jj >> 3) * nsplit * 8 + (jj & 7)) * N + n;
+    const float* src = partial + ((long long)(jj >> 3) * nsplit * 8 + (jj & 7)) * N + n;
     float s = 0.f;
     if (live)
-        for (int k = q; k < nsplit; k += 8) s += p[(long long)k * 8 * N];
+        for (int k = q; k < nsplit; k += 8) s += src[(long long)k * 8 * N];
     s += __shfl_xor(s, 1, 64);
     s += __shfl_xor(s, 2, 64);
     s += __shfl_xor(s, 4, 64);
@@ -303,8 +330,8 @@ static int up_splits(int Trows, int N) {
     return n;
 }
 
-size_t lora_up_scratch_bytes(int rank, int n_max) {
-    return (size_t)ceil_div(rank, 8) * kLoraMaxSplits * 8 * (size_t)n_max * sizeof(float);
+size_t lora_up_scratch_bytes(int rank, int n_sum) {
+    return (size_t)ceil_div(rank, 8) * kLoraMaxSplits * 8 * (size_t)n_sum * sizeof(float);
 }
 
 template <typename T>
@@ -348,29 +375,41 @@ int launch_lora_down(alch_dtype dt, const LoraDown* jobs, int n_jobs, int Trows,
     return ALCH_OK;
 }
 
-template <typename T>
-static int lora_up_t(const void* S, long long lds, const void* X, long long ldx, int Trows, int N, int r, float alpha,
-                     void* C, long long ldc, bool transposed, int accumulate, float* scratch, hipStream_t stream) {
-    const int nsplit = Trows > 0 ? up_splits(Trows, N) : 0;
-    if (nsplit > 0) {
-        const int rps = ceil_div(Trows, nsplit);
-        k_lora_up_partial<T><<<dim3(ceil_div(N, 512), nsplit, r / 8), 256, 0, stream>>>((const T*)S, lds, (const T*)X, ldx,
-                                                                                       Trows, N, rps, scratch);
+int launch_lora_up(alch_dtype dt, const LoraUp* jobs, int n_jobs, int Trows, int r, float alpha, int accumulate,
+                   float* scratch, hipStream_t stream) {
+    if (n_jobs < 1 || n_jobs > kLoraUpJobs) return fail(ALCH_ERR_INVALID_ARG, "adapter gradient: 1..%d problems per launch", kLoraUpJobs);
+    if (r % 8 || r <= 0) return fail(ALCH_ERR_UNSUPPORTED, "adapter gradient: rank must be a positive multiple of 8");
+    LoraUpParams p;
+    p.Trows = Trows; p.r = r; p.accumulate = accumulate; p.alpha = alpha; p.scratch = scratch;
+    double flops = 0, bytes = 0;
+    long long off = 0;
+    int max_slabs = 1, max_split = 0, max_n = 1;
+    for (int i = 0; i < kLoraUpJobs; ++i) {
+        const LoraUp& j = jobs[i < n_jobs ? i : 0];
+        if (i < n_jobs && (j.N % 8 || j.ldx % 8 || j.lds % 8))
+            return fail(ALCH_ERR_UNSUPPORTED, "adapter gradient: widths and strides must be multiples of 8");
+        const int nsplit = Trows > 0 ? up_splits(Trows, j.N) : 0;
+        p.job[i] = LoraUpJob{j.S, j.lds, j.X, j.ldx, j.N, nsplit, nsplit > 0 ? ceil_div(Trows, nsplit) : 0, j.C, j.ldc, j.transposed, off};
+        if (i < n_jobs) {
+            off += (long long)(r / 8) * kLoraMaxSplits * 8 * j.N;  // the job's share of the scratch
+            flops += 2.0 * Trows * j.N * r;
+            bytes += (double)Trows * j.N * dtype_size(dt);
+            max_slabs = std::max(max_slabs, ceil_div(j.N, 512));
+            max_split = std::max(max_split, nsplit);
+            max_n = std::max(max_n, j.N);
+        }
     }
-    k_lora_up_finish<T><<<ceil_div((long long)N * r * 8, 256LL), 256, 0, stream>>>(scratch, nsplit, N, r, alpha, (T*)C, ldc,
-                                                                              transposed ? 1 : 0, accumulate);
+    TraceScope ts(kTraceLora, flops, bytes, stream);
+    const dim3 grid_f(ceil_div((long long)max_n * r * 8, 256LL), n_jobs);
+    if (dt == ALCH_BF16) {
+        if (max_split > 0) k_lora_up_partial<__bf16><<<dim3(max_slabs, max_split, n_jobs * (r / 8)), 256, 0, stream>>>(p);
+        k_lora_up_finish<__bf16><<<grid_f, 256, 0, stream>>>(p);
+    } else {
+        if (max_split > 0) k_lora_up_partial<float><<<dim3(max_slabs, max_split, n_jobs * (r / 8)), 256, 0, stream>>>(p);
+        k_lora_up_finish<float><<<grid_f, 256, 0, stream>>>(p);
+    }
     ALCH_HIP_TRY(hipGetLastError());
     return ALCH_OK;
-}
-
-int launch_lora_up(alch_dtype dt, const void* S, long long lds, const void* X, long long ldx, int Trows, int N, int r,
-                   float alpha, void* C, long long ldc, bool transposed, int accumulate, float* scratch,
-                   hipStream_t stream) {
-    if (N % 8 || ldx % 8 || lds % 8 || r % 8 || r <= 0)
-        return fail(ALCH_ERR_UNSUPPORTED, "adapter gradient: widths, strides and rank must be multiples of 8");
-    TraceScope ts(kTraceLora, 2.0 * Trows * N * r, (double)Trows * N * dtype_size(dt), stream);
-    return dt == ALCH_BF16 ? lora_up_t<__bf16>(S, lds, X, ldx, Trows, N, r, alpha, C, ldc, transposed, accumulate, scratch, stream)
-                           : lora_up_t<float>(S, lds, X, ldx, Trows, N, r, alpha, C, ldc, transposed, accumulate, scratch, stream);
 }
 
 int launch_lora_prep(alch_dtype dt, const LoraPrepParams& p, int n_jobs, hipStream_t stream) {
