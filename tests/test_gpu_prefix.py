@@ -117,6 +117,27 @@ def test_partial_record_with_shared_prefixes(dtype, shape_name, prompts, respons
         assert rel_err(to_np(out[k]), ref[k]) <= TOL[dtype], (k, rel_err(to_np(out[k]), ref[k]))
 
 
+@pytest.mark.parametrize("dtype,shape_name,prompts,responses", [CASES[0], CASES[3]])
+def test_loss_mask_on_a_shared_prefix_batch(dtype, shape_name, prompts, responses):
+    # loss mask = zeroed dY rows (the prompt rows of a top layer carry no loss): the row-local part may run on the
+    # kept rows only, the attention backward still reaches the prompt's keys and values
+    import paper_2503_01066_amd as A
+    shp, osh, b, W, X, _, _, rec, dY = make(dtype, shape_name, prompts, responses, 31)
+    T = X.shape[0]
+    mask = np.zeros(T, np.uint8)
+    mask[int(b["cu"][b["n_prompts"]]):] = 1          # responses only
+    mask[np.asarray(b["cu"][1:b["n_prompts"] + 1]) - 1] = 1   # and the last row of every prompt
+    dYz = dY.copy()
+    dYz[mask == 0] = 0
+    ref = layer_backward_reuse_prefix(osh, b["cu"], b["prefix"], f64(rec), f64(W), dYz)
+    batch = A.Batch(b["cu"], positions=b["positions"], prefix=b["prefix"])
+    out = A.alch_layer_backward(alch_shape(shp, dtype), batch, dev_record(rec, dtype), {k: to_dev(v, dtype) for k, v in W.items()},
+                                to_dev(dY, dtype), loss_mask=torch.from_numpy(mask).cuda())
+    torch.cuda.synchronize()
+    for k in ["dX"] + ["d" + w for w in WEIGHT_KEYS]:
+        assert rel_err(to_np(out[k]), ref[k]) <= TOL[dtype], (k, rel_err(to_np(out[k]), ref[k]))
+
+
 def test_whole_batch_forward_with_prefixes_equals_the_oracle():
     import paper_2503_01066_amd as A
     dtype = "bf16"
