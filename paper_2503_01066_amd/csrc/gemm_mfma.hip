@@ -190,7 +190,8 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
     // kSplit: one tile per work-group; work-group w of an XCD takes part w / rem of tile q_end + w % rem
     const int rem = per_xcd - p.q_end;
     const int ks = kSplit ? (int)(blockIdx.x / 8) / rem : 0;
-    for (int q = kSplit ? p.q_end + (int)(blockIdx.x / 8) % rem : (int)(blockIdx.x / 8); q < (kSplit ? per_xcd : p.q_end);
+    // (q_end comes from the host's tile count; with a device-resident row count the XCD's share may be shorter)
+    for (int q = kSplit ? p.q_end + (int)(blockIdx.x / 8) % rem : (int)(blockIdx.x / 8); q < (kSplit ? per_xcd : min(p.q_end, per_xcd));
          q += kSplit ? per_xcd : (int)(gridDim.x / 8)) {
     const int t = (blockIdx.x % 8) * per_xcd + q;
     if (t >= nt) break;
