@@ -246,3 +246,21 @@ def test_six_stream_record_passes_validation_but_missing_required_tensors_do_not
         ptrs[missing] = None
         sv = B.CSaved(*ptrs, 0)
         assert L.alch_layer_backward(C.byref(s), C.byref(b), C.byref(sv), C.byref(w), P, None, P, C.byref(g), P, 1 << 40, None) == -1
+
+
+def test_gemm_rejects_bad_arguments():
+    L = A.lib()
+    P = 0x10000
+    term = (B.CGemmTerm * 1)(B.CGemmTerm(P, P, 64, 64, 256))
+    call = lambda **kw: L.alch_gemm_ws(kw.get("dtype", 1), kw.get("M", 256), kw.get("N", 256), 1, 0, kw.get("n_terms", 1),
+                                       kw.get("terms", term), kw.get("C", P), kw.get("ldc", 256), 0, kw.get("ws", None),
+                                       kw.get("ws_bytes", 0), None)
+    assert L.alch_gemm_workspace_bytes() == 64 << 20
+    assert call(dtype=7) == -1
+    assert call(M=-1) == -2
+    assert call(n_terms=0) == -1 and call(n_terms=5) == -1 and call(terms=None) == -1
+    assert call(C=None) == -1 and call(ldc=8) == -1
+    assert call(ws=P + 4, ws_bytes=64 << 20) == -1 and "workspace" in _err()
+    bad = (B.CGemmTerm * 1)(B.CGemmTerm(P, P, 64, 32, 256))      # lda < K of a k-major operand
+    assert call(terms=bad) == -2
+    assert call(M=0) == 0                                           # nothing to do, nothing launched
