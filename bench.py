@@ -681,8 +681,8 @@ def run_copy(args, torch, A):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build measures one GPU only (--gpus 1); multi-GPU sharding is design-only "
-              "(see DESIGN.md)", file=sys.stderr)
+        print("bench.py: this build measures one GPU only (--gpus 1); sharding over several GPUs (by sequence, one "
+              "exchange of the weight gradients) is described in the design notes and not built", file=sys.stderr)
         sys.exit(2)
     import torch
     import paper_2503_01066_amd as A
