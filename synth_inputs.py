@@ -18,6 +18,8 @@ SHAPES = {
     "llama70b": (8192, 64, 8, 128, 28672, 1e-5, 500000.0),
     "phi4":     (5120, 40, 10, 128, 17920, 1e-5, 250000.0),   # the third model of the paper's evaluation (Section 6)
 }
+# a test shape whose fused q/k/v weight gradient has 48 x 8 = 384 output tiles in three row ranges
+SHAPES["wideqkv"] = (2048, 64, 16, 128, 512, 1e-5, 10000.0)
 SHAPE_FIELDS = ("hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn", "rms_eps", "rope_base")
 
 

@@ -218,6 +218,24 @@ def test_config2_full_size_adapter_mode_sampled_outputs():
         assert torch.isfinite(v.float()).all(), k
 
 
+def test_split_products_with_several_outputs_and_operand_pairs():
+    # 2 x 512 tokens on a layer whose [dWq; dWk; dWv] product has 384 output tiles in three row ranges (its last round
+    # of 128 tiles is split in two along the tokens) and whose data-gradient products have 32 tiles and up to three
+    # operand pairs (every tile split): element-by-element against the oracle
+    shp = synth.shape_dict("wideqkv")
+    osh = oracle_shape(shp)
+    cu = synth.ragged_cu([512, 512])
+    T = 1024
+    W = synth.layer_weights(shp, 7, "bf16", std=0.02, gain_std=0.1)
+    rec = synth.drawn_record(shp, T, 8, "bf16")
+    rec["LSE"] = attention_lse(osh, cu, rec["Q"].astype(np.float64), rec["K"].astype(np.float64)).astype(np.float32)
+    dY = synth.activations(T, shp["hidden"], 9, "bf16", std=0.01)
+    ref = layer_backward_reuse(osh, cu, None, f64(rec), f64(W), dY)
+    out = gpu_layer(shp, cu, W, rec, dY)
+    for k in ["dX"] + ["d" + w for w in WEIGHT_KEYS]:
+        assert rel_err(to_np(out[k]), ref[k]) <= 2e-2, (k, rel_err(to_np(out[k]), ref[k]))
+
+
 def test_shared_prompt_equals_duplicated_prefill_at_real_width():
     # Property that holds at any size (Section 4.1: chosen and rejected share the prompt's prefill): the DPO step on
     # [prompts | responses with a prefix] gives the loss and gradients of the step that prefills prompt + response
