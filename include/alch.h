@@ -136,6 +136,18 @@ int alch_capture_pack(const alch_batch* batch, const uint8_t* keep_mask, int32_t
 
 size_t alch_capture_pack_workspace_bytes(int32_t total_tokens);
 
+/*
+ * alch_capture_gather: the gather of alch_capture_pack alone, for further streams of the same batch and
+ * mask (Section 4.1: one prefill batch is recorded layer after layer; which tokens are kept does not change
+ * from layer to layer, so the mask is scanned once).  kept_index and n_kept_and_status are the device
+ * outputs of an earlier alch_capture_pack on this batch, complete in stream order before this call; for every
+ * stream k and r < min(n_kept, dst_capacity_rows): dst_k[r, :] = src_k[kept_index[r], :]  (bit-for-bit).
+ * dst_capacity_rows must not exceed the capacity that earlier call was given.
+ */
+int alch_capture_gather(const alch_batch* batch, int32_t n_streams, const alch_stream* streams,
+                        int64_t dst_capacity_rows, const int32_t* kept_index,
+                        const int32_t* n_kept_and_status, void* hip_stream);
+
 /* ------------------------------------------------------------------------------------
  * Family 2: backward from saved activations (Section 1; Section 4.2; Section 4.3.2).
  */

@@ -115,6 +115,9 @@ def lib():
     L.alch_capture_pack.restype = C.c_int
     L.alch_capture_pack.argtypes = [C.POINTER(CBatch), C.c_void_p, C.c_int32, C.POINTER(CStream), C.c_int64,
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.alch_capture_gather.restype = C.c_int
+    L.alch_capture_gather.argtypes = [C.POINTER(CBatch), C.c_int32, C.POINTER(CStream), C.c_int64, C.c_void_p,
+                                      C.c_void_p, C.c_void_p]
     L.alch_layer_backward.restype = C.c_int
     L.alch_layer_backward.argtypes = [C.POINTER(LayerShape), C.POINTER(CBatch), C.POINTER(CSaved),
                                       C.POINTER(CWeights), C.c_void_p, C.c_void_p, C.c_void_p,
@@ -238,6 +241,24 @@ def alch_capture_pack(batch, keep_mask, streams, capacity=None, dsts=None, strea
     _check(L.alch_capture_pack(C.byref(batch.c), _ptr(keep_mask), len(streams), arr, capacity, _ptr(kept_index),
                                _ptr(cu_kept), _ptr(status), _ptr(ws), ws.numel(), _stream_handle(stream)))
     return kept_index, cu_kept, status, dsts
+
+
+def alch_capture_gather(batch, kept_index, status, streams, capacity=None, dsts=None, stream=None):
+    """Gathers further streams with the index of an earlier alch_capture_pack on the same batch and mask
+    (kept_index, status = its second and third return values).  Returns dsts."""
+    L = lib()
+    dev = kept_index.device
+    capacity = batch.total_tokens if capacity is None else int(capacity)
+    if dsts is None:
+        dsts = [torch.empty((capacity, s.shape[1]), dtype=s.dtype, device=dev) for s in streams]
+    arr = (CStream * max(len(streams), 1))()
+    for i, (s, d) in enumerate(zip(streams, dsts)):
+        assert s.numel() == 0 or (s.stride(1) == 1 and d.is_contiguous())
+        row_stride = s.stride(0) if s.numel() > 0 else s.shape[1]
+        arr[i] = CStream(s.data_ptr(), d.data_ptr(), s.shape[1] * s.element_size(), row_stride * s.element_size())
+    _check(L.alch_capture_gather(C.byref(batch.c), len(streams), arr, capacity, _ptr(kept_index), _ptr(status),
+                                 _stream_handle(stream)))
+    return dsts
 
 
 def _saved_struct(saved, version):

@@ -710,6 +710,8 @@ int alch_gemm_ws(alch_dtype dtype, int32_t M, int32_t N, int32_t a_kmajor, int32
 
 size_t alch_capture_pack_workspace_bytes(int32_t total_tokens) { return pack_workspace_bytes(total_tokens); }
 
+static int check_streams(int32_t n_streams, const alch_stream* streams, int T, int64_t dst_capacity_rows);
+
 int alch_capture_pack(const alch_batch* batch, const uint8_t* keep_mask, int32_t n_streams,
                       const alch_stream* streams, int64_t dst_capacity_rows, int32_t* kept_index, int32_t* cu_kept,
                       int32_t* n_kept_and_status, void* workspace, size_t workspace_bytes, void* hip_stream) {
@@ -717,25 +719,41 @@ int alch_capture_pack(const alch_batch* batch, const uint8_t* keep_mask, int32_t
     ALCH_TRY(check_batch(batch));
     if (batch->total_tokens > 0 && !keep_mask) return fail(ALCH_ERR_INVALID_ARG, "keep_mask is NULL");
     OPTIONAL_PTR(keep_mask, "keep_mask");
-    if (n_streams < 0) return fail(ALCH_ERR_INVALID_ARG, "n_streams < 0");
-    if (n_streams > 0 && !streams) return fail(ALCH_ERR_INVALID_ARG, "streams is NULL");
-    if (dst_capacity_rows < 0) return fail(ALCH_ERR_INVALID_ARG, "dst_capacity_rows < 0");
+    ALCH_TRY(check_streams(n_streams, streams, batch->total_tokens, dst_capacity_rows));
     if (dst_capacity_rows > 0 && !kept_index) return fail(ALCH_ERR_INVALID_ARG, "kept_index is NULL");
     if (!cu_kept || !n_kept_and_status) return fail(ALCH_ERR_INVALID_ARG, "cu_kept / n_kept_and_status is NULL");
-    for (int k = 0; k < n_streams; ++k) {
-        const alch_stream& s = streams[k];
-        if (s.row_bytes == 0 || s.row_bytes % 4) return fail(ALCH_ERR_SHAPE, "stream %d: row_bytes %zu not a positive multiple of 4", k, s.row_bytes);
-        if (s.src_row_stride_bytes < s.row_bytes || s.src_row_stride_bytes % 4)
-            return fail(ALCH_ERR_SHAPE, "stream %d: src_row_stride_bytes %zu < row_bytes or not a multiple of 4", k, s.src_row_stride_bytes);
-        if ((batch->total_tokens > 0 && !s.src) || (dst_capacity_rows > 0 && !s.dst)) return fail(ALCH_ERR_INVALID_ARG, "stream %d: NULL src or dst", k);
-        if ((reinterpret_cast<uintptr_t>(s.src) | reinterpret_cast<uintptr_t>(s.dst)) & 3u)
-            return fail(ALCH_ERR_INVALID_ARG, "stream %d: src or dst not 4-byte aligned", k);
-    }
     const size_t need = pack_workspace_bytes(batch->total_tokens);
     if (!workspace || workspace_bytes < need) return fail(ALCH_ERR_WORKSPACE, "workspace %zu bytes < %zu needed", workspace_bytes, need);
     return launch_pack(keep_mask, batch->total_tokens, batch->cu_seqlens, batch->n_seqs, n_streams, streams,
                        dst_capacity_rows, kept_index, cu_kept, n_kept_and_status, workspace,
                        static_cast<hipStream_t>(hip_stream));
+}
+
+static int check_streams(int32_t n_streams, const alch_stream* streams, int T, int64_t dst_capacity_rows) {
+    if (n_streams < 0) return fail(ALCH_ERR_INVALID_ARG, "n_streams < 0");
+    if (n_streams > 0 && !streams) return fail(ALCH_ERR_INVALID_ARG, "streams is NULL");
+    if (dst_capacity_rows < 0) return fail(ALCH_ERR_INVALID_ARG, "dst_capacity_rows < 0");
+    for (int k = 0; k < n_streams; ++k) {
+        const alch_stream& s = streams[k];
+        if (s.row_bytes == 0 || s.row_bytes % 4) return fail(ALCH_ERR_SHAPE, "stream %d: row_bytes %zu not a positive multiple of 4", k, s.row_bytes);
+        if (s.src_row_stride_bytes < s.row_bytes || s.src_row_stride_bytes % 4)
+            return fail(ALCH_ERR_SHAPE, "stream %d: src_row_stride_bytes %zu < row_bytes or not a multiple of 4", k, s.src_row_stride_bytes);
+        if ((T > 0 && !s.src) || (dst_capacity_rows > 0 && !s.dst)) return fail(ALCH_ERR_INVALID_ARG, "stream %d: NULL src or dst", k);
+        if ((reinterpret_cast<uintptr_t>(s.src) | reinterpret_cast<uintptr_t>(s.dst)) & 3u)
+            return fail(ALCH_ERR_INVALID_ARG, "stream %d: src or dst not 4-byte aligned", k);
+    }
+    return ALCH_OK;
+}
+
+int alch_capture_gather(const alch_batch* batch, int32_t n_streams, const alch_stream* streams, int64_t dst_capacity_rows,
+                        const int32_t* kept_index, const int32_t* n_kept_and_status, void* hip_stream) {
+    clear_error();
+    ALCH_TRY(check_batch(batch));
+    ALCH_TRY(check_streams(n_streams, streams, batch->total_tokens, dst_capacity_rows));
+    if (dst_capacity_rows > 0 && !kept_index) return fail(ALCH_ERR_INVALID_ARG, "kept_index is NULL");
+    if (!n_kept_and_status) return fail(ALCH_ERR_INVALID_ARG, "n_kept_and_status is NULL");
+    return launch_pack_gather(batch->total_tokens, n_streams, streams, dst_capacity_rows, kept_index, n_kept_and_status,
+                              static_cast<hipStream_t>(hip_stream));
 }
 
 size_t alch_layer_backward_workspace_bytes(const alch_layer_shape* shape, int32_t total_tokens, int32_t max_seqlen) {

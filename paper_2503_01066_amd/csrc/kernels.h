@@ -11,6 +11,8 @@ size_t pack_workspace_bytes(int total_tokens);
 int launch_pack(const uint8_t* mask, int T, const int* cu_seqlens, int n_seqs, int n_streams,
                 const alch_stream* streams, long long capacity, int* kept_index, int* cu_kept,
                 int* n_kept_and_status, void* workspace, hipStream_t stream, bool traced = true);
+int launch_pack_gather(int T, int n_streams, const alch_stream* streams, long long capacity, const int* kept_index,
+                       const int* n_kept_and_status, hipStream_t stream, bool traced = true);
 
 // ---- GEMM ------------------------------------------------------------------------------
 // C[M,N] (+)= sum over segments of A_s(M,K_s) * B_s(K_s,N), fp32 accumulation.

@@ -185,6 +185,12 @@ int launch_pack(const uint8_t* mask, int T, const int* cu_seqlens, int n_seqs, i
                                               n_kept_and_status, cu_kept);
     }
     ALCH_HIP_TRY(hipGetLastError());
+    return launch_pack_gather(T, n_streams, streams, capacity, kept_index, n_kept_and_status, stream, traced);
+}
+
+// The gather alone, from an index and a row count already on the device.
+int launch_pack_gather(int T, int n_streams, const alch_stream* streams, long long capacity, const int* kept_index,
+                       const int* n_kept_and_status, hipStream_t stream, bool traced) {
     if (T == 0 || capacity == 0) return ALCH_OK;
 
     // traced bytes of the gather: per kept row (read once + written once); the row count is on the device

@@ -73,6 +73,22 @@ def test_capture_pack_rejects_bad_arguments():
     assert L.alch_capture_pack(None, P, 1, st, 5, P, P, P, P, 1024, None) == -1
 
 
+def test_capture_gather_rejects_bad_arguments():
+    L = A.lib()
+    P = 0x1000
+    b = _batch([0, 3, 5])
+    st = (B.CStream * 1)(B.CStream(P, P, 16, 16))
+    call = lambda **kw: L.alch_capture_gather(C.byref(kw.get("b", b)), kw.get("n", 1), kw.get("st", st), kw.get("cap", 5),
+                                              kw.get("idx", P), kw.get("status", P), None)
+    assert call(idx=None) == -1 and "kept_index" in _err()
+    assert call(status=None) == -1
+    assert call(n=-1) == -1 and call(st=None) == -1 and call(cap=-1) == -1
+    assert call(st=(B.CStream * 1)(B.CStream(P, P, 6, 16))) == -2
+    assert call(st=(B.CStream * 1)(B.CStream(P, None, 16, 16))) == -1
+    assert call(b=_batch([0, 3, 2], T=2, max_len=3)) == -2
+    assert call(cap=0, idx=None) == 0          # nothing can be written: nothing is launched
+
+
 def test_layer_backward_rejects_bad_arguments():
     L = A.lib()
     P = 0x10000

@@ -114,3 +114,28 @@ def test_deterministic_bits():
     b = run_pack(cu, mask, srcs)
     n = a[2][0]
     assert np.array_equal(a[0][:n], b[0][:n]) and np.array_equal(a[3][0][:n], b[3][0][:n])
+
+
+@pytest.mark.parametrize("keep,capacity", [(0.3, None), (0.0, None), (1.0, None), (0.6, 1000)])
+def test_gather_with_the_index_of_an_earlier_pack(keep, capacity):
+    # one scan per batch, one gather per layer: the streams of a second "layer" are gathered with the index the
+    # first call left on the device; bit-exact against the oracle on those streams, also when the capacity cuts
+    import paper_2503_01066_amd as A
+    rng = np.random.default_rng(17)
+    cu = synth.ragged_cu([700, 0, 3000, 1, 513])
+    T = int(cu[-1])
+    mask = synth.keep_mask(T, keep, 2)
+    first, second = streams_for(T, rng, widths=(64,)), streams_for(T, rng, widths=(24, 8, 520))
+    batch = A.Batch(cu)
+    kept, cu_kept, status, _ = A.alch_capture_pack(batch, torch.from_numpy(mask).cuda(), [torch.from_numpy(s).cuda() for s in first],
+                                                   capacity=capacity)
+    wide = torch.zeros((T, 600), dtype=torch.int16, device="cuda")          # one stream as a column slice
+    wide[:, 40:560] = torch.from_numpy(second[2].view(np.int16)).cuda()
+    devs = [torch.from_numpy(second[0].view(np.int16)).cuda(), torch.from_numpy(second[1].view(np.int16)).cuda(), wide[:, 40:560]]
+    dsts = A.alch_capture_gather(batch, kept, status, devs, capacity=capacity)
+    torch.cuda.synchronize()
+    ok, _, opacked = gather_pack(mask, cu, second)
+    n = len(ok) if capacity is None else min(len(ok), capacity)
+    assert int(status[0]) == len(ok) and int(status[1]) == (0 if capacity is None or len(ok) <= capacity else 1)
+    for d, o in zip(dsts, opacked):
+        assert np.array_equal(d[:n].cpu().numpy().view(np.uint8), o[:n].view(np.uint8))
