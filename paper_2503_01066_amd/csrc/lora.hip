@@ -323,7 +323,7 @@ __global__ __launch_bounds__(256) void k_lora_prep(LoraPrepParams p) {
 
 static int up_splits(int Trows, int N) {
     const int slabs = ceil_div(N, 512);
-    int n = ceil_div(512, slabs);
+    int n = ceil_div(256, slabs);
     if (n < 4) n = 4;
     if (n > kLoraMaxSplits) n = kLoraMaxSplits;
     if (n > Trows) n = Trows > 0 ? Trows : 1;
