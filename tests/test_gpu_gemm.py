@@ -98,3 +98,29 @@ def test_gemm_split_short_batches(a_k, b_k, M, N, Ks):
     torch.cuda.synchronize()
     assert rel_err(to_np(C0), ref) < 6e-3 and rel_err(to_np(C1), ref) < 6e-3
     assert torch.equal(C1, C2)
+
+
+def test_gemm_random_shapes_with_scratch():
+    # seeded random sizes around the thresholds of the split (tile counts near 128, 256, 384; short and long
+    # contractions; ragged edges), all three layouts, one or two operand pairs, with and without accumulate
+    import paper_2503_01066_amd as A_
+    rng = np.random.default_rng(2024)
+    ws = torch.empty(A_.lib().alch_gemm_workspace_bytes(), dtype=torch.uint8, device="cuda")
+    for case in range(14):
+        a_k, b_k = [(True, False), (False, False), (True, True)][case % 3]
+        tm, tn = int(rng.integers(1, 26)), int(rng.integers(1, 26))
+        M = tm * 256 - int(rng.integers(0, 32)) * 8
+        N = tn * 256 - int(rng.integers(0, 32)) * 8
+        Ks = [int(rng.integers(2, 40)) * 64 for _ in range(int(rng.integers(1, 3)))]
+        acc = bool(rng.integers(0, 2))
+        terms, ref = [], 0.0
+        for K in Ks:
+            A, B, r = operands(rng, M, N, K, a_k, b_k, "bf16")
+            terms.append((to_dev(A, "bf16"), to_dev(B, "bf16"), K))
+            ref = ref + r
+        C0 = synth.quantize(rng.standard_normal((M, N)).astype(np.float32) * 20, "bf16")
+        C = to_dev(C0, "bf16")
+        A_.alch_gemm(M, N, terms, a_k, b_k, out=C, accumulate=acc, workspace=ws)
+        torch.cuda.synchronize()
+        want = ref + C0 if acc else ref
+        assert rel_err(to_np(C), want) < 6e-3, (case, M, N, Ks, a_k, b_k, acc)
