@@ -270,3 +270,22 @@ def test_stack_backward_dpo_with_adapters_on_a_frozen_base():
             for k in ("dA" + p, "dB" + p):
                 e = rel_err(to_np(out["layers"][l][k]), want["layers"][l][k])
                 assert e <= tol, (l, k, e)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_layer_backward_random_prefix_batches(seed):
+    # seeded random batches: 1-3 prompts of 1-400 tokens, 0-3 responses of 0-200 tokens each, on the matrix-core path
+    import paper_2503_01066_amd as A
+    rng = np.random.default_rng(100 + seed)
+    n_p = int(rng.integers(1, 4))
+    prompts = [int(rng.integers(1, 401)) for _ in range(n_p)]
+    responses = [[int(rng.integers(0, 201)) for _ in range(int(rng.integers(0, 4)))] for _ in range(n_p)]
+    dtype = "bf16"
+    shp, osh, b, W, X, _, _, rec, dY = make(dtype, "medium", prompts, responses, 40 + seed)
+    ref = layer_backward_reuse_prefix(osh, b["cu"], b["prefix"], f64(rec), f64(W), dY)
+    batch = A.Batch(b["cu"], positions=b["positions"], prefix=b["prefix"])
+    out = A.alch_layer_backward(alch_shape(shp, dtype), batch, dev_record(rec, dtype),
+                                {k: to_dev(v, dtype) for k, v in W.items()}, to_dev(dY, dtype))
+    torch.cuda.synchronize()
+    for k in ["dX"] + ["d" + w for w in WEIGHT_KEYS]:
+        assert rel_err(to_np(out[k]), ref[k]) <= TOL[dtype], (prompts, responses, k, rel_err(to_np(out[k]), ref[k]))
