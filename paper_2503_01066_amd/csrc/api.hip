@@ -489,8 +489,13 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
         add_out(d, p.dHn, 0, H);
         ALCH_TRY(launch_gemm(d, st));
     }
-    if (!hn_ready && (g.dWg || g.dWu || wants(ALCH_PROJ_G) || wants(ALCH_PROJ_U)))
-        ALCH_TRY(launch_rmsnorm_fwd(dt, mX2, w.g2, p.Hn, T, H, s.rms_eps, st, ndev));
+    // dX2 = dY + RMSNorm-2 backward(dH2); dg2.  The same pass over X2 leaves H2 for the weight and adapter gradients
+    // of the gate and up projections (unless the record completion above already formed it).
+    {
+        const bool need_h2 = !hn_ready && (g.dWg || g.dWu || wants(ALCH_PROJ_G) || wants(ALCH_PROJ_U));
+        ALCH_TRY(launch_rmsnorm_bwd(dt, p.dHn, mX2, w.g2, mY, nullptr, mdX2, g.dg2, acc, p.partial, T, H, s.rms_eps, st, ndev,
+                                    need_h2 ? p.Hn : nullptr));
+    }
     {
         const void* dys[2] = {p.dGU, at(p.dGU, F, E)};
         const int outs2[2] = {F, F};
@@ -521,8 +526,6 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
             ALCH_TRY(launch_gemm(d, st));
         }
     }
-    // dX2 = dY + RMSNorm-2 backward(dH2); dg2
-    ALCH_TRY(launch_rmsnorm_bwd(dt, p.dHn, mX2, w.g2, mY, nullptr, mdX2, g.dg2, acc, p.partial, T, H, s.rms_eps, st, ndev));
 
     if (has(ALCH_PROJ_O)) {
         const void* dys[1] = {mdX2};
@@ -584,8 +587,13 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
         add_out(d, p.dHn, 0, H);
         ALCH_TRY(launch_gemm(d, st));
     }
-    if (g.dWq || g.dWk || g.dWv || wants(ALCH_PROJ_Q) || wants(ALCH_PROJ_K) || wants(ALCH_PROJ_V))
-        ALCH_TRY(launch_rmsnorm_fwd(dt, sv.X, w.g1, p.Hn, T, H, s.rms_eps, st));
+    // dX = dX2 + RMSNorm-1 backward(dH1); dg1.  The same pass over X leaves H1 for the weight and adapter gradients of
+    // the q, k, v projections.
+    {
+        const bool need_h1 = g.dWq || g.dWk || g.dWv || wants(ALCH_PROJ_Q) || wants(ALCH_PROJ_K) || wants(ALCH_PROJ_V);
+        ALCH_TRY(launch_rmsnorm_bwd(dt, p.dHn, sv.X, w.g1, p.dX2, nullptr, dX, g.dg1, acc, p.partial, T, H, s.rms_eps, st, nullptr,
+                                    need_h1 ? p.Hn : nullptr));
+    }
     {
         const void* dys[3] = {p.dQKV, at(p.dQKV, QD, E), at(p.dQKV, QD + KD, E)};
         const int outs3[3] = {QD, KD, KD};
@@ -613,8 +621,6 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
             }
         }
     }
-    // dX = dX2 + RMSNorm-1 backward(dH1); dg1
-    ALCH_TRY(launch_rmsnorm_bwd(dt, p.dHn, sv.X, w.g1, p.dX2, nullptr, dX, g.dg1, acc, p.partial, T, H, s.rms_eps, st));
     return ALCH_OK;
 }
 

@@ -76,10 +76,12 @@ int launch_rmsnorm_fwd(alch_dtype dt, const void* X, const void* g, void* H, int
                        hipStream_t stream, const int* rows_dev = nullptr);
 // dX = resid + rmsnorm_bwd(dH; X, g)   (resid may be NULL; resid_mask zeroes resid rows where mask==0);
 // dg (+)= sum_t dH*X*r  (dg may be NULL).  partial: fp32 scratch [rmsnorm_bwd_blocks(T), width].
+// hn_out (may be NULL): also writes the normalised rows X*r*g themselves, the operand of the weight gradients
+// that follow, so that X is read once for both.
 int rmsnorm_bwd_blocks(int T);
 int launch_rmsnorm_bwd(alch_dtype dt, const void* dH, const void* X, const void* g, const void* resid,
                        const uint8_t* resid_mask, void* dX, void* dg, int accumulate, float* partial, int T,
-                       int width, float eps, hipStream_t stream, const int* rows_dev = nullptr);
+                       int width, float eps, hipStream_t stream, const int* rows_dev = nullptr, void* hn_out = nullptr);
 // inv[t] = rank of token t among the first *n_rows entries of index (the kept tokens), -1 if absent
 int launch_rank_of_kept(const int* index, const int* n_rows, int* inv, int T, hipStream_t stream);
 // out [T, row_bytes] = src[inv[t], :] where inv[t] >= 0, zeros elsewhere

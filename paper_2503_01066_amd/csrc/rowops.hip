@@ -177,7 +177,7 @@ __global__ __launch_bounds__(256) void k_rmsnorm_bwd_bf16(const __bf16* __restri
                                                           const __bf16* __restrict__ g, const __bf16* __restrict__ resid,
                                                           const uint8_t* __restrict__ resid_mask, __bf16* __restrict__ dX,
                                                           float* __restrict__ partial, int Trows, int width, float eps,
-                                                          const int* __restrict__ rows_dev) {
+                                                          const int* __restrict__ rows_dev, __bf16* __restrict__ hn_out) {
     __shared__ float sred[NC * 512];
     if (rows_dev) Trows = min(Trows, *rows_dev);  // row count decided on the device (compacted rows)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -233,6 +233,12 @@ __global__ __launch_bounds__(256) void k_rmsnorm_bwd_bf16(const __bf16* __restri
                     dgp[k][e] += d * x * r;
                 }
                 *reinterpret_cast<bf16x8_t*>(dX + row * width + col) = ov;
+                if (hn_out) {  // the normalised row itself (the forward's value), for the weight gradients that follow
+                    bf16x8_t hv;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) hv[e] = (__bf16)((float)xv[k][e] * r * (float)gv[k][e]);
+                    *reinterpret_cast<bf16x8_t*>(hn_out + row * width + col) = hv;
+                }
             }
         }
     }
@@ -308,7 +314,7 @@ __global__ __launch_bounds__(256) void k_rmsnorm_bwd_bf16_split(const __bf16* __
                                                                 const uint8_t* __restrict__ resid_mask,
                                                                 __bf16* __restrict__ dX, float* __restrict__ partial,
                                                                 int Trows, int width, float eps,
-                                                                const int* __restrict__ rows_dev) {
+                                                                const int* __restrict__ rows_dev, __bf16* __restrict__ hn_out) {
     constexpr int RPB = 4 / WPR;  // rows per work-group per iteration
     __shared__ float rsum[2][4][2];
     __shared__ float sred[2 * 4 * 8 * 64];  // [part][chunk][element][lane], used when two rows share a work-group
@@ -375,6 +381,12 @@ __global__ __launch_bounds__(256) void k_rmsnorm_bwd_bf16_split(const __bf16* __
                     dgp[k][e] += d * x * r;
                 }
                 *reinterpret_cast<bf16x8_t*>(dX + row * width + col[k]) = ov;
+                if (hn_out) {  // the normalised row itself (the forward's value), for the weight gradients that follow
+                    bf16x8_t hv;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) hv[e] = (__bf16)((float)xv[k][e] * r * (float)gv[k][e]);
+                    *reinterpret_cast<bf16x8_t*>(hn_out + row * width + col[k]) = hv;
+                }
             }
         }
     }
@@ -404,15 +416,15 @@ __global__ __launch_bounds__(256) void k_rmsnorm_bwd_bf16_split(const __bf16* __
 
 static int rmsnorm_bwd_bf16_fast(const void* dH, const void* X, const void* g, const void* resid,
                                  const uint8_t* resid_mask, void* dX, void* dg, int accumulate, float* partial, int T_,
-                                 int width, float eps, hipStream_t stream, const int* rows_dev) {
+                                 int width, float eps, hipStream_t stream, const int* rows_dev, void* hn_out) {
     const int nblk = ceil_div(T_, 4) < kNormFastBlocks ? ceil_div(T_, 4) : kNormFastBlocks;
     float* part = dg ? partial : nullptr;
 #define ALCH_NORM_BWD(NC)                                                                                          \
     k_rmsnorm_bwd_bf16<NC><<<nblk, 256, 0, stream>>>((const __bf16*)dH, (const __bf16*)X, (const __bf16*)g,         \
-                                                     (const __bf16*)resid, resid_mask, (__bf16*)dX, part, T_, width, eps, rows_dev)
+                                                     (const __bf16*)resid, resid_mask, (__bf16*)dX, part, T_, width, eps, rows_dev, (__bf16*)hn_out)
 #define ALCH_NORM_BWD_SPLIT(WPR)                                                                                    \
     k_rmsnorm_bwd_bf16_split<WPR><<<nblk, 256, 0, stream>>>((const __bf16*)dH, (const __bf16*)X, (const __bf16*)g,  \
-                                                            (const __bf16*)resid, resid_mask, (__bf16*)dX, part, T_, width, eps, rows_dev)
+                                                            (const __bf16*)resid, resid_mask, (__bf16*)dX, part, T_, width, eps, rows_dev, (__bf16*)hn_out)
     if (width <= 1024) ALCH_NORM_BWD(2);
     else if (width <= 2048) ALCH_NORM_BWD(4);
     else if (width <= 4096) ALCH_NORM_BWD_SPLIT(2);
@@ -426,7 +438,7 @@ static int rmsnorm_bwd_bf16_fast(const void* dH, const void* X, const void* g, c
 
 int launch_rmsnorm_bwd(alch_dtype dt, const void* dH, const void* X, const void* g, const void* resid,
                        const uint8_t* resid_mask, void* dX, void* dg, int accumulate, float* partial, int T,
-                       int width, float eps, hipStream_t stream, const int* rows_dev) {
+                       int width, float eps, hipStream_t stream, const int* rows_dev, void* hn_out) {
     if (width > 256 * kNormMaxCols) return fail(ALCH_ERR_UNSUPPORTED, "hidden %d > %d", width, 256 * kNormMaxCols);
     if (T <= 0) {
         // no rows: the gain gradient is zero (or unchanged when accumulating)
@@ -440,9 +452,10 @@ int launch_rmsnorm_bwd(alch_dtype dt, const void* dH, const void* X, const void*
         return ALCH_OK;
     }
     if (dt == ALCH_BF16 && width % 8 == 0 && aligned16(dH) && aligned16(X) && aligned16(g) && aligned16(dX) &&
-        (!resid || aligned16(resid)))
-        return rmsnorm_bwd_bf16_fast(dH, X, g, resid, resid_mask, dX, dg, accumulate, partial, T, width, eps, stream, rows_dev);
+        (!resid || aligned16(resid)) && (!hn_out || (aligned16(hn_out) && hn_out != dX)))
+        return rmsnorm_bwd_bf16_fast(dH, X, g, resid, resid_mask, dX, dg, accumulate, partial, T, width, eps, stream, rows_dev, hn_out);
     if (rows_dev) return fail(ALCH_ERR_UNSUPPORTED, "device-side row count needs the bf16 row kernel");
+    if (hn_out) ALCH_TRY(launch_rmsnorm_fwd(dt, X, g, hn_out, T, width, eps, stream));  // plain kernels: the forward's own kernel
     return dt == ALCH_BF16
                ? rmsnorm_bwd_t<__bf16>(dH, X, g, resid, resid_mask, dX, dg, accumulate, partial, T, width, eps, stream)
                : rmsnorm_bwd_t<float>(dH, X, g, resid, resid_mask, dX, dg, accumulate, partial, T, width, eps, stream);
