@@ -280,3 +280,32 @@ def test_gemm_rejects_bad_arguments():
     bad = (B.CGemmTerm * 1)(B.CGemmTerm(P, P, 64, 32, 256))      # lda < K of a k-major operand
     assert call(terms=bad) == -2
     assert call(M=0) == 0                                           # nothing to do, nothing launched
+
+
+def test_header_is_plain_c_and_links_from_c(tmp_path):
+    # the boundary is a C ABI: the header must compile as C99 on its own, and a C program must link against the
+    # library and reach an entry point that needs no GPU
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    hdr = os.path.join(root, "include", "alch.h")
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", hdr], check=True)
+    src = tmp_path / "t.c"
+    src.write_text(r"""
+#include "alch.h"
+#include <stdio.h>
+int main(void) {
+    printf("%s %lu\n", alch_version(), (unsigned long)alch_gemm_workspace_bytes());
+    return alch_gemm(ALCH_BF16, -1, 4, 1, 0, 1, 0, 0, 4, 0, 0) == ALCH_ERR_SHAPE ? 0 : 1;
+}
+""")
+    exe = tmp_path / "t"
+    lib = A.library_path()
+    subprocess.run([gcc, "-std=c99", "-I", os.path.join(root, "include"), str(src), "-o", str(exe), lib,
+                    "-Wl,-rpath," + os.path.dirname(lib)], check=True)
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert r.stdout.startswith("alch ")
