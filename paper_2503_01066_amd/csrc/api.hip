@@ -504,7 +504,7 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
     if (g.dWg || g.dWu) {  // [dWg; dWu] = [dG | dU]^T H2
         if (g.dWg && g.dWu) {
             GemmDesc d = gemm_ws(dt, 2 * F, H, false, false);
-        d.k_dev = ndev;
+            d.k_dev = ndev;
             add_seg(d, p.dGU, 2 * (long long)F, p.Hn, H, T);
             add_out(d, g.dWg, 0, H);
             add_out(d, g.dWu, F, H);
@@ -519,7 +519,7 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
             }
         } else {
             GemmDesc d = gemm_ws(dt, F, H, false, false);
-        d.k_dev = ndev;
+            d.k_dev = ndev;
             add_seg(d, g.dWg ? p.dGU : at(p.dGU, F, E), 2 * (long long)F, p.Hn, H, T);
             add_out(d, g.dWg ? g.dWg : g.dWu, 0, H);
             d.accumulate = acc;
