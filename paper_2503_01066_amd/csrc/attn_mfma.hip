@@ -520,7 +520,9 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_dq_mfma(AttnMfmaParams p) {
 #pragma unroll
         for (int jb = 0; jb < 2; ++jb) {
             const int j0 = jt + jb * 32;
-            // (blocks wholly above the diagonal are computed and masked to zero, see the dK/dV kernel)
+            // a 32-key block wholly above this wavefront's diagonal contributes nothing: skipped (the other
+            // wavefronts of the work-group, further down the diagonal, still need the tile)
+            if (!in_pre && j0 > i0 + 31) continue;
             const char* bk = tk + jb * 32 * 256;
             const char* bv = tv + jb * 32 * 256;
             f32x16 St, dPt;  // transposed: rows = keys, columns = queries
