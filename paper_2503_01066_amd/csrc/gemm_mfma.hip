@@ -398,7 +398,8 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
         // (a wave reads back only what it wrote itself: no barrier needed in between)
         const int n = n0 + wn * 128 + (lane & 15) * 8;
         if (p.epilogue == kEpiSwigluBwd) {
-            // G and U rows are fetched eight row-steps at a time before any store is issued: the
+            // G and U rows (read once, never again: non-temporal loads keep them out of the way of the operand
+            // panels in L2) are fetched eight row-steps at a time before any store is issued: the
             // compiler may not move a load above a store it cannot prove disjoint, and one round trip
             // to memory per row-step would leave the epilogue bound by latency.
             constexpr int kBatch = 8;
@@ -409,8 +410,8 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
                 for (int k = 0; k < kBatch; ++k) {
                     const int m = m0 + wm * 128 + 4 * (q0 + k) + (lane >> 4);
                     if (m < Mv && n < p.N) {
-                        g8[k] = *reinterpret_cast<const bf16x8*>(p.G + (long long)m * p.ldgu + n);
-                        u8[k] = *reinterpret_cast<const bf16x8*>(p.U + (long long)m * p.ldgu + n);
+                        g8[k] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(p.G + (long long)m * p.ldgu + n));
+                        u8[k] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(p.U + (long long)m * p.ldgu + n));
                     }
                 }
 #pragma unroll
