@@ -234,6 +234,20 @@ def test_split_products_with_several_outputs_and_operand_pairs():
     out = gpu_layer(shp, cu, W, rec, dY)
     for k in ["dX"] + ["d" + w for w in WEIGHT_KEYS]:
         assert rel_err(to_np(out[k]), ref[k]) <= 2e-2, (k, rel_err(to_np(out[k]), ref[k]))
+    # accumulate into gradients that already hold something: the finish kernel of a split product adds the old value
+    import paper_2503_01066_amd as A
+    rng = np.random.default_rng(3)
+    scale = {k: float(np.abs(ref["d" + k]).max()) for k in WEIGHT_KEYS}
+    old = {"d" + k: synth.quantize((rng.standard_normal(W[k].shape) * scale[k]).astype(np.float32), "bf16") for k in WEIGHT_KEYS}
+    grads = {k: to_dev(v, "bf16") for k, v in old.items()}
+    drec = {k: to_dev(rec[k], "bf16") for k in REC}
+    drec["LSE"] = torch.from_numpy(rec["LSE"]).cuda()
+    A.alch_layer_backward(alch_shape(shp, "bf16"), A.Batch(cu), drec, {k: to_dev(v, "bf16") for k, v in W.items()},
+                          to_dev(dY, "bf16"), grads=grads, accumulate=True)
+    torch.cuda.synchronize()
+    for k in WEIGHT_KEYS:
+        want = ref["d" + k] + old["d" + k].astype(np.float64)
+        assert rel_err(to_np(grads["d" + k]), want) <= 2e-2, k
 
 
 def test_shared_prompt_equals_duplicated_prefill_at_real_width():
