@@ -289,3 +289,37 @@ def test_layer_backward_random_prefix_batches(seed):
     torch.cuda.synchronize()
     for k in ["dX"] + ["d" + w for w in WEIGHT_KEYS]:
         assert rel_err(to_np(out[k]), ref[k]) <= TOL[dtype], (prompts, responses, k, rel_err(to_np(out[k]), ref[k]))
+
+
+@pytest.mark.parametrize("dtype,shape_name,V", [("f32", "tiny", 61), ("bf16", "medium", 1024)])
+def test_dpo_head_alone_with_more_items_than_one_chunk(dtype, shape_name, V):
+    # no layers: the call is the DPO head + final-norm backward.  9,000 scored tokens exceed the 8,192-row chunk of
+    # the head, so the logits of every chunk are formed twice (log-probabilities, then gradients); rows score
+    # zero, one or two tokens
+    import paper_2503_01066_amd as A
+    from oracle.prefix import dpo_head
+    shp = synth.shape_dict(shape_name)
+    osh = oracle_shape(shp)
+    H, T, M, n_pairs = shp["hidden"], 9500, 9000, 3
+    rng = np.random.default_rng(12)
+    Xf = synth.normal(rng, (T, H), 1.0, dtype)
+    gf = synth.quantize(1.0 + 0.1 * rng.standard_normal(H).astype(np.float32), dtype)
+    Wlm = synth.normal(rng, (V, H), 0.3 if shape_name == "tiny" else 0.05, dtype)
+    rows = np.sort(rng.integers(0, T, M)).astype(np.int32)
+    labels = rng.integers(0, V, M).astype(np.int32)
+    slots = rng.integers(0, 2 * n_pairs, M).astype(np.int32)
+    # per-token log-probabilities are about -log V: a reference near the policy keeps z of order one
+    ref = np.array([-(slots == s).sum() * np.log(V) for s in range(2 * n_pairs)], np.float32) + rng.normal(0, 1, 2 * n_pairs).astype(np.float32)
+    beta = 0.05
+    loss, dX, dg, dW, z = dpo_head(osh, Xf.astype(np.float64), gf.astype(np.float64), Wlm.astype(np.float64), rows, labels, slots,
+                                   ref.astype(np.float64), beta)
+    cu = synth.ragged_cu([T])
+    out = A.alch_stack_backward_dpo(alch_shape(shp, dtype), A.Batch(cu), [], [], to_dev(Xf, dtype), to_dev(gf, dtype),
+                                    to_dev(Wlm, dtype), rows, labels, slots, ref, beta)
+    torch.cuda.synchronize()
+    tol = TOL[dtype]
+    zs = max(1.0, np.abs(z).max())
+    assert np.abs(to_np(out["z"]) - z).max() <= 5 * tol * zs, (to_np(out["z"]), z)
+    assert abs(out["loss"].item() - loss) <= 5 * tol * max(1.0, abs(loss))
+    for k, want in (("dX_embed", dX), ("dg_final", dg), ("dW_lm", dW)):
+        assert rel_err(to_np(out[k]), want) <= 5 * tol, (k, rel_err(to_np(out[k]), want))
