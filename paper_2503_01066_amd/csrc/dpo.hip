@@ -104,6 +104,92 @@ __global__ __launch_bounds__(256) void k_dpo_grad(T* __restrict__ logits, long l
     }
 }
 
+// bf16 fast paths of the two kernels above: one 1024-thread work-group per row, 16-byte accesses.  The
+// log-probability kernel keeps the row in registers (up to 16 chunks of 8 logits per thread, vocab <= 131072),
+// so it reads the logits once; the gradient kernel streams them.  Both need vocab and ld to be multiples of 8
+// and a 16-byte aligned base.
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_d;
+static constexpr int kRowThreads = 1024, kRowChunks = 16;
+
+__global__ __launch_bounds__(kRowThreads) void k_dpo_logp_bf16_row(const __bf16* __restrict__ logits, long long ld, int vocab,
+                                                                    const int* __restrict__ labels, float* __restrict__ logp,
+                                                                    float* __restrict__ logz) {
+    __shared__ float red[kRowThreads / 64];
+    const int m = blockIdx.x;
+    const __bf16* row = logits + (long long)m * ld;
+    const int nchunks = vocab >> 3;
+    bf16x8_d x[kRowChunks];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < kRowChunks; ++k) {
+        const int c = threadIdx.x + k * kRowThreads;
+        if (c < nchunks) {
+            x[k] = *reinterpret_cast<const bf16x8_d*>(row + c * 8);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) mx = fmaxf(mx, (float)x[k][e]);
+        }
+    }
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) mx = fmaxf(mx, __shfl_xor(mx, d, 64));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    mx = red[0];
+#pragma unroll
+    for (int w = 1; w < kRowThreads / 64; ++w) mx = fmaxf(mx, red[w]);
+    __syncthreads();
+    // (the empty asm keeps the row packed in registers: without it the compiler carries fp32 copies across)
+#pragma unroll
+    for (int k = 0; k < kRowChunks; ++k) asm volatile("" : "+v"(x[k]));
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < kRowChunks; ++k) {
+        const int c = threadIdx.x + k * kRowThreads;
+        if (c < nchunks) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s += __expf((float)x[k][e] - mx);
+        }
+    }
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) s += __shfl_xor(s, d, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        s = 0.f;
+        for (int w = 0; w < kRowThreads / 64; ++w) s += red[w];
+        const float lz = mx + __logf(s);
+        const int label = labels[m];
+        logz[m] = lz;
+        logp[m] = (label >= 0 && label < vocab) ? (float)row[label] - lz : 0.f;
+    }
+}
+
+__global__ __launch_bounds__(kRowThreads) void k_dpo_grad_bf16_row(__bf16* __restrict__ logits, long long ld, int vocab,
+                                                                    const int* __restrict__ labels, const int* __restrict__ slots,
+                                                                    const float* __restrict__ logz, const float* __restrict__ w_slot,
+                                                                    int n_slots) {
+    const int m = blockIdx.x;
+    __bf16* row = logits + (long long)m * ld;
+    const int label = labels[m], slot = slots[m];
+    const bool scored = label >= 0 && label < vocab && slot >= 0 && slot < n_slots;
+    const float w = scored ? w_slot[slot] : 0.f;
+    const float lz = logz[m];
+    const int nchunks = vocab >> 3;
+    for (int c = threadIdx.x; c < nchunks; c += kRowThreads) {
+        bf16x8_d x = *reinterpret_cast<const bf16x8_d*>(row + c * 8), g;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float v = -w * __expf((float)x[e] - lz);
+            if (c * 8 + e == label) v += w;
+            g[e] = (__bf16)v;
+        }
+        *reinterpret_cast<bf16x8_d*>(row + c * 8) = g;
+    }
+}
+
+static bool rows_vectorisable(const void* logits, long long ld, int vocab) {
+    return vocab % 8 == 0 && ld % 8 == 0 && (reinterpret_cast<uintptr_t>(logits) & 15) == 0;
+}
+
 // out[row, :] = sum of src[m, :] over the run of items with item_row[m] == row (items sorted by row); the
 // first item of a run does the sum.  Rows without an item keep the zeros written before.
 template <typename T>
@@ -129,7 +215,9 @@ __global__ __launch_bounds__(256) void k_fill_zero(T* __restrict__ x, long long 
 int launch_dpo_logp(alch_dtype dt, const void* logits, long long ld, int rows, int vocab, const int* labels, float* logp,
                     float* logz, hipStream_t stream) {
     if (rows <= 0) return ALCH_OK;
-    if (dt == ALCH_BF16) k_dpo_logp<__bf16><<<rows, 256, 0, stream>>>((const __bf16*)logits, ld, vocab, labels, logp, logz);
+    if (dt == ALCH_BF16 && rows_vectorisable(logits, ld, vocab) && vocab <= 8 * kRowThreads * kRowChunks)
+        k_dpo_logp_bf16_row<<<rows, kRowThreads, 0, stream>>>((const __bf16*)logits, ld, vocab, labels, logp, logz);
+    else if (dt == ALCH_BF16) k_dpo_logp<__bf16><<<rows, 256, 0, stream>>>((const __bf16*)logits, ld, vocab, labels, logp, logz);
     else k_dpo_logp<float><<<rows, 256, 0, stream>>>((const float*)logits, ld, vocab, labels, logp, logz);
     ALCH_HIP_TRY(hipGetLastError());
     return ALCH_OK;
@@ -146,7 +234,9 @@ int launch_dpo_weights(const float* logp, const int* slots, const int* labels, i
 int launch_dpo_grad(alch_dtype dt, void* logits, long long ld, int rows, int vocab, const int* labels, const int* slots,
                     const float* logz, const float* w_slot, int n_slots, hipStream_t stream) {
     if (rows <= 0) return ALCH_OK;
-    if (dt == ALCH_BF16) k_dpo_grad<__bf16><<<rows, 256, 0, stream>>>((__bf16*)logits, ld, vocab, labels, slots, logz, w_slot, n_slots);
+    if (dt == ALCH_BF16 && rows_vectorisable(logits, ld, vocab))
+        k_dpo_grad_bf16_row<<<rows, kRowThreads, 0, stream>>>((__bf16*)logits, ld, vocab, labels, slots, logz, w_slot, n_slots);
+    else if (dt == ALCH_BF16) k_dpo_grad<__bf16><<<rows, 256, 0, stream>>>((__bf16*)logits, ld, vocab, labels, slots, logz, w_slot, n_slots);
     else k_dpo_grad<float><<<rows, 256, 0, stream>>>((float*)logits, ld, vocab, labels, slots, logz, w_slot, n_slots);
     ALCH_HIP_TRY(hipGetLastError());
     return ALCH_OK;

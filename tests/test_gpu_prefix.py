@@ -291,7 +291,7 @@ def test_layer_backward_random_prefix_batches(seed):
         assert rel_err(to_np(out[k]), ref[k]) <= TOL[dtype], (prompts, responses, k, rel_err(to_np(out[k]), ref[k]))
 
 
-@pytest.mark.parametrize("dtype,shape_name,V", [("f32", "tiny", 61), ("bf16", "medium", 1024)])
+@pytest.mark.parametrize("dtype,shape_name,V", [("f32", "tiny", 61), ("bf16", "medium", 1024), ("bf16", "medium", 1001)])
 def test_dpo_head_alone_with_more_items_than_one_chunk(dtype, shape_name, V):
     # no layers: the call is the DPO head + final-norm backward.  9,000 scored tokens exceed the 8,192-row chunk of
     # the head, so the logits of every chunk are formed twice (log-probabilities, then gradients); rows score
