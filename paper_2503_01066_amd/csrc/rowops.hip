@@ -471,8 +471,30 @@ __global__ __launch_bounds__(256) void k_swiglu_act(const T* __restrict__ G, con
     }
 }
 
+// bf16, 8 elements per thread (n a multiple of 8, 16-byte aligned operands)
+__global__ __launch_bounds__(256) void k_swiglu_act_bf16x8(const bf16x8_t* __restrict__ G, const bf16x8_t* __restrict__ U,
+                                                           bf16x8_t* __restrict__ Act, long long n8) {
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n8; i += (long long)gridDim.x * 256) {
+        const bf16x8_t g = __builtin_nontemporal_load(G + i), u = __builtin_nontemporal_load(U + i);
+        bf16x8_t a;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float gf = (float)g[e];
+            a[e] = (__bf16)(gf / (1.f + __expf(-gf)) * (float)u[e]);
+        }
+        Act[i] = a;
+    }
+}
+
 int launch_swiglu_act(alch_dtype dt, const void* G, const void* U, void* Act, long long n, hipStream_t stream) {
     if (n <= 0) return ALCH_OK;
+    if (dt == ALCH_BF16 && n % 8 == 0 && aligned16(G) && aligned16(U) && aligned16(Act)) {
+        const long long n8 = n / 8;
+        const int grid8 = (int)((n8 + 255) / 256 < 256 * 32 ? (n8 + 255) / 256 : 256 * 32);
+        k_swiglu_act_bf16x8<<<grid8, 256, 0, stream>>>((const bf16x8_t*)G, (const bf16x8_t*)U, (bf16x8_t*)Act, n8);
+        ALCH_HIP_TRY(hipGetLastError());
+        return ALCH_OK;
+    }
     const int grid = (int)((n + 255) / 256 < 256 * 16 ? (n + 255) / 256 : 256 * 16);
     if (dt == ALCH_BF16)
         k_swiglu_act<__bf16><<<grid, 256, 0, stream>>>((const __bf16*)G, (const __bf16*)U, (__bf16*)Act, n);
@@ -574,10 +596,65 @@ __global__ __launch_bounds__(256) void k_rope(T* __restrict__ x, long long ld, i
     }
 }
 
+// bf16, head_dim a multiple of 16: a thread owns 8 consecutive pairs of one token, computes their sines and
+// cosines once and applies them to every kHeadLanes-th head (all heads of a token share the angles).
+static constexpr int kHeadLanes = 8;
+__global__ __launch_bounds__(256) void k_rope_bf16x8(__bf16* __restrict__ x, long long ld, int Trows, int n_heads, int D,
+                                                     const int* __restrict__ positions, const int* __restrict__ cu_seqlens,
+                                                     int n_seqs, float log2_base, float sign) {
+    const int half = D >> 1, kc = half >> 3;  // 8-pair chunks per head
+    const int per_tok = kc * kHeadLanes;
+    const long long n = (long long)Trows * per_tok;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) {
+        const long long t = i / per_tok;
+        const int rem = (int)(i - t * per_tok);
+        const int hl = rem / kc, k0 = (rem - hl * kc) * 8;
+        if (hl >= n_heads) continue;
+        int pos;
+        if (positions) {
+            pos = positions[t];
+        } else {
+            int lo = 0, hi = n_seqs;
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (cu_seqlens[mid] <= t) lo = mid; else hi = mid;
+            }
+            pos = (int)t - cu_seqlens[lo];
+        }
+        float sn[8], cs[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float theta = exp2f(-2.f * (float)(k0 + e) / (float)D * log2_base);
+            sincosf((float)pos * theta, &sn[e], &cs[e]);
+            sn[e] *= sign;
+        }
+        for (int h = hl; h < n_heads; h += kHeadLanes) {
+            __bf16* p = x + t * ld + (long long)h * D + k0;
+            const bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(p), b = *reinterpret_cast<const bf16x8_t*>(p + half);
+            bf16x8_t ra, rb;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float af = (float)a[e], bf = (float)b[e];
+                ra[e] = (__bf16)(af * cs[e] - bf * sn[e]);
+                rb[e] = (__bf16)(bf * cs[e] + af * sn[e]);
+            }
+            *reinterpret_cast<bf16x8_t*>(p) = ra;
+            *reinterpret_cast<bf16x8_t*>(p + half) = rb;
+        }
+    }
+}
+
 int launch_rope(alch_dtype dt, void* x, long long ld, int T, int n_heads, int D, const int* positions,
                 const int* cu_seqlens, int n_seqs, float base, float sign, hipStream_t stream) {
     const long long n = (long long)T * n_heads * (D / 2);
     if (n <= 0) return ALCH_OK;
+    if (dt == ALCH_BF16 && D % 16 == 0 && ld % 8 == 0 && aligned16(x)) {
+        const long long nt = (long long)T * (D / 16) * kHeadLanes;
+        const int g = (int)((nt + 255) / 256 < 256 * 32 ? (nt + 255) / 256 : 256 * 32);
+        k_rope_bf16x8<<<g, 256, 0, stream>>>((__bf16*)x, ld, T, n_heads, D, positions, cu_seqlens, n_seqs, log2f(base), sign);
+        ALCH_HIP_TRY(hipGetLastError());
+        return ALCH_OK;
+    }
     const int grid = (int)((n + 255) / 256 < 256 * 16 ? (n + 255) / 256 : 256 * 16);
     const float l2 = log2f(base);
     if (dt == ALCH_BF16)
@@ -599,10 +676,28 @@ __global__ __launch_bounds__(256) void k_masked_copy(const T* __restrict__ a, co
     }
 }
 
+// 16 bytes per thread; `per_row` = 16-byte chunks in a row (the row bytes are a multiple of 16)
+__global__ __launch_bounds__(256) void k_masked_copy_x16(const uint4* __restrict__ a, const uint8_t* __restrict__ mask,
+                                                         uint4* __restrict__ out, long long n16, int per_row) {
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n16; i += (long long)gridDim.x * 256) {
+        uint4 v = a[i];
+        if (mask && mask[i / per_row] == 0) v = make_uint4(0u, 0u, 0u, 0u);
+        out[i] = v;
+    }
+}
+
 int launch_masked_copy(alch_dtype dt, const void* a, const uint8_t* mask, void* out, int T, int width,
                        hipStream_t stream) {
     const long long n = (long long)T * width;
     if (n <= 0) return ALCH_OK;
+    const long long row_bytes = (long long)width * (long long)dtype_size(dt);
+    if (row_bytes % 16 == 0 && aligned16(a) && aligned16(out)) {
+        const long long n16 = (long long)T * (row_bytes / 16);
+        const int g = (int)((n16 + 255) / 256 < 256 * 32 ? (n16 + 255) / 256 : 256 * 32);
+        k_masked_copy_x16<<<g, 256, 0, stream>>>((const uint4*)a, mask, (uint4*)out, n16, (int)(row_bytes / 16));
+        ALCH_HIP_TRY(hipGetLastError());
+        return ALCH_OK;
+    }
     const int grid = (int)((n + 255) / 256 < 256 * 16 ? (n + 255) / 256 : 256 * 16);
     if (dt == ALCH_BF16)
         k_masked_copy<__bf16><<<grid, 256, 0, stream>>>((const __bf16*)a, mask, (__bf16*)out, T, width);
