@@ -242,13 +242,17 @@ def run_layer(args, torch, A):
         step()
     torch.cuda.synchronize()
     A.alch_trace_enable(True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]  # step boundaries, current stream
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for i in range(args.steps):
         step()
+        marks[i + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     A.alch_trace_enable(False)
     trace = A.alch_trace_collect()
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
 
     ms_step = dt / args.steps * 1e3
     by = {}
@@ -271,6 +275,8 @@ def run_layer(args, torch, A):
         "metric": METRIC, "value": T * args.steps / dt, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "ms_per_step_median": per_step[len(per_step) // 2] if per_step else None,
+        "ms_per_step_min": per_step[0] if per_step else None,
         "config": {"workload": descr,
                    "hidden": H, "q_heads": shp["n_q_heads"], "kv_heads": shp["n_kv_heads"],
                    "head_dim": shp["head_dim"], "ffn": F, "tokens": T, "seq_len": S},
