@@ -20,6 +20,8 @@ SHAPES = {
 }
 # a test shape whose fused q/k/v weight gradient has 48 x 8 = 384 output tiles in three row ranges
 SHAPES["wideqkv"] = (2048, 64, 16, 128, 512, 1e-5, 10000.0)
+# widths that are multiples of neither 8 nor 16 elements: every kernel takes its element-wise path
+SHAPES["odd"] = (20, 2, 1, 12, 22, 1e-5, 10000.0)
 SHAPE_FIELDS = ("hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn", "rms_eps", "rope_base")
 
 

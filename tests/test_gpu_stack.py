@@ -100,7 +100,9 @@ def test_stack_nothing_counted_and_hooks():
 
 @pytest.mark.parametrize("dtype,shape_name,lens,wstd", [("f32", "config1", [128, 128], 0.02),
                                                          ("bf16", "medium", [300, 77, 1], 0.02),
-                                                         ("bf16", "medium64", [90, 60], 0.05)])
+                                                         ("bf16", "medium64", [90, 60], 0.05),
+                                                         ("bf16", "odd", [33, 8], 0.3),
+                                                         ("f32", "odd", [33, 8], 0.3)])
 def test_layer_forward_and_reuse_equals_recompute(dtype, shape_name, lens, wstd):
     import paper_2503_01066_amd as A
     cu = synth.ragged_cu(lens)
