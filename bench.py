@@ -33,7 +33,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config2", choices=["config2", "config3", "config4", "config5", "dpo", "short", "copy"])
+    ap.add_argument("--workload", default="config2", choices=["config2", "config3", "config4", "config5", "dpo", "short", "copy", "gemm"])
     ap.add_argument("--layers", type=int, default=32, help="config4: number of layers")
     ap.add_argument("--loss-mask", action="store_true", help="config5: zero dY rows with a Bernoulli(0.25) loss mask")
     ap.add_argument("--lora-rank", type=int, default=0,
@@ -691,6 +691,62 @@ def run_copy(args, torch, A):
                          "unit": "GB/s", "frac": gbps / PEAK_HBM_GBPS, "traffic": None}}
 
 
+def run_gemm(args, torch, A):
+    """Ceiling check of the contraction kernel: every product shape of the config-2 layer backward (and a square
+    one), timed through alch_gemm and through torch.matmul (the vendor library) on the same operands, with
+    Gaussian and with all-zero data (the matrix pipes draw less power on zeros, which shows how far the clock
+    granted under load, not the kernel, sets the rate)."""
+    dev, bf = "cuda", torch.bfloat16
+    T, H, F, QKV = 8192, 4096, 14336, 6144
+    shapes = [("dAct = dY Wd", T, F, H, True, False), ("dH2 = dGU [Wg;Wu]", T, H, 2 * F, True, False),
+              ("dO = dX2 Wo", T, H, H, True, False), ("dH1 = dQKV Wqkv", T, H, QKV, True, False),
+              ("dWd = dY^T Act", H, F, T, False, False), ("dWgu = dGU^T H2", 2 * F, H, T, False, False),
+              ("dWo = dX2^T O", H, H, T, False, False), ("dWqkv = dQKV^T H1", QKV, H, T, False, False),
+              ("square, y = x W^T", 8192, 8192, 8192, True, True)]
+    ws = torch.empty(A.lib().alch_gemm_workspace_bytes(), dtype=torch.uint8, device=dev)
+    g = torch.Generator(device=dev).manual_seed(0)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.steps
+
+    rows, tot = [], {"alch": 0.0, "vendor": 0.0, "flops": 0.0}
+    for name, M, N, K, a_k, b_k in shapes:
+        row = {"product": name, "M": M, "N": N, "K": K}
+        for data in ("gaussian", "zeros"):
+            mk = (lambda *sh: torch.randn(sh, generator=g, device=dev, dtype=torch.float32).to(bf)) if data == "gaussian" \
+                else (lambda *sh: torch.zeros(sh, device=dev, dtype=bf))
+            a = mk(M, K) if a_k else mk(K, M)
+            b = mk(N, K) if b_k else mk(K, N)
+            out = torch.empty((M, N), dtype=bf, device=dev)
+            am = a if a_k else a.t()
+            bm = b.t() if b_k else b
+            ms_a = timed(lambda: A.alch_gemm(M, N, [(a, b, K)], a_k, b_k, out=out, workspace=ws))
+            ms_v = timed(lambda: torch.matmul(am, bm, out=out))
+            fl = 2.0 * M * N * K
+            row[data] = {"alch_tflops": fl / ms_a / 1e9, "vendor_tflops": fl / ms_v / 1e9}
+            if data == "gaussian" and not name.startswith("square"):
+                tot["alch"] += ms_a; tot["vendor"] += ms_v; tot["flops"] += fl
+            del a, b, out
+        rows.append(row)
+    ach = tot["flops"] / tot["alch"] / 1e9
+    return {"metric": "contraction TFLOP/s over the config-2 products (ceiling check against the vendor library)",
+            "value": ach, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": tot["alch"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "gemm: the eight products of the config-2 layer backward, one launch each, Gaussian data"},
+            "vendor_tflops": tot["flops"] / tot["vendor"] / 1e9, "products": rows,
+            "roofline": {"kernel": "k_gemm_mfma", "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
+                         "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None}}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -705,7 +761,7 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     out = {"config2": run_layer, "config5": run_layer, "short": run_layer, "config3": run_config3, "config4": run_config4,
-           "dpo": run_dpo, "copy": run_copy}[args.workload](args, torch, A)
+           "dpo": run_dpo, "copy": run_copy, "gemm": run_gemm}[args.workload](args, torch, A)
     if not args.no_cpu_baseline and args.workload == "config4":
         # extrapolated, and labelled so: one layer on 4 x 2048 tokens, scaled by flops
         b = cpu_baseline_layer("config2")
@@ -716,7 +772,7 @@ def main():
         out["cpu_baseline"] = b
     elif not args.no_cpu_baseline and args.workload == "dpo":
         out["cpu_baseline"] = cpu_baseline_dpo(args.layers)
-    elif not args.no_cpu_baseline and args.workload != "copy":
+    elif not args.no_cpu_baseline and args.workload not in ("copy", "gemm"):
         out["cpu_baseline"] = cpu_baseline_config3() if args.workload == "config3" else cpu_baseline_layer(args.workload)
     print(json.dumps(out))
 

@@ -7,10 +7,12 @@
 // projections (x.W^T, both k-major).
 //
 // Design for CDNA4:
-//   * 256x256x64 tile per work-group, 4 wavefronts of 64 lanes, each owning 128x128 of the
+//   * 256x256 tile per work-group, contraction in steps of 32, 4 wavefronts of 64 lanes, each owning 128x128 of the
 //     tile as 4x4 MFMA 32x32x16 bf16 accumulators (256 accumulator registers per lane).
 //   * Tiles are fetched HBM/L2 -> LDS with 16-byte direct-to-LDS buffer loads (no
-//     registers in between), double buffered: 2 x (32 KB A + 32 KB B) of the 160 KB LDS.
+//     registers in between) into a ring of stages that fills the 160 KB LDS: five stages of
+//     [A 256x32 | B 32x256], or, when A is k-major, three 64-k-wide super-stages of A and four stages
+//     of B, so that every load of A covers whole 128-byte lines (see tile_offsets_wide).
 //     A direct-to-LDS load writes lane-linearly, so the bank-conflict swizzle is applied
 //     by permuting which global 16-byte chunk each lane fetches.
 //   * Operands whose contraction index is contiguous in memory are read from LDS with
@@ -140,6 +142,33 @@ __device__ __forceinline__ bf16x8 read_frag(const char* stage, int idx0 /*first 
     }
 }
 
+// ---- k-major A staged 64 k wide ---------------------------------------------------------------
+// A k-major tile fetched 32 k at a time takes 64 bytes of every row: each 128-byte line then crosses the
+// L2 -> L1 path twice (once per k-tile; the 32 KB L1 has long lost it by the second time).  With AK the A
+// operand is therefore staged in super-stages of 64 k: [2 halves of 128 rows][128 bytes], 32 KB, three of
+// them, and one wave-wide load covers 8 whole lines.  A super-stage is filled by two batches (rows 0-127,
+// rows 128-255), one per k-tile step, so the loads per step stay what they are for the 32-wide layout; the
+// B operand keeps 32-wide stages, four of them, behind the three super-stages (96 + 64 = 160 KB).
+//   slot (16-byte units) inside a half = rl*8 + (c ^ ((rl>>1)&7)), rl = row & 127, c = 16-byte chunk of the
+//   row's 64 k: 16 consecutive rows at one logical chunk then cover all 64 banks once (ds_read_b128).
+__device__ __forceinline__ void tile_offsets_wide(uint32_t (&voff)[8], int wave, int lane, long long ld, int valid) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int sl = (wave * 4 + j) * 64 + lane;
+            const int rl = sl >> 3, c = (sl & 7) ^ ((rl >> 1) & 7), row = h * 128 + rl;
+            voff[h * 4 + j] = row < valid ? (uint32_t)((row * ld + c * 8) * 2) : kOobOffset;
+        }
+}
+
+// fragment of k-tile `par` (0/1) of a super-stage: rows idx0 + (lane&31), k = par*32 + kk*16 + 8*(lane>>5) ..+7
+__device__ __forceinline__ bf16x8 read_frag_wide(const char* sup, int par, int idx0, int kk, int lane) {
+    const int row = idx0 + (lane & 31), rl = row & 127;
+    const int c = (par * 4 + kk * 2 + (lane >> 5)) ^ ((rl >> 1) & 7);
+    return *reinterpret_cast<const bf16x8*>(sup + (row >> 7) * kOperandStageBytes + rl * 128 + c * 16);
+}
+
 struct Frags {
     bf16x8 a[4], b[4];
 };
@@ -176,6 +205,16 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
     __shared__ __attribute__((aligned(1024))) char smem[kStages * 2 * kOperandStageBytes];
     const uint32_t lds0 = (uint32_t)(uintptr_t)ALCH_LDS(smem);
     constexpr int kStage = 2 * kOperandStageBytes;
+    // AK: A in three 64-wide super-stages, B in four 32-wide stages behind them (see tile_offsets_wide);
+    // otherwise kStages stages of [A | B].  kU = steps after which every ring is back at its first stage.
+    constexpr bool kWide = AK;
+    constexpr int kU = kWide ? 12 : kStages;
+    constexpr int kDepth = kWide ? 4 : kStages;  // k-tiles of B (and their share of A) resident at a time
+    constexpr uint32_t kWideB0 = 3 * kStage;
+    auto a_off = [](int st) -> uint32_t { return kWide ? (uint32_t)((st / 2) % 3) * kStage : (uint32_t)(st % kStages) * kStage; };
+    auto b_off = [](int st) -> uint32_t {
+        return kWide ? kWideB0 + (uint32_t)(st % 4) * kOperandStageBytes : (uint32_t)(st % kStages) * kStage + kOperandStageBytes;
+    };
 
     // ---- work-group -> output tile: XCD-contiguous chunks, banded raster inside a chunk
     // The grid is persistent (one work-group per compute unit): each work-group walks its share of
@@ -243,8 +282,9 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
             pa += (long long)lo * stepa;
             pb += (long long)lo * stepb;
         }
-        uint32_t va[4], vb[4];
-        tile_offsets<AK>(va, wave, lane, lda, Mv - m0);
+        uint32_t va[kWide ? 8 : 4], vb[4];
+        if constexpr (kWide) tile_offsets_wide(va, wave, lane, lda, Mv - m0);
+        else tile_offsets<AK>(va, wave, lane, lda, Mv - m0);
         tile_offsets<BKM>(vb, wave, lane, ldb, p.N - n0);
 
         // Loads of the next k-tile go out one instruction at a time between MFMAs (a burst of
@@ -285,31 +325,80 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
                          : "s"(sa_step), "s"(sb_step)
                          : "scc");
         };
-#define ALCH_DMA_A(stage, j) dma16(ra, lds0 + (stage) * kStage + (uint32_t)(wave * 4 + (j)) * 1024u, va[j])
-#define ALCH_DMA_B(stage, j) dma16(rb, lds0 + (stage) * kStage + kOperandStageBytes + (uint32_t)(wave * 4 + (j)) * 1024u, vb[j])
+        // kWide: the two streams advance separately.  A moves by 128 bytes (64 k) after every second batch
+        // (a_inc alternates 0, 128); its batches are counted in a_left, B's k-tiles in tiles_left.
+        int a_left = (nk + 1) & ~1, a_inc = 0;
+        auto open_a = [&]() {
+            int na;
+            asm volatile("s_cmp_gt_i32 %1, 0\n\ts_cselect_b32 %0, %2, 0" : "=&s"(na) : "s"(a_left), "s"(a_rem) : "scc");
+            ra[0] = (int)a_lo; ra[1] = (int)a_hi; ra[2] = na; ra[3] = 0x00020000;
+            asm volatile("s_add_u32 %0, %0, %4\n\ts_addc_u32 %1, %1, 0\n\ts_sub_i32 %2, %2, %4\n\ts_max_i32 %2, %2, 0\n\t"
+                         "s_sub_i32 %4, 128, %4\n\ts_sub_i32 %3, %3, 1"
+                         : "+s"(a_lo), "+s"(a_hi), "+s"(a_rem), "+s"(a_left), "+s"(a_inc)
+                         :
+                         : "scc");
+        };
+        auto open_b = [&]() {
+            int nbb;
+            asm volatile("s_cmp_gt_i32 %1, 0\n\ts_cselect_b32 %0, %2, 0" : "=&s"(nbb) : "s"(tiles_left), "s"(b_rem) : "scc");
+            rb[0] = (int)b_lo; rb[1] = (int)b_hi; rb[2] = nbb; rb[3] = 0x00020000;
+            asm volatile("s_add_u32 %0, %0, %4\n\ts_addc_u32 %1, %1, 0\n\ts_sub_i32 %2, %2, %4\n\ts_max_i32 %2, %2, 0\n\t"
+                         "s_sub_i32 %3, %3, 1"
+                         : "+s"(b_lo), "+s"(b_hi), "+s"(b_rem), "+s"(tiles_left)
+                         : "s"(sb_step)
+                         : "scc");
+        };
+        // Refill issued in step `st`: !kWide: k-tile st + kStages of both operands into the stage of k-tile st.
+        // kWide: A batch st + 5 = half (st+5)&1 of super-tile (st+5)/2, B k-tile st + 4 into the stage of k-tile st.
+#define ALCH_DMA_A(st, j)                                                                                              \
+    dma16(ra, lds0 + (kWide ? a_off((st) + 5) + (uint32_t)(((st) + 5) & 1) * kOperandStageBytes : a_off(st)) +          \
+                  (uint32_t)(wave * 4 + (j)) * 1024u, va[kWide ? (((st) + 5) & 1) * 4 + (j) : (j)])
+#define ALCH_DMA_B(st, j) dma16(rb, lds0 + b_off(st) + (uint32_t)(wave * 4 + (j)) * 1024u, vb[j])
 #define ALCH_MFMA(F, i, j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(F.b[j], F.a[i], acc[i][j], 0, 0, 0)
 #define ALCH_SB() __builtin_amdgcn_sched_barrier(0)
-#define ALCH_RA(F, st, kk, i) F.a[i] = read_frag<AK>(st, wm * 128 + (i) * 32, kk, lane)
-#define ALCH_RB(F, st, kk, i) F.b[i] = read_frag<BKM>((st) + kOperandStageBytes, wn * 128 + (i) * 32, kk, lane)
+        // fragment reads of k-tile step `st`
+        auto frag_a = [&](int st, int kk, int i) -> bf16x8 {
+            if constexpr (kWide) return read_frag_wide(smem + a_off(st), st & 1, wm * 128 + i * 32, kk, lane);
+            else return read_frag<AK>(smem + a_off(st), wm * 128 + i * 32, kk, lane);
+        };
+#define ALCH_RA(F, st, kk, i) F.a[i] = frag_a(st, kk, i)
+#define ALCH_RB(F, st, kk, i) F.b[i] = read_frag<BKM>(smem + b_off(st), wn * 128 + (i) * 32, kk, lane)
 
         // all waves are done with the previous segment's stages before they are refilled
         __syncthreads();
+        if constexpr (kWide) {
+            // A batches 0..4 (steps -5..-1 of the refill numbering) and B k-tiles 0..3; k-tile 0 needs the
+            // first two batches and B k-tile 0: they go first, the 24 loads behind them may still be in flight
 #pragma unroll
-        for (int s = 0; s < kStages; ++s) {
-            open_next();
+            for (int b = 0; b < 5; ++b) {
+                open_a();
 #pragma unroll
-            for (int j = 0; j < 4; ++j) { ALCH_DMA_A(s, j); ALCH_DMA_B(s, j); }
-        }
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoadsPerTile * (kStages - 1)) : "memory");
-        __syncthreads();
-        Frags f0, f1;
-        read_frags<AK, BKM>(f0, smem, smem + kOperandStageBytes, wm, wn, 0, lane);
-        for (int kt = 0; kt < nk; kt += kStages) {
+                for (int j = 0; j < 4; ++j) ALCH_DMA_A(b - 5, j);
+                if (b >= 1) {
+                    open_b();
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) ALCH_DMA_B(b - 1, j);
+                }
+            }
+            asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+        } else {
 #pragma unroll
             for (int s = 0; s < kStages; ++s) {
+                open_next();
+#pragma unroll
+                for (int j = 0; j < 4; ++j) { ALCH_DMA_A(s, j); ALCH_DMA_B(s, j); }
+            }
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoadsPerTile * (kStages - 1)) : "memory");
+        }
+        __syncthreads();
+        Frags f0, f1;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { ALCH_RA(f0, 0, 0, i); ALCH_RB(f0, 0, 0, i); }
+        for (int kt = 0; kt < nk; kt += kU) {
+#pragma unroll
+            for (int s = 0; s < kU; ++s) {
                 if (kt + s < nk) {
-                    const char* st = smem + s * kStage;
-                    const char* stn = smem + ((s + 1) % kStages) * kStage;
+                    const int st = s, stn = (s + 1) % kU;
                     // ---- first half: MFMAs on k 0..15 of this stage, fragment reads for k 16..31
                     ALCH_SB();
                     ALCH_RA(f1, st, 1, 0); ALCH_RA(f1, st, 1, 1); ALCH_MFMA(f0, 0, 0); ALCH_MFMA(f0, 0, 1); ALCH_SB();
@@ -320,10 +409,11 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(MfmaGemmParams p) {
                     ALCH_MFMA(f0, 3, 0); ALCH_MFMA(f0, 3, 1); ALCH_MFMA(f0, 3, 2); ALCH_MFMA(f0, 3, 3);
                     ALCH_SB();
                     // k-tile kt+s+1 has landed (this wave's share), and this wave's reads of stage s are done
-                    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(kLoadsPerTile * (kStages - 2)) : "memory");
+                    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(kLoadsPerTile * (kDepth - 2)) : "memory");
                     __syncthreads();
                     // ---- second half: MFMAs on k 16..31, refill of stage s, fragment reads of the next stage
-                    open_next();
+                    if constexpr (kWide) { open_a(); open_b(); }
+                    else open_next();
                     ALCH_SB();
                     ALCH_DMA_A(s, 0); ALCH_RA(f0, stn, 0, 0); ALCH_RA(f0, stn, 0, 1); ALCH_MFMA(f1, 0, 0); ALCH_MFMA(f1, 0, 1); ALCH_SB();
                     ALCH_DMA_A(s, 1); ALCH_RA(f0, stn, 0, 2); ALCH_RA(f0, stn, 0, 3); ALCH_MFMA(f1, 0, 2); ALCH_MFMA(f1, 0, 3); ALCH_SB();
@@ -635,6 +725,7 @@ int launch_gemm_mfma(const GemmDesc& d, hipStream_t stream) {
             p.split_ws = static_cast<float*>(d.split_ws);
             p.split_s = s;
             p.split_per = ceil_div(nk_total, s);
+            if (d.a_kmajor) p.split_per += p.split_per & 1;  // parts start on a 64-k boundary: whole 128-byte lines of A
         }
     }
     const int grid_split = 8 * rem * p.split_s;
