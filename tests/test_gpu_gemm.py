@@ -124,3 +124,25 @@ def test_gemm_random_shapes_with_scratch():
         torch.cuda.synchronize()
         want = ref + C0 if acc else ref
         assert rel_err(to_np(C), want) < 6e-3, (case, M, N, Ks, a_k, b_k, acc)
+
+
+@pytest.mark.parametrize("a_k,b_k", [(True, False), (False, False), (True, True)])
+def test_gemm_operands_as_column_slices_of_wider_buffers(a_k, b_k):
+    # row strides larger than the rows (operands are column ranges of fused buffers, as dQ|dK|dV or G|U are), a row
+    # count that leaves the lower half of the last 256-row tile partly empty, three operand pairs of unequal length
+    import paper_2503_01066_amd as A_
+    rng = np.random.default_rng(77)
+    M, N, Ks = 392, 520, [64, 320, 1024]
+    ws = torch.empty(A_.lib().alch_gemm_workspace_bytes(), dtype=torch.uint8, device="cuda")
+    terms, ref = [], 0.0
+    for i, K in enumerate(Ks):
+        A, B, r = operands(rng, M, N, K, a_k, b_k, "bf16")
+        pa, pb = 8 * (i + 1), 64 * i + 8
+        Aw = np.zeros((A.shape[0], A.shape[1] + 2 * pa), A.dtype); Aw[:, pa:pa + A.shape[1]] = A
+        Bw = np.zeros((B.shape[0], B.shape[1] + 2 * pb), B.dtype); Bw[:, pb:pb + B.shape[1]] = B
+        terms.append((to_dev(Aw, "bf16")[:, pa:pa + A.shape[1]], to_dev(Bw, "bf16")[:, pb:pb + B.shape[1]], K))
+        ref = ref + r
+    for w in (None, ws):
+        C = A_.alch_gemm(M, N, terms, a_k, b_k, workspace=w)
+        torch.cuda.synchronize()
+        assert rel_err(to_np(C), ref) < 6e-3, (a_k, b_k, w is None)
