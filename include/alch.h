@@ -148,6 +148,25 @@ int alch_capture_gather(const alch_batch* batch, int32_t n_streams, const alch_s
                         int64_t dst_capacity_rows, const int32_t* kept_index,
                         const int32_t* n_kept_and_status, void* hip_stream);
 
+/*
+ * alch_capture_pack_static: alch_capture_pack for callers that cannot allocate or hand over device
+ * scratch: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and error behaviour, minus the workspace: the scan's block counters live in a
+ * 64 KiB array inside the library's device image (one copy per GPU, held until the process ends).
+ * The call allocates nothing and frees nothing.
+ *   - total_tokens above alch_capture_pack_static_max_tokens() (about 66.8 million) is rejected with
+ *     ALCH_ERR_UNSUPPORTED before anything is enqueued; use alch_capture_pack with a workspace then.
+ *   - every call on a GPU shares that GPU's array, on whatever stream: calls that overlap in time on
+ *     one GPU race on it.  Calls in stream order on one stream are safe, and nothing has to be cleared
+ *     between them (each call overwrites every counter it later reads).
+ *   - the device that is current at the call is the one whose array is used; it must be the device of
+ *     the buffers and of hip_stream.
+ */
+int alch_capture_pack_static(const alch_batch* batch, const uint8_t* keep_mask, int32_t n_streams,
+                             const alch_stream* streams, int64_t dst_capacity_rows, int32_t* kept_index,
+                             int32_t* cu_kept, int32_t* n_kept_and_status, void* hip_stream);
+size_t alch_capture_pack_static_max_tokens(void);
+
 /* ------------------------------------------------------------------------------------
  * Family 2: backward from saved activations (Section 1; Section 4.2; Section 4.3.2).
  */

@@ -115,6 +115,11 @@ def lib():
     L.alch_capture_pack.restype = C.c_int
     L.alch_capture_pack.argtypes = [C.POINTER(CBatch), C.c_void_p, C.c_int32, C.POINTER(CStream), C.c_int64,
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.alch_capture_pack_static.restype = C.c_int
+    L.alch_capture_pack_static.argtypes = [C.POINTER(CBatch), C.c_void_p, C.c_int32, C.POINTER(CStream), C.c_int64,
+                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.alch_capture_pack_static_max_tokens.restype = C.c_size_t
+    L.alch_capture_pack_static_max_tokens.argtypes = []
     L.alch_capture_gather.restype = C.c_int
     L.alch_capture_gather.argtypes = [C.POINTER(CBatch), C.c_int32, C.POINTER(CStream), C.c_int64, C.c_void_p,
                                       C.c_void_p, C.c_void_p]
@@ -241,6 +246,21 @@ def alch_capture_pack(batch, keep_mask, streams, capacity=None, dsts=None, strea
     _check(L.alch_capture_pack(C.byref(batch.c), _ptr(keep_mask), len(streams), arr, capacity, _ptr(kept_index),
                                _ptr(cu_kept), _ptr(status), _ptr(ws), ws.numel(), _stream_handle(stream)))
     return kept_index, cu_kept, status, dsts
+
+
+def alch_capture_pack_static(batch, keep_mask, streams, dsts, kept_index, cu_kept, status, stream=None):
+    """alch_capture_pack on the library's built-in scratch: every buffer, outputs included, comes from the
+    caller, and neither this wrapper nor the library allocates device memory."""
+    L = lib()
+    arr = (CStream * max(len(streams), 1))()
+    for i, (s, d) in enumerate(zip(streams, dsts)):
+        assert s.numel() == 0 or (s.stride(1) == 1 and d.is_contiguous())
+        row_stride = s.stride(0) if s.numel() > 0 else s.shape[1]
+        arr[i] = CStream(s.data_ptr(), d.data_ptr(), s.shape[1] * s.element_size(), row_stride * s.element_size())
+    capacity = min([int(kept_index.numel())] + [int(d.shape[0]) for d in dsts])
+    _check(L.alch_capture_pack_static(C.byref(batch.c), _ptr(keep_mask), len(streams), arr, capacity,
+                                      _ptr(kept_index), _ptr(cu_kept), _ptr(status), _stream_handle(stream)))
+    return capacity
 
 
 def alch_capture_gather(batch, kept_index, status, streams, capacity=None, dsts=None, stream=None):

@@ -735,6 +735,65 @@ int alch_capture_pack(const alch_batch* batch, const uint8_t* keep_mask, int32_t
                        static_cast<hipStream_t>(hip_stream));
 }
 
+// ---- capture/pack without a workspace argument ------------------------------------------------
+// The scan's block counters live in a file-scope device array instead of caller memory.  The array's
+// name is only a host-side handle: its device address is looked up once per device and that address is
+// what the kernels receive.
+static constexpr size_t kPackScratchBytes = 64 * 1024;
+static constexpr int kPackScratchMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kPackScratchBytes];
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[kPackScratchMaxDevices] = {};
+
+static int pack_scratch_for_current_device(void** out) {
+    int dev = -1;
+    ALCH_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kPackScratchMaxDevices) return fail(ALCH_ERR_UNSUPPORTED, "device ordinal %d >= %d", dev, kPackScratchMaxDevices);
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        ALCH_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(ALCH_ERR_HIP, "hipGetSymbolAddress returned a NULL address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return ALCH_OK;
+}
+
+size_t alch_capture_pack_static_max_tokens(void) {
+    // largest T whose scan scratch (pack_workspace_bytes) fits the array
+    long long lo = 0, hi = INT32_MAX;
+    while (lo < hi) {
+        long long mid = (lo + hi + 1) / 2;
+        if (pack_workspace_bytes((int)mid) <= kPackScratchBytes) lo = mid; else hi = mid - 1;
+    }
+    return (size_t)lo;
+}
+
+int alch_capture_pack_static(const alch_batch* batch, const uint8_t* keep_mask, int32_t n_streams,
+                             const alch_stream* streams, int64_t dst_capacity_rows, int32_t* kept_index,
+                             int32_t* cu_kept, int32_t* n_kept_and_status, void* hip_stream) {
+    clear_error();
+    ALCH_TRY(check_batch(batch));
+    if (batch->total_tokens > 0 && !keep_mask) return fail(ALCH_ERR_INVALID_ARG, "keep_mask is NULL");
+    OPTIONAL_PTR(keep_mask, "keep_mask");
+    ALCH_TRY(check_streams(n_streams, streams, batch->total_tokens, dst_capacity_rows));
+    if (dst_capacity_rows > 0 && !kept_index) return fail(ALCH_ERR_INVALID_ARG, "kept_index is NULL");
+    if (!cu_kept || !n_kept_and_status) return fail(ALCH_ERR_INVALID_ARG, "cu_kept / n_kept_and_status is NULL");
+    const size_t need = pack_workspace_bytes(batch->total_tokens);
+    if (need > kPackScratchBytes)
+        return fail(ALCH_ERR_UNSUPPORTED, "total_tokens %d exceeds the %zu tokens the built-in scratch (%zu bytes) serves; "
+                    "use alch_capture_pack with a workspace", batch->total_tokens, alch_capture_pack_static_max_tokens(),
+                    kPackScratchBytes);
+    void* ws = nullptr;
+    ALCH_TRY(pack_scratch_for_current_device(&ws));
+    // Nothing in the scratch has to start at zero: the count kernel writes every block counter the later
+    // kernels read, so the contents an earlier call left behind are never seen.
+    return launch_pack(keep_mask, batch->total_tokens, batch->cu_seqlens, batch->n_seqs, n_streams, streams,
+                       dst_capacity_rows, kept_index, cu_kept, n_kept_and_status, ws,
+                       static_cast<hipStream_t>(hip_stream));
+}
+
 static int check_streams(int32_t n_streams, const alch_stream* streams, int T, int64_t dst_capacity_rows) {
     if (n_streams < 0) return fail(ALCH_ERR_INVALID_ARG, "n_streams < 0");
     if (n_streams > 0 && !streams) return fail(ALCH_ERR_INVALID_ARG, "streams is NULL");

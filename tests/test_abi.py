@@ -73,6 +73,24 @@ def test_capture_pack_rejects_bad_arguments():
     assert L.alch_capture_pack(None, P, 1, st, 5, P, P, P, P, 1024, None) == -1
 
 
+def test_capture_pack_static_rejects_bad_arguments_and_sizes_beyond_its_scratch():
+    L = A.lib()
+    P = 0x10000
+    b = _batch([0, 3, 5])
+    st = (B.CStream * 1)(B.CStream(P, P, 8, 8))
+    call = lambda **kw: L.alch_capture_pack_static(C.byref(kw.get("b", b)), kw.get("mask", P), kw.get("n", 1), kw.get("st", st),
+                                                   kw.get("cap", 5), kw.get("idx", P), kw.get("cu", P), kw.get("status", P), None)
+    assert call(mask=None) == -1 and "keep_mask" in _err()
+    assert call(idx=None) == -1 and call(cu=None) == -1 and call(status=None) == -1 and call(cap=-1) == -1
+    assert call(st=(B.CStream * 1)(B.CStream(P, P, 6, 8))) == -2 and "row_bytes" in _err()
+    assert call(b=_batch([0, 3, 2], T=2, max_len=3)) == -2
+    # the built-in scratch serves a stated maximum; beyond it the call fails before anything is enqueued
+    limit = L.alch_capture_pack_static_max_tokens()
+    assert 1 << 24 <= limit < 1 << 31
+    assert L.alch_capture_pack_workspace_bytes(limit) <= 64 * 1024 < L.alch_capture_pack_workspace_bytes(limit + 4096)
+    assert call(b=_batch([0, limit + 1])) == -5 and "scratch" in _err()
+
+
 def test_capture_gather_rejects_bad_arguments():
     L = A.lib()
     P = 0x1000
