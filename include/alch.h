@@ -285,7 +285,8 @@ typedef struct {
  *   saved, weights, wgrads  HOST arrays of n_layers structs (wgrads may be NULL)
  *   X_final   [T,hidden] output of the last layer (the saved prefill output)
  *   g_final   [hidden] gain of the final RMSNorm;  W_lm [vocab,hidden]
- *   labels    device int32 [T]; a position counts if label >= 0 (and loss_mask != 0)
+ *   labels    device int32 [T]; a position counts if 0 <= label < vocab (and loss_mask != 0); any other label,
+ *             negative or beyond the vocabulary, marks a position that is ignored
  *   loss = -(1/N) sum_counted log softmax(RMSNorm(X_final) W_lm^T)[label]; N = 0 gives
  *          loss 0 and zero gradients.  Logits are produced and consumed in row chunks and
  *          never stored whole.

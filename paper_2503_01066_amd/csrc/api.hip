@@ -414,8 +414,10 @@ static int layer_backward_enqueue(const alch_layer_shape& s, const alch_batch& b
     //     products take their row or contraction count from device memory), and dX2, dO are scattered back
     //     into zero-filled [T, width] tensors for the attention backward, which is dense in the keys;
     //   otherwise dY is copied once with the masked rows zeroed and every step runs on all T rows.
+    // (the compacted products take their sizes from device memory, which only the matrix-core kernel supports:
+    // its 2 GiB operand limit, reached first by [dG | dU], is part of the decision, taken before anything is enqueued)
     const bool compact = loss_mask && T > 0 && !lo && dt == ALCH_BF16 && H % 64 == 0 && F % 64 == 0 && QD % 64 == 0 &&
-                         aligned16(dY);
+                         aligned16(dY) && (long long)T * 2 * F * (long long)E < (1LL << 31);
     const void *mY = dY, *mX2 = sv.X2, *mO = sv.O, *mG = sv.G, *mU = sv.U;  // inputs of the row-local part
     void *mdX2 = p.dX2, *mdO = p.dO;                                      // its outputs
     const int* ndev = nullptr;                                              // device-resident row count
@@ -935,6 +937,8 @@ static int stack_backward_impl(const alch_layer_shape* shape, int32_t n_layers, 
         if (dpo->n_items > 0 && (!dpo->item_row || !dpo->item_label || !dpo->item_slot || !dpo->item_row_host))
             return fail(ALCH_ERR_INVALID_ARG, "dpo: item_row / item_label / item_slot / item_row_host is NULL");
         if (dpo->n_pairs > 0 && !dpo->ref_logp) return fail(ALCH_ERR_INVALID_ARG, "dpo: ref_logp is NULL");
+        if (((size_t)shape->hidden * dtype_size(shape->dtype)) % 16)
+            return fail(ALCH_ERR_UNSUPPORTED, "dpo: a hidden row of %d elements is not a multiple of 16 bytes", shape->hidden);
         for (int m = 0; m < dpo->n_items; ++m) {
             const int r = dpo->item_row_host[m];
             if (r < 0 || r >= batch->total_tokens) return fail(ALCH_ERR_SHAPE, "dpo: item_row[%d] = %d outside the batch", m, r);
@@ -1016,15 +1020,16 @@ static int stack_backward_impl(const alch_layer_shape* shape, int32_t n_layers, 
         // With a loss mask (bf16, matrix-core shapes) only the counted tokens -- label >= 0 and mask byte nonzero --
         // go through the head: their Hf rows and labels are gathered, the three products and the cross-entropy
         // take their row counts from device memory, and dHf is scattered back into a zero-filled [T, H].
-        compact_head = loss_mask && T > 0 && dt == ALCH_BF16 && H % 64 == 0 && vocab % 64 == 0;
-        ALCH_TRY(launch_count_labels(labels, loss_mask, T, p.n_counted, p.row_loss, st));
+        compact_head = loss_mask && T > 0 && dt == ALCH_BF16 && H % 64 == 0 && vocab % 64 == 0 &&
+                       (long long)kHeadChunkRows * vocab * (long long)E < (1LL << 31);
+        ALCH_TRY(launch_count_labels(labels, loss_mask, T, vocab, p.n_counted, p.row_loss, st));
         ALCH_TRY(launch_rmsnorm_fwd(dt, X_final, g_final, p.Hf, T, H, s.rms_eps, st));
         const void* head_in = p.Hf;
         void* head_out = p.dHf;
         const int* head_labels = labels;
         const uint8_t* head_mask = loss_mask;
         if (compact_head) {
-            ALCH_TRY(launch_counted_mask(labels, loss_mask, T, p.h_counted, st));
+            ALCH_TRY(launch_counted_mask(labels, loss_mask, T, vocab, p.h_counted, st));
             const alch_stream rows1[1] = {{p.Hf, p.h_Hf, (size_t)H * E, (size_t)H * E}};
             ALCH_TRY(launch_pack(p.h_counted, T, batch->cu_seqlens, 0, 1, rows1, T, p.h_index, p.h_cu, p.h_n, p.h_packws, st, false));
             ALCH_TRY(launch_gather_int(labels, p.h_index, p.h_n, p.h_labels, T, st));

@@ -175,7 +175,7 @@ int launch_attn_fwd(alch_dtype dt, const void* Q, const void* K, const void* V, 
 
 // ---- LM head + cross-entropy ---------------------------------------------------------------
 // n_counted[0] = #{t : labels[t] >= 0 and (mask == NULL or mask[t] != 0)}; row_loss[0..T) = 0
-int launch_count_labels(const int* labels, const uint8_t* loss_mask, int T, int* n_counted, float* row_loss,
+int launch_count_labels(const int* labels, const uint8_t* loss_mask, int T, int vocab, int* n_counted, float* row_loss,
                         hipStream_t stream);
 // One chunk of logits rows [rows, vocab] (row stride ld), in place: logits -> dlogits =
 // (softmax - onehot(label)) / N for counted rows, 0 otherwise; row_loss[r] = -log softmax[label].
@@ -183,7 +183,7 @@ int launch_ce_chunk(alch_dtype dt, void* logits, long long ld, int rows, int voc
                     const uint8_t* loss_mask, const int* n_counted, float* row_loss, hipStream_t stream,
                     const int* rows_dev = nullptr);
 // counted[t] = label >= 0 and loss-mask byte nonzero; chunk_rows[c] = rows of chunk c among the first *n_rows rows
-int launch_counted_mask(const int* labels, const uint8_t* loss_mask, int T, uint8_t* counted, hipStream_t stream);
+int launch_counted_mask(const int* labels, const uint8_t* loss_mask, int T, int vocab, uint8_t* counted, hipStream_t stream);
 int launch_chunk_rows(const int* n_rows, int n_chunks, int chunk, int* chunk_rows, hipStream_t stream);
 // dst[r] = src[index[r]] for r < min(*n_rows, T)
 int launch_gather_int(const int* src, const int* index, const int* n_rows, int* dst, int T, hipStream_t stream);

@@ -20,13 +20,18 @@ __device__ __forceinline__ float wsum2(float v) {
     return v;
 }
 
+// A position counts when its label names a vocabulary entry (0 <= label < vocab) and its loss-mask byte, if a
+// mask is given, is nonzero: one predicate for the count, the counted mask and the row kernels.
+__device__ __forceinline__ bool label_counts(int label, int vocab) { return (unsigned)label < (unsigned)vocab; }
+
 __global__ __launch_bounds__(256) void k_count_labels(const int* __restrict__ labels, const uint8_t* __restrict__ mask,
-                                                      int T, int* __restrict__ n_counted, float* __restrict__ row_loss) {
+                                                      int T, int vocab, int* __restrict__ n_counted,
+                                                      float* __restrict__ row_loss) {
     // single block: deterministic count
     __shared__ int part[4];
     int c = 0;
     for (int t = threadIdx.x; t < T; t += 256) {
-        c += (labels[t] >= 0 && (!mask || mask[t] != 0)) ? 1 : 0;
+        c += (label_counts(labels[t], vocab) && (!mask || mask[t] != 0)) ? 1 : 0;
         row_loss[t] = 0.f;
     }
 #pragma unroll
@@ -46,7 +51,7 @@ __global__ __launch_bounds__(256) void k_ce_chunk(T* __restrict__ logits, long l
     if (rows_dev && r >= *rows_dev) return;  // row count decided on the device (compacted rows)
     T* row = logits + (long long)r * ld;
     const int label = labels[r];
-    const bool counted = label >= 0 && label < vocab && (!mask || mask[r] != 0);
+    const bool counted = label_counts(label, vocab) && (!mask || mask[r] != 0);
     if (!counted) {
         for (int v = threadIdx.x; v < vocab; v += 256) row[v] = (T)0.f;
         return;
@@ -92,7 +97,7 @@ __global__ __launch_bounds__(kCeThreads) void k_ce_chunk_bf16_row(__bf16* __rest
     if (rows_dev && r >= *rows_dev) return;  // row count decided on the device (compacted rows)
     __bf16* row = logits + (long long)r * ld;
     const int label = labels[r];
-    const bool counted = label >= 0 && label < vocab && (!mask || mask[r] != 0);
+    const bool counted = label_counts(label, vocab) && (!mask || mask[r] != 0);
     const int nchunks = vocab >> 3;
     if (!counted) {
         bf16x8_c z;
@@ -176,11 +181,11 @@ __global__ __launch_bounds__(256) void k_finish_loss(const float* __restrict__ r
     }
 }
 
-// counted[t] = 1 where the token contributes to the loss (label >= 0 and loss-mask byte nonzero)
+// counted[t] = 1 where the token contributes to the loss (0 <= label < vocab and loss-mask byte nonzero)
 __global__ __launch_bounds__(256) void k_counted_mask(const int* __restrict__ labels, const uint8_t* __restrict__ mask,
-                                                      int T, uint8_t* __restrict__ counted) {
+                                                      int T, int vocab, uint8_t* __restrict__ counted) {
     for (int t = blockIdx.x * 256 + threadIdx.x; t < T; t += gridDim.x * 256)
-        counted[t] = (labels[t] >= 0 && (!mask || mask[t] != 0)) ? 1 : 0;
+        counted[t] = (label_counts(labels[t], vocab) && (!mask || mask[t] != 0)) ? 1 : 0;
 }
 // chunk_rows[c] = number of the n compacted rows that fall into row chunk c
 __global__ void k_chunk_rows(const int* __restrict__ n_rows, int n_chunks, int chunk, int* __restrict__ chunk_rows) {
@@ -202,9 +207,9 @@ int launch_gather_int(const int* src, const int* index, const int* n_rows, int* 
     ALCH_HIP_TRY(hipGetLastError());
     return ALCH_OK;
 }
-int launch_counted_mask(const int* labels, const uint8_t* loss_mask, int T, uint8_t* counted, hipStream_t stream) {
+int launch_counted_mask(const int* labels, const uint8_t* loss_mask, int T, int vocab, uint8_t* counted, hipStream_t stream) {
     if (T <= 0) return ALCH_OK;
-    k_counted_mask<<<ceil_div(T, 256) < 1024 ? ceil_div(T, 256) : 1024, 256, 0, stream>>>(labels, loss_mask, T, counted);
+    k_counted_mask<<<ceil_div(T, 256) < 1024 ? ceil_div(T, 256) : 1024, 256, 0, stream>>>(labels, loss_mask, T, vocab, counted);
     ALCH_HIP_TRY(hipGetLastError());
     return ALCH_OK;
 }
@@ -215,9 +220,9 @@ int launch_chunk_rows(const int* n_rows, int n_chunks, int chunk, int* chunk_row
     return ALCH_OK;
 }
 
-int launch_count_labels(const int* labels, const uint8_t* loss_mask, int T, int* n_counted, float* row_loss,
+int launch_count_labels(const int* labels, const uint8_t* loss_mask, int T, int vocab, int* n_counted, float* row_loss,
                         hipStream_t stream) {
-    k_count_labels<<<1, 256, 0, stream>>>(labels, loss_mask, T, n_counted, row_loss);
+    k_count_labels<<<1, 256, 0, stream>>>(labels, loss_mask, T, vocab, n_counted, row_loss);
     ALCH_HIP_TRY(hipGetLastError());
     return ALCH_OK;
 }

@@ -37,6 +37,23 @@ def cosine(gpu, ref):
     return float(a @ b / n) if n > 0 else 1.0
 
 
+def check_all(out, ref, tol, label, keys=None, min_cosine=0.999):
+    """Parity bar on every output tensor: max|gpu - oracle| / max|oracle| <= tol.  The cosine similarity is
+    reported beside it (printed with -s / on failure) and must not fall below min_cosine."""
+    rows, worst = [], 0.0
+    for k in (keys if keys is not None else out.keys()):
+        g = to_np(out[k])
+        e, c = rel_err(g, ref[k]), cosine(g, ref[k])
+        rows.append("%s %-8s rel_err %.3e  cosine %.6f" % (label, k, e, c))
+        worst = max(worst, e)
+    print("\n".join(rows), flush=True)
+    for k, line in zip((keys if keys is not None else out.keys()), rows):
+        g = to_np(out[k])
+        assert rel_err(g, ref[k]) <= tol, line
+        assert cosine(g, ref[k]) >= min_cosine, line
+    return worst
+
+
 def oracle_shape(shp):
     from oracle import LayerShape
     return LayerShape(shp["hidden"], shp["n_q_heads"], shp["n_kv_heads"], shp["head_dim"], shp["ffn"],

@@ -1,14 +1,14 @@
-"""Full-size parity in the launch configuration bench.py times (config 2: one Llama-3-8B-shaped
-layer, bf16, 4 x 2048 tokens), on sampled outputs the oracle can compute one by one, plus a
-full-width / short-batch case checked element by element, plus config-3-sized capture/pack."""
+"""Full-size parity in the launch configurations bench.py times: config 2 (one Llama-3-8B-shaped layer,
+bf16, 4 x 2048 tokens) and config 5 (one Llama-3-70B-shaped layer, 2 x 4096 tokens, dense and with the
+loss mask), every output element by element against the fp64 oracle; full-width / short-batch cases;
+config-3-sized capture/pack; the adapter mode at config-2 size on sampled outputs."""
 import numpy as np
 import pytest
 import torch
 
 import synth_inputs as synth
-from helpers import to_dev, to_np, f64, rel_err, oracle_shape, alch_shape
+from helpers import to_dev, to_np, f64, rel_err, oracle_shape, alch_shape, check_all
 from oracle import layer_backward_reuse, attention_lse, gather_pack, WEIGHT_KEYS
-from oracle.layer import layer_backward_reuse_tail_rows, _rms_norm, _sigmoid
 
 pytestmark = pytest.mark.gpu
 REC = ("X", "X2", "Q", "K", "V", "O", "G", "U")
@@ -45,58 +45,49 @@ def test_real_layer_width_short_batch_elementwise(shape_name):
         assert e <= 2e-2, (k, e)
 
 
-def test_config2_full_size_sampled_outputs():
-    shp = synth.shape_dict("llama8b")
+def _full_size_layer(shape_name, B, S, mask_rate=None):
+    """One bench-sized layer step (drawn record, LSE from the drawn Q, K), oracle and GPU on the same bits,
+    every output compared element by element."""
+    import paper_2503_01066_amd as A
+    shp = synth.shape_dict(shape_name)
     osh = oracle_shape(shp)
-    S, B = 2048, 4
     cu = synth.uniform_cu(B, S)
     T = B * S
-    H, F = shp["hidden"], shp["ffn"]
     W = synth.layer_weights(shp, 0, "bf16")
     rec = synth.drawn_record(shp, T, 1, "bf16")
     print("lse ...", flush=True)
     rec["LSE"] = attention_lse(osh, cu, rec["Q"].astype(np.float64), rec["K"].astype(np.float64)).astype(np.float32)
-    dY = synth.activations(T, H, 2, "bf16", std=0.01)
+    dY = synth.activations(T, shp["hidden"], 2, "bf16", std=0.01)
+    mask = None if mask_rate is None else synth.keep_mask(T, mask_rate, 3)
     print("gpu ...", flush=True)
-    out = gpu_layer(shp, cu, W, rec, dY)
-    W64 = f64(W)
-    rng = np.random.default_rng(3)
+    dW = {k: to_dev(v, "bf16") for k, v in W.items()}
+    drec = {k: to_dev(rec[k], "bf16") for k in REC}
+    drec["LSE"] = torch.from_numpy(rec["LSE"]).cuda()
+    out = A.alch_layer_backward(alch_shape(shp, "bf16"), A.Batch(cu), drec, dW, to_dev(dY, "bf16"),
+                                loss_mask=None if mask is None else torch.from_numpy(mask).cuda())
+    torch.cuda.synchronize()
+    out = {k: v.float().cpu() for k, v in out.items()}      # free the device before the oracle takes the host
+    del dW, drec
+    torch.cuda.empty_cache()
+    print("oracle ...", flush=True)
+    ref = layer_backward_reuse(osh, cu, None, f64(rec), f64(W), dY.astype(np.float64), mask)
+    return out, ref
 
-    # (a) dX rows of the last tokens of two sequences (exact by causality)
-    m = 24
-    dX = to_np(out["dX"])
-    for s in (0, 3):
-        a, b = s * S, (s + 1) * S
-        seq = {k: rec[k][a:b].astype(np.float64) for k in REC + ("LSE",)}
-        tail = layer_backward_reuse_tail_rows(osh, None, seq, W64, dY[b - m:b].astype(np.float64))
-        e = np.abs(dX[b - m:b] - tail).max() / np.abs(tail).max()
-        assert e <= 2e-2, ("dX tail", s, e)
 
-    # (b) sampled entries of dWd = dY^T (silu(G) * U)
-    dWd = to_np(out["dWd"])
-    G64, U64, dY64 = rec["G"].astype(np.float64), rec["U"].astype(np.float64), dY.astype(np.float64)
-    oo, ii = rng.integers(0, H, 48), rng.integers(0, F, 48)
-    want = np.array([np.sum(dY64[:, o] * (G64[:, i] * _sigmoid(G64[:, i]) * U64[:, i])) for o, i in zip(oo, ii)])
-    scale = np.abs(want).max()
-    assert np.abs(dWd[oo, ii] - want).max() <= 2e-2 * scale
+def test_config2_full_size_every_output_elementwise():
+    # config 2 as bench.py times it: Llama-3-8B-shaped layer, 4 x 2048 tokens; dX, the seven weight gradients
+    # and both gain gradients, every element
+    out, ref = _full_size_layer("llama8b", 4, 2048)
+    assert set(out) == {"dX"} | {"d" + k for k in WEIGHT_KEYS}
+    check_all(out, ref, 2e-2, "config2")
 
-    # (c) sampled entries of dWg, dWu = dG^T H2, dU^T H2 with dAct[:, f] = dY Wd[:, f]
-    X2 = rec["X2"].astype(np.float64)
-    H2, _ = _rms_norm(X2, W64["g2"], osh.rms_eps)
-    dWg, dWu = to_np(out["dWg"]), to_np(out["dWu"])
-    ff, hh = rng.integers(0, F, 12), rng.integers(0, H, 12)
-    wg, wu = [], []
-    for f, h in zip(ff, hh):
-        dAct = dY64 @ W64["Wd"][:, f]
-        sg = _sigmoid(G64[:, f])
-        wg.append(np.sum(dAct * U64[:, f] * sg * (1 + G64[:, f] * (1 - sg)) * H2[:, h]))
-        wu.append(np.sum(dAct * G64[:, f] * sg * H2[:, h]))
-    wg, wu = np.array(wg), np.array(wu)
-    # the bar is relative to the largest entry of the tensor; the samples give a lower bound of it
-    assert np.abs(dWg[ff, hh] - wg).max() <= 2e-2 * max(np.abs(wg).max(), np.abs(dWg).max())
-    assert np.abs(dWu[ff, hh] - wu).max() <= 2e-2 * max(np.abs(wu).max(), np.abs(dWu).max())
-    for k, v in out.items():
-        assert torch.isfinite(v.float()).all(), k
+
+@pytest.mark.parametrize("mask_rate", [0.25, None])
+def test_config5_full_size_every_output_elementwise(mask_rate):
+    # config 5 as bench.py times it: Llama-3-70B-shaped layer, 2 x 4096 tokens, with the Bernoulli(0.25) loss mask
+    # the configuration names (row-compacted path) and dense
+    out, ref = _full_size_layer("llama70b", 2, 4096, mask_rate)
+    check_all(out, ref, 2e-2, "config5 mask=%s" % mask_rate)
 
 
 def test_config3_sized_capture_pack_one_layer():
@@ -154,24 +145,22 @@ def test_llama70b_width_short_batch_elementwise_with_loss_mask():
         assert e <= 2e-2, (k, e)
 
 
-def test_config2_full_size_adapter_mode_sampled_outputs():
+def test_config2_full_size_adapter_mode_every_output_elementwise():
     # the paper's training setting at the size bench.py times (frozen 8B-shaped base, rank-8 adapters on all seven
-    # projections, 4 x 2048 tokens): dX rows by causality at the merged weights, sampled adapter-gradient entries
-    # from their definitions
+    # projections, 4 x 2048 tokens): dX and all fourteen adapter gradients, every element
     import paper_2503_01066_amd as A
-    from oracle.lora import merged_weights
+    from oracle.lora import layer_backward_reuse_lora
     shp = synth.shape_dict("llama8b")
     osh = oracle_shape(shp)
     S, B, r, scale = 2048, 4, 8, 2.0
     cu = synth.uniform_cu(B, S)
     T = B * S
-    H, F = shp["hidden"], shp["ffn"]
     W = synth.layer_weights(shp, 0, "bf16")
     lora = synth.lora_adapters(shp, r, 5, "bf16", std=0.05)
     rec = synth.drawn_record(shp, T, 1, "bf16")
     print("lse ...", flush=True)
     rec["LSE"] = attention_lse(osh, cu, rec["Q"].astype(np.float64), rec["K"].astype(np.float64)).astype(np.float32)
-    dY = synth.activations(T, H, 2, "bf16", std=0.01)
+    dY = synth.activations(T, shp["hidden"], 2, "bf16", std=0.01)
     print("gpu ...", flush=True)
     drec = {k: to_dev(rec[k], "bf16") for k in REC}
     drec["LSE"] = torch.from_numpy(rec["LSE"]).cuda()
@@ -179,43 +168,14 @@ def test_config2_full_size_adapter_mode_sampled_outputs():
                                      {p: (to_dev(a, "bf16"), to_dev(b, "bf16")) for p, (a, b) in lora.items()}, r, scale,
                                      to_dev(dY, "bf16"))
     torch.cuda.synchronize()
+    out = {k: v.float().cpu() for k, v in out.items()}
+    del drec
+    torch.cuda.empty_cache()
+    print("oracle ...", flush=True)
     lora64 = {p: (a.astype(np.float64), b.astype(np.float64)) for p, (a, b) in lora.items()}
-    Wm = merged_weights(f64(W), lora64, scale)
-    rng = np.random.default_rng(4)
-
-    # (a) dX rows of the last tokens of a sequence (exact by causality), merged weights
-    m = 16
-    dX = to_np(out["dX"])
-    a, b = 2 * S, 3 * S
-    seq = {k: rec[k][a:b].astype(np.float64) for k in REC + ("LSE",)}
-    tail = layer_backward_reuse_tail_rows(osh, None, seq, Wm, dY[b - m:b].astype(np.float64))
-    e = np.abs(dX[b - m:b] - tail).max() / np.abs(tail).max()
-    assert e <= 2e-2, ("dX tail", e)
-
-    # (b) down-projection adapter: dB_d = s dY^T (Act A_d^T), dA_d = s (dY B_d)^T Act, all entries of the small matrices
-    G64, U64, dY64 = rec["G"].astype(np.float64), rec["U"].astype(np.float64), dY.astype(np.float64)
-    Act = G64 * _sigmoid(G64) * U64
-    Ad, Bd = lora64["d"]
-    want_dB = scale * dY64.T @ (Act @ Ad.T)
-    want_dA = scale * (dY64 @ Bd).T @ Act
-    assert rel_err(to_np(out["dBd"]), want_dB) <= 2e-2
-    assert rel_err(to_np(out["dAd"]), want_dA) <= 2e-2
-
-    # (c) gate adapter, sampled columns f: dG[:, f] from dAct[:, f] = dY Wd'[:, f]; dB_g[f, :] = s dG[:, f]^T (H2 A_g^T)
-    H2, _ = _rms_norm(rec["X2"].astype(np.float64), Wm["g2"], osh.rms_eps)
-    Ag, Bg = lora64["g"]
-    t1 = scale * (H2 @ Ag.T)
-    dBg = to_np(out["dBg"])
-    ff = rng.integers(0, F, 10)
-    want = []
-    for f in ff:
-        dAct = dY64 @ Wm["Wd"][:, f]
-        sg = _sigmoid(G64[:, f])
-        want.append((dAct * U64[:, f] * sg * (1 + G64[:, f] * (1 - sg))) @ t1)
-    want = np.array(want)
-    assert np.abs(dBg[ff] - want).max() <= 2e-2 * max(np.abs(want).max(), np.abs(dBg).max())
-    for k, v in out.items():
-        assert torch.isfinite(v.float()).all(), k
+    ref = layer_backward_reuse_lora(osh, cu, None, f64(rec), f64(W), lora64, scale, dY.astype(np.float64))
+    assert {"dX"} | {"d" + m + p for p in lora for m in "AB"} <= set(out)
+    check_all(out, ref, 2e-2, "config2 adapters")
 
 
 def test_split_products_with_several_outputs_and_operand_pairs():

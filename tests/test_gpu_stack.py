@@ -5,7 +5,7 @@ import pytest
 import torch
 
 import synth_inputs as synth
-from helpers import TOL, to_dev, to_np, f64, rel_err, oracle_shape, alch_shape
+from helpers import TOL, to_dev, to_np, f64, rel_err, oracle_shape, alch_shape, check_all
 from oracle import stack_forward, stack_backward_reuse, layer_forward, layer_backward_recompute, WEIGHT_KEYS
 
 pytestmark = pytest.mark.gpu
@@ -128,7 +128,7 @@ def test_layer_forward_and_reuse_equals_recompute(dtype, shape_name, lens, wstd)
     out = A.alch_layer_backward(shape, batch, rec, dW, to_dev(dY, dtype))
     torch.cuda.synchronize()
     for k, v in out.items():
-        assert rel_err(to_np(v), ref[k]) <= (tol if dtype == "f32" else 3e-2), k
+        assert rel_err(to_np(v), ref[k]) <= tol, (k, rel_err(to_np(v), ref[k]))
 
 
 def test_stack_from_four_stream_records():
@@ -166,3 +166,55 @@ def test_stack_loss_mask_compacts_head_and_top_layer(keep):
             assert float(out[k].abs().max()) == 0.0, k
     else:
         check_stack(out, ref, "bf16", L)
+
+
+def _head_case(shape_name, V, lens, seed, dtype="bf16", wstd=0.02):
+    """Inputs of the head alone (no layers): saved stack output, final gain, LM head, next-token labels drawn
+    uniformly over the whole vocabulary (the last position of every sequence is ignored)."""
+    shp = synth.shape_dict(shape_name)
+    cu = synth.ragged_cu(lens)
+    T, H = int(cu[-1]), shp["hidden"]
+    rng = np.random.default_rng(seed)
+    Xf = synth.normal(rng, (T, H), 1.0, dtype)
+    gf = synth.quantize(1.0 + 0.1 * rng.standard_normal(H).astype(np.float32), dtype)
+    Wlm = synth.normal(rng, (V, H), wstd, dtype)
+    labels = rng.integers(0, V, T).astype(np.int32)
+    labels[np.asarray(cu[1:]) - 1] = -1
+    return shp, cu, Xf, gf, Wlm, labels
+
+
+def _check_head(shp, cu, Xf, gf, Wlm, labels, mask, label, oracle_labels=None):
+    from oracle.stack import _head_loss_and_grads
+    out = run_stack(shp, "bf16", cu, [], [], Xf, gf, Wlm, labels, mask)
+    out = {k: (v.float().cpu() if torch.is_tensor(v) else v) for k, v in out.items()}
+    torch.cuda.empty_cache()
+    loss, dX, dg, dW = _head_loss_and_grads(oracle_shape(shp), Xf.astype(np.float64), gf.astype(np.float64),
+                                            Wlm.astype(np.float64), labels if oracle_labels is None else oracle_labels, mask)
+    print("%s loss gpu %.6f oracle %.6f" % (label, out["loss"].item(), loss), flush=True)
+    assert abs(out["loss"].item() - loss) <= 2e-2 * max(1.0, abs(loss))
+    check_all(out, dict(dX_embed=dX, dg_final=dg, dW_lm=dW), 2e-2, label, keys=("dX_embed", "dg_final", "dW_lm"))
+
+
+@pytest.mark.parametrize("keep", [None, 0.5])
+def test_head_alone_at_the_real_vocabulary(keep):
+    # the head config 4 runs: vocabulary 128,256 (16,032 eight-logit chunks per row, so every thread of the
+    # one-row-in-registers cross-entropy kernel holds 15 or 16 chunks and the label falls in any of them), hidden
+    # 4096, ragged rows; with a loss mask the counted rows are compacted first
+    shp, cu, Xf, gf, Wlm, labels = _head_case("llama8b", 128256, [1200, 1, 900, 499], 21)
+    mask = None if keep is None else synth.keep_mask(int(cu[-1]), keep, 22)
+    _check_head(shp, cu, Xf, gf, Wlm, labels, mask, "head V=128256 keep=%s" % keep)
+
+
+@pytest.mark.parametrize("keep", [None, 0.9])
+def test_head_alone_second_row_chunk_and_labels_beyond_the_vocabulary(keep):
+    # 8,300 dense rows: the second 8,192-row chunk of the head is not empty (labels, row losses and the accumulation
+    # of dW_lm across chunks at a row offset); 20,032 logits per row = three register chunks per thread.  Labels at or
+    # beyond the vocabulary are ignored positions, like negative ones.
+    shp, cu, Xf, gf, Wlm, labels = _head_case("medium", 20032, [5000, 3300], 23, wstd=0.05)
+    T = int(cu[-1])
+    beyond = np.random.default_rng(5).choice(T, 40, replace=False)
+    labels[beyond] = 20032 + (beyond % 7)
+    oracle_labels = labels.copy()
+    oracle_labels[beyond] = -1
+    mask = None if keep is None else synth.keep_mask(T, keep, 24)
+    _check_head(shp, cu, Xf, gf, Wlm, labels, mask, "head V=20032 T=8300 keep=%s" % keep, oracle_labels)
