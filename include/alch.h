@@ -35,8 +35,11 @@
  *
  * General conventions
  *   - Every pointer is DEVICE memory unless marked "host".  The caller owns every
- *     buffer, including the workspace; the library allocates no device memory and
- *     keeps no state between calls.
+ *     buffer, including the workspace; the library allocates no device memory.  It keeps
+ *     no state between calls with two exceptions, both opt-in: the launch trace
+ *     (alch_trace_enable / alch_trace_collect: a process-wide list of HIP events, guarded by
+ *     a mutex) and the built-in scratch of alch_capture_pack_static (one 64 KiB device
+ *     array per GPU).  Neither changes any result.
  *   - Every call validates its arguments on the host first, then enqueues kernels on
  *     `hip_stream` (a hipStream_t passed as void*, NULL = the default stream) and
  *     returns without synchronising.  ALCH_OK means "enqueued".
@@ -437,7 +440,10 @@ int alch_attention_forward(const alch_layer_shape* shape, const alch_batch* batc
  * HIP events on the caller's stream; alch_trace_collect waits for them, writes up to max_records
  * records (HOST array) in launch order, and forgets them.  flops / bytes are the algorithmic
  * work of the launch (2*M*N*K for a contraction; rows read once + written once for the gather).
- * The trace is process-wide; enable it from one thread.
+ * The trace is process-wide state of the library (the only state besides the scratch of
+ * alch_capture_pack_static); the switch is atomic and the record list is guarded by a mutex, so
+ * calls from several threads are safe, but their records interleave.  Each traced launch creates
+ * and records two HIP events, so timings taken with the trace on include that host-side cost.
  */
 typedef enum {
     ALCH_TRACE_GEMM_MFMA = 0, ALCH_TRACE_GEMM_GENERIC = 1, ALCH_TRACE_PACK_SCAN = 2,

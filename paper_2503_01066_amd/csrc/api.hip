@@ -6,6 +6,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -31,12 +32,12 @@ struct TraceRec {
     hipEvent_t e0, e1;
 };
 static std::mutex g_trace_mu;
-static bool g_trace_on = false;
+static std::atomic<bool> g_trace_on{false};
 static std::vector<TraceRec*> g_trace;
 static constexpr size_t kTraceMax = 1 << 16;
 
 TraceScope::TraceScope(int kind, double flops, double bytes, hipStream_t s) : rec(nullptr), stream(s) {
-    if (!g_trace_on) return;
+    if (!g_trace_on.load(std::memory_order_acquire)) return;
     std::lock_guard<std::mutex> lk(g_trace_mu);
     if (g_trace.size() >= kTraceMax) return;
     TraceRec* r = new TraceRec{kind, flops, bytes, nullptr, nullptr};
@@ -656,7 +657,7 @@ extern "C" {
 
 int alch_trace_enable(int32_t enable) {
     std::lock_guard<std::mutex> lk(g_trace_mu);
-    g_trace_on = enable != 0;
+    g_trace_on.store(enable != 0, std::memory_order_release);
     return ALCH_OK;
 }
 

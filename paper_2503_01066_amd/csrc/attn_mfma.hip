@@ -7,7 +7,7 @@
 // Two kernels, no atomics, deterministic:
 //   dK/dV kernel: a work-group owns 128 keys of one (sequence, kv head) -- 32 per wavefront,
 //     their K and V fragments held in registers -- and streams 64-query tiles of Q and dO of
-//     every query head of the group through LDS (direct-to-LDS loads, three stages, software pipelined).
+//     every query head of the group through LDS (direct-to-LDS loads, four stages, software pipelined).
 //       S = Q K^T, dP = dO V^T            (tile rows from LDS with ds_read_b128)
 //       P, dS in the accumulator layout feed straight back as the left operand of
 //       dV += P^T dO, dK += dS^T Q        (dO, Q rows read with the transposing LDS read)
@@ -166,7 +166,7 @@ __device__ __forceinline__ bf16x8 global_frag_d(const __bf16* base, long long ld
 // ends of the sequences): the tile stream is the concatenation of those, sequence by sequence.
 template <bool kPrefix>
 __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
-    __shared__ __attribute__((aligned(1024))) char smem[3 * kStageBytes];
+    __shared__ __attribute__((aligned(1024))) char smem[4 * kStageBytes];
     const uint32_t lds0 = (uint32_t)(uintptr_t)ALCH_LDS(smem);
     // Work-groups are handed out in order of blockIdx.z first, so z counts the work down: a key block
     // with `rem` blocks of queries at or after it costs rem units, and the heaviest of all sequences
@@ -229,30 +229,20 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
         }
         // (past the end of the stream the cursor wraps; its tiles are then loaded with zero extent)
     };
-    // Tile `it` of the stream goes to stage it % 3.  Beyond the end of the stream the loads are issued with
-    // zero extent: they move nothing and keep every wave's count of outstanding loads the same.
-    auto issue = [&](const Cursor& q, int it) {
-        const int row_first = q.qt * kTileRows, rows_valid = it < n_it ? q.n - row_first : 0;
-        const long long row = (long long)(q.row0 + row_first);
-        const uint32_t st = lds0 + (uint32_t)(it % 3) * kStageBytes;
-        issue_rows_tile(p.Q + row * p.ldq + q.h * kD, p.ldq, rows_valid, st, wave, voff);
-        issue_rows_tile(p.dO + row * p.ldq + q.h * kD, p.ldq, rows_valid, st + kTileBytes, wave, voff);
-        if (wave == 0) issue_row_scalars(p.LSE + row * p.Hq + q.h, p.Hq, rows_valid, st + 2 * kTileBytes, lane);
-        if (wave == 1) issue_row_scalars(p.delta + row * p.Hq + q.h, p.Hq, rows_valid, st + 2 * kTileBytes + 256, lane);
-    };
-
-    // Software pipeline over the tile stream, three LDS stages.  Entering iteration `it`, of tile `it`
-    // (two blocks of 32 queries) the wave holds P, dS of block 0 packed to bf16 and the raw scores
-    // S = Q K^T, dP = dO V^T of block 1.  The iteration waits for tile it+1 and meets the other waves
-    // (every wave is then past its reads of tile it-1, whose stage receives tile it+2), then runs 64
-    // matrix instructions back to back, in 16 groups of four:
+    // Software pipeline over the tile stream, four LDS stages (tile t in stage t & 3).  Entering iteration
+    // `it`, of tile `it` (two blocks of 32 queries) the wave holds P, dS of block 0 packed to bf16 and the raw
+    // scores S = Q K^T, dP = dO V^T of block 1.  The iteration waits for its own loads of tile it+1 (issued two
+    // iterations ago) and meets the other waves (every wave is then past its reads of tile it-1, whose stage
+    // receives tile it+3), then runs 64 matrix instructions in 16 groups of four:
     //   groups 0-7:  dV += P^T dO, dK += dS^T Q of block 0   |  S, dP of block 0 of tile it+1
     //   groups 8-15: the same for block 1                     |  S, dP of block 1 of tile it+1
-    // so the transposing LDS reads of one product and the row reads of the other are covered by
-    // independent matrix work (six LDS reads per group, issued two groups ahead of their use).  The same
-    // instruction stream carries, in the shadow of the matrix instructions, the nine direct-to-LDS loads
-    // of tile it+2 (one per group) and all of the exp/mask/pack work: block 1 of tile `it` during groups
-    // 0-7 (its consumers, groups 8-15, find it ready) and block 0 of tile it+1 during groups 8-15.
+    // Every matrix instruction is followed by its share of everything else, pinned in place (a wave issues in
+    // order, so vector work only overlaps a matrix instruction that was issued before it): the six LDS reads of
+    // the group two ahead, half of the exp/mask/dS work of two score elements (block 1 of tile `it` during
+    // groups 0-7, block 0 of tile it+1 during groups 8-15), one of the nine direct-to-LDS loads of tile it+3,
+    // the LSE / delta rows the coming groups need, and once per iteration the stream bookkeeping and the
+    // buffer descriptors of the tile the next iteration loads.  Beyond the end of the stream the loads are
+    // issued with zero extent: they move nothing and keep every wave's count of outstanding loads the same.
     f32x16 S1, dP1;         // raw scores of block 1 of the current tile
     bf16x8 pf0[2], dsf0[2]; // P, dS of block 0 of the current tile
     const int jl = j0 + (lane & 31);  // this lane's key
@@ -293,18 +283,47 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
         }
     };
 
+    // Buffer descriptors of one tile's loads (Q rows, dO rows, and for the first two waves LSE / delta).
+    struct LoadDesc { i32x4 q, dO, sc; };
+    auto desc_of = [&](const Cursor& q, bool live) {
+        const int rows = live ? q.n - q.qt * kTileRows : 0;
+        const long long ext = rows > 0 ? ((long long)(rows - 1) * p.ldq + kD) * 2 : 0;
+        const long long row = (long long)(q.row0 + q.qt * kTileRows);
+        LoadDesc d;
+        d.q = rsrc_of(p.Q + row * p.ldq + q.h * kD, ext);
+        d.dO = rsrc_of(p.dO + row * p.ldq + q.h * kD, ext);
+        d.sc = rsrc_of((wave == 0 ? p.LSE : p.delta) + row * p.Hq + q.h,
+                       (rows > 0 && wave < 2) ? ((long long)(rows - 1) * p.Hq + 1) * 4 : 0);
+        return d;
+    };
+    // LDS address of the row-scalar load of this wave: LSE (wave 0), delta (wave 1); the other two waves issue the
+    // same instruction with zero extent into the stage's padding, so every wave has nine loads per tile in flight
+    const uint32_t sc_lds = 2 * kTileBytes + (wave < 2 ? (uint32_t)wave * 256u : 512u + (uint32_t)(wave - 2) * 256u);
+    const uint32_t sc_voff = (uint32_t)(lane * p.Hq * 4);
+    auto issue_tile = [&](const LoadDesc& d, uint32_t st) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) dma16(d.q, st + (uint32_t)(wave * 4 + j) * 1024u, voff[j]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) dma16(d.dO, st + kTileBytes + (uint32_t)(wave * 4 + j) * 1024u, voff[j]);
+        dma4(d.sc, st + sc_lds, sc_voff);
+    };
+    // Four LDS stages, tile t in stage t & 3; iteration `it` works on tiles it and it+1 and loads tile it+3.
     Cursor q_ld{seq, seq_start, len, qt0, qt0 + nqt, kv * G, qt0};
-    issue(q_ld, 0);
     Meta m_cur = meta_of(q_ld);
+    issue_tile(desc_of(q_ld, 0 < n_it), lds0);
     advance(q_ld);
-    issue(q_ld, 1);
     Meta m_nxt = meta_of(q_ld);
-    advance(q_ld);  // now at tile 2, the next one to load
-    if (wave < 2)
-        asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
-    else
-        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    issue_tile(desc_of(q_ld, 1 < n_it), lds0 + kStageBytes);
+    advance(q_ld);
+    Meta m_nn = meta_of(q_ld);
+    issue_tile(desc_of(q_ld, 2 < n_it), lds0 + 2 * kStageBytes);
+    advance(q_ld);  // now at tile 3, the one iteration 0 loads
+    Meta m_n3 = meta_of(q_ld);
+    LoadDesc dsc = desc_of(q_ld, 3 < n_it);
+    advance(q_ld);
+    asm volatile("s_waitcnt vmcnt(18)" ::: "memory");
     __syncthreads();
+    f32x4 l1[4], d1[4];  // LSE, delta of block 1 of the current tile
     {   // tile 0: scores of both blocks, P and dS of block 0
         f32x16 S0, dP0;
 #pragma unroll
@@ -324,100 +343,124 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
             pf0[ks] = pack8(S0, ks);
             dsf0[ks] = pack8(dP0, ks);
         }
+        load_row_scalars(smem, 1, l1, d1);
     }
 
-    // stream state, advanced by one tile per iteration (no divisions in the loop): LDS byte offsets of the
-    // stages of tiles it, it+1, it+2; mask data of tiles it (m_cur) and it+1 (m_nxt); position of tile it+2 (q_ld)
-    uint32_t s_cur = 0, s_nxt = kStageBytes, s_ld = 2 * kStageBytes;
+#define ALCH_SB __builtin_amdgcn_sched_barrier(0)
+    struct Frags { bf16x8 rdo, rq, dq, ddo; };
     for (int it = 0; it < n_it; ++it) {
-        const char* tq = smem + s_cur;
+        const char* tq = smem + (uint32_t)(it & 3) * kStageBytes;
         const char* tdo = tq + kTileBytes;
-        f32x4 l1[4], d1[4];  // LSE, delta of block 1 of this tile
-        load_row_scalars(tq, 1, l1, d1);
-
-        __builtin_amdgcn_sched_barrier(0);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // tile it+1 (the only loads in flight)
-        __syncthreads();
-        // Loads of tile it+2: descriptors now, the nine load instructions one per group below (a
-        // burst of them would hold the wave at the issue stage for over a thousand cycles).
-        const int rows2 = it + 2 < n_it ? q_ld.n - q_ld.qt * kTileRows : 0;
-        const uint32_t st2 = lds0 + s_ld;
-        const long long ext2 = rows2 > 0 ? ((long long)(rows2 - 1) * p.ldq + kD) * 2 : 0;
-        const long long row2 = (long long)(q_ld.row0 + q_ld.qt * kTileRows);
-        const int h_ld = q_ld.h;
-        const i32x4 rs_q = rsrc_of(p.Q + row2 * p.ldq + h_ld * kD, ext2);
-        const i32x4 rs_do = rsrc_of(p.dO + row2 * p.ldq + h_ld * kD, ext2);
-        const i32x4 rs_sc = rsrc_of((wave == 0 ? p.LSE : p.delta) + row2 * p.Hq + h_ld,
-                                    rows2 > 0 ? ((long long)(rows2 - 1) * p.Hq + 1) * 4 : 0);
-        const char* nq = smem + s_nxt;
+        const char* nq = smem + (uint32_t)((it + 1) & 3) * kStageBytes;
         const char* ndo = nq + kTileBytes;
-        f32x4 ln[4], dn[4];  // LSE, delta of block 0 of the next tile (its stage is complete since the barrier)
-        load_row_scalars(nq, 0, ln, dn);
-        __builtin_amdgcn_sched_barrier(0);
+        const uint32_t st3 = lds0 + (uint32_t)((it + 3) & 3) * kStageBytes;
 
-        struct Frags { bf16x8 rdo, rq, dq, ddo; };
-        auto load_group = [&](int g) {
-            const int ib = g >> 3, ks = (g >> 2) & 1, nb = g & 3, kk = ks * 4 + nb;
-            Frags f;
-            f.rdo = lds_frag_rows(tdo + ib * 32 * 256, lane_r0, lane_r1, ks, nb);
-            f.rq = lds_frag_rows(tq + ib * 32 * 256, lane_r0, lane_r1, ks, nb);
-            f.dq = lds_frag_d(nq + ib * 32 * 256, lane_d, kk);
-            f.ddo = lds_frag_d(ndo + ib * 32 * 256, lane_d, kk);
-            return f;
-        };
+        ALCH_SB;
+        asm volatile("s_waitcnt vmcnt(9)" ::: "memory");  // tile it+1 has landed (tile it+2 may still be on its way)
+        __syncthreads();
+        ALCH_SB;
+
+        f32x4 ln[4], dn[4];  // LSE, delta of block 0 of the next tile
         Frags fr[3];
-        fr[0] = load_group(0);
-        fr[1] = load_group(1);
+        auto ld_rdo = [&](int g) { fr[g % 3].rdo = lds_frag_rows(tdo + (g >> 3) * 32 * 256, lane_r0, lane_r1, (g >> 2) & 1, g & 3); };
+        auto ld_rq = [&](int g) { fr[g % 3].rq = lds_frag_rows(tq + (g >> 3) * 32 * 256, lane_r0, lane_r1, (g >> 2) & 1, g & 3); };
+        auto ld_d = [&](int g) {
+            const int kk = ((g >> 2) & 1) * 4 + (g & 3);
+            fr[g % 3].dq = lds_frag_d(nq + (g >> 3) * 32 * 256, lane_d, kk);
+            fr[g % 3].ddo = lds_frag_d(ndo + (g >> 3) * 32 * 256, lane_d, kk);
+        };
+        ld_rdo(0); ld_rq(0); ld_d(0);
+        ld_rdo(1); ld_rq(1); ld_d(1);
         f32x16 Sn0, dPn0, Sn1, dPn1;  // scores of the next tile
         bf16x8 pf1[2], dsf1[2], pfn[2], dsfn[2];
+        Meta m_n4;
+        LoadDesc dsc_next;
+        // One element of the softmax gradient in two halves, each pinned where it is written so that it is issued
+        // between two matrix instructions: h1 = masked exponent -> probability, h2 = dS = p (dP - delta).
+        {
+            auto sm_h1 = [&](f32x16& sc, const f32x4 (&l)[4], const Meta& m, int blk, int e) {
+                const int rel0 = m.ibase + blk * 32 + 4 * half - (kPrefix ? m.sub : jl);
+                const unsigned live = kPrefix ? m.live : live_own;
+                const unsigned rel = (unsigned)(rel0 + 8 * (e >> 2) + (e & 3));
+                float arg = __builtin_fmaf(sc[e], sl2, -l[e >> 2][e & 3] * kLog2e);
+                arg = rel >= live ? -INFINITY : arg;
+                float pr = __builtin_amdgcn_exp2f(arg);
+                asm volatile("" : "+v"(pr));
+                sc[e] = pr;
+            };
+            auto sm_h2 = [&](const f32x16& sc, f32x16& dp, const f32x4 (&d)[4], int e) {
+                float t = sc[e] * (dp[e] - d[e >> 2][e & 3]);
+                asm volatile("" : "+v"(t));
+                dp[e] = t;
+            };
 #pragma unroll
-        for (int g = 0; g < 16; ++g) {
-            const int ib = g >> 3, ks = (g >> 2) & 1, nb = g & 3, kk = ks * 4 + nb;
-            if (g < 4) dma16(rs_q, st2 + (uint32_t)(wave * 4 + g) * 1024u, voff[g & 3]);
-            else if (g < 8) dma16(rs_do, st2 + kTileBytes + (uint32_t)(wave * 4 + g - 4) * 1024u, voff[g & 3]);
-            else if (g == 8 && wave < 2) dma4(rs_sc, st2 + 2 * kTileBytes + (uint32_t)wave * 256u, (uint32_t)(lane * p.Hq * 4));
-            if (g + 2 < 16) fr[(g + 2) % 3] = load_group(g + 2);
-            if (g < 8) {
-                softmax_part(S1, dP1, l1, d1, m_cur, 1, 2 * g, 2);
-                if (g == 3) { pf1[0] = pack8(S1, 0); dsf1[0] = pack8(dP1, 0); }
-                if (g == 7) { pf1[1] = pack8(S1, 1); dsf1[1] = pack8(dP1, 1); }
-            } else {
-                softmax_part(Sn0, dPn0, ln, dn, m_nxt, 0, 2 * (g - 8), 2);
-                if (g == 11) { pfn[0] = pack8(Sn0, 0); dsfn[0] = pack8(dPn0, 0); }
-                if (g == 15) { pfn[1] = pack8(Sn0, 1); dsfn[1] = pack8(dPn0, 1); }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            const Frags& f = fr[g % 3];
-            if (ib == 0) {
+            for (int g = 0; g < 16; ++g) {
+                const int ib = g >> 3, ks = (g >> 2) & 1, nb = g & 3, kk = ks * 4 + nb;
+                const int ea = ib == 0 ? 2 * g : 2 * (g - 8), eb = ea + 1;
+                const Frags& f = fr[g % 3];
+                // slot 0
+                if (g + 2 < 16) ld_rdo(g + 2);
+                if (ib == 0) sm_h1(S1, l1, m_cur, 1, ea); else sm_h1(Sn0, ln, m_nxt, 0, ea);
+                ALCH_SB;
+                dV[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ib == 0 ? pf0[ks] : pf1[ks], f.rdo, dV[nb], 0, 0, 0);
+                ALCH_SB;
+                // slot 1
+                if (g + 2 < 16) ld_rq(g + 2);
+                if (ib == 0) sm_h1(S1, l1, m_cur, 1, eb); else sm_h1(Sn0, ln, m_nxt, 0, eb);
+                ALCH_SB;
+                dK[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ib == 0 ? dsf0[ks] : dsf1[ks], f.rq, dK[nb], 0, 0, 0);
+                ALCH_SB;
+                // slot 2
+                if (g + 2 < 16) ld_d(g + 2);
+                if (ib == 0) { sm_h2(S1, dP1, d1, ea); sm_h2(S1, dP1, d1, eb); }
+                else { sm_h2(Sn0, dPn0, dn, ea); sm_h2(Sn0, dPn0, dn, eb); }
+                ALCH_SB;
                 if (g == 0) {
 #pragma unroll
                     for (int e = 0; e < 16; ++e) Sn0[e] = dPn0[e] = 0.f;
                 }
-                dV[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf0[ks], f.rdo, dV[nb], 0, 0, 0);
-                dK[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf0[ks], f.rq, dK[nb], 0, 0, 0);
-                Sn0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.dq, kf[kk], Sn0, 0, 0, 0);
-                dPn0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ddo, vf[kk], dPn0, 0, 0, 0);
-            } else {
                 if (g == 8) {
 #pragma unroll
                     for (int e = 0; e < 16; ++e) Sn1[e] = dPn1[e] = 0.f;
                 }
-                dV[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf1[ks], f.rdo, dV[nb], 0, 0, 0);
-                dK[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf1[ks], f.rq, dK[nb], 0, 0, 0);
-                Sn1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.dq, kf[kk], Sn1, 0, 0, 0);
-                dPn1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ddo, vf[kk], dPn1, 0, 0, 0);
+                if (ib == 0) Sn0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.dq, kf[kk], Sn0, 0, 0, 0);
+                else Sn1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.dq, kf[kk], Sn1, 0, 0, 0);
+                ALCH_SB;
+                // slot 3: the loads of tile it+3, the row scalars the next groups need, the stream bookkeeping, packs
+                if (g < 4) dma16(dsc.q, st3 + (uint32_t)(wave * 4 + g) * 1024u, voff[g & 3]);
+                else if (g < 8) dma16(dsc.dO, st3 + kTileBytes + (uint32_t)(wave * 4 + g - 4) * 1024u, voff[g & 3]);
+                else if (g == 8) dma4(dsc.sc, st3 + sc_lds, sc_voff);
+                if (g < 4) {       // LSE, delta of block 0 of tile it+1 (used from group 8 on)
+                    const float* sc_n = reinterpret_cast<const float*>(nq + 2 * kTileBytes);
+                    ln[g] = *reinterpret_cast<const f32x4*>(sc_n + 8 * g + 4 * half);
+                    dn[g] = *reinterpret_cast<const f32x4*>(sc_n + 64 + 8 * g + 4 * half);
+                }
+                if (g >= 12) {     // LSE, delta of block 1 of tile it+1 (used by the next iteration's groups 0-7)
+                    const float* sc_n = reinterpret_cast<const float*>(nq + 2 * kTileBytes);
+                    l1[g - 12] = *reinterpret_cast<const f32x4*>(sc_n + 32 + 8 * (g - 12) + 4 * half);
+                    d1[g - 12] = *reinterpret_cast<const f32x4*>(sc_n + 64 + 32 + 8 * (g - 12) + 4 * half);
+                }
+                if (g == 9) {      // position and descriptors of tile it+4, which the next iteration loads
+                    m_n4 = meta_of(q_ld);
+                    dsc_next = desc_of(q_ld, it + 4 < n_it);
+                    advance(q_ld);
+                }
+                if (g == 3) { pf1[0] = pack8(S1, 0); dsf1[0] = pack8(dP1, 0); asm volatile("" : "+v"(pf1[0]), "+v"(dsf1[0])); }
+                if (g == 7) { pf1[1] = pack8(S1, 1); dsf1[1] = pack8(dP1, 1); asm volatile("" : "+v"(pf1[1]), "+v"(dsf1[1])); }
+                if (g == 11) { pfn[0] = pack8(Sn0, 0); dsfn[0] = pack8(dPn0, 0); asm volatile("" : "+v"(pfn[0]), "+v"(dsfn[0])); }
+                if (g == 15) { pfn[1] = pack8(Sn0, 1); dsfn[1] = pack8(dPn0, 1); asm volatile("" : "+v"(pfn[1]), "+v"(dsfn[1])); }
+                ALCH_SB;
+                if (ib == 0) dPn0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ddo, vf[kk], dPn0, 0, 0, 0);
+                else dPn1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.ddo, vf[kk], dPn1, 0, 0, 0);
+                ALCH_SB;
             }
-            __builtin_amdgcn_sched_barrier(0);
         }
         // hand over to the next iteration
         S1 = Sn1; dP1 = dPn1;
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) { pf0[ks] = pfn[ks]; dsf0[ks] = dsfn[ks]; }
-        const uint32_t s_free = s_cur;
-        s_cur = s_nxt; s_nxt = s_ld; s_ld = s_free;
-        m_cur = m_nxt;
-        m_nxt = meta_of(q_ld);
-        advance(q_ld);
+        m_cur = m_nxt; m_nxt = m_nn; m_nn = m_n3; m_n3 = m_n4;
+        dsc = dsc_next;
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 

@@ -1,8 +1,9 @@
 // Capture/pack: mask scan and row gather (Section 4.1 of the paper: only the tokens of the
 // prefill that are to be trained on are recorded; Section 5: one record per layer).
 //
-// The scan is three small kernels over the byte mask (per-block popcount, scan of the
-// block counts, index fill); the gather runs one work-group per kept row,
+// The scan is one single-work-group kernel for batches of up to 262,144 tokens, and beyond that four small
+// kernels over the byte mask (per-block popcount, scan of the block counts, index fill, per-sequence counts)
+// with the block counts in caller-provided scratch; the gather runs one work-group per kept row,
 // moving 16 bytes per lane per access.  Everything is bit-exact and
 // deterministic: the output order is the ascending token order.
 #include "common.h"
@@ -122,6 +123,65 @@ __global__ __launch_bounds__(64) void k_pack_cu(const uint8_t* __restrict__ mask
     if (threadIdx.x == 0) cu_kept[s] = (blk < nblocks ? block_offsets[blk] : n_kept_and_status[0]) + count;
 }
 
+// ---- the whole scan in one launch, for batches of up to kOneLaunchTokens tokens ------------------------
+// One work-group of 1024 threads; thread i owns the tokens [i * chunk, (i + 1) * chunk) with chunk a multiple
+// of 16 (<= 256): it counts its kept tokens, the block scans the 1024 counts, and the thread writes the indices
+// of its kept tokens; then one thread per sequence boundary forms cu_kept from the scanned counts.  A prefill
+// batch of the paper's sizes (tens of thousands of tokens) is a mask of tens of kilobytes: four launches of the
+// general path cost more than the work.
+static constexpr int kOneLaunchThreads = 1024;
+static constexpr int kOneLaunchTokens = kOneLaunchThreads * 256;
+
+__global__ __launch_bounds__(kOneLaunchThreads) void k_pack_scan_one(const uint8_t* __restrict__ mask, int T, int chunk,
+                                                                      const int* __restrict__ cu_seqlens, int n_bounds,
+                                                                      int* __restrict__ kept_index, int* __restrict__ cu_kept,
+                                                                      int* __restrict__ n_kept_and_status, long long capacity) {
+    __shared__ int prefix[kOneLaunchThreads];            // kept tokens before each thread's chunk
+    __shared__ int wave_sum[kOneLaunchThreads / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int t_begin = tid * chunk;
+    int count = 0;
+    for (int t0 = t_begin; t0 < t_begin + chunk && t0 < T; t0 += kTokPerThread) {
+        uint32_t bits;
+        count += nonzero_bytes16(mask, t0, T, bits);
+    }
+    const int inc = wave_inclusive_scan(count);
+    if (lane == 63) wave_sum[wave] = inc;
+    __syncthreads();
+    int before = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < kOneLaunchThreads / 64; ++w) {
+        const int sw = wave_sum[w];
+        if (w < wave) before += sw;
+        total += sw;
+    }
+    const int ex = before + inc - count;
+    prefix[tid] = ex;
+    if (tid == 0) {
+        n_kept_and_status[0] = total;
+        n_kept_and_status[1] = (long long)total > capacity ? 1 : 0;
+    }
+    long long pos = ex;
+    for (int t0 = t_begin; t0 < t_begin + chunk && t0 < T; t0 += kTokPerThread) {
+        uint32_t bits;
+        nonzero_bytes16(mask, t0, T, bits);
+        while (bits) {
+            const int i = __ffs(bits) - 1;
+            bits &= bits - 1;
+            if (pos < capacity) kept_index[pos] = t0 + i;
+            ++pos;
+        }
+    }
+    __syncthreads();
+    for (int s = tid; s < n_bounds; s += kOneLaunchThreads) {
+        const int end = cu_seqlens[s];
+        const int owner = end / chunk;  // thread whose chunk holds token `end` (>= 1024 only for end == T at full chunks)
+        int c = owner < kOneLaunchThreads ? prefix[owner] : total;
+        for (int t = owner * chunk; t < end; ++t) c += mask[t] != 0;
+        cu_kept[s] = c;
+    }
+}
+
 // ---- gather ---------------------------------------------------------------------------
 
 struct GatherArgs {
@@ -176,7 +236,12 @@ int launch_pack(const uint8_t* mask, int T, const int* cu_seqlens, int n_seqs, i
                 int* n_kept_and_status, void* workspace, hipStream_t stream, bool traced) {
     int* block_offsets = static_cast<int*>(workspace);
     const int nblocks = T > 0 ? ceil_div(T, kTokPerBlock) : 0;
-    {
+    if (T <= kOneLaunchTokens) {
+        TraceScope ts(traced ? kTracePackScan : kTraceRowOps, 0.0, (double)T + 4.0 * (n_seqs + 1), stream);
+        const int chunk = (int)round_up((size_t)ceil_div(T > 0 ? T : 1, kOneLaunchThreads), kTokPerThread);
+        k_pack_scan_one<<<1, kOneLaunchThreads, 0, stream>>>(mask, T, chunk, cu_seqlens, n_seqs + 1, kept_index, cu_kept,
+                                                             n_kept_and_status, capacity);
+    } else {
     TraceScope ts(traced ? kTracePackScan : kTraceRowOps, 0.0, (double)T + 4.0 * (n_seqs + 1), stream);
     if (nblocks > 0) k_pack_count<<<nblocks, kScanThreads, 0, stream>>>(mask, T, block_offsets);
     k_pack_scan_blocks<<<1, kScanThreads, 0, stream>>>(block_offsets, nblocks, n_kept_and_status, capacity);

@@ -87,6 +87,17 @@ def test_many_blocks_ragged_tail_and_odd_widths():
     check(cu2, np.ones(8192, np.uint8), streams_for(8192, rng, widths=(8,)))
 
 
+def test_batches_beyond_the_single_launch_scan():
+    # up to 262,144 tokens the mask scan is one single-work-group launch; beyond that the four-kernel scan with block
+    # counts in the workspace runs: both sides of the limit, ragged, with empty sequences and a boundary inside a chunk
+    rng = np.random.default_rng(6)
+    for lens, keep in (([150000, 0, 112143, 1], 0.3), ([262144], 0.5), ([200000, 62145], 0.1), ([300001, 7, 0, 123457], 0.25)):
+        cu = synth.ragged_cu(lens)
+        T = int(cu[-1])
+        mask = synth.keep_mask(T, keep, 8)
+        check(cu, mask, streams_for(T, rng, widths=(8, 2)))
+
+
 def test_more_streams_than_one_launch_takes():
     rng = np.random.default_rng(2)
     cu = synth.ragged_cu([100, 37])

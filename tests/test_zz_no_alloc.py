@@ -1,6 +1,7 @@
 """alch_capture_pack_static (the entry point that neither takes nor allocates a workspace) against
 alch_capture_pack and the gather oracle: two calls in a row on the same output buffers, the second on a
-smaller batch, so that whatever the first call left in the library's built-in scratch is still there."""
+smaller batch, so that whatever the first call left in the library's built-in scratch is still there, and a third
+on a batch small enough for the single-launch scan."""
 import numpy as np
 import pytest
 import torch
@@ -22,21 +23,24 @@ def _case(lens, keep, seed, widths):
 
 def test_static_scratch_matches_workspace_call_twice_in_a_row():
     import paper_2503_01066_amd as A
-    widths = (64, 8, 520)
-    big = _case([3000, 0, 4100, 1, 5000, 777], 0.4, 0, widths)        # several scan blocks, ragged tail
-    small = _case([130, 61, 0, 200], 0.7, 5, widths)                   # fewer blocks than the call before
+    # (batches of up to 262,144 tokens are scanned by a single launch that needs no scratch: the first two cases
+    # are larger, so their block counters do live in the built-in array; the third takes the single-launch scan)
+    widths = (8, 8, 24)
+    big = _case([150000, 0, 170100, 1, 50000, 777], 0.4, 0, widths)   # 91 scan blocks, ragged tail
+    small = _case([130000, 61, 0, 140200], 0.7, 5, widths)            # fewer blocks than the call before
+    tiny = _case([130, 61, 0, 200], 0.7, 7, widths)
     cap = big[1]
     # caller-owned outputs, allocated once and reused by both calls (the entry point itself allocates nothing)
     kept = torch.empty(cap, dtype=torch.int32, device="cuda")
     status = torch.empty(2, dtype=torch.int32, device="cuda")
     dsts = [torch.empty((cap, w), dtype=torch.int16, device="cuda") for w in widths]
-    for cu, T, mask, srcs in (big, small):
+    for cu, T, mask, srcs in (big, small, tiny):
         batch = A.Batch(cu)
         dmask = torch.from_numpy(mask).cuda()
-        wide = torch.zeros((T, 600), dtype=torch.int16, device="cuda")  # third stream: column slice of a fused buffer
-        wide[:, 40:560] = torch.from_numpy(srcs[2].view(np.int16)).cuda()
+        wide = torch.zeros((T, 40), dtype=torch.int16, device="cuda")   # third stream: column slice of a fused buffer
+        wide[:, 8:32] = torch.from_numpy(srcs[2].view(np.int16)).cuda()
         devs = [torch.from_numpy(srcs[0].view(np.int16)).cuda(), torch.from_numpy(srcs[1].view(np.int16)).cuda(),
-                wide[:, 40:560]]
+                wide[:, 8:32]]
         cu_kept = torch.empty(batch.n_seqs + 1, dtype=torch.int32, device="cuda")
         for t in [kept, status, cu_kept] + dsts:
             t.fill_(-1)
