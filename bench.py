@@ -49,13 +49,18 @@ def parse():
     ap.add_argument("--scan-once", action="store_true",
                     help="config3: scan the mask for the first layer only, alch_capture_gather for the other 31")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-baseline-full", action="store_true",
+                    help="time the oracle on the whole workload (config 3: all 32 layers; config 5: 2 x 4096 tokens) "
+                         "instead of the bounded sample; takes several minutes of host time")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="config2: leave out the `also` object (configs 3, 4 and 5 measured in the same run)")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"),
                     help="measured HBM bytes per launch (from the rocprofv3 --pmc summaries)")
     return ap.parse_args()
 
 
-def cpu_baseline_layer(workload, seed=0):
-    """The fp64 oracle, as it stands, on a bounded sample of the layer workload."""
+def cpu_baseline_layer(workload, seed=0, full=False):
+    """The fp64 oracle, as it stands, on a bounded sample of the layer workload (full: on all of it)."""
     import synth_inputs as synth
     from oracle import LayerShape, layer_backward_reuse, attention_lse
     shape_name = LAYER_WORKLOADS[workload][0]
@@ -66,8 +71,9 @@ def cpu_baseline_layer(workload, seed=0):
         cores = os.cpu_count()
     shp = synth.shape_dict(shape_name)
     osh = LayerShape(*[shp[k] for k in synth.SHAPE_FIELDS])
-    # a bounded sample (10-20 s of host time): config 2 in full (4 x 2048); of config 5, 2 sequences of 512 tokens
-    n_seq, S = (4, 2048) if workload == "config2" else ((1, 512) if workload == "short" else (2, 512))
+    # a bounded sample (10-30 s of host time): config 2 in full (4 x 2048); of config 5, one sequence of 2048 tokens
+    # (the whole 2 x 4096 with full=True, about two minutes)
+    n_seq, S = (4, 2048) if workload == "config2" else ((1, 512) if workload == "short" else ((2, 4096) if full else (1, 2048)))
     cu = np.arange(n_seq + 1) * S
     Ttot = n_seq * S
     W = {k: v.astype(np.float64) for k, v in synth.layer_weights(shp, seed, "bf16").items()}
@@ -114,7 +120,7 @@ def cpu_baseline_dpo(layers, seed=0):
                       "responses x 128 tokens: response share of the forward + full backward, fp64 numpy, %.1f s" % (layers, dt)}
 
 
-def cpu_baseline_config3(seed=0, layers=3):
+def cpu_baseline_config3(seed=0, layers=4):
     """The gather oracle, as it stands, on the config-3 batch for a bounded number of layers."""
     import synth_inputs as synth
     from oracle import gather_pack
@@ -253,6 +259,12 @@ def run_layer(args, torch, A):
     A.alch_trace_enable(False)
     trace = A.alch_trace_collect()
     per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    # the same K steps once more with the launch trace off (no event creation / recording in the loop)
+    t1 = time.perf_counter()
+    for i in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_untraced = (time.perf_counter() - t1) / args.steps * 1e3
 
     ms_step = dt / args.steps * 1e3
     by = {}
@@ -271,6 +283,12 @@ def run_layer(args, torch, A):
     pk = by.get("pack_gather", [0, 0, 1e-9, 1])
     pack_gbps = pk[1] * T / (pk[2] * 1e-3) / 1e9       # traced bytes are per kept row
     attn_flops = 10.0 * shp["head_dim"] * shp["n_q_heads"] * n_keep * S * (S + 1) / 2
+    kms = {k: v[2] / args.steps for k, v in by.items()}
+    pack_ms = kms.get("pack_scan", 0.0) + kms.get("pack_gather", 0.0)
+    bwd_ms = ms_step - pack_ms                         # the layer backward alone: the step minus the capture/pack call
+    attn_ms = kms.get("attn_bwd", 0.0)
+    row_bytes_rw = pk[1] / max(pk[3], 1)                # traced bytes of a gather launch are per kept row
+    call_bytes = row_bytes_rw * T + T_src + 4.0 * T + 8.0 * (n_src + 1)   # + mask read, index written, cu in / out
     out = {
         "metric": METRIC, "value": T * args.steps / dt, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
@@ -280,9 +298,22 @@ def run_layer(args, torch, A):
         "config": {"workload": descr,
                    "hidden": H, "q_heads": shp["n_q_heads"], "kv_heads": shp["n_kv_heads"],
                    "head_dim": shp["head_dim"], "ffn": F, "tokens": T, "seq_len": S},
+        "ms_per_step_untraced": ms_untraced,
         "step_tflops": (gemm_flops_step + attn_flops) / 1e12,
         "step_mfma_frac": (gemm_flops_step + attn_flops) / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "backward_only_ms": bwd_ms,
+        "backward_only_mfma_frac": (gemm_flops_step + attn_flops) / (bwd_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "attention_backward": {"ms": attn_ms,
+                               "tflops_5_contractions": attn_flops / 1e12,
+                               "mfma_frac_5_contractions": attn_flops / max(attn_ms, 1e-9) / 1e9 / PEAK_BF16_TFLOPS,
+                               "tflops_4_contractions": 0.8 * attn_flops / 1e12,
+                               "mfma_frac_4_contractions": 0.8 * attn_flops / max(attn_ms, 1e-9) / 1e9 / PEAK_BF16_TFLOPS,
+                               "note": "causal pairs only; 5 = S recompute, dP, dV, dK, dQ; 4 leaves the S recompute out; "
+                                       "the two kernels execute 7 (S and dP are formed in both)"},
         "capture_gbps": pack_gbps,
+        "capture_call_gbps": call_bytes / max(pack_ms, 1e-9) / 1e6,
+        "capture_mask": "whole sequences (%d of %d prompts): a record feeds the backward only if every token of a kept "
+                        "sequence is kept; the per-token Bernoulli(0.25) mask of config 3 is measured in also.config3" % (n_keep, n_src),
         "roofline": {"kernel": "k_gemm_mfma (all contractions of the layer backward)", "bound": "mfma",
                      "achieved": achieved_tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved_tf / PEAK_BF16_TFLOPS,
@@ -292,7 +323,7 @@ def run_layer(args, torch, A):
                           "unit": "GB/s", "frac": pack_gbps / PEAK_HBM_GBPS,
                           "traffic": load_traffic(args.traffic_json, "pack_gather_%s_bytes_per_launch" % args.workload),
                           "avg_launch_ms": pk[2] / max(pk[3], 1)},
-        "kernel_ms_per_step": {k: v[2] / args.steps for k, v in by.items()},
+        "kernel_ms_per_step": kms,
     }
     if "lora" in by:
         lo = by["lora"]
@@ -662,10 +693,13 @@ def run_config3(args, torch, A):
                                (", mask scanned once per batch" if args.scan_once else ""),
                    "tokens": T, "kept": n_kept, "bytes_per_kept_token_per_layer": row_rw / 2},
         "capture_gbps": gbps,
+        "capture_call_gbps": total_bytes * args.steps / ((ms + sum(r[3] for r in trace if r[0] == "pack_scan")) * 1e-3) / 1e9,
         "roofline": {"kernel": "k_pack_gather", "bound": "hbm", "achieved": gbps, "peak": PEAK_HBM_GBPS,
                      "unit": "GB/s", "frac": gbps / PEAK_HBM_GBPS,
                      "traffic": load_traffic(args.traffic_json, "pack_gather_config3_bytes_per_launch"),
+                     "algorithmic_bytes_per_launch": row_rw * n_kept,
                      "avg_launch_ms": ms / len(pk)},
+        "whole_job_frac_of_hbm_peak": total_bytes * args.steps / dt / 1e9 / PEAK_HBM_GBPS,
     }
 
 
@@ -760,20 +794,60 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
-    out = {"config2": run_layer, "config5": run_layer, "short": run_layer, "config3": run_config3, "config4": run_config4,
-           "dpo": run_dpo, "copy": run_copy, "gemm": run_gemm}[args.workload](args, torch, A)
-    if not args.no_cpu_baseline and args.workload == "config4":
+    runners = {"config2": run_layer, "config5": run_layer, "short": run_layer, "config3": run_config3, "config4": run_config4,
+               "dpo": run_dpo, "copy": run_copy, "gemm": run_gemm}
+    out = runners[args.workload](args, torch, A)
+    P_tok_cfg2 = 4.0 * (2 * 4096 * 4096 + 2 * 4096 * 1024 + 3 * 4096 * 14336) + 10.0 * 128 * 32 * 2049 / 2
+
+    def config4_baseline(res, layer_baseline):
         # extrapolated, and labelled so: one layer on 4 x 2048 tokens, scaled by flops
-        b = cpu_baseline_layer("config2")
-        per_tok = out["step_tflops"] * 1e12 / out["config"]["tokens"]
-        P_tok = 4.0 * (2 * 4096 * 4096 + 2 * 4096 * 1024 + 3 * 4096 * 14336) + 10.0 * 128 * 32 * 2049 / 2
-        b["value"] = b["value"] * P_tok / per_tok
+        b = dict(layer_baseline)
+        per_tok = res["step_tflops"] * 1e12 / res["config"]["tokens"]
+        b["value"] = b["value"] * P_tok_cfg2 / per_tok
         b["sample"] = "EXTRAPOLATED by flop count from: " + b["sample"]
-        out["cpu_baseline"] = b
+        return b
+
+    if not args.no_cpu_baseline and args.workload == "config4":
+        out["cpu_baseline"] = config4_baseline(out, cpu_baseline_layer("config2"))
     elif not args.no_cpu_baseline and args.workload == "dpo":
         out["cpu_baseline"] = cpu_baseline_dpo(args.layers)
     elif not args.no_cpu_baseline and args.workload not in ("copy", "gemm"):
-        out["cpu_baseline"] = cpu_baseline_config3() if args.workload == "config3" else cpu_baseline_layer(args.workload)
+        out["cpu_baseline"] = cpu_baseline_config3(layers=32 if args.cpu_baseline_full else 4) if args.workload == "config3" \
+            else cpu_baseline_layer(args.workload, full=args.cpu_baseline_full)
+
+    if args.workload == "config2" and not args.headline_only and not (args.lora_rank or args.frozen_base or args.loss_mask
+                                                                        or args.six_stream or args.four_stream):
+        # The other configurations of the method's evaluation, measured in the same run, each with its own step
+        # count, roofline and oracle baseline.  A failure in one of them is recorded and does not hide the headline.
+        import copy
+        import gc
+        keep = ("value", "unit", "steps", "warmup", "ms_per_step", "ms_per_step_untraced", "dtype", "config", "roofline",
+                "roofline_pack", "capture_gbps", "capture_call_gbps", "whole_job_frac_of_hbm_peak", "step_tflops",
+                "step_mfma_frac", "backward_only_ms", "backward_only_mfma_frac", "attention_backward", "kernel_ms_per_step",
+                "loss", "loss_expected_random_init", "recompute_tokens_per_s", "reuse_speedup_over_recompute", "cpu_baseline")
+        also = {}
+
+        def leg(name, workload, steps, warmup, baseline, **flags):
+            a = copy.copy(args)
+            a.workload, a.steps, a.warmup = workload, steps, warmup
+            for k, v in flags.items():
+                setattr(a, k, v)
+            try:
+                gc.collect()
+                torch.cuda.empty_cache()
+                res = runners[workload](a, torch, A)
+                if baseline is not None and not args.no_cpu_baseline:
+                    res["cpu_baseline"] = baseline(res)
+                also[name] = {k: res[k] for k in keep if k in res}
+            except Exception as e:   # noqa: BLE001  (reported in the line, never silently dropped)
+                also[name] = {"error": "%s: %s" % (type(e).__name__, e)}
+
+        leg("config3", "config3", 10, 3, lambda r: cpu_baseline_config3(layers=32))
+        base5 = {}
+        leg("config5_dense", "config5", 10, 2, lambda r: base5.setdefault("b", cpu_baseline_layer("config5", full=True)))
+        leg("config5_loss_mask", "config5", 10, 2, lambda r: base5.get("b") or cpu_baseline_layer("config5", full=True), loss_mask=True)
+        leg("config4", "config4", 2, 1, lambda r: config4_baseline(r, out["cpu_baseline"]) if "cpu_baseline" in out else None)
+        out["also"] = also
     print(json.dumps(out))
 
 
