@@ -140,7 +140,7 @@ static LayerBwdPlan plan_layer_bwd(const alch_layer_shape& s, int T, void* ws, s
     p.dX2 = a.take(t * H * E);
     p.dO = a.take(t * QD * E);
     p.dQKV = a.take(t * (QD + 2 * KD) * E);
-    p.delta = static_cast<float*>(a.take(t * s.n_q_heads * sizeof(float)));
+    p.delta = static_cast<float*>(a.take(2 * t * s.n_q_heads * sizeof(float)));  // delta, and LSE * log2(e) behind it
     p.partial = static_cast<float*>(a.take((size_t)rmsnorm_bwd_blocks(T) * H * sizeof(float)));
     p.O_re = a.take(t * QD * E);
     p.X2_re = a.take(t * H * E);

@@ -15,6 +15,7 @@
 //     tiles of K and V:  S^T = K Q^T, dP^T = V dO^T, dQ += dS K.
 // The LDS tile is [rows][128] bf16 with the 16-byte chunk index XOR-ed by a function of the row
 // that makes both the row-major and the transposing reads bank-conflict free.
+#include <type_traits>
 #include "kernels.h"
 
 namespace alch {
@@ -37,6 +38,7 @@ struct AttnMfmaParams {
     const __bf16 *Q, *K, *V, *O, *dO;
     const float* LSE;
     float* delta;  // written by the dQ kernel (row sums of dO*O), read by the dK/dV kernel
+    float* lse2;   // LSE * log2(e), written by the dQ kernel for the dK/dV kernel (its exponent is one fused multiply-add)
     __bf16 *dQ, *dK, *dV;
     const int* cu;
     const int* prefix;     // null, or per sequence: -1 / the earlier sequence whose keys it also attends to
@@ -209,9 +211,15 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
 
     // The tile stream: for the key block's own sequence and then (kPrefix) every sequence that names it as
     // prefix, for every query head of the group, the 64-query tiles qt_first .. qt_end-1 of that sequence.
+    // Without prefixes the stream is ordered in two passes over the heads of the group: first the (at most two)
+    // tiles of every head that meet the diagonal of the key block, which need the causal mask, then all the
+    // others, which need none -- rows and keys past the end of the sequence are zero-filled by the loads, so
+    // they contribute exactly nothing to rows that are stored.  n_mask iterations take the masked code.
+    const int n_diag = kPrefix ? nqt : min(2, nqt);
+    const int n_mask = kPrefix ? n_it : G * n_diag;
     struct Cursor {
         int c, row0, n;         // sequence of the queries, its first row in the batch, its length
-        int qt_first, qt_end;   // its tiles that this key block meets
+        int qt_first, qt_end;   // its tiles that this key block meets in the current pass
         int h, qt;              // query head and tile of the current position
     };
     auto advance = [&](Cursor& q) {
@@ -219,6 +227,12 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
         q.qt = q.qt_first;
         if (++q.h < kv * G + G) return;
         q.h = kv * G;
+        if constexpr (!kPrefix) {
+            if (q.qt_first == qt0 && nqt > n_diag) {  // second pass: the tiles past the diagonal
+                q.qt_first = q.qt = qt0 + n_diag;
+                q.qt_end = qt0 + nqt;
+            }
+        }
         if constexpr (kPrefix) {
             int c = q.c + 1;
             while (c < p.n_seqs && !(p.prefix[c] == seq && p.cu[c + 1] > p.cu[c])) ++c;
@@ -267,7 +281,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
 #pragma unroll
         for (int e = e0; e < e0 + n; ++e) {
             const unsigned rel = (unsigned)(rel0 + 8 * (e >> 2) + (e & 3));
-            float arg = __builtin_fmaf(s[e], sl2, -l[e >> 2][e & 3] * kLog2e);
+            float arg = __builtin_fmaf(s[e], sl2, -l[e >> 2][e & 3]);
             arg = rel >= live ? -INFINITY : arg;
             const float pr = __builtin_amdgcn_exp2f(arg);
             s[e] = pr;
@@ -292,7 +306,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
         LoadDesc d;
         d.q = rsrc_of(p.Q + row * p.ldq + q.h * kD, ext);
         d.dO = rsrc_of(p.dO + row * p.ldq + q.h * kD, ext);
-        d.sc = rsrc_of((wave == 0 ? p.LSE : p.delta) + row * p.Hq + q.h,
+        d.sc = rsrc_of((wave == 0 ? p.lse2 : p.delta) + row * p.Hq + q.h,
                        (rows > 0 && wave < 2) ? ((long long)(rows - 1) * p.Hq + 1) * 4 : 0);
         return d;
     };
@@ -308,7 +322,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
         dma4(d.sc, st + sc_lds, sc_voff);
     };
     // Four LDS stages, tile t in stage t & 3; iteration `it` works on tiles it and it+1 and loads tile it+3.
-    Cursor q_ld{seq, seq_start, len, qt0, qt0 + nqt, kv * G, qt0};
+    Cursor q_ld{seq, seq_start, len, qt0, qt0 + n_diag, kv * G, qt0};
     Meta m_cur = meta_of(q_ld);
     issue_tile(desc_of(q_ld, 0 < n_it), lds0);
     advance(q_ld);
@@ -348,7 +362,8 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
 
 #define ALCH_SB __builtin_amdgcn_sched_barrier(0)
     struct Frags { bf16x8 rdo, rq, dq, ddo; };
-    for (int it = 0; it < n_it; ++it) {
+    auto iteration = [&](auto masked_tag, int it) __attribute__((always_inline)) {
+        constexpr bool kMasked = decltype(masked_tag)::value;
         const char* tq = smem + (uint32_t)(it & 3) * kStageBytes;
         const char* tdo = tq + kTileBytes;
         const char* nq = smem + (uint32_t)((it + 1) & 3) * kStageBytes;
@@ -379,11 +394,13 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
         // between two matrix instructions: h1 = masked exponent -> probability, h2 = dS = p (dP - delta).
         {
             auto sm_h1 = [&](f32x16& sc, const f32x4 (&l)[4], const Meta& m, int blk, int e) {
-                const int rel0 = m.ibase + blk * 32 + 4 * half - (kPrefix ? m.sub : jl);
-                const unsigned live = kPrefix ? m.live : live_own;
-                const unsigned rel = (unsigned)(rel0 + 8 * (e >> 2) + (e & 3));
-                float arg = __builtin_fmaf(sc[e], sl2, -l[e >> 2][e & 3] * kLog2e);
-                arg = rel >= live ? -INFINITY : arg;
+                float arg = __builtin_fmaf(sc[e], sl2, -l[e >> 2][e & 3]);
+                if constexpr (kMasked) {
+                    const int rel0 = m.ibase + blk * 32 + 4 * half - (kPrefix ? m.sub : jl);
+                    const unsigned live = kPrefix ? m.live : live_own;
+                    const unsigned rel = (unsigned)(rel0 + 8 * (e >> 2) + (e & 3));
+                    arg = rel >= live ? -INFINITY : arg;
+                }
                 float pr = __builtin_amdgcn_exp2f(arg);
                 asm volatile("" : "+v"(pr));
                 sc[e] = pr;
@@ -461,6 +478,11 @@ __global__ __launch_bounds__(256) void k_attn_bwd_dkv_mfma(AttnMfmaParams p) {
         for (int ks = 0; ks < 2; ++ks) { pf0[ks] = pfn[ks]; dsf0[ks] = dsfn[ks]; }
         m_cur = m_nxt; m_nxt = m_nn; m_nn = m_n3; m_n3 = m_n4;
         dsc = dsc_next;
+    };
+    {
+        int it = 0;
+        for (; it < n_mask && it < n_it; ++it) iteration(std::true_type{}, it);
+        for (; it < n_it; ++it) iteration(std::false_type{}, it);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
@@ -507,6 +529,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_dq_mfma(AttnMfmaParams p) {
     const int i = i0 + (lane & 31);  // this lane's query (accumulator column)
     const bool i_ok = i < len;
     const float lse2 = i_ok ? p.LSE[(long long)(seq_start + i) * p.Hq + h] * kLog2e : 0.f;
+    if (i_ok && half == 0) p.lse2[(long long)(seq_start + i) * p.Hq + h] = lse2;
     // delta_i = sum_d dO[i,d] O[i,d]: each lane holds 64 of the 128 elements of its query's dO row
     float del = 0.f;
     {
@@ -763,7 +786,7 @@ bool attn_mfma_supported(const AttnArgs& a) {
 int launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t stream) {
     AttnMfmaParams p;
     p.Q = (const __bf16*)a.Q; p.K = (const __bf16*)a.K; p.V = (const __bf16*)a.V; p.dO = (const __bf16*)a.dO;
-    p.O = (const __bf16*)a.O; p.LSE = a.LSE; p.delta = a.delta;
+    p.O = (const __bf16*)a.O; p.LSE = a.LSE; p.delta = a.delta; p.lse2 = a.delta + (size_t)a.T * a.Hq;
     p.positions = a.positions; p.rope_log2_base = a.rope_base > 0.f ? log2f(a.rope_base) : 0.f;
     p.dQ = (__bf16*)a.dQ; p.dK = (__bf16*)a.dK; p.dV = (__bf16*)a.dV;
     p.cu = a.cu_seqlens; p.prefix = a.prefix; p.n_seqs = a.n_seqs; p.Hq = a.Hq; p.Hkv = a.Hkv;

@@ -151,7 +151,8 @@ struct AttnArgs {
     const int* prefix_host = nullptr;
     const void *Q, *K, *V, *O, *dO;  // dense [T, heads*D]
     const float* LSE;                // [T, Hq]
-    float* delta;                    // scratch [T, Hq]: row sums of dO*O, produced inside launch_attn_bwd
+    float* delta;                    // scratch [2, T, Hq]: row sums of dO*O, produced inside launch_attn_bwd; the
+                                     // matrix-core kernels keep LSE * log2(e) in the second half
     void *dQ, *dK, *dV;              // row stride ld_dqkv elements; dQ, dK, dV adjacent: [dQ | dK | dV] rows
     long long ld_dqkv;
     // rope_base > 0: dQ and dK come out already rotated by minus the RoPE angle (RoPE backward)
