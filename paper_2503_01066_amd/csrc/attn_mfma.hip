@@ -543,6 +543,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_dq_mfma(AttnMfmaParams p) {
         del += __shfl_xor(del, 32, 64);
         if (i_ok && half == 0) p.delta[(long long)(seq_start + i) * p.Hq + h] = del;
     }
+    const float ndel = -del;
     f32x16 dQ[4];
 #pragma unroll
     for (int n = 0; n < 4; ++n)
@@ -591,9 +592,11 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_dq_mfma(AttnMfmaParams p) {
             if (!in_pre && j0 > i0 + 31) continue;
             const char* bk = tk + jb * 32 * 256;
             const char* bv = tv + jb * 32 * 256;
-            f32x16 St, dPt;  // transposed: rows = keys, columns = queries
+            // transposed: rows = keys, columns = queries.  dP starts from -delta (every element of a lane belongs
+            // to the lane's query), so the accumulator comes out as dP - delta
+            f32x16 St, dPt;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) St[e] = dPt[e] = 0.f;
+            for (int e = 0; e < 16; ++e) { St[e] = 0.f; dPt[e] = ndel; }
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk) {
                 St = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_d(bk, lane_d, kk), qf[kk], St, 0, 0, 0);
@@ -602,7 +605,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_dq_mfma(AttnMfmaParams p) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(St[e], sl2, -lse2));
-                dPt[e] = pr * (dPt[e] - del);
+                dPt[e] = pr * dPt[e];
             }
             if (!i_ok || j0 + 31 > lim0) {
 #pragma unroll
