@@ -1,6 +1,7 @@
 // Plain tiled GEMM in fp32 arithmetic for the fp32 storage type and for bf16 problems whose
 // shapes or alignments the matrix-core kernel does not take.  Same contract as the
 // matrix-core kernel (segments, split outputs, accumulate); correctness first.
+#include <algorithm>
 #include "kernels.h"
 #include <hip/hip_bf16.h>
 
@@ -134,6 +135,57 @@ int launch_gemm_generic(const GemmDesc& d, hipStream_t stream) {
     return ALCH_OK;
 }
 
+// The matrix-core kernel addresses an operand through one buffer descriptor and refuses operands of 2 GiB or more.
+// The operands that grow with the batch are indexed by tokens: the rows of a k-major A (data gradients, forward)
+// or the contraction index of a weight gradient.  A product refused for that reason alone is cut along that
+// index into bands the kernel takes: row bands are independent products; contraction bands accumulate into the
+// output one after the other (sum in fp32 inside a band, one rounding to the storage type per band).
+// Returns true when the product was launched that way (rc holds the status).
+static bool launch_gemm_in_bands(const GemmDesc& d, hipStream_t stream, int& rc) {
+    if (d.dtype != ALCH_BF16 || d.m_dev || d.k_dev || d.row_mask || d.n_out != 1 || d.out[0].m_begin != 0) return false;
+    const long long kLimit = (1LL << 31) - 1;
+    const bool rows = d.a_kmajor;                        // bands over M
+    const bool contr = !d.a_kmajor && !d.b_kmajor;       // bands over K (single operand pair)
+    if (!rows && !contr) return false;
+    if (contr && d.n_seg != 1) return false;
+    long long ld_max = 1;
+    for (int s = 0; s < d.n_seg; ++s) ld_max = std::max(ld_max, contr ? std::max(d.seg[s].lda, d.seg[s].ldb) : d.seg[s].lda);
+    if (d.epilogue == kEpiSwigluBwd) ld_max = std::max(ld_max, std::max(d.ldgu, d.out[0].ldc));
+    const long long total = rows ? d.M : d.seg[0].K;
+    long long band = kLimit / (ld_max * 2) / 256 * 256;
+    if (band < 256 || band >= total) return false;       // nothing to gain, or not the reason of the refusal
+    auto band_desc = [&](long long b0, long long n) {
+        GemmDesc e = d;
+        if (rows) {
+            e.M = (int)n;
+            for (int s = 0; s < d.n_seg; ++s) e.seg[s].A = static_cast<const char*>(d.seg[s].A) + b0 * d.seg[s].lda * 2;
+            e.out[0].C = static_cast<char*>(d.out[0].C) + b0 * d.out[0].ldc * 2;
+            if (d.epilogue == kEpiSwigluBwd) {
+                e.G = static_cast<const char*>(d.G) + b0 * d.ldgu * 2;
+                e.U = static_cast<const char*>(d.U) + b0 * d.ldgu * 2;
+                if (d.act_out) e.act_out = static_cast<char*>(d.act_out) + b0 * (long long)d.N * 2;
+            }
+        } else {
+            e.seg[0].K = (int)n;
+            e.seg[0].A = static_cast<const char*>(d.seg[0].A) + b0 * d.seg[0].lda * 2;
+            e.seg[0].B = static_cast<const char*>(d.seg[0].B) + b0 * d.seg[0].ldb * 2;
+            e.accumulate = b0 == 0 ? d.accumulate : 1;
+        }
+        return e;
+    };
+    for (long long b0 = 0; b0 < total; b0 += band)
+        if (!gemm_mfma_supported(band_desc(b0, std::min(band, total - b0)))) return false;
+    rc = ALCH_OK;
+    for (long long b0 = 0; b0 < total && rc == ALCH_OK; b0 += band) {
+        const GemmDesc e = band_desc(b0, std::min(band, total - b0));
+        double k_total = 0;
+        for (int s = 0; s < e.n_seg; ++s) k_total += e.seg[s].K;
+        TraceScope ts(kTraceGemmMfma, 2.0 * e.M * e.N * k_total, ((double)e.M * k_total + (double)e.N * k_total + (double)e.M * e.N) * 2, stream);
+        rc = launch_gemm_mfma(e, stream);
+    }
+    return true;
+}
+
 int launch_gemm(const GemmDesc& d, hipStream_t stream) {
     if (d.M <= 0 || d.N <= 0) return ALCH_OK;
     double k_total = 0;
@@ -150,6 +202,8 @@ int launch_gemm(const GemmDesc& d, hipStream_t stream) {
         TraceScope ts(kTraceGemmMfma, flops, bytes, stream);
         return launch_gemm_mfma(d, stream);
     }
+    int rc = ALCH_OK;
+    if (launch_gemm_in_bands(d, stream, rc)) return rc;
     TraceScope ts(kTraceGemmGeneric, flops, bytes, stream);
     return launch_gemm_generic(d, stream);
 }

@@ -146,3 +146,31 @@ def test_gemm_operands_as_column_slices_of_wider_buffers(a_k, b_k):
         C = A_.alch_gemm(M, N, terms, a_k, b_k, workspace=w)
         torch.cuda.synchronize()
         assert rel_err(to_np(C), ref) < 6e-3, (a_k, b_k, w is None)
+
+
+@pytest.mark.parametrize("a_k,b_k", [(True, False), (False, False)])
+def test_gemm_token_indexed_operand_of_more_than_2_gib(a_k, b_k):
+    # an operand whose rows are tokens, 40,000 rows of a [*, 28672] buffer (2.3 GB): beyond what one launch of the
+    # matrix-core kernel addresses; the product is cut into row bands (data gradient) or contraction bands
+    # (weight gradient) of that kernel instead of dropping to the plain fp32 kernel
+    import paper_2503_01066_amd as A_
+    rng = np.random.default_rng(5)
+    T, wide = 40000, 28672
+    big = torch.zeros((T, wide), dtype=torch.bfloat16, device="cuda")
+    if a_k:      # C[T, 256] = A[T, 128] B[128, 256], A a column slice of the big buffer
+        M, N, K = T, 256, 128
+        A, B, ref = operands(rng, M, N, K, True, False, "bf16")
+        big[:, 64:64 + K] = to_dev(A, "bf16")
+        terms = [(big[:, 64:64 + K], to_dev(B, "bf16"), K)]
+    else:        # C[256, 128] (+)= A[T, 256]^T B[T, 128], A a column slice of the big buffer, contraction over tokens
+        M, N, K = 256, 128, T
+        A, B, ref = operands(rng, M, N, K, False, False, "bf16")
+        big[:, 64:64 + M] = to_dev(A, "bf16")
+        terms = [(big[:, 64:64 + M], to_dev(B, "bf16"), K)]
+    A_.alch_trace_enable(True)
+    C = A_.alch_gemm(M, N, terms, a_k, b_k)
+    torch.cuda.synchronize()
+    A_.alch_trace_enable(False)
+    kinds = [r[0] for r in A_.alch_trace_collect()]
+    assert kinds and all(k == "gemm_mfma" for k in kinds) and len(kinds) >= 2, kinds
+    assert rel_err(to_np(C), ref) < (6e-3 if a_k else 1.2e-2)   # contraction bands round once per band
