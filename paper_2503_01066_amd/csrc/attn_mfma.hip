@@ -518,6 +518,55 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_dq_mfma(AttnMfmaParams p) {
     const int kv = h / (p.Hq / p.Hkv);
     const int i0 = qb * 128 + wave * 32;  // this wave's first query
 
+    const uint32_t lane_d = frag_d_lane(lane), lane_r0 = frag_rows_lane(lane, 0), lane_r1 = frag_rows_lane(lane, 1);
+    uint32_t voff[4];
+    tile_voffsets(voff, p.ldk, wave, lane);
+    // key tiles: all tiles of the prefix sequence (if any), then own tiles 0 .. the last one that holds a
+    // key <= the work-group's last query
+    const int pre = p.prefix ? p.prefix[seq] : -1;
+    const int pre_start = pre >= 0 ? p.cu[pre] : 0, pre_len = pre >= 0 ? p.cu[pre + 1] - pre_start : 0;
+    const int npt = (pre_len + kTileRows - 1) / kTileRows;
+    const int last_q = min(qb * 128 + 127, len - 1);
+    const int n_it = npt + last_q / kTileRows + 1;
+    const float sl2 = p.scale * kLog2e;
+    // Buffer descriptors of a tile from scalar arithmetic alone: base of the sequence's K / V plus the tile's byte
+    // offset, extent = what is left of the sequence (rows past its end read as zero), both below 2 GiB.
+    const long long kv_off = (long long)kv * kD;
+    const unsigned long long baseK_own = reinterpret_cast<unsigned long long>(p.K + (long long)seq_start * p.ldk + kv_off);
+    const unsigned long long baseV_own = reinterpret_cast<unsigned long long>(p.V + (long long)seq_start * p.ldk + kv_off);
+    const unsigned long long baseK_pre = reinterpret_cast<unsigned long long>(p.K + (long long)pre_start * p.ldk + kv_off);
+    const unsigned long long baseV_pre = reinterpret_cast<unsigned long long>(p.V + (long long)pre_start * p.ldk + kv_off);
+    const unsigned tile_bytes = (unsigned)(kTileRows * p.ldk * 2);   // distance of two tiles
+    struct TileSrc { i32x4 k, v; };
+    auto desc = [&](unsigned long long base, int rows) {
+        const unsigned n = rows > 0 ? (unsigned)(((long long)(min(rows, kTileRows) - 1) * p.ldk + kD) * 2) : 0u;
+        i32x4 r;
+        r[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)base);
+        r[1] = __builtin_amdgcn_readfirstlane((int)((unsigned)(base >> 32) & 0xffffu));
+        r[2] = __builtin_amdgcn_readfirstlane((int)n);
+        r[3] = 0x00020000;
+        return r;
+    };
+    auto tile_src = [&](int it) {
+        const bool in_pre = it < npt;
+        const int tile = in_pre ? it : it - npt;
+        const int rows = it < n_it ? (in_pre ? pre_len : len) - tile * kTileRows : 0;  // past the last tile: nothing moves
+        const unsigned long long off = (unsigned long long)tile * tile_bytes;
+        TileSrc t;
+        t.k = desc((in_pre ? baseK_pre : baseK_own) + off, rows);
+        t.v = desc((in_pre ? baseV_pre : baseV_own) + off, rows);
+        return t;
+    };
+    // load j (0..7) of a wave's share of tile `it`: four 1 KB pieces of the K tile, four of the V tile
+    auto issue_piece = [&](const TileSrc& t, int it, int j) {
+        const uint32_t st = lds0 + (uint32_t)(it & 1) * kStageBytes + (j < 4 ? 0u : (uint32_t)kTileBytes);
+        dma16(j < 4 ? t.k : t.v, st + (uint32_t)(wave * 4 + (j & 3)) * 1024u, voff[j & 3]);
+    };
+    {   // the first tile is on its way while the Q, dO and O fragments below are fetched
+        const TileSrc t0 = tile_src(0);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) issue_piece(t0, 0, j);
+    }
     const __bf16* Qb = p.Q + (long long)seq_start * p.ldq + h * kD;
     const __bf16* dOb = p.dO + (long long)seq_start * p.ldq + h * kD;
     bf16x8 qf[8], gf[8];
@@ -550,33 +599,14 @@ __global__ __launch_bounds__(256, 2) void k_attn_bwd_dq_mfma(AttnMfmaParams p) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) dQ[n][e] = 0.f;
 
-    const uint32_t lane_d = frag_d_lane(lane), lane_r0 = frag_rows_lane(lane, 0), lane_r1 = frag_rows_lane(lane, 1);
-    uint32_t voff[4];
-    tile_voffsets(voff, p.ldk, wave, lane);
-    // key tiles: all tiles of the prefix sequence (if any), then own tiles 0 .. the last one that holds a
-    // key <= the work-group's last query
-    const int pre = p.prefix ? p.prefix[seq] : -1;
-    const int pre_start = pre >= 0 ? p.cu[pre] : 0, pre_len = pre >= 0 ? p.cu[pre + 1] - pre_start : 0;
-    const int npt = (pre_len + kTileRows - 1) / kTileRows;
-    const int last_q = min(qb * 128 + 127, len - 1);
-    const int n_it = npt + last_q / kTileRows + 1;
-    const float sl2 = p.scale * kLog2e;
-
-    auto issue = [&](int it) {
-        const bool in_pre = it < npt;
-        const int row_first = (in_pre ? it : it - npt) * kTileRows;
-        const int rows_valid = (in_pre ? pre_len : len) - row_first;
-        const long long row = (long long)((in_pre ? pre_start : seq_start) + row_first);
-        const uint32_t st = lds0 + (uint32_t)(it & 1) * kStageBytes;
-        issue_rows_tile(p.K + row * p.ldk + kv * kD, p.ldk, rows_valid, st, wave, voff);
-        issue_rows_tile(p.V + row * p.ldk + kv * kD, p.ldk, rows_valid, st + kTileBytes, wave, voff);
-    };
-
-    issue(0);
     for (int it = 0; it < n_it; ++it) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        if (it + 1 < n_it) issue(it + 1);
+        {   // the loads of tile it+1 (two waves share a SIMD: while this one queues its loads the other computes)
+            const TileSrc tn = tile_src(it + 1);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) issue_piece(tn, it + 1, j);
+        }
         const char* tk = smem + (it & 1) * kStageBytes;
         const char* tv = tk + kTileBytes;
         // keys of this tile count from 0 inside their own sequence; key j is visible to query i when
