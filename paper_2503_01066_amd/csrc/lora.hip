@@ -83,82 +83,146 @@ __global__ __launch_bounds__(256) void k_lora_down(const T* __restrict__ X, long
 
 // ---- down on the matrix cores (bf16, K a multiple of 64): eight multiply-adds per streamed element are
 // too many for the vector ALU to keep up with HBM, so the [32 rows x 16 k] x [16 k x 32 columns] MFMA does
-// them (columns >= r are zero operands).  A work-group owns 32 rows; its four wavefronts split K and fold
-// their sums through LDS in a fixed order.  Up to three (X, S, Y) problems per launch (blockIdx.z).
+// them.  A matrix-instruction operand wants one row per lane (a wave-wide load of that shape touches 64 cache
+// lines for 1 KB); the rows are fetched as whole 128-byte lines straight into LDS instead (buffer_load ... lds,
+// eight lanes per line) and the operands are read from there, which also lets several S share one pass over X.
+//
+// A problem = one streamed X [Trows, K] and up to four groups of eight columns of the output, each with its
+// own [rows <= 8, K] matrix S and its own destination (problems that share X are merged by the host: the t1
+// of q, k, v, or of gate and up, cost one pass).  A work-group owns 32 rows; its four wavefronts split K in
+// chunks of 64 and fold their sums through LDS in a fixed order.  Every wavefront runs a private ring of
+// stages [X 32 rows x 128 B | S 8 rows x 128 B per group]: no barrier inside the loop.  16-byte piece c of
+// row r sits at position c ^ ((r >> 1) & 7) of the row, which makes the operand reads conflict-free.
 typedef __attribute__((ext_vector_type(16))) float f32x16_l;
-struct LoraDownJob {
-    const __bf16* X; long long ldx; int K;
-    const __bf16* S; long long lds; int r;   // r = 0: zero-fill the slot
-    __bf16* Y;
+typedef __attribute__((ext_vector_type(4))) int i32x4_l;
+struct LoraDownGroup {
+    const __bf16* S; long long lds; int rows;  // rows = 0: no such group
+    __bf16* Y;                                 // first of the group's eight output columns
+};
+static constexpr int kDownProblems = 6, kDownGroups = 4;
+struct LoraDownProblem {
+    const __bf16* X; long long ldx; int K, ngroups;
+    LoraDownGroup g[kDownGroups];
 };
 struct LoraDownParams {
-    LoraDownJob job[3];
+    LoraDownProblem pr[kDownProblems];
+    __bf16* slot[3]; int slot_r[3]; int nslots;  // output slots: columns slot_r .. slot_cols-1 are zero-filled
     int Trows; long long ldy; float alpha; int slot_cols;
 };
+template <int kG> struct DownCfg {
+    static constexpr int kStageBytes = 4096 + kG * 1024;
+    static constexpr int kStages = kG == 1 ? 7 : kG == 2 ? 6 : kG == 3 ? 5 : 4;  // at most 36 KB per wavefront
+};
+__device__ __forceinline__ void lora_dma16(i32x4_l r, uint32_t lds_addr, uint32_t voff) {
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_addr), "v"(voff), "s"(r)
+                 : "memory", "m0");
+}
+__device__ __forceinline__ i32x4_l lora_rsrc(const void* p, long long bytes) {
+    const uint32_t n = bytes <= 0 ? 0u : (bytes > 0x7fffffffLL ? 0x7fffffffu : (uint32_t)bytes);
+    const uint64_t a = reinterpret_cast<uint64_t>(p);
+    i32x4_l r;
+    r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+    r[1] = __builtin_amdgcn_readfirstlane((int)((uint32_t)(a >> 32) & 0xffffu));
+    r[2] = __builtin_amdgcn_readfirstlane((int)n);
+    r[3] = 0x00020000;
+    return r;
+}
+template <int kG>
 __global__ __launch_bounds__(256) void k_lora_down_mfma(LoraDownParams p) {
+    constexpr int kStageBytes = DownCfg<kG>::kStageBytes, kStages = DownCfg<kG>::kStages;
+    __shared__ __attribute__((aligned(1024))) char smem[4 * kStages * kStageBytes];
     __shared__ float red[3][64][17];
-    const LoraDownJob jb = p.job[blockIdx.z];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int c = lane & 31, kh = lane >> 5;
     const long long t0 = (long long)blockIdx.x * 32;
-    const int j0 = blockIdx.y * 32;  // first output column of this pass
+    const int rows_valid = (int)(p.Trows - t0 < 32 ? p.Trows - t0 : 32);
+    if (blockIdx.y == 0) {  // the columns past the rank of every output slot
+        const int pieces = p.slot_cols >> 3;
+        const bf16x8_l z = {(__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f};
+        for (int sl = 0; sl < p.nslots; ++sl)
+            for (int idx = threadIdx.x; idx < 32 * pieces; idx += 256) {
+                const int row = idx / pieces, piece = idx % pieces;
+                if (row < rows_valid && piece * 8 >= p.slot_r[sl])
+                    *reinterpret_cast<bf16x8_l*>(p.slot[sl] + (t0 + row) * p.ldy + piece * 8) = z;
+            }
+    }
+    const LoraDownProblem& pb = p.pr[blockIdx.y];
+    if (pb.ngroups == 0) return;
+    const int nc = pb.K >> 6;
+    const int c_lo = wave * nc / 4, n = (wave + 1) * nc / 4 - c_lo;  // this wavefront's chunks of 64 k
+    char* wbase = smem + wave * (kStages * kStageBytes);
+    const uint32_t lds_w = (uint32_t)(uintptr_t)((__attribute__((address_space(3))) void*)wbase);
+    // per-lane source offsets of the loads: lane -> (row 8j + lane/8, piece (lane & 7) ^ swizzle of the LDS row)
+    const int row8 = lane >> 3, q = lane & 7;
+    uint32_t voff_x[4], voff_s[kG];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int row = 8 * j + row8;
+        voff_x[j] = (uint32_t)(row * pb.ldx * 2 + ((q ^ ((row >> 1) & 7)) << 4));
+    }
+#pragma unroll
+    for (int g = 0; g < kG; ++g) voff_s[g] = (uint32_t)(row8 * pb.g[g].lds * 2 + ((q ^ (((8 * g + row8) >> 1) & 7)) << 4));
+    const __bf16* xb = pb.X + t0 * pb.ldx + (long long)c_lo * 64;
+    const long long x_bytes = rows_valid > 0 ? ((long long)(rows_valid - 1) * pb.ldx + 64) * 2 : 0;
+    auto issue = [&](int i) {
+        const uint32_t st = lds_w + (uint32_t)(i % kStages) * kStageBytes;
+        const bool live = i < n;
+        const i32x4_l rx = lora_rsrc(xb + (long long)i * 64, live ? x_bytes : 0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) lora_dma16(rx, st + (uint32_t)j * 1024u, voff_x[j]);
+#pragma unroll
+        for (int g = 0; g < kG; ++g) {
+            const LoraDownGroup& gr = pb.g[g];
+            const i32x4_l rs = lora_rsrc(gr.S + (long long)(c_lo + i) * 64,
+                                         live && gr.rows > 0 ? ((long long)(gr.rows - 1) * gr.lds + 64) * 2 : 0);
+            lora_dma16(rs, st + 4096u + (uint32_t)g * 1024u, voff_s[g]);
+        }
+    };
     f32x16_l acc;
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-    if (j0 < jb.r) {
-        const int kq = jb.K / 4;  // this wave's share of K (a multiple of 16)
-        // rows past the end and columns past r read a valid row instead: their results are never stored
-        const long long tr = t0 + c < p.Trows ? t0 + c : p.Trows - 1;
-        const int jc = j0 + c < jb.r ? j0 + c : 0;
-        const __bf16* xp = jb.X + tr * jb.ldx + wave * kq + 8 * kh;
-        const __bf16* sp = jb.S + (long long)jc * jb.lds + wave * kq + 8 * kh;
-        // batches of 128 k (eight 16-byte loads of X and of S per lane), double buffered: the loads of
-        // the next batch are in flight while the matrix instructions consume the current one
-        auto load_batch = [&](bf16x8_l (&a)[8], bf16x8_l (&b)[8], int kb) {
+    // operand read offsets inside a stage: X row c, S row c (columns past the groups read a row that exists;
+    // their results are never stored)
+    const int cs = c < 8 * kG ? c : (c & 7);
+    uint32_t off_a[4], off_b[4];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                a[u] = *reinterpret_cast<const bf16x8_l*>(xp + kb + 16 * u);
-                b[u] = *reinterpret_cast<const bf16x8_l*>(sp + kb + 16 * u);
-            }
-        };
-        auto mma_batch = [&](const bf16x8_l (&a)[8], const bf16x8_l (&b)[8]) {
-#pragma unroll
-            for (int u = 0; u < 8; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u], b[u], acc, 0, 0, 0);
-        };
-        const int nb = kq / 128;
-        bf16x8_l a0[8], b0[8], a1[8], b1[8];
-        if (nb > 0) load_batch(a0, b0, 0);
-        int i = 0;
-        for (; i + 2 <= nb; i += 2) {
-            load_batch(a1, b1, (i + 1) * 128);
-            __builtin_amdgcn_sched_barrier(0);
-            mma_batch(a0, b0);
-            __builtin_amdgcn_sched_barrier(0);
-            if (i + 2 < nb) load_batch(a0, b0, (i + 2) * 128);
-            __builtin_amdgcn_sched_barrier(0);
-            mma_batch(a1, b1);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if (i < nb) mma_batch(a0, b0);
-        int k = nb * 128;
-        for (; k < kq; k += 16) {
-            const bf16x8_l a = *reinterpret_cast<const bf16x8_l*>(xp + k);
-            const bf16x8_l b = *reinterpret_cast<const bf16x8_l*>(sp + k);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
-        }
+    for (int u = 0; u < 4; ++u) {
+        off_a[u] = (uint32_t)(c * 128 + (((2 * u + kh) ^ ((c >> 1) & 7)) << 4));
+        off_b[u] = (uint32_t)(4096 + cs * 128 + (((2 * u + kh) ^ ((cs >> 1) & 7)) << 4));
     }
+#pragma unroll
+    for (int s = 0; s < kStages - 1; ++s) issue(s);
+    for (int i = 0; i < n; ++i) {
+        issue(i + kStages - 1);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((kStages - 1) * (4 + kG)) : "memory");
+        const char* st = wbase + (i % kStages) * kStageBytes;
+        bf16x8_l a[4], b[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            a[u] = *reinterpret_cast<const bf16x8_l*>(st + off_a[u]);
+            b[u] = *reinterpret_cast<const bf16x8_l*>(st + off_b[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u], b[u], acc, 0, 0, 0);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     if (wave > 0) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) red[wave - 1][lane][e] = acc[e];
     }
     __syncthreads();
     if (wave == 0) {
+        __bf16* yp = nullptr;
+        int yrows = 0;
+#pragma unroll
+        for (int g = 0; g < kG; ++g)
+            if ((c >> 3) == g && g < pb.ngroups) { yp = pb.g[g].Y; yrows = pb.g[g].rows; }
         // accumulator element e: row 8*(e>>2) + 4*kh + (e&3), column c
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             const float v = ((acc[e] + red[0][lane][e]) + red[1][lane][e]) + red[2][lane][e];
-            const long long t = t0 + 8 * (e >> 2) + 4 * kh + (e & 3);
-            if (t < p.Trows && j0 + c < p.slot_cols) jb.Y[t * p.ldy + j0 + c] = (__bf16)(j0 + c < jb.r ? p.alpha * v : 0.f);
+            const int row = 8 * (e >> 2) + 4 * kh + (e & 3);
+            if (row < rows_valid && (c & 7) < yrows) yp[(t0 + row) * p.ldy + (c & 7)] = (__bf16)(p.alpha * v);
         }
     }
 }
@@ -351,21 +415,42 @@ int launch_lora_down(alch_dtype dt, const LoraDown* jobs, int n_jobs, int Trows,
         if (j.K % 8 || j.ldx % 8 || j.r % 8 || (j.r > 0 && j.lds % 8))
             return fail(ALCH_ERR_UNSUPPORTED, "adapter product: widths, strides and rank must be multiples of 8");
         if (j.r > 0) { flops += 2.0 * Trows * j.K * j.r; bytes += (double)Trows * j.K * dtype_size(dt); }
-        fast = fast && j.K % 64 == 0 && aligned16(j.X) && (j.r == 0 || aligned16(j.S));
+        if (j.r > slot_cols) return fail(ALCH_ERR_INVALID_ARG, "adapter product: rank exceeds the output slot");
+        fast = fast && j.K % 64 == 0 && aligned16(j.X) && aligned16(j.Y) && (j.r == 0 || aligned16(j.S)) && 32 * j.ldx < (1LL << 30);
     }
     if (slot_cols % 8 || ldy % 8) return fail(ALCH_ERR_UNSUPPORTED, "adapter product: slot width must be a multiple of 8");
     if (Trows <= 0) return ALCH_OK;
     // algorithmic bytes: each streamed activation once (nothing for slots that are only zero-filled)
-    TraceScope ts(kTraceLora, flops, bytes, stream);
     if (fast) {
-        LoraDownParams p;
-        for (int i = 0; i < 3; ++i) {
-            const LoraDown& j = jobs[i < n_jobs ? i : 0];
-            p.job[i] = LoraDownJob{(const __bf16*)j.X, j.ldx, j.K, (const __bf16*)j.S, j.lds, j.r, (__bf16*)j.Y};
+        // problems: the eight-column groups of all jobs, those of equal X merged four at a time
+        LoraDownParams p = {};
+        int np = 0, most = 0;
+        p.nslots = n_jobs;
+        for (int i = 0; i < n_jobs; ++i) {
+            const LoraDown& j = jobs[i];
+            p.slot[i] = (__bf16*)j.Y;
+            p.slot_r[i] = j.r;
+            for (int g0 = 0; g0 < j.r; g0 += 8) {
+                LoraDownProblem* pb = np > 0 ? &p.pr[np - 1] : nullptr;
+                if (!pb || pb->X != (const __bf16*)j.X || pb->ldx != j.ldx || pb->K != j.K || pb->ngroups == kDownGroups) {
+                    pb = &p.pr[np++];
+                    pb->X = (const __bf16*)j.X; pb->ldx = j.ldx; pb->K = j.K; pb->ngroups = 0;
+                }
+                pb->g[pb->ngroups++] = LoraDownGroup{(const __bf16*)j.S + (long long)g0 * j.lds, j.lds, 8, (__bf16*)j.Y + g0};
+                most = std::max(most, pb->ngroups);
+            }
         }
         p.Trows = Trows; p.ldy = ldy; p.alpha = alpha; p.slot_cols = slot_cols;
-        k_lora_down_mfma<<<dim3(ceil_div(Trows, 32), ceil_div(slot_cols, 32), n_jobs), 256, 0, stream>>>(p);
+        bytes = 0;
+        for (int i = 0; i < np; ++i) bytes += (double)Trows * p.pr[i].K * dtype_size(dt);
+        TraceScope ts(kTraceLora, flops, bytes, stream);
+        const dim3 grid(ceil_div(Trows, 32), std::max(np, 1));
+        if (most <= 1) k_lora_down_mfma<1><<<grid, 256, 0, stream>>>(p);
+        else if (most == 2) k_lora_down_mfma<2><<<grid, 256, 0, stream>>>(p);
+        else if (most == 3) k_lora_down_mfma<3><<<grid, 256, 0, stream>>>(p);
+        else k_lora_down_mfma<4><<<grid, 256, 0, stream>>>(p);
     } else {
+        TraceScope ts(kTraceLora, flops, bytes, stream);
         for (int i = 0; i < n_jobs; ++i) {
             if (dt == ALCH_BF16) lora_down_valu<__bf16>(jobs[i], Trows, alpha, ldy, slot_cols, stream);
             else lora_down_valu<float>(jobs[i], Trows, alpha, ldy, slot_cols, stream);
